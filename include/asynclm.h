@@ -1,0 +1,146 @@
+/*
+ * libasynclm - the inference process of asynchronous LLM function calling (arXiv 2412.07017)
+ * on one AMD MI355X (gfx950): autoregressive decoding that keeps running while function calls
+ * execute, plus in-flight injection of interrupt tokens into the live K/V cache.
+ *
+ * What the calls mean follows the paper's statement of the problem:
+ *   - Sec. 5 / Fig. 4: the system intercepts the model's autoregressive token generation; one
+ *     iteration is "forward over the newest token(s) -> next-token distribution -> pick a token".
+ *   - Sec. 3.2: when a call returns, an interrupt block is inserted at the end of the token stream
+ *     (the LLM context) and generation resumes after the block.
+ *   - Sec. 5.3: queued interrupts are appended to the generated tokens and processed by the model
+ *     in its next forward pass; this never happens in the middle of a step.
+ *   - Sec. 5.5: the stateless alternative recomputes the whole context per interrupt; both see the
+ *     same context, so after any successful call the logits of a sequence equal those of a
+ *     from-scratch pass of the decoder over that sequence's whole token stream.
+ * The control plane of the paper (CML grammar, token monitor, executor, interrupt queue, critical
+ * sections, trap handling) sits above this interface and only hands it integer token ids.
+ *
+ * Model: Llama-style decoder (RMSNorm with eps inside the root, rotary embedding on half-split
+ * pairs (i, i+head_dim/2) with angle pos * theta^(-2i/head_dim), grouped-query causal attention
+ * scaled by 1/sqrt(head_dim), SwiGLU feed-forward, no biases, separate output head).
+ *
+ * Conventions
+ *   - Every function returns 0 on success or a negative ASYNCLM_E_* code.  A failed call leaves the
+ *     sequence (length, cache, logits) unchanged, except ASYNCLM_E_DEVICE which poisons the context.
+ *   - "device pointer" = memory of the GPU that was current when asynclm_create ran; "host pointer"
+ *     = ordinary process memory.  The library never frees or writes caller memory other than the
+ *     documented outputs.
+ *   - One caller thread per context.  Work is enqueued on the HIP stream given at create; calls
+ *     that return data to the host synchronise that stream, the others may return before the GPU
+ *     has finished.
+ *   - All device memory the library needs (K/V cache, rotary table, activations, logits) is
+ *     allocated in asynclm_create; no other call allocates.
+ */
+#ifndef ASYNCLM_H
+#define ASYNCLM_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define ASYNCLM_OK           0
+#define ASYNCLM_E_INVAL     -1   /* null pointer, bad sequence index, token id outside [0, vocab), count <= 0, bad shape */
+#define ASYNCLM_E_STATE     -2   /* decode / inject / logits on an empty sequence; prefill on a non-empty one */
+#define ASYNCLM_E_CAPACITY  -3   /* the call would grow a sequence beyond max_positions (checked before any change) */
+#define ASYNCLM_E_NOMEM     -4   /* device or host allocation failed in asynclm_create */
+#define ASYNCLM_E_DEVICE    -5   /* a HIP call failed; the context is unusable afterwards */
+
+#define ASYNCLM_DTYPE_FP32 0
+#define ASYNCLM_DTYPE_BF16 1
+
+typedef struct asynclm_ctx asynclm_ctx;   /* opaque; owned by the library */
+
+typedef struct {
+    int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, ffn, vocab;
+    float   rms_eps, rope_theta;
+    int32_t dtype;           /* ASYNCLM_DTYPE_*: storage type of all matrices and of the K/V cache */
+    int32_t max_seqs;        /* number of independent sequences (>= 1) */
+    int32_t max_positions;   /* K/V capacity per sequence, in tokens */
+} asynclm_config;
+/* Shape limits: head_dim in {64, 128}; n_q_heads a multiple of n_kv_heads with ratio <= 8;
+ * d_model, ffn multiples of 8; everything > 0. */
+
+/* Device pointers, borrowed: they must stay valid and unchanged until asynclm_destroy.
+ * Matrices are row-major [out, in] in `dtype`; norm gains are fp32 whatever `dtype` is.
+ * The six per-layer members are HOST arrays of n_layers device pointers (read during create). */
+typedef struct {
+    const void *embed;        /* [vocab, d_model] */
+    const float *final_norm;  /* [d_model] */
+    const void *lm_head;      /* [vocab, d_model] */
+    const float *const *attn_norm;  /* each [d_model] */
+    const void *const *wqkv;        /* each [(n_q_heads + 2 n_kv_heads) head_dim, d_model]: query rows, key rows, value rows */
+    const void *const *wo;          /* each [d_model, n_q_heads head_dim] */
+    const float *const *ffn_norm;   /* each [d_model] */
+    const void *const *wgate_up;    /* each [2 ffn, d_model]: gate rows, then up rows */
+    const void *const *wdown;       /* each [d_model, ffn] */
+} asynclm_weights;
+
+/* Create a context on the current HIP device.  `hip_stream` is a hipStream_t (NULL = the null
+ * stream) on which all work is enqueued; it is borrowed.  On failure *out is NULL. */
+int asynclm_create(asynclm_ctx **out, const asynclm_config *cfg, const asynclm_weights *w, void *hip_stream);
+
+/* Waits for outstanding work, frees everything the library allocated.  NULL is allowed. */
+int asynclm_destroy(asynclm_ctx *ctx);
+
+/* Start a sequence: process n >= 1 prompt tokens (host pointer) into the empty sequence `seq`.
+ * Afterwards the logits predict the token that follows the prompt. */
+int asynclm_prefill(asynclm_ctx *ctx, int32_t seq, const int32_t *tokens, int32_t n);
+
+/* One decoding step (Fig. 4): choose the next token - `forced_token` if >= 0, else the greedy
+ * argmax of the current logits, lowest index on ties, computed on the device - append it to the
+ * sequence and run one forward pass, leaving the logits for the token after it.
+ * token_out (host pointer, may be NULL): receives the chosen token; passing NULL avoids the
+ * stream synchronisation that reading it back needs. */
+int asynclm_decode_step(asynclm_ctx *ctx, int32_t seq, int32_t forced_token, int32_t *token_out);
+
+/* In-flight interrupt injection (Sec. 3.2, 5.3): append the k >= 1 tokens (host pointer) to the end
+ * of the live context of `seq` without touching the cached prefix, and leave the logits for the
+ * token after the block.  Legal between any two decoding steps of a non-empty sequence. */
+int asynclm_inject_interrupt(asynclm_ctx *ctx, int32_t seq, const int32_t *tokens, int32_t k);
+
+/* Copy the current next-token logits of `seq` (fp32) to out_host[0..n); n must equal vocab.
+ * Synchronises the stream. */
+int asynclm_logits(asynclm_ctx *ctx, int32_t seq, float *out_host, int32_t n);
+
+/* Device address of the same fp32[vocab] logits (valid until destroy; contents change with every
+ * call on `seq`, in stream order). */
+int asynclm_logits_device(asynclm_ctx *ctx, int32_t seq, const float **out_dev);
+
+/* Number of tokens in the context of `seq` (prompt + generated + injected). */
+int asynclm_seq_len(asynclm_ctx *ctx, int32_t seq, int32_t *len);
+
+/* Forget the sequence: length 0, cache rows reusable. */
+int asynclm_reset(asynclm_ctx *ctx, int32_t seq);
+
+/* Block until all enqueued work of this context has finished. */
+int asynclm_synchronize(asynclm_ctx *ctx);
+
+/* Tuning knobs; all have working defaults.  Unknown names give ASYNCLM_E_INVAL.
+ *   "chunk"        rows processed per forward pass by prefill / inject (1 .. built-in maximum);
+ *                  1 = token by token through the decode kernels
+ *   "graph"        1 = replay decoding steps as a captured HIP graph, 0 = launch kernels one by one
+ *   "attn_split"   0 = choose the number of sequence splits of decode attention from the length,
+ *                  n > 0 = always use n */
+int asynclm_set_option(asynclm_ctx *ctx, const char *name, int32_t value);
+
+/* Per-kernel-class GPU time of ONE decoding step (forced token), measured with HIP events around
+ * every launch (graphs off for this step).  The step is a real step: the sequence grows by one.
+ * names_out: receives a pointer to a static array of class names; ms_out[0..n_classes) receives the
+ * summed milliseconds and launches_out[0..n_classes) the number of launches per class.
+ * Returns the number of classes (>= 0) or a negative error.  Pass cap = capacity of the arrays. */
+int asynclm_profile_step(asynclm_ctx *ctx, int32_t seq, int32_t forced_token, const char *const **names_out,
+                         float *ms_out, int32_t *launches_out, int32_t cap);
+
+/* Text for an error code; never NULL. */
+const char *asynclm_strerror(int code);
+
+/* Library version, e.g. "0.1.0". */
+const char *asynclm_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ASYNCLM_H */

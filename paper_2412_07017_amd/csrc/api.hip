@@ -1,0 +1,424 @@
+// C ABI of libasynclm: sequence state machine, argument checking, memory, launch order.
+#include "../../include/asynclm.h"
+#include "common.h"
+#include "launch.h"
+
+#include <cmath>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <map>
+#include <new>
+#include <vector>
+
+using namespace asynclm;
+
+struct asynclm_ctx {
+    asynclm_config cfg{};
+    Geom g{};
+    hipStream_t stream = nullptr;
+    int device = 0;
+    bool poisoned = false;
+    hipError_t last_hip = hipSuccess;
+
+    const void* embed = nullptr; const float* final_norm = nullptr; const void* lm_head = nullptr;
+    std::vector<const float*> attn_norm, ffn_norm;
+    std::vector<const void*> wqkv, wo, wgate_up, wdown;
+
+    std::vector<void*> allocs;          // everything from hipMalloc
+    void* kv = nullptr;                 // [seq][layer][k|v][Hkv][max_pos][dh] in cfg.dtype
+    float* logits = nullptr;            // [max_seqs][V]
+    DecodeBuffers b{};
+    int32_t* token_host = nullptr;      // pinned, 1 int
+
+    std::vector<int32_t> len;           // host mirror of the sequence lengths
+
+    // options
+    int opt_chunk = 1, opt_graph = 1, opt_attn_split = 0;
+
+    std::map<int, hipGraphExec_t> graphs;   // key: nsplit * 2 + with_head
+
+    // profiling of one step
+    bool prof = false;
+    std::vector<hipEvent_t> prof_events;
+    std::vector<int> prof_class;
+};
+
+namespace {
+
+const char* const kClassNames[KC_COUNT] = {
+    "begin_step", "embed", "qkv_rope_kvwrite", "attn_decode", "o_proj_residual", "gate_up_swiglu",
+    "down_residual", "lm_head", "argmax", "chunk_prep", "chunk_gemm", "chunk_attn", "chunk_misc"};
+
+// With ASYNCLM_VERBOSE set in the environment, HIP failures are reported on stderr.
+void report_hip(const char* where, hipError_t e) {
+    if (std::getenv("ASYNCLM_VERBOSE")) std::fprintf(stderr, "[asynclm] %s: %s\n", where, hipGetErrorString(e));
+}
+
+int fail_device(asynclm_ctx* c, hipError_t e) {
+    report_hip("device call failed", e);
+    c->poisoned = true;
+    c->last_hip = e;
+    return ASYNCLM_E_DEVICE;
+}
+
+#define HIPCK(c, expr)                                         \
+    do {                                                       \
+        hipError_t _e = (expr);                                \
+        if (_e != hipSuccess) return fail_device((c), _e);     \
+    } while (0)
+
+template <class F>
+hipError_t run(asynclm_ctx* c, int kc, F&& f) {
+    if (!c->prof) return f();
+    hipEvent_t e0, e1;
+    hipError_t e;
+    if ((e = hipEventCreate(&e0)) != hipSuccess) return e;
+    if ((e = hipEventCreate(&e1)) != hipSuccess) return e;
+    c->prof_events.push_back(e0); c->prof_events.push_back(e1); c->prof_class.push_back(kc);
+    if ((e = hipEventRecord(e0, c->stream)) != hipSuccess) return e;
+    if ((e = f()) != hipSuccess) return e;
+    return hipEventRecord(e1, c->stream);
+}
+
+size_t elem_bytes(const asynclm_ctx* c) { return c->cfg.dtype == ASYNCLM_DTYPE_FP32 ? 4 : 2; }
+
+void* kv_layer_ptr(const asynclm_ctx* c, int layer) {
+    return (char*)c->kv + (size_t)layer * c->g.kv_layer_stride * elem_bytes(c);
+}
+
+int pick_nsplit(const asynclm_ctx* c, int len_after) {
+    if (c->opt_attn_split > 0) return c->opt_attn_split < ATTN_MAX_SPLIT ? c->opt_attn_split : ATTN_MAX_SPLIT;
+    int want = (len_after + 63) / 64, n = 1;
+    while (n < want && n < ATTN_MAX_SPLIT) n *= 2;
+    return n;
+}
+
+// One forward pass of a single row whose token/position are already in the step descriptor.
+hipError_t forward_single(asynclm_ctx* c, int seq, bool with_head, int nsplit) {
+    const int dt = c->cfg.dtype;
+    const Geom& g = c->g;
+    hipStream_t s = c->stream;
+    hipError_t e;
+    if ((e = run(c, KC_EMBED, [&] { return launch_embed(dt, c->embed, c->b, g, s); }))) return e;
+    for (int l = 0; l < c->cfg.n_layers; ++l) {
+        void* kvl = kv_layer_ptr(c, l);
+        if ((e = run(c, KC_QKV, [&] { return launch_qkv(dt, c->wqkv[l], c->attn_norm[l], kvl, c->b, g, s); }))) return e;
+        if ((e = run(c, KC_ATTN, [&] { return launch_attn_decode(dt, kvl, nsplit, c->b, g, s); }))) return e;
+        if ((e = run(c, KC_OPROJ, [&] { return launch_oproj(dt, c->wo[l], c->b, g, s); }))) return e;
+        if ((e = run(c, KC_GATEUP, [&] { return launch_gateup(dt, c->wgate_up[l], c->ffn_norm[l], c->b, g, s); }))) return e;
+        if ((e = run(c, KC_DOWN, [&] { return launch_down(dt, c->wdown[l], c->b, g, s); }))) return e;
+    }
+    if (with_head) {
+        // logits of every sequence live in one array; the kernels pick the row from the descriptor
+        if ((e = run(c, KC_LMHEAD, [&] { return launch_lmhead(dt, c->lm_head, c->final_norm, c->logits + (size_t)seq * g.V, c->b, g, s); }))) return e;
+        if ((e = run(c, KC_ARGMAX, [&] { return launch_argmax(c->logits, c->b, g, s); }))) return e;
+    }
+    return hipSuccess;
+}
+
+// The same pass, replayed from a captured graph (one graph per split count / head flag / sequence).
+hipError_t forward_single_graph(asynclm_ctx* c, int seq, bool with_head, int nsplit) {
+    const int key = ((seq * (ATTN_MAX_SPLIT + 1) + nsplit) << 1) | (with_head ? 1 : 0);
+    auto it = c->graphs.find(key);
+    if (it == c->graphs.end()) {
+        hipError_t e;
+        hipGraph_t graph = nullptr;
+        if ((e = hipStreamBeginCapture(c->stream, hipStreamCaptureModeRelaxed))) return e;
+        e = forward_single(c, seq, with_head, nsplit);
+        hipError_t e2 = hipStreamEndCapture(c->stream, &graph);
+        if (e) { if (graph) hipGraphDestroy(graph); return e; }
+        if (e2) return e2;
+        hipGraphExec_t exec = nullptr;
+        e = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0);
+        hipGraphDestroy(graph);
+        if (e) return e;
+        it = c->graphs.emplace(key, exec).first;
+    }
+    return hipGraphLaunch(it->second, c->stream);
+}
+
+hipError_t step_one_token(asynclm_ctx* c, int seq, int forced, bool with_head) {
+    hipError_t e;
+    const int nsplit = pick_nsplit(c, c->len[seq] + 1);
+    if ((e = run(c, KC_BEGIN, [&] { return launch_begin_step(c->b, seq, forced, c->stream); }))) return e;
+    if (c->opt_graph && !c->prof) e = forward_single_graph(c, seq, with_head, nsplit);
+    else e = forward_single(c, seq, with_head, nsplit);
+    if (e) return e;
+    c->len[seq] += 1;
+    return hipSuccess;
+}
+
+template <class T>
+hipError_t dev_alloc(asynclm_ctx* c, T** p, size_t count) {
+    void* v = nullptr;
+    hipError_t e = hipMalloc(&v, count * sizeof(T) > 0 ? count * sizeof(T) : 16);
+    if (e != hipSuccess) return e;
+    c->allocs.push_back(v);
+    *p = (T*)v;
+    return hipSuccess;
+}
+
+bool config_ok(const asynclm_config* k) {
+    if (k->n_layers <= 0 || k->d_model <= 0 || k->n_q_heads <= 0 || k->n_kv_heads <= 0 || k->ffn <= 0 || k->vocab <= 0) return false;
+    if (k->head_dim != 64 && k->head_dim != 128) return false;
+    if (k->n_q_heads % k->n_kv_heads) return false;
+    const int grp = k->n_q_heads / k->n_kv_heads;
+    if (grp != 1 && grp != 2 && grp != 4 && grp != 8) return false;
+    if (k->d_model % 8 || k->ffn % 8) return false;
+    if (k->dtype != ASYNCLM_DTYPE_FP32 && k->dtype != ASYNCLM_DTYPE_BF16) return false;
+    if (k->max_seqs < 1 || k->max_positions < 1) return false;
+    if (!(k->rms_eps >= 0.f) || !(k->rope_theta > 0.f)) return false;
+    return true;
+}
+
+int check_seq(const asynclm_ctx* c, int32_t seq) {
+    if (!c) return ASYNCLM_E_INVAL;
+    if (c->poisoned) return ASYNCLM_E_DEVICE;
+    if (seq < 0 || seq >= c->cfg.max_seqs) return ASYNCLM_E_INVAL;
+    return ASYNCLM_OK;
+}
+
+int check_tokens(const asynclm_ctx* c, const int32_t* t, int32_t n) {
+    if (!t || n <= 0) return ASYNCLM_E_INVAL;
+    for (int i = 0; i < n; ++i)
+        if (t[i] < 0 || t[i] >= c->cfg.vocab) return ASYNCLM_E_INVAL;
+    return ASYNCLM_OK;
+}
+
+// Append n >= 1 tokens to a sequence and leave logits for the token after them.
+int append_tokens(asynclm_ctx* c, int seq, const int32_t* tokens, int n) {
+    for (int i = 0; i < n; ++i) HIPCK(c, step_one_token(c, seq, tokens[i], i == n - 1));
+    return ASYNCLM_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int asynclm_create(asynclm_ctx** out, const asynclm_config* cfg, const asynclm_weights* w, void* hip_stream) {
+    if (out) *out = nullptr;
+    if (!out || !cfg || !w) return ASYNCLM_E_INVAL;
+    if (!config_ok(cfg)) return ASYNCLM_E_INVAL;
+    if (!w->embed || !w->final_norm || !w->lm_head || !w->attn_norm || !w->wqkv || !w->wo || !w->ffn_norm ||
+        !w->wgate_up || !w->wdown)
+        return ASYNCLM_E_INVAL;
+    for (int l = 0; l < cfg->n_layers; ++l)
+        if (!w->attn_norm[l] || !w->wqkv[l] || !w->wo[l] || !w->ffn_norm[l] || !w->wgate_up[l] || !w->wdown[l])
+            return ASYNCLM_E_INVAL;
+
+    asynclm_ctx* c = new (std::nothrow) asynclm_ctx();
+    if (!c) return ASYNCLM_E_NOMEM;
+    hipError_t e0;
+    c->cfg = *cfg;
+    c->stream = (hipStream_t)hip_stream;
+    if (!c->stream) c->opt_graph = 0;   // the null stream cannot be captured
+    if ((e0 = hipGetDevice(&c->device)) != hipSuccess) { report_hip("hipGetDevice", e0); delete c; return ASYNCLM_E_DEVICE; }
+
+    c->embed = w->embed; c->final_norm = w->final_norm; c->lm_head = w->lm_head;
+    for (int l = 0; l < cfg->n_layers; ++l) {
+        c->attn_norm.push_back(w->attn_norm[l]); c->ffn_norm.push_back(w->ffn_norm[l]);
+        c->wqkv.push_back(w->wqkv[l]); c->wo.push_back(w->wo[l]);
+        c->wgate_up.push_back(w->wgate_up[l]); c->wdown.push_back(w->wdown[l]);
+    }
+
+    Geom& g = c->g;
+    g.d = cfg->d_model; g.Hq = cfg->n_q_heads; g.Hkv = cfg->n_kv_heads; g.dh = cfg->head_dim;
+    g.F = cfg->ffn; g.V = cfg->vocab; g.max_pos = cfg->max_positions; g.eps = cfg->rms_eps;
+    g.scale = (float)(1.0 / std::sqrt((double)cfg->head_dim));
+    g.kv_head_stride = (size_t)g.max_pos * g.dh;
+    g.kv_plane_stride = g.kv_head_stride * g.Hkv;
+    g.kv_layer_stride = g.kv_plane_stride * 2;
+    g.kv_seq_stride = g.kv_layer_stride * cfg->n_layers;
+    c->len.assign(cfg->max_seqs, 0);
+
+    auto bail = [&](int code) { asynclm_destroy(c); return code; };
+    hipError_t e;
+#define ALLOC(ptr, count) if ((e = dev_alloc(c, &(ptr), (count))) != hipSuccess) { report_hip("hipMalloc " #ptr, e); return bail(e == hipErrorOutOfMemory ? ASYNCLM_E_NOMEM : ASYNCLM_E_DEVICE); }
+    {
+        char* kvp = nullptr;
+        ALLOC(kvp, g.kv_seq_stride * (size_t)cfg->max_seqs * elem_bytes(c));
+        c->kv = kvp;
+    }
+    ALLOC(c->logits, (size_t)cfg->max_seqs * g.V);
+    ALLOC(c->b.step, 1);
+    ALLOC(c->b.seq_state, (size_t)cfg->max_seqs);
+    ALLOC(c->b.token_log, 1);
+    ALLOC(c->b.x, (size_t)g.d);
+    ALLOC(c->b.q, (size_t)g.Hq * g.dh);
+    ALLOC(c->b.o, (size_t)g.Hq * g.dh);
+    ALLOC(c->b.a, (size_t)g.F);
+    ALLOC(c->b.part_acc, (size_t)g.Hq * ATTN_MAX_SPLIT * g.dh);
+    ALLOC(c->b.part_ml, (size_t)g.Hq * ATTN_MAX_SPLIT * 2);
+    ALLOC(c->b.attn_counters, (size_t)g.Hkv);
+    ALLOC(c->b.amax_v, (size_t)ARGMAX_MAX_BLOCKS);
+    ALLOC(c->b.amax_i, (size_t)ARGMAX_MAX_BLOCKS);
+    ALLOC(c->b.amax_counter, 1);
+    float *rc = nullptr, *rs = nullptr;
+    const size_t half = g.dh / 2, rope_n = (size_t)g.max_pos * half;
+    ALLOC(rc, rope_n);
+    ALLOC(rs, rope_n);
+#undef ALLOC
+    c->b.rope_cos = rc; c->b.rope_sin = rs;
+
+    // rotary table: angle(pos, i) = pos * theta^(-2i/dh), formed in double, stored as fp32
+    {
+        std::vector<float> hc(rope_n), hs(rope_n);
+        std::vector<double> inv(half);
+        for (size_t i = 0; i < half; ++i) inv[i] = std::pow((double)cfg->rope_theta, -2.0 * (double)i / (double)g.dh);
+        for (int p = 0; p < g.max_pos; ++p)
+            for (size_t i = 0; i < half; ++i) {
+                const double ang = (double)p * inv[i];
+                hc[(size_t)p * half + i] = (float)std::cos(ang);
+                hs[(size_t)p * half + i] = (float)std::sin(ang);
+            }
+        if (hipMemcpy(rc, hc.data(), rope_n * sizeof(float), hipMemcpyHostToDevice) != hipSuccess ||
+            hipMemcpy(rs, hs.data(), rope_n * sizeof(float), hipMemcpyHostToDevice) != hipSuccess)
+            return bail(ASYNCLM_E_DEVICE);
+    }
+    if (hipMemset(c->b.seq_state, 0, sizeof(SeqState) * cfg->max_seqs) != hipSuccess ||
+        hipMemset(c->b.attn_counters, 0, sizeof(int32_t) * g.Hkv) != hipSuccess ||
+        hipMemset(c->b.amax_counter, 0, sizeof(int32_t)) != hipSuccess ||
+        hipMemset(c->b.step, 0, sizeof(StepDesc)) != hipSuccess)
+        return bail(ASYNCLM_E_DEVICE);
+    if (hipHostMalloc((void**)&c->token_host, 64, hipHostMallocDefault) != hipSuccess) return bail(ASYNCLM_E_NOMEM);
+    const int max_k = g.F > g.d ? (g.F > g.Hq * g.dh ? g.F : g.Hq * g.dh) : (g.d > g.Hq * g.dh ? g.d : g.Hq * g.dh);
+    if ((e = decode_init(cfg->dtype, max_k)) != hipSuccess) { report_hip("decode_init", e); return bail(ASYNCLM_E_DEVICE); }
+    if ((e = hipDeviceSynchronize()) != hipSuccess) { report_hip("hipDeviceSynchronize", e); return bail(ASYNCLM_E_DEVICE); }
+    *out = c;
+    return ASYNCLM_OK;
+}
+
+int asynclm_destroy(asynclm_ctx* c) {
+    if (!c) return ASYNCLM_OK;
+    hipStreamSynchronize(c->stream);
+    for (auto& kv : c->graphs) hipGraphExecDestroy(kv.second);
+    for (hipEvent_t ev : c->prof_events) hipEventDestroy(ev);
+    for (void* p : c->allocs) hipFree(p);
+    if (c->token_host) hipHostFree(c->token_host);
+    delete c;
+    return ASYNCLM_OK;
+}
+
+int asynclm_prefill(asynclm_ctx* c, int32_t seq, const int32_t* tokens, int32_t n) {
+    int r = check_seq(c, seq);
+    if (r) return r;
+    if ((r = check_tokens(c, tokens, n))) return r;
+    if (c->len[seq] != 0) return ASYNCLM_E_STATE;
+    if (n > c->cfg.max_positions) return ASYNCLM_E_CAPACITY;
+    return append_tokens(c, seq, tokens, n);
+}
+
+int asynclm_decode_step(asynclm_ctx* c, int32_t seq, int32_t forced_token, int32_t* token_out) {
+    int r = check_seq(c, seq);
+    if (r) return r;
+    if (forced_token >= c->cfg.vocab) return ASYNCLM_E_INVAL;
+    if (c->len[seq] == 0) return ASYNCLM_E_STATE;
+    if (c->len[seq] + 1 > c->cfg.max_positions) return ASYNCLM_E_CAPACITY;
+    HIPCK(c, step_one_token(c, seq, forced_token < 0 ? -1 : forced_token, true));
+    if (token_out) {
+        HIPCK(c, hipMemcpyAsync(c->token_host, c->b.token_log, sizeof(int32_t), hipMemcpyDeviceToHost, c->stream));
+        HIPCK(c, hipStreamSynchronize(c->stream));
+        *token_out = *c->token_host;
+    }
+    return ASYNCLM_OK;
+}
+
+int asynclm_inject_interrupt(asynclm_ctx* c, int32_t seq, const int32_t* tokens, int32_t k) {
+    int r = check_seq(c, seq);
+    if (r) return r;
+    if ((r = check_tokens(c, tokens, k))) return r;
+    if (c->len[seq] == 0) return ASYNCLM_E_STATE;
+    if ((int64_t)c->len[seq] + k > c->cfg.max_positions) return ASYNCLM_E_CAPACITY;
+    return append_tokens(c, seq, tokens, k);
+}
+
+int asynclm_logits(asynclm_ctx* c, int32_t seq, float* out_host, int32_t n) {
+    int r = check_seq(c, seq);
+    if (r) return r;
+    if (!out_host || n != c->cfg.vocab) return ASYNCLM_E_INVAL;
+    if (c->len[seq] == 0) return ASYNCLM_E_STATE;
+    HIPCK(c, hipMemcpyAsync(out_host, c->logits + (size_t)seq * c->g.V, sizeof(float) * n, hipMemcpyDeviceToHost, c->stream));
+    HIPCK(c, hipStreamSynchronize(c->stream));
+    return ASYNCLM_OK;
+}
+
+int asynclm_logits_device(asynclm_ctx* c, int32_t seq, const float** out_dev) {
+    int r = check_seq(c, seq);
+    if (r) return r;
+    if (!out_dev) return ASYNCLM_E_INVAL;
+    *out_dev = c->logits + (size_t)seq * c->g.V;
+    return ASYNCLM_OK;
+}
+
+int asynclm_seq_len(asynclm_ctx* c, int32_t seq, int32_t* len) {
+    int r = check_seq(c, seq);
+    if (r) return r;
+    if (!len) return ASYNCLM_E_INVAL;
+    *len = c->len[seq];
+    return ASYNCLM_OK;
+}
+
+int asynclm_reset(asynclm_ctx* c, int32_t seq) {
+    int r = check_seq(c, seq);
+    if (r) return r;
+    HIPCK(c, hipMemsetAsync(c->b.seq_state + seq, 0, sizeof(SeqState), c->stream));
+    c->len[seq] = 0;
+    return ASYNCLM_OK;
+}
+
+int asynclm_synchronize(asynclm_ctx* c) {
+    if (!c) return ASYNCLM_E_INVAL;
+    if (c->poisoned) return ASYNCLM_E_DEVICE;
+    HIPCK(c, hipStreamSynchronize(c->stream));
+    return ASYNCLM_OK;
+}
+
+int asynclm_set_option(asynclm_ctx* c, const char* name, int32_t value) {
+    if (!c || !name) return ASYNCLM_E_INVAL;
+    if (!std::strcmp(name, "chunk")) { if (value < 1) return ASYNCLM_E_INVAL; c->opt_chunk = value; return ASYNCLM_OK; }
+    if (!std::strcmp(name, "graph")) { c->opt_graph = (value && c->stream) ? 1 : 0; return ASYNCLM_OK; }
+    if (!std::strcmp(name, "attn_split")) { if (value < 0 || value > ATTN_MAX_SPLIT) return ASYNCLM_E_INVAL; c->opt_attn_split = value; return ASYNCLM_OK; }
+    return ASYNCLM_E_INVAL;
+}
+
+int asynclm_profile_step(asynclm_ctx* c, int32_t seq, int32_t forced_token, const char* const** names_out,
+                         float* ms_out, int32_t* launches_out, int32_t cap) {
+    int r = check_seq(c, seq);
+    if (r) return r;
+    if (!ms_out || !launches_out || cap < KC_COUNT || forced_token < 0 || forced_token >= c->cfg.vocab) return ASYNCLM_E_INVAL;
+    if (c->len[seq] == 0) return ASYNCLM_E_STATE;
+    if (c->len[seq] + 1 > c->cfg.max_positions) return ASYNCLM_E_CAPACITY;
+    for (hipEvent_t ev : c->prof_events) hipEventDestroy(ev);
+    c->prof_events.clear(); c->prof_class.clear();
+    c->prof = true;
+    hipError_t e = step_one_token(c, seq, forced_token, true);
+    c->prof = false;
+    if (e) return fail_device(c, e);
+    HIPCK(c, hipStreamSynchronize(c->stream));
+    for (int i = 0; i < KC_COUNT; ++i) { ms_out[i] = 0.f; launches_out[i] = 0; }
+    for (size_t i = 0; i < c->prof_class.size(); ++i) {
+        float ms = 0.f;
+        HIPCK(c, hipEventElapsedTime(&ms, c->prof_events[2 * i], c->prof_events[2 * i + 1]));
+        ms_out[c->prof_class[i]] += ms;
+        launches_out[c->prof_class[i]] += 1;
+    }
+    if (names_out) *names_out = kClassNames;
+    return KC_COUNT;
+}
+
+const char* asynclm_strerror(int code) {
+    switch (code) {
+        case ASYNCLM_OK: return "ok";
+        case ASYNCLM_E_INVAL: return "invalid argument";
+        case ASYNCLM_E_STATE: return "call not allowed in this sequence state";
+        case ASYNCLM_E_CAPACITY: return "sequence would exceed max_positions";
+        case ASYNCLM_E_NOMEM: return "out of memory";
+        case ASYNCLM_E_DEVICE: return "HIP error (context unusable)";
+        default: return "unknown error";
+    }
+}
+
+const char* asynclm_version(void) { return "0.1.0"; }
+
+}  // extern "C"

@@ -1,0 +1,89 @@
+// Shared declarations of the library's translation units (host + device).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+namespace asynclm {
+
+typedef uint16_t bf16_t;   // raw bfloat16 bits
+
+// Per-launch descriptor living in device memory.  Kernels read the token, its position and the
+// sequence from here, so the launch parameters of a decoding step never change and the whole
+// step can be replayed as a captured graph.
+struct StepDesc {
+    int32_t token;   // token processed by this forward pass (decode path)
+    int32_t pos;     // absolute position of the first row of this pass = sequence length before it
+    int32_t seq;     // sequence index
+    int32_t rows;    // rows in this pass (1 for decode)
+};
+
+struct SeqState {
+    int32_t len;         // tokens in the cache
+    int32_t next_token;  // greedy argmax of the current logits
+};
+
+// Geometry of the model and of the K/V cache, passed by value to kernels.
+struct Geom {
+    int32_t d, Hq, Hkv, dh, F, V;
+    int32_t max_pos;
+    float eps;
+    float scale;            // 1/sqrt(dh)
+    // K/V cache element strides: [seq][layer][k|v][Hkv][max_pos][dh]
+    size_t kv_head_stride, kv_plane_stride, kv_layer_stride, kv_seq_stride;
+};
+
+enum KernelClass {
+    KC_BEGIN = 0, KC_EMBED, KC_QKV, KC_ATTN, KC_OPROJ, KC_GATEUP, KC_DOWN, KC_LMHEAD, KC_ARGMAX,
+    KC_CHUNK_PREP, KC_CHUNK_GEMM, KC_CHUNK_ATTN, KC_CHUNK_MISC, KC_COUNT
+};
+
+// ---- device helpers -------------------------------------------------------------------------
+
+__device__ __forceinline__ float bf16_lo(uint32_t u) { return __uint_as_float(u << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t u) { return __uint_as_float(u & 0xffff0000u); }
+
+// round-to-nearest-even fp32 -> bf16 bits (inputs are finite)
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
+    uint32_t u = __float_as_uint(f);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (bf16_t)(u >> 16);
+}
+
+template <typename T> struct Elem;
+template <> struct Elem<float> {
+    static constexpr int EPL = 4;   // elements in one 16-byte lane load
+    __device__ static __forceinline__ void expand(const uint4& v, float (&f)[4]) {
+        f[0] = __uint_as_float(v.x); f[1] = __uint_as_float(v.y);
+        f[2] = __uint_as_float(v.z); f[3] = __uint_as_float(v.w);
+    }
+    __device__ static __forceinline__ float load1(const float* p) { return *p; }
+    __device__ static __forceinline__ void store1(float* p, float v) { *p = v; }
+};
+template <> struct Elem<bf16_t> {
+    static constexpr int EPL = 8;
+    __device__ static __forceinline__ void expand(const uint4& v, float (&f)[8]) {
+        f[0] = bf16_lo(v.x); f[1] = bf16_hi(v.x); f[2] = bf16_lo(v.y); f[3] = bf16_hi(v.y);
+        f[4] = bf16_lo(v.z); f[5] = bf16_hi(v.z); f[6] = bf16_lo(v.w); f[7] = bf16_hi(v.w);
+    }
+    __device__ static __forceinline__ float load1(const bf16_t* p) { return __uint_as_float(((uint32_t)*p) << 16); }
+    __device__ static __forceinline__ void store1(bf16_t* p, float v) { *p = f32_to_bf16(v); }
+};
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+// 16-byte streaming load (data that is read once: weights)
+__device__ __forceinline__ uint4 load16_stream(const void* p) {
+    u32x4 v = __builtin_nontemporal_load((const u32x4*)p);
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ uint4 load16(const void* p) { return *(const uint4*)p; }
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+
+}  // namespace asynclm

@@ -1,0 +1,554 @@
+// Batch-1 decoding step on gfx950: bandwidth-bound matrix-vector kernels with fused
+// RMSNorm / rotary / K-V write / SwiGLU / residual epilogues, split-sequence attention,
+// on-device greedy argmax.  All activations stay in fp32; only weights and K/V are stored
+// in the model's dtype.
+#include "common.h"
+#include "launch.h"
+
+namespace asynclm {
+
+// ---------------------------------------------------------------------------------------------
+// step bookkeeping
+// ---------------------------------------------------------------------------------------------
+
+// Chooses the token of this step (forced, or the greedy one left by the previous forward pass),
+// publishes it and its position to the step descriptor, and grows the sequence by one.
+__global__ void k_begin_step(StepDesc* step, SeqState* st, int32_t seq, int32_t forced, int32_t* token_log) {
+    if (threadIdx.x == 0 && blockIdx.x == 0) {
+        SeqState s = st[seq];
+        int32_t tok = forced >= 0 ? forced : s.next_token;
+        step->token = tok;
+        step->pos = s.len;
+        step->seq = seq;
+        step->rows = 1;
+        st[seq].len = s.len + 1;
+        *token_log = tok;
+    }
+}
+
+template <typename WT>
+__global__ __launch_bounds__(256) void k_embed(const WT* __restrict__ E, const StepDesc* __restrict__ step,
+                                               float* __restrict__ x, int d) {
+    const WT* row = E + (size_t)step->token * d;
+    for (int i = blockIdx.x * 256 + threadIdx.x; i < d; i += gridDim.x * 256) x[i] = Elem<WT>::load1(row + i);
+}
+
+// ---------------------------------------------------------------------------------------------
+// matrix-vector product, one row pair ("unit") per wave at a time
+// ---------------------------------------------------------------------------------------------
+
+enum { EPI_STORE = 0, EPI_RESID = 1, EPI_SWIGLU = 2, EPI_QKV = 3 };
+
+struct GemvArgs {
+    const void* W;          // [rows, K] row-major
+    int32_t rows, K;
+    int32_t units;          // row pairs to compute
+    int32_t units_per_wg;   // multiple of 4 * NU
+    const float* x;         // [K] fp32 input vector
+    const float* gain;      // [K] RMSNorm gain, or nullptr for no normalisation
+    float* y;               // output (meaning depends on the epilogue)
+    const float* res;       // residual input (EPI_RESID)
+    float* q_out;           // EPI_QKV: rotated queries [Hq*dh]
+    void* kv_layer;         // EPI_QKV: this layer's K plane of sequence 0
+    const float* rope_cos;  // [max_pos, dh/2]
+    const float* rope_sin;
+    const StepDesc* step;
+    int32_t layer;
+};
+
+template <int EPI>
+__device__ __forceinline__ void unit_rows(int u, const GemvArgs& a, const Geom& g, int& rA, int& rB) {
+    if (EPI == EPI_SWIGLU) { rA = u; rB = g.F + u; }                 // gate row, up row
+    else if (EPI == EPI_QKV) {                                        // the two halves of a rotary pair
+        const int half = g.dh >> 1;
+        const int h = u / half, i = u - h * half;
+        rA = h * g.dh + i; rB = rA + half;
+    } else { rA = 2 * u; rB = min(2 * u + 1, a.rows - 1); }
+}
+
+template <typename WT, int EPI, int NU>
+__global__ __launch_bounds__(256) void k_gemv(GemvArgs a, Geom g) {
+    constexpr int EPL = Elem<WT>::EPL;
+    constexpr int NP = EPL / 4;       // LDS planes: element k lives in plane (k % EPL) / 4
+    constexpr int PRE = 2;            // k-steps of the first unit set fetched before x is staged
+    extern __shared__ float xs[];
+    __shared__ float red[4];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int K = a.K, Kg = K / EPL;
+    const WT* W = (const WT*)a.W;
+    const int u_base = blockIdx.x * a.units_per_wg;
+    const int iters = a.units_per_wg / (4 * NU);
+
+    // ---- issue the first weight loads; they do not depend on the activations
+    uint4 pre[NU][2][PRE];
+    {
+#pragma unroll
+        for (int j = 0; j < NU; ++j) {
+            int u = min(u_base + wave * NU + j, a.units - 1), rA, rB;
+            unit_rows<EPI>(u, a, g, rA, rB);
+#pragma unroll
+            for (int s = 0; s < PRE; ++s) {
+                int gi = min(lane + s * 64, Kg - 1);
+                pre[j][0][s] = load16_stream(W + (size_t)rA * K + (size_t)gi * EPL);
+                pre[j][1][s] = load16_stream(W + (size_t)rB * K + (size_t)gi * EPL);
+            }
+        }
+    }
+
+    // ---- stage x (times the norm gain) into LDS, planar so that lanes read consecutive 16 B
+    float ss = 0.f;
+    for (int k4 = tid; k4 < K / 4; k4 += 256) {
+        float4 v = ((const float4*)a.x)[k4];
+        ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+        if (a.gain) {
+            float4 gn = ((const float4*)a.gain)[k4];
+            v.x *= gn.x; v.y *= gn.y; v.z *= gn.z; v.w *= gn.w;
+        }
+        const int grp = k4 / NP, pl = k4 - grp * NP;
+        ((float4*)xs)[pl * Kg + grp] = v;
+    }
+    ss = wave_sum(ss);
+    if (lane == 0) red[wave] = ss;
+    __syncthreads();
+    const float nscale = a.gain ? rsqrtf((red[0] + red[1] + red[2] + red[3]) / (float)K + g.eps) : 1.f;
+
+    for (int it = 0; it < iters; ++it) {
+        int rA[NU], rB[NU], uu[NU];
+        float accA[NU], accB[NU];
+#pragma unroll
+        for (int j = 0; j < NU; ++j) {
+            uu[j] = u_base + (it * 4 + wave) * NU + j;
+            unit_rows<EPI>(min(uu[j], a.units - 1), a, g, rA[j], rB[j]);
+            accA[j] = 0.f; accB[j] = 0.f;
+        }
+        int g0 = lane;
+        if (it == 0) {
+#pragma unroll
+            for (int s = 0; s < PRE; ++s) {
+                const int gi = lane + s * 64;
+                if (gi < Kg) {
+                    float xv[EPL];
+#pragma unroll
+                    for (int p = 0; p < NP; ++p) {
+                        float4 t = ((const float4*)xs)[p * Kg + gi];
+                        xv[4 * p] = t.x; xv[4 * p + 1] = t.y; xv[4 * p + 2] = t.z; xv[4 * p + 3] = t.w;
+                    }
+#pragma unroll
+                    for (int j = 0; j < NU; ++j) {
+                        float wa[EPL], wb[EPL];
+                        Elem<WT>::expand(pre[j][0][s], wa);
+                        Elem<WT>::expand(pre[j][1][s], wb);
+#pragma unroll
+                        for (int e = 0; e < EPL; ++e) { accA[j] = fmaf(wa[e], xv[e], accA[j]); accB[j] = fmaf(wb[e], xv[e], accB[j]); }
+                    }
+                }
+            }
+            g0 = lane + PRE * 64;
+        }
+        const WT* pA[NU]; const WT* pB[NU];
+#pragma unroll
+        for (int j = 0; j < NU; ++j) { pA[j] = W + (size_t)rA[j] * K; pB[j] = W + (size_t)rB[j] * K; }
+#pragma unroll 4
+        for (int gi = g0; gi < Kg; gi += 64) {
+            uint4 va[NU], vb[NU];
+#pragma unroll
+            for (int j = 0; j < NU; ++j) {
+                va[j] = load16_stream(pA[j] + (size_t)gi * EPL);
+                vb[j] = load16_stream(pB[j] + (size_t)gi * EPL);
+            }
+            float xv[EPL];
+#pragma unroll
+            for (int p = 0; p < NP; ++p) {
+                float4 t = ((const float4*)xs)[p * Kg + gi];
+                xv[4 * p] = t.x; xv[4 * p + 1] = t.y; xv[4 * p + 2] = t.z; xv[4 * p + 3] = t.w;
+            }
+#pragma unroll
+            for (int j = 0; j < NU; ++j) {
+                float wa[EPL], wb[EPL];
+                Elem<WT>::expand(va[j], wa);
+                Elem<WT>::expand(vb[j], wb);
+#pragma unroll
+                for (int e = 0; e < EPL; ++e) { accA[j] = fmaf(wa[e], xv[e], accA[j]); accB[j] = fmaf(wb[e], xv[e], accB[j]); }
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < NU; ++j) {
+            const float sa = wave_sum(accA[j]) * nscale, sb = wave_sum(accB[j]) * nscale;
+            if (lane != 0 || uu[j] >= a.units) continue;
+            if (EPI == EPI_STORE) {
+                a.y[rA[j]] = sa;
+                if (2 * uu[j] + 1 < a.rows) a.y[rB[j]] = sb;
+            } else if (EPI == EPI_RESID) {
+                a.y[rA[j]] = a.res[rA[j]] + sa;
+                if (2 * uu[j] + 1 < a.rows) a.y[rB[j]] = a.res[rB[j]] + sb;
+            } else if (EPI == EPI_SWIGLU) {
+                a.y[uu[j]] = sa / (1.f + expf(-sa)) * sb;
+            } else {
+                const int half = g.dh >> 1;
+                const int h = uu[j] / half, i = uu[j] - h * half;
+                const int pos = a.step->pos;
+                if (h < g.Hq + g.Hkv) {
+                    const float c = a.rope_cos[(size_t)pos * half + i], s = a.rope_sin[(size_t)pos * half + i];
+                    const float ra = sa * c - sb * s, rb = sb * c + sa * s;
+                    if (h < g.Hq) { a.q_out[h * g.dh + i] = ra; a.q_out[h * g.dh + i + half] = rb; }
+                    else {
+                        WT* kp = (WT*)a.kv_layer + (size_t)a.step->seq * g.kv_seq_stride + (size_t)(h - g.Hq) * g.kv_head_stride + (size_t)pos * g.dh;
+                        Elem<WT>::store1(kp + i, ra); Elem<WT>::store1(kp + i + half, rb);
+                    }
+                } else {
+                    WT* vp = (WT*)a.kv_layer + g.kv_plane_stride + (size_t)a.step->seq * g.kv_seq_stride + (size_t)(h - g.Hq - g.Hkv) * g.kv_head_stride + (size_t)pos * g.dh;
+                    Elem<WT>::store1(vp + i, sa); Elem<WT>::store1(vp + i + half, sb);
+                }
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// split-sequence decode attention: one query per head against the cached prefix
+// ---------------------------------------------------------------------------------------------
+
+struct AttnArgs {
+    const float* q;         // [Hq*dh], rotated, unscaled
+    const void* kv_layer;   // this layer's K plane of sequence 0
+    const StepDesc* step;
+    float* o;               // [Hq*dh]
+    float* part_acc;        // [Hq][nsplit][dh]
+    float* part_ml;         // [Hq][nsplit][2]
+    int32_t* counters;      // [Hkv], zero between launches
+    int32_t nsplit;
+};
+
+template <typename KVT, int DH, int G>
+__global__ __launch_bounds__(256) void k_attn_decode(AttnArgs a, Geom g) {
+    constexpr int EPL = Elem<KVT>::EPL;
+    constexpr int LPR = DH / EPL;       // lanes that cover one cached row
+    constexpr int PPW = 64 / LPR;       // positions per wave-wide load
+    __shared__ float s_m[4][G], s_l[4][G], s_acc[4][G][DH];
+    __shared__ int s_last;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int sub = lane / LPR, c = lane % LPR;
+    const int kvh = blockIdx.x, split = blockIdx.y, nsplit = a.nsplit;
+    const int len = a.step->pos + 1;
+    // split boundaries: equal shares rounded up to whole workgroup iterations
+    const int quantum = 4 * PPW;
+    int per = (len + nsplit - 1) / nsplit;
+    per = (per + quantum - 1) / quantum * quantum;
+    const int s0 = min(split * per, len), s1 = min(s0 + per, len);
+
+    const KVT* Kp = (const KVT*)a.kv_layer + (size_t)a.step->seq * g.kv_seq_stride + (size_t)kvh * g.kv_head_stride;
+    const KVT* Vp = Kp + g.kv_plane_stride;
+
+    float qr[G][EPL];
+#pragma unroll
+    for (int h = 0; h < G; ++h)
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) qr[h][e] = a.q[(kvh * G + h) * DH + c * EPL + e] * g.scale;
+
+    float m[G], l[G], acc[G][EPL];
+#pragma unroll
+    for (int h = 0; h < G; ++h) {
+        m[h] = -INFINITY; l[h] = 0.f;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) acc[h][e] = 0.f;
+    }
+
+    // UN position groups per trip: all their K/V loads are issued before the first is used
+    constexpr int UN = 4;
+    for (int p0 = s0 + wave * PPW; p0 < s1; p0 += 4 * PPW * UN) {
+        uint4 kr[UN], vr[UN];
+#pragma unroll
+        for (int u = 0; u < UN; ++u) {
+            const int p = p0 + u * 4 * PPW + sub;
+            const int pc = p < s1 ? p : s1 - 1;
+            kr[u] = load16(Kp + (size_t)pc * DH + c * EPL);
+            vr[u] = load16(Vp + (size_t)pc * DH + c * EPL);
+        }
+#pragma unroll
+        for (int u = 0; u < UN; ++u) {
+            const bool valid = p0 + u * 4 * PPW + sub < s1;
+            float kf[EPL], vf[EPL];
+            Elem<KVT>::expand(kr[u], kf);
+            Elem<KVT>::expand(vr[u], vf);
+#pragma unroll
+            for (int h = 0; h < G; ++h) {
+                float s = 0.f;
+#pragma unroll
+                for (int e = 0; e < EPL; ++e) s = fmaf(qr[h][e], kf[e], s);
+#pragma unroll
+                for (int o = 1; o < LPR; o <<= 1) s += __shfl_xor(s, o, 64);
+                if (!valid) s = -INFINITY;
+                float mx = s;
+#pragma unroll
+                for (int o = LPR; o < 64; o <<= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
+                // group u = 0 always holds the valid position p0, so m is finite from then on
+                const float mn = fmaxf(m[h], mx);
+                const float corr = expf(m[h] - mn);     // exp(-inf) = 0 on the very first group
+                const float pr = expf(s - mn);
+                l[h] = l[h] * corr + pr;
+#pragma unroll
+                for (int e = 0; e < EPL; ++e) acc[h][e] = fmaf(pr, vf[e], acc[h][e] * corr);
+                m[h] = mn;
+            }
+        }
+    }
+
+    // fold the PPW position groups of the wave (they share m)
+#pragma unroll
+    for (int h = 0; h < G; ++h) {
+#pragma unroll
+        for (int o = LPR; o < 64; o <<= 1) {
+            l[h] += __shfl_xor(l[h], o, 64);
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) acc[h][e] += __shfl_xor(acc[h][e], o, 64);
+        }
+        if (sub == 0) {
+            if (c == 0) { s_m[wave][h] = m[h]; s_l[wave][h] = l[h]; }
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) s_acc[wave][h][c * EPL + e] = acc[h][e];
+        }
+    }
+    __syncthreads();
+
+    // fold the four waves; a wave without positions has m = -inf, l = 0
+    for (int t = tid; t < G * DH; t += 256) {
+        const int h = t / DH, dim = t - h * DH;
+        float M = fmaxf(fmaxf(s_m[0][h], s_m[1][h]), fmaxf(s_m[2][h], s_m[3][h]));
+        float L = 0.f, A = 0.f;
+        if (M > -INFINITY) {
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                const float f = expf(s_m[w][h] - M);
+                L += s_l[w][h] * f; A += s_acc[w][h][dim] * f;
+            }
+        }
+        const int hq = kvh * G + h;
+        if (nsplit == 1) {
+            a.o[hq * DH + dim] = A / L;
+        } else {
+            a.part_acc[((size_t)hq * nsplit + split) * DH + dim] = A;
+            if (dim == 0) { a.part_ml[((size_t)hq * nsplit + split) * 2] = M; a.part_ml[((size_t)hq * nsplit + split) * 2 + 1] = L; }
+        }
+    }
+    if (nsplit == 1) return;
+
+    // the workgroup that finishes last for this kv head merges the splits, in split order
+    __threadfence();
+    __syncthreads();
+    if (tid == 0) {
+        const int ticket = atomicAdd(&a.counters[kvh], 1);
+        s_last = (ticket == nsplit - 1);
+    }
+    __syncthreads();
+    if (!s_last) return;
+    __threadfence();
+    for (int t = tid; t < G * DH; t += 256) {
+        const int h = t / DH, dim = t - h * DH, hq = kvh * G + h;
+        const float* ml = a.part_ml + (size_t)hq * nsplit * 2;
+        float M = -INFINITY;
+        for (int s = 0; s < nsplit; ++s) M = fmaxf(M, __builtin_nontemporal_load(ml + 2 * s));
+        float L = 0.f, A = 0.f;
+        for (int s = 0; s < nsplit; ++s) {
+            const float ms = __builtin_nontemporal_load(ml + 2 * s);
+            if (ms > -INFINITY) {
+                const float f = expf(ms - M);
+                L += __builtin_nontemporal_load(ml + 2 * s + 1) * f;
+                A += __builtin_nontemporal_load(a.part_acc + ((size_t)hq * nsplit + s) * DH + dim) * f;
+            }
+        }
+        a.o[hq * DH + dim] = A / L;
+    }
+    if (tid == 0) a.counters[kvh] = 0;
+}
+
+// ---------------------------------------------------------------------------------------------
+// greedy argmax over the vocabulary: per-block (max, lowest index), last block merges
+// ---------------------------------------------------------------------------------------------
+
+__device__ __forceinline__ void amax_merge(float& bv, int& bi, float v, int i) {
+    if (v > bv || (v == bv && i < bi)) { bv = v; bi = i; }
+}
+
+__global__ __launch_bounds__(256) void k_argmax(const float* __restrict__ logits_base, int V, const StepDesc* step,
+                                                SeqState* st, float* part_v, int32_t* part_i, int32_t* counter) {
+    __shared__ float sv[4];
+    __shared__ int si[4];
+    __shared__ int s_last;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int seq = step->seq;
+    const float* logits = logits_base + (size_t)seq * V;
+    const int nb = gridDim.x;
+    const int per = (V + nb - 1) / nb;
+    const int i0 = blockIdx.x * per, i1 = min(V, i0 + per);
+    float bv = -INFINITY; int bi = 0x7fffffff;
+    for (int i = i0 + tid; i < i1; i += 256) amax_merge(bv, bi, logits[i], i);
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        const float ov = __shfl_xor(bv, o, 64); const int oi = __shfl_xor(bi, o, 64);
+        amax_merge(bv, bi, ov, oi);
+    }
+    if (lane == 0) { sv[wave] = bv; si[wave] = bi; }
+    __syncthreads();
+    if (tid == 0) {
+        for (int w = 1; w < 4; ++w) amax_merge(bv, bi, sv[w], si[w]);
+        part_v[blockIdx.x] = bv; part_i[blockIdx.x] = bi;
+        __threadfence();
+        s_last = (atomicAdd(counter, 1) == nb - 1);
+    }
+    __syncthreads();
+    if (!s_last) return;
+    __threadfence();
+    bv = -INFINITY; bi = 0x7fffffff;
+    for (int b = tid; b < nb; b += 256) amax_merge(bv, bi, __builtin_nontemporal_load(part_v + b), __builtin_nontemporal_load(part_i + b));
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        const float ov = __shfl_xor(bv, o, 64); const int oi = __shfl_xor(bi, o, 64);
+        amax_merge(bv, bi, ov, oi);
+    }
+    __syncthreads();
+    if (lane == 0) { sv[wave] = bv; si[wave] = bi; }
+    __syncthreads();
+    if (tid == 0) {
+        for (int w = 1; w < 4; ++w) amax_merge(bv, bi, sv[w], si[w]);
+        st[seq].next_token = bi;
+        *counter = 0;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// launchers
+// ---------------------------------------------------------------------------------------------
+
+template <typename WT, int EPI>
+static hipError_t launch_gemv_t(const GemvArgs& a0, const Geom& g, hipStream_t s) {
+    constexpr int NU = 2;
+    GemvArgs a = a0;
+    // units per workgroup: enough workgroups to cover the chip several times, few enough that
+    // staging x is amortised over many rows
+    int upw = 4 * NU;
+    while (upw < 64 && (a.units + upw * 2 - 1) / (upw * 2) >= 1024) upw *= 2;
+    a.units_per_wg = upw;
+    const int grid = (a.units + upw - 1) / upw;
+    const size_t lds = (size_t)a.K * sizeof(float);
+    hipLaunchKernelGGL((k_gemv<WT, EPI, NU>), dim3(grid), dim3(256), lds, s, a, g);
+    return hipGetLastError();
+}
+
+template <typename WT>
+static hipError_t launch_gemv_w(int epi, const GemvArgs& a, const Geom& g, hipStream_t s) {
+    switch (epi) {
+        case EPI_STORE: return launch_gemv_t<WT, EPI_STORE>(a, g, s);
+        case EPI_RESID: return launch_gemv_t<WT, EPI_RESID>(a, g, s);
+        case EPI_SWIGLU: return launch_gemv_t<WT, EPI_SWIGLU>(a, g, s);
+        default: return launch_gemv_t<WT, EPI_QKV>(a, g, s);
+    }
+}
+
+template <typename WT, int EPI>
+static hipError_t set_lds_t(int bytes) {
+    return hipFuncSetAttribute((const void*)(k_gemv<WT, EPI, 2>), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+}
+
+hipError_t decode_init(int dtype, int max_k) {
+    const int bytes = max_k * (int)sizeof(float);
+    if (bytes <= 64 * 1024) return hipSuccess;
+    hipError_t e;
+    if (dtype == 0) {
+        if ((e = set_lds_t<float, EPI_STORE>(bytes))) return e;
+        if ((e = set_lds_t<float, EPI_RESID>(bytes))) return e;
+        if ((e = set_lds_t<float, EPI_SWIGLU>(bytes))) return e;
+        if ((e = set_lds_t<float, EPI_QKV>(bytes))) return e;
+    } else {
+        if ((e = set_lds_t<bf16_t, EPI_STORE>(bytes))) return e;
+        if ((e = set_lds_t<bf16_t, EPI_RESID>(bytes))) return e;
+        if ((e = set_lds_t<bf16_t, EPI_SWIGLU>(bytes))) return e;
+        if ((e = set_lds_t<bf16_t, EPI_QKV>(bytes))) return e;
+    }
+    return hipSuccess;
+}
+
+static hipError_t launch_gemv(int dtype, int epi, const GemvArgs& a, const Geom& g, hipStream_t s) {
+    return dtype == 0 ? launch_gemv_w<float>(epi, a, g, s) : launch_gemv_w<bf16_t>(epi, a, g, s);
+}
+
+hipError_t launch_begin_step(const DecodeBuffers& b, int seq, int forced, hipStream_t s) {
+    hipLaunchKernelGGL(k_begin_step, dim3(1), dim3(64), 0, s, b.step, b.seq_state, seq, forced, b.token_log);
+    return hipGetLastError();
+}
+
+hipError_t launch_embed(int dtype, const void* E, const DecodeBuffers& b, const Geom& g, hipStream_t s) {
+    const int grid = (g.d + 255) / 256;
+    if (dtype == 0) hipLaunchKernelGGL(k_embed<float>, dim3(grid), dim3(256), 0, s, (const float*)E, b.step, b.x, g.d);
+    else hipLaunchKernelGGL(k_embed<bf16_t>, dim3(grid), dim3(256), 0, s, (const bf16_t*)E, b.step, b.x, g.d);
+    return hipGetLastError();
+}
+
+hipError_t launch_qkv(int dtype, const void* wqkv, const float* gain, void* kv_layer, const DecodeBuffers& b,
+                      const Geom& g, hipStream_t s) {
+    GemvArgs a{};
+    a.W = wqkv; a.rows = (g.Hq + 2 * g.Hkv) * g.dh; a.K = g.d; a.units = a.rows / 2;
+    a.x = b.x; a.gain = gain; a.q_out = b.q; a.kv_layer = kv_layer;
+    a.rope_cos = b.rope_cos; a.rope_sin = b.rope_sin; a.step = b.step;
+    return launch_gemv(dtype, EPI_QKV, a, g, s);
+}
+
+hipError_t launch_oproj(int dtype, const void* wo, const DecodeBuffers& b, const Geom& g, hipStream_t s) {
+    GemvArgs a{};
+    a.W = wo; a.rows = g.d; a.K = g.Hq * g.dh; a.units = (a.rows + 1) / 2;
+    a.x = b.o; a.gain = nullptr; a.y = b.x; a.res = b.x; a.step = b.step;
+    return launch_gemv(dtype, EPI_RESID, a, g, s);
+}
+
+hipError_t launch_gateup(int dtype, const void* wgu, const float* gain, const DecodeBuffers& b, const Geom& g, hipStream_t s) {
+    GemvArgs a{};
+    a.W = wgu; a.rows = 2 * g.F; a.K = g.d; a.units = g.F;
+    a.x = b.x; a.gain = gain; a.y = b.a; a.step = b.step;
+    return launch_gemv(dtype, EPI_SWIGLU, a, g, s);
+}
+
+hipError_t launch_down(int dtype, const void* wd, const DecodeBuffers& b, const Geom& g, hipStream_t s) {
+    GemvArgs a{};
+    a.W = wd; a.rows = g.d; a.K = g.F; a.units = (a.rows + 1) / 2;
+    a.x = b.a; a.gain = nullptr; a.y = b.x; a.res = b.x; a.step = b.step;
+    return launch_gemv(dtype, EPI_RESID, a, g, s);
+}
+
+hipError_t launch_lmhead(int dtype, const void* wout, const float* gain, float* logits, const DecodeBuffers& b,
+                         const Geom& g, hipStream_t s) {
+    GemvArgs a{};
+    a.W = wout; a.rows = g.V; a.K = g.d; a.units = (a.rows + 1) / 2;
+    a.x = b.x; a.gain = gain; a.y = logits; a.step = b.step;
+    return launch_gemv(dtype, EPI_STORE, a, g, s);
+}
+
+template <typename KVT, int DH>
+static hipError_t launch_attn_t(const AttnArgs& a, const Geom& g, hipStream_t s) {
+    const dim3 grid(g.Hkv, a.nsplit), block(256);
+    switch (g.Hq / g.Hkv) {
+        case 1: hipLaunchKernelGGL((k_attn_decode<KVT, DH, 1>), grid, block, 0, s, a, g); break;
+        case 2: hipLaunchKernelGGL((k_attn_decode<KVT, DH, 2>), grid, block, 0, s, a, g); break;
+        case 4: hipLaunchKernelGGL((k_attn_decode<KVT, DH, 4>), grid, block, 0, s, a, g); break;
+        case 8: hipLaunchKernelGGL((k_attn_decode<KVT, DH, 8>), grid, block, 0, s, a, g); break;
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_attn_decode(int dtype, const void* kv_layer, int nsplit, const DecodeBuffers& b, const Geom& g, hipStream_t s) {
+    AttnArgs a{};
+    a.q = b.q; a.kv_layer = kv_layer; a.step = b.step; a.o = b.o;
+    a.part_acc = b.part_acc; a.part_ml = b.part_ml; a.counters = b.attn_counters; a.nsplit = nsplit;
+    if (dtype == 0) return g.dh == 64 ? launch_attn_t<float, 64>(a, g, s) : launch_attn_t<float, 128>(a, g, s);
+    return g.dh == 64 ? launch_attn_t<bf16_t, 64>(a, g, s) : launch_attn_t<bf16_t, 128>(a, g, s);
+}
+
+hipError_t launch_argmax(const float* logits_base, const DecodeBuffers& b, const Geom& g, hipStream_t s) {
+    int nb = (g.V + 2047) / 2048;
+    if (nb > ARGMAX_MAX_BLOCKS) nb = ARGMAX_MAX_BLOCKS;
+    hipLaunchKernelGGL(k_argmax, dim3(nb), dim3(256), 0, s, logits_base, g.V, b.step, b.seq_state, b.amax_v, b.amax_i, b.amax_counter);
+    return hipGetLastError();
+}
+
+}  // namespace asynclm
