@@ -1,0 +1,203 @@
+#!/usr/bin/env python3
+"""Benchmark of the interruptible-decoding hot path on one MI355X.
+
+One "step" of this benchmark is one pass of the whole hot path of the 8B-shaped workload:
+BLOCK greedy decoding steps at batch 1 (token chosen on the device, read back by the host as
+the paper's token monitor needs it) followed by one in-flight injection of an interrupt block
+into the live K/V cache.  The default workload is the Llama-3-8B-shaped preset: bf16,
+1024-token prompt, 24-token interrupts every 64 decoding steps.
+
+Prints ONE JSON line:
+  value          generated tokens per second over the timed steps, injections included
+  decode_*       decode-only rate and its fraction of the HBM roofline (algorithmic bytes / time / 8 TB/s)
+  inject_*       microseconds per interrupt and its cost in decoding steps
+  roofline       dominant kernel (gate/up projection + SwiGLU): algorithmic bytes per launch over
+                 its mean duration measured here with HIP events on the library's stream
+  cpu_baseline   the CPU oracle timed on this host on a bounded sample (a baseline, not a target)
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK = 8.0e12  # bytes/s, MI355X published peak
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=4)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="8b", choices=["tiny", "8b", "8b-long", "70b"])
+    ap.add_argument("--layers", type=int, default=0, help="truncate the model (0 = full depth); for experiments only")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--chunk", type=int, default=0, help="override the library's rows per forward pass for prefill/inject")
+    return ap.parse_args()
+
+
+def cpu_baseline(wl, model, w_dev, spec, seconds_budget=25.0):
+    """Times the oracle's cached decoder (fp32 numpy) on this host: decode steps on 2- and 4-layer
+    truncations of the same weights, extrapolated linearly in depth to the full model."""
+    import numpy as np
+    import torch
+    import asynclm_inputs as ai
+    from oracle import asynclm_oracle as orc
+    try:
+        import threadpoolctl
+        threads = max((p.get("num_threads", 1) for p in threadpoolctl.threadpool_info()), default=1)
+    except Exception:
+        threads = os.cpu_count() or 1
+    conv = lambda t: t.detach().to("cpu").to(torch.float32).numpy()
+    depth = min(4, model.n_layers)
+    w = {k: conv(w_dev[k]) for k in ("embed", "final_norm", "lm_head")}
+    for k in ("attn_norm", "wqkv", "wo", "ffn_norm", "wgate_up", "wdown"):
+        w[k] = [conv(t) for t in w_dev[k][:depth]]
+    P = min(64, len(spec["prompt"]))
+    times = {}
+    t_begin = time.perf_counter()
+    for nl in sorted({max(depth // 2, 1), depth}):
+        sh = orc.Shape.of(ai.truncated(model, nl))
+        dec = orc.CachedDecoder(sh, w, dtype=np.float32)
+        dec.prefill(spec["prompt"][:P])
+        n, t0 = 0, time.perf_counter()
+        while n < 4 or (time.perf_counter() - t0 < seconds_budget / 4 and n < 32):
+            dec.decode_step()
+            n += 1
+        times[nl] = (time.perf_counter() - t0) / n
+    ks = sorted(times)
+    if len(ks) == 2:
+        per_layer = (times[ks[1]] - times[ks[0]]) / (ks[1] - ks[0])
+        head = max(times[ks[0]] - per_layer * ks[0], 0.0)
+    else:
+        per_layer, head = times[ks[0]] / ks[0], 0.0
+    full = per_layer * model.n_layers + head
+    return {
+        "value": 1.0 / full, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+        "sample": "oracle CachedDecoder (numpy fp32, BLAS matmuls) decode steps after a %d-token prompt on %s-layer "
+                  "truncations of the same weights (%s s/step), extrapolated linearly to %d layers + output head; "
+                  "%.1f s of CPU work" % (P, "/".join(map(str, ks)), "/".join("%.3f" % times[k] for k in ks),
+                                          model.n_layers, time.perf_counter() - t_begin),
+    }
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (--gpus must be 1)", file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+    import asynclm_inputs as ai
+    import paper_2412_07017_amd as pkg
+
+    wl = ai.preset(args.workload)
+    model = wl.model if not args.layers else ai.truncated(wl.model, args.layers)
+    spec = ai.build_workload(args.workload)
+    block = wl.intr_every if wl.intr_every else 16
+    k_intr = wl.intr_len
+    n_blocks = args.warmup + args.steps
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    t0 = time.perf_counter()
+    w_dev = ai.make_weights(model, device=dev)
+    torch.cuda.synchronize()
+    t_weights = time.perf_counter() - t0
+
+    stream = torch.cuda.Stream(device=dev)
+    max_pos = wl.prompt_len + n_blocks * (block + k_intr) + 64
+    lm = pkg.AsyncLM(model, w_dev, max_positions=max_pos, stream=stream)
+    if args.chunk:
+        lm.set_option("chunk", args.chunk)
+    t0 = time.perf_counter()
+    lm.prefill(0, spec["prompt"])
+    lm.synchronize()
+    t_prefill = time.perf_counter() - t0
+
+    intr = [ai.uniform_tokens(ai.MASTER_SEED, 102, k_intr, model.vocab, sub=j) for j in range(n_blocks)]
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+
+    def run_block(j, rec):
+        e0, e1, e2 = ev(), ev(), ev()
+        e0.record(stream)
+        for _ in range(block):
+            lm.decode_step(0)                       # greedy on the device, token returned to the host
+        e1.record(stream)
+        lm.inject_interrupt(0, intr[j])
+        e2.record(stream)
+        rec.append((e0, e1, e2))
+
+    rec = []
+    for j in range(args.warmup):
+        run_block(j, rec)
+    lm.synchronize()
+    torch.cuda.synchronize()
+    rec = []
+    len_start = lm.seq_len(0)
+    t0 = time.perf_counter()
+    for j in range(args.warmup, n_blocks):
+        run_block(j, rec)
+    lm.synchronize()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    len_end = lm.seq_len(0)
+
+    dec_ms = [a.elapsed_time(b) for a, b, c in rec]
+    inj_ms = [b.elapsed_time(c) for a, b, c in rec]
+    ms_dec_step = float(np.mean(dec_ms)) / block
+    ms_inject = float(np.mean(inj_ms))
+    tokens = args.steps * block
+    L_mid = (len_start + len_end) / 2.0
+    bytes_step = model.weight_bytes_per_step() + L_mid * model.kv_bytes_per_position() \
+        + model.kv_bytes_per_position() + 4 * model.vocab
+    decode_tok_s = 1000.0 / ms_dec_step
+    decode_frac = bytes_step / (ms_dec_step * 1e-3) / HBM_PEAK
+
+    # dominant kernel: gate/up projection + SwiGLU (half of all weight bytes), timed per launch
+    prof_ms, prof_n = 0.0, 0
+    classes = {}
+    for _ in range(5):
+        p = lm.profile_step(0, 1)
+        for name, d in p.items():
+            c = classes.setdefault(name, {"ms": 0.0, "launches": 0})
+            c["ms"] += d["ms"]; c["launches"] += d["launches"]
+    gu = classes["gate_up_swiglu"]
+    gu_ms = gu["ms"] / gu["launches"]
+    eb = model.elem_bytes
+    gu_bytes = 2 * model.ffn * model.d_model * eb + 4 * model.d_model * 2 + 4 * model.ffn
+    roofline = {"bound": "hbm", "kernel": "gate_up_swiglu (k_gemv)", "achieved": gu_bytes / (gu_ms * 1e-3) / 1e9,
+                "peak": HBM_PEAK / 1e9, "unit": "GB/s", "traffic": None,
+                "bytes_per_launch": gu_bytes, "ms_per_launch": gu_ms}
+    roofline["frac"] = roofline["achieved"] / roofline["peak"]
+    per_class = {k: {"ms_per_step": v["ms"] / 5, "launches_per_step": v["launches"] // 5} for k, v in classes.items()}
+    lm.synchronize()
+
+    out = {
+        "metric": "decode tokens/s @ batch 1 (% HBM roofline); us per k-token interrupt inject",
+        "value": tokens / wall, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": wall * 1e3 / args.steps, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32 accumulate over %s weights and K/V" % model.dtype, "data": "synthetic",
+        "config": {"workload": "%s: %d layers, d %d, %dq/%dkv heads x %d, ffn %d, vocab %d, %s; batch 1, prompt %d; "
+                               "step = %d greedy decode steps + one %d-token interrupt inject"
+                               % (wl.name, model.n_layers, model.d_model, model.n_q_heads, model.n_kv_heads,
+                                  model.head_dim, model.ffn, model.vocab, model.dtype, wl.prompt_len, block, k_intr),
+                   "context_len": [len_start, len_end], "seed": ai.MASTER_SEED},
+        "decode_tokens_per_s": decode_tok_s, "decode_ms_per_token": ms_dec_step,
+        "decode_hbm_frac": decode_frac, "decode_bytes_per_token": bytes_step,
+        "inject_us": ms_inject * 1e3, "inject_tokens": k_intr, "inject_in_decode_steps": ms_inject / ms_dec_step,
+        "prefill_s": t_prefill, "weights_s": t_weights,
+        "roofline": roofline, "kernel_classes": per_class,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl, model, w_dev, spec)
+    lm.close()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -51,6 +51,15 @@ extern "C" {
 #define ASYNCLM_DTYPE_FP32 0
 #define ASYNCLM_DTYPE_BF16 1
 
+/* Storage of cached keys and values.
+ * AUTO: fp32 for fp32 models; for bf16 models a PAIR of bf16 planes, hi = bf16(x) and
+ *       lo = bf16(x - hi) (about 16 mantissa bits, 4 bytes per element), which keeps the logits within
+ *       the bf16 parity tolerance of an fp32 reference at any depth.
+ * BF16: bf16 models only: the hi plane alone (2 bytes per element).  Halves cache size and traffic; the
+ *       rounding of K and V then moves logits by several 1e-2 on N(0, 0.02)-initialised models. */
+#define ASYNCLM_KV_AUTO 0
+#define ASYNCLM_KV_BF16 1
+
 typedef struct asynclm_ctx asynclm_ctx;   /* opaque; owned by the library */
 
 typedef struct {
@@ -59,6 +68,7 @@ typedef struct {
     int32_t dtype;           /* ASYNCLM_DTYPE_*: storage type of all matrices and of the K/V cache */
     int32_t max_seqs;        /* number of independent sequences (>= 1) */
     int32_t max_positions;   /* K/V capacity per sequence, in tokens */
+    int32_t kv_format;       /* ASYNCLM_KV_* */
 } asynclm_config;
 /* Shape limits: head_dim in {64, 128}; n_q_heads a multiple of n_kv_heads with ratio <= 8;
  * d_model, ffn multiples of 8; everything > 0. */

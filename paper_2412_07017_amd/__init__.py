@@ -5,7 +5,7 @@ decoding path runs in the library's kernels; Python only marshals arguments.  Py
 by callers for device memory and streams and is not needed to import this package.
 """
 from .binding import (AsyncLM, AsyncLMError, library_path, load_library, E_INVAL, E_STATE, E_CAPACITY,
-                      E_NOMEM, E_DEVICE, API_SYMBOLS)
+                      E_NOMEM, E_DEVICE, API_SYMBOLS, KV_AUTO, KV_BF16)
 
 __all__ = ["AsyncLM", "AsyncLMError", "library_path", "load_library", "E_INVAL", "E_STATE", "E_CAPACITY",
-           "E_NOMEM", "E_DEVICE", "API_SYMBOLS"]
+           "E_NOMEM", "E_DEVICE", "API_SYMBOLS", "KV_AUTO", "KV_BF16"]

@@ -8,6 +8,7 @@ from typing import Dict, List, Optional, Sequence
 import numpy as np
 
 E_INVAL, E_STATE, E_CAPACITY, E_NOMEM, E_DEVICE = -1, -2, -3, -4, -5
+KV_AUTO, KV_BF16 = 0, 1
 
 API_SYMBOLS = [
     "asynclm_create", "asynclm_destroy", "asynclm_prefill", "asynclm_decode_step",
@@ -20,7 +21,7 @@ API_SYMBOLS = [
 class _Config(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("n_layers", "d_model", "n_q_heads", "n_kv_heads", "head_dim", "ffn", "vocab")] + \
                [("rms_eps", C.c_float), ("rope_theta", C.c_float)] + \
-               [(n, C.c_int32) for n in ("dtype", "max_seqs", "max_positions")]
+               [(n, C.c_int32) for n in ("dtype", "max_seqs", "max_positions", "kv_format")]
 
 
 class _Weights(C.Structure):
@@ -102,14 +103,15 @@ class AsyncLM:
     """One library context.  `weights` holds torch tensors on the GPU (kept alive here);
     `stream` is a torch.cuda.Stream (or None for the null stream)."""
 
-    def __init__(self, model, weights: Dict[str, object], max_positions: int, max_seqs: int = 1, stream=None):
+    def __init__(self, model, weights: Dict[str, object], max_positions: int, max_seqs: int = 1, stream=None,
+                 kv_format: int = 0):
         self._lib = load_library()
         self._h = C.c_void_p()
         self._keep = (weights, stream)
         self.vocab = model.vocab
         cfg = _Config(model.n_layers, model.d_model, model.n_q_heads, model.n_kv_heads, model.head_dim,
                       model.ffn, model.vocab, model.rms_eps, model.rope_theta,
-                      0 if model.dtype == "fp32" else 1, max_seqs, max_positions)
+                      0 if model.dtype == "fp32" else 1, max_seqs, max_positions, kv_format)
         L = model.n_layers
         arr = lambda ts: (C.c_void_p * L)(*[t.data_ptr() for t in ts])
         self._arrays = [arr(weights[k]) for k in ("attn_norm", "wqkv", "wo", "ffn_norm", "wgate_up", "wdown")]

@@ -168,6 +168,7 @@ bool config_ok(const asynclm_config* k) {
     if (k->d_model % 8 || k->ffn % 8) return false;
     if (k->dtype != ASYNCLM_DTYPE_FP32 && k->dtype != ASYNCLM_DTYPE_BF16) return false;
     if (k->max_seqs < 1 || k->max_positions < 1) return false;
+    if (k->kv_format != ASYNCLM_KV_AUTO && !(k->kv_format == ASYNCLM_KV_BF16 && k->dtype == ASYNCLM_DTYPE_BF16)) return false;
     if (!(k->rms_eps >= 0.f) || !(k->rope_theta > 0.f)) return false;
     return true;
 }
@@ -226,10 +227,15 @@ int asynclm_create(asynclm_ctx** out, const asynclm_config* cfg, const asynclm_w
     g.d = cfg->d_model; g.Hq = cfg->n_q_heads; g.Hkv = cfg->n_kv_heads; g.dh = cfg->head_dim;
     g.F = cfg->ffn; g.V = cfg->vocab; g.max_pos = cfg->max_positions; g.eps = cfg->rms_eps;
     g.scale = (float)(1.0 / std::sqrt((double)cfg->head_dim));
-    g.kv_head_stride = (size_t)g.max_pos * g.dh;
-    g.kv_plane_stride = g.kv_head_stride * g.Hkv;
-    g.kv_layer_stride = g.kv_plane_stride * 2;
-    g.kv_seq_stride = g.kv_layer_stride * cfg->n_layers;
+    {
+        const bool pair = cfg->dtype == ASYNCLM_DTYPE_BF16 && cfg->kv_format != ASYNCLM_KV_BF16;
+        const size_t plane = (size_t)g.max_pos * g.dh * g.Hkv;
+        g.kv_head_stride = (size_t)g.max_pos * g.dh;
+        g.kv_lo_offset = pair ? plane : 0;
+        g.kv_v_offset = pair ? 2 * plane : plane;
+        g.kv_layer_stride = pair ? 4 * plane : 2 * plane;
+        g.kv_seq_stride = g.kv_layer_stride * cfg->n_layers;
+    }
     c->len.assign(cfg->max_seqs, 0);
 
     auto bail = [&](int code) { asynclm_destroy(c); return code; };

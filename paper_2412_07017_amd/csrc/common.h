@@ -30,8 +30,9 @@ struct Geom {
     int32_t max_pos;
     float eps;
     float scale;            // 1/sqrt(dh)
-    // K/V cache element strides: [seq][layer][k|v][Hkv][max_pos][dh]
-    size_t kv_head_stride, kv_plane_stride, kv_layer_stride, kv_seq_stride;
+    // K/V cache, element strides: [seq][layer][k|v][hi|lo][Hkv][max_pos][dh].  The lo plane exists
+    // only in the paired bf16 format, where a value is stored as bf16(x) + bf16(x - bf16(x)).
+    size_t kv_head_stride, kv_v_offset, kv_lo_offset /* 0: no lo plane */, kv_layer_stride, kv_seq_stride;
 };
 
 enum KernelClass {

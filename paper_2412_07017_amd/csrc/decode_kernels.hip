@@ -56,6 +56,15 @@ struct GemvArgs {
     int32_t layer;
 };
 
+// Cache write: fp32 as is; bf16 as the rounded value, plus the rounded remainder in the lo plane
+// when the cache has one.
+__device__ __forceinline__ void kv_store(float* p, float v, size_t) { *p = v; }
+__device__ __forceinline__ void kv_store(bf16_t* p, float v, size_t lo_offset) {
+    const bf16_t hi = f32_to_bf16(v);
+    *p = hi;
+    if (lo_offset) p[lo_offset] = f32_to_bf16(v - __uint_as_float((uint32_t)hi << 16));
+}
+
 template <int EPI>
 __device__ __forceinline__ void unit_rows(int u, const GemvArgs& a, const Geom& g, int& rA, int& rB) {
     if (EPI == EPI_SWIGLU) { rA = u; rB = g.F + u; }                 // gate row, up row
@@ -194,11 +203,11 @@ __global__ __launch_bounds__(256) void k_gemv(GemvArgs a, Geom g) {
                     if (h < g.Hq) { a.q_out[h * g.dh + i] = ra; a.q_out[h * g.dh + i + half] = rb; }
                     else {
                         WT* kp = (WT*)a.kv_layer + (size_t)a.step->seq * g.kv_seq_stride + (size_t)(h - g.Hq) * g.kv_head_stride + (size_t)pos * g.dh;
-                        Elem<WT>::store1(kp + i, ra); Elem<WT>::store1(kp + i + half, rb);
+                        kv_store(kp + i, ra, g.kv_lo_offset); kv_store(kp + i + half, rb, g.kv_lo_offset);
                     }
                 } else {
-                    WT* vp = (WT*)a.kv_layer + g.kv_plane_stride + (size_t)a.step->seq * g.kv_seq_stride + (size_t)(h - g.Hq - g.Hkv) * g.kv_head_stride + (size_t)pos * g.dh;
-                    Elem<WT>::store1(vp + i, sa); Elem<WT>::store1(vp + i + half, sb);
+                    WT* vp = (WT*)a.kv_layer + g.kv_v_offset + (size_t)a.step->seq * g.kv_seq_stride + (size_t)(h - g.Hq - g.Hkv) * g.kv_head_stride + (size_t)pos * g.dh;
+                    kv_store(vp + i, sa, g.kv_lo_offset); kv_store(vp + i + half, sb, g.kv_lo_offset);
                 }
             }
         }
@@ -220,7 +229,7 @@ struct AttnArgs {
     int32_t nsplit;
 };
 
-template <typename KVT, int DH, int G>
+template <typename KVT, int DH, int G, bool PAIR>
 __global__ __launch_bounds__(256) void k_attn_decode(AttnArgs a, Geom g) {
     constexpr int EPL = Elem<KVT>::EPL;
     constexpr int LPR = DH / EPL;       // lanes that cover one cached row
@@ -239,7 +248,7 @@ __global__ __launch_bounds__(256) void k_attn_decode(AttnArgs a, Geom g) {
     const int s0 = min(split * per, len), s1 = min(s0 + per, len);
 
     const KVT* Kp = (const KVT*)a.kv_layer + (size_t)a.step->seq * g.kv_seq_stride + (size_t)kvh * g.kv_head_stride;
-    const KVT* Vp = Kp + g.kv_plane_stride;
+    const KVT* Vp = Kp + g.kv_v_offset;
 
     float qr[G][EPL];
 #pragma unroll
@@ -258,13 +267,17 @@ __global__ __launch_bounds__(256) void k_attn_decode(AttnArgs a, Geom g) {
     // UN position groups per trip: all their K/V loads are issued before the first is used
     constexpr int UN = 4;
     for (int p0 = s0 + wave * PPW; p0 < s1; p0 += 4 * PPW * UN) {
-        uint4 kr[UN], vr[UN];
+        uint4 kr[UN], vr[UN], krl[PAIR ? UN : 1], vrl[PAIR ? UN : 1];
 #pragma unroll
         for (int u = 0; u < UN; ++u) {
             const int p = p0 + u * 4 * PPW + sub;
             const int pc = p < s1 ? p : s1 - 1;
             kr[u] = load16(Kp + (size_t)pc * DH + c * EPL);
             vr[u] = load16(Vp + (size_t)pc * DH + c * EPL);
+            if (PAIR) {
+                krl[u] = load16(Kp + g.kv_lo_offset + (size_t)pc * DH + c * EPL);
+                vrl[u] = load16(Vp + g.kv_lo_offset + (size_t)pc * DH + c * EPL);
+            }
         }
 #pragma unroll
         for (int u = 0; u < UN; ++u) {
@@ -272,6 +285,13 @@ __global__ __launch_bounds__(256) void k_attn_decode(AttnArgs a, Geom g) {
             float kf[EPL], vf[EPL];
             Elem<KVT>::expand(kr[u], kf);
             Elem<KVT>::expand(vr[u], vf);
+            if (PAIR) {
+                float kl[EPL], vl[EPL];
+                Elem<KVT>::expand(krl[u], kl);
+                Elem<KVT>::expand(vrl[u], vl);
+#pragma unroll
+                for (int e = 0; e < EPL; ++e) { kf[e] += kl[e]; vf[e] += vl[e]; }
+            }
 #pragma unroll
             for (int h = 0; h < G; ++h) {
                 float s = 0.f;
@@ -344,21 +364,40 @@ __global__ __launch_bounds__(256) void k_attn_decode(AttnArgs a, Geom g) {
     __syncthreads();
     if (!s_last) return;
     __threadfence();
-    for (int t = tid; t < G * DH; t += 256) {
-        const int h = t / DH, dim = t - h * DH, hq = kvh * G + h;
-        const float* ml = a.part_ml + (size_t)hq * nsplit * 2;
-        float M = -INFINITY;
-        for (int s = 0; s < nsplit; ++s) M = fmaxf(M, __builtin_nontemporal_load(ml + 2 * s));
-        float L = 0.f, A = 0.f;
-        for (int s = 0; s < nsplit; ++s) {
-            const float ms = __builtin_nontemporal_load(ml + 2 * s);
-            if (ms > -INFINITY) {
-                const float f = expf(ms - M);
-                L += __builtin_nontemporal_load(ml + 2 * s + 1) * f;
-                A += __builtin_nontemporal_load(a.part_acc + ((size_t)hq * nsplit + s) * DH + dim) * f;
-            }
+    // weights of the splits: f_s = exp(m_s - M) / L, staged in LDS (reuses the wave buffers)
+    float* s_f = &s_acc[0][0][0];                 // [G][ATTN_MAX_SPLIT] factors
+    float* s_lv = s_f + G * ATTN_MAX_SPLIT;       // [G][ATTN_MAX_SPLIT] partial sums
+    for (int t = tid; t < G * nsplit; t += 256) {
+        const int h = t / nsplit, sp = t - h * nsplit;
+        const float* ml = a.part_ml + ((size_t)(kvh * G + h) * nsplit + sp) * 2;
+        s_f[h * ATTN_MAX_SPLIT + sp] = ml[0];
+        s_lv[h * ATTN_MAX_SPLIT + sp] = ml[1];
+    }
+    __syncthreads();
+    if (tid < G) {
+        float M = -INFINITY, L = 0.f;
+        for (int sp = 0; sp < nsplit; ++sp) M = fmaxf(M, s_f[tid * ATTN_MAX_SPLIT + sp]);
+        for (int sp = 0; sp < nsplit; ++sp) {
+            const float ms = s_f[tid * ATTN_MAX_SPLIT + sp];
+            const float f = ms > -INFINITY ? expf(ms - M) : 0.f;
+            L += s_lv[tid * ATTN_MAX_SPLIT + sp] * f;
+            s_f[tid * ATTN_MAX_SPLIT + sp] = f;
         }
-        a.o[hq * DH + dim] = A / L;
+        const float inv = 1.f / L;
+        for (int sp = 0; sp < nsplit; ++sp) s_f[tid * ATTN_MAX_SPLIT + sp] *= inv;
+    }
+    __syncthreads();
+    for (int t = tid; t < G * DH / 4; t += 256) {
+        const int h = t / (DH / 4), d4 = t - h * (DH / 4), hq = kvh * G + h;
+        const float4* src = (const float4*)(a.part_acc + (size_t)hq * nsplit * DH) + d4;
+        float4 r = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll 8
+        for (int sp = 0; sp < nsplit; ++sp) {
+            const float4 v = src[(size_t)sp * (DH / 4)];
+            const float f = s_f[h * ATTN_MAX_SPLIT + sp];
+            r.x = fmaf(v.x, f, r.x); r.y = fmaf(v.y, f, r.y); r.z = fmaf(v.z, f, r.z); r.w = fmaf(v.w, f, r.w);
+        }
+        ((float4*)(a.o + (size_t)hq * DH))[d4] = r;
     }
     if (tid == 0) a.counters[kvh] = 0;
 }
@@ -523,14 +562,14 @@ hipError_t launch_lmhead(int dtype, const void* wout, const float* gain, float* 
     return launch_gemv(dtype, EPI_STORE, a, g, s);
 }
 
-template <typename KVT, int DH>
+template <typename KVT, int DH, bool PAIR>
 static hipError_t launch_attn_t(const AttnArgs& a, const Geom& g, hipStream_t s) {
     const dim3 grid(g.Hkv, a.nsplit), block(256);
     switch (g.Hq / g.Hkv) {
-        case 1: hipLaunchKernelGGL((k_attn_decode<KVT, DH, 1>), grid, block, 0, s, a, g); break;
-        case 2: hipLaunchKernelGGL((k_attn_decode<KVT, DH, 2>), grid, block, 0, s, a, g); break;
-        case 4: hipLaunchKernelGGL((k_attn_decode<KVT, DH, 4>), grid, block, 0, s, a, g); break;
-        case 8: hipLaunchKernelGGL((k_attn_decode<KVT, DH, 8>), grid, block, 0, s, a, g); break;
+        case 1: hipLaunchKernelGGL((k_attn_decode<KVT, DH, 1, PAIR>), grid, block, 0, s, a, g); break;
+        case 2: hipLaunchKernelGGL((k_attn_decode<KVT, DH, 2, PAIR>), grid, block, 0, s, a, g); break;
+        case 4: hipLaunchKernelGGL((k_attn_decode<KVT, DH, 4, PAIR>), grid, block, 0, s, a, g); break;
+        case 8: hipLaunchKernelGGL((k_attn_decode<KVT, DH, 8, PAIR>), grid, block, 0, s, a, g); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
@@ -540,8 +579,9 @@ hipError_t launch_attn_decode(int dtype, const void* kv_layer, int nsplit, const
     AttnArgs a{};
     a.q = b.q; a.kv_layer = kv_layer; a.step = b.step; a.o = b.o;
     a.part_acc = b.part_acc; a.part_ml = b.part_ml; a.counters = b.attn_counters; a.nsplit = nsplit;
-    if (dtype == 0) return g.dh == 64 ? launch_attn_t<float, 64>(a, g, s) : launch_attn_t<float, 128>(a, g, s);
-    return g.dh == 64 ? launch_attn_t<bf16_t, 64>(a, g, s) : launch_attn_t<bf16_t, 128>(a, g, s);
+    if (dtype == 0) return g.dh == 64 ? launch_attn_t<float, 64, false>(a, g, s) : launch_attn_t<float, 128, false>(a, g, s);
+    if (g.kv_lo_offset) return g.dh == 64 ? launch_attn_t<bf16_t, 64, true>(a, g, s) : launch_attn_t<bf16_t, 128, true>(a, g, s);
+    return g.dh == 64 ? launch_attn_t<bf16_t, 64, false>(a, g, s) : launch_attn_t<bf16_t, 128, false>(a, g, s);
 }
 
 hipError_t launch_argmax(const float* logits_base, const DecodeBuffers& b, const Geom& g, hipStream_t s) {

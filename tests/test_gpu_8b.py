@@ -1,0 +1,146 @@
+"""GPU parity on the Llama-3-8B-shaped bf16 preset.
+
+Tolerance (bf16 presets): max |logit error| <= 2e-2 against the fp32 CPU oracle that keeps K/V and all
+activations in fp32 (so the bf16 K/V cache of the GPU path is charged to the budget); greedy ids
+identical wherever the oracle's top-2 margin exceeds 1e-2.
+
+* the whole 8B workload (1024-token prompt, 256 greedy tokens, 24-token interrupts after tokens
+  64/128/192) on the first 4 layers of the seeded model, teacher-forced with the oracle's stream;
+* a shorter stream on the full 32-layer model.
+Weights are generated once on the GPU by the seeded generator and copied to the host for the oracle
+(the generator is integer arithmetic plus one fp32 multiply, bit-identical on both devices; checked in
+test_gpu_tiny.py and below on a slice).
+"""
+import numpy as np
+import pytest
+import torch
+
+import asynclm_inputs as ai
+from asynclm_inputs import generator as gen
+from oracle import asynclm_oracle as orc
+
+pytestmark = pytest.mark.gpu
+
+TOL = 2e-2
+MARGIN = 1e-2
+
+
+def _host_weights(w_dev):
+    conv = lambda t: t.detach().to("cpu").to(torch.float32).numpy()
+    return {k: ([conv(t) for t in v] if isinstance(v, list) else conv(v)) for k, v in w_dev.items()}
+
+
+def _compare_stream(lm, ref, spec, n_decode, events, gate_ids=True):
+    ev = {n: t for n, t in events}
+    worst, n_checked, n_gated = 0.0, 0, 0
+    for j in range(n_decode):
+        got = lm.logits(0)
+        assert np.isfinite(got).all()
+        want = ref["choose_logits"][j]
+        worst = max(worst, float(np.abs(got - want).max()))
+        if gate_ids and orc.top2_margin(want) > MARGIN:
+            assert int(np.argmax(got)) == ref["generated"][j], (j, orc.top2_margin(want))
+            n_gated += 1
+        n_checked += 1
+        assert lm.decode_step(0, forced_token=ref["generated"][j]) == ref["generated"][j]
+        if j + 1 in ev:
+            lm.inject_interrupt(0, ev[j + 1])
+            worst = max(worst, float(np.abs(lm.logits(0) - ref["inject_logits"][j + 1]).max()))
+    worst = max(worst, float(np.abs(lm.logits(0) - ref["final_logits"]).max()))
+    return worst, n_checked, n_gated
+
+
+@pytest.fixture(scope="module")
+def trunc4():
+    wl = ai.preset("8b")
+    model = ai.truncated(wl.model, wl.parity_layers)
+    dev = torch.device("cuda:0")
+    w_dev = ai.make_weights(model, device=dev)
+    torch.cuda.synchronize()
+    w_cpu = _host_weights(w_dev)
+    spec = ai.build_workload("8b")
+    return wl, model, w_dev, w_cpu, spec
+
+
+def test_generator_slice_identical_on_cpu_and_gpu(trunc4):
+    wl, model, w_dev, w_cpu, spec = trunc4
+    tid = gen.TID_LAYER_BASE + gen.TID_LAYER_STRIDE * 3 + gen.TID_WDOWN
+    n = model.d_model * model.ffn
+    for start in (0, 12345678, n - 4096):
+        host = gen.gaussian_flat(ai.MASTER_SEED, tid, start, 4096, 0.02).to(torch.bfloat16)
+        assert torch.equal(host, w_dev["wdown"][3].view(-1)[start:start + 4096].cpu())
+
+
+@pytest.mark.timeout(900)
+def test_8b_workload_on_4_layers_matches_oracle(trunc4):
+    import paper_2412_07017_amd as pkg
+    wl, model, w_dev, w_cpu, spec = trunc4
+    ref = orc.run_stream(orc.Shape.of(model), w_cpu, spec["prompt"], spec["n_decode"], spec["events"], dtype=np.float32,
+                         progress=lambda j: print("oracle step", j, flush=True) if j % 64 == 0 else None)
+    assert len(ref["stream"]) == 1024 + 256 + 72
+    stream = torch.cuda.Stream()
+    lm = pkg.AsyncLM(model, w_dev, max_positions=1408, stream=stream)
+    lm.prefill(0, spec["prompt"])
+    worst, n, n_gated = _compare_stream(lm, ref, spec, spec["n_decode"], spec["events"])
+    print("8b/4-layer: max |logit err| = %.3e over %d vectors, %d margin-gated ids identical" % (worst, n + 4, n_gated))
+    assert lm.seq_len(0) == 1352
+    # free-running greedy from the same prompt reproduces the oracle's stream up to the first near tie
+    lm.reset(0)
+    lm.prefill(0, spec["prompt"])
+    ev = {n_: t for n_, t in spec["events"]}
+    for j in range(spec["n_decode"]):
+        tok = lm.decode_step(0)
+        if tok != ref["generated"][j]:
+            assert orc.top2_margin(ref["choose_logits"][j]) <= MARGIN, j
+            assert tok in np.argsort(ref["choose_logits"][j])[-2:]
+            break
+        if j + 1 in ev:
+            lm.inject_interrupt(0, ev[j + 1])
+    lm.close()
+    assert worst <= TOL, worst
+
+
+@pytest.mark.timeout(900)
+def test_single_plane_bf16_cache_matches_oracle_with_rounded_cache(trunc4):
+    """The 2-byte cache format (hi plane only) rounds K and V to bf16 when they are written.  That
+    rounding is a storage decision of the format, so the oracle takes it at the same point
+    (kv_round=True) and the usual tolerance applies; against the unrounded oracle this format is
+    outside the tolerance by construction (the gap is printed)."""
+    import paper_2412_07017_amd as pkg
+    wl, model, w_dev, w_cpu, spec = trunc4
+    prompt, n_decode, events = spec["prompt"][:512], 40, [(20, spec["events"][0][1])]
+    sh = orc.Shape.of(model)
+    ref_q = orc.run_stream(sh, w_cpu, prompt, n_decode, events, dtype=np.float32, kv_round=True)
+    lm = pkg.AsyncLM(model, w_dev, max_positions=640, stream=torch.cuda.Stream(), kv_format=pkg.KV_BF16)
+    lm.prefill(0, prompt)
+    worst, n, _ = _compare_stream(lm, ref_q, spec, n_decode, events, gate_ids=False)
+    # same stream through the unrounded oracle, teacher-forced, to show the cost of the format itself
+    dec = orc.CachedDecoder(sh, w_cpu, dtype=np.float32)
+    dec.prefill(prompt)
+    gap = float(np.abs(dec.logits - ref_q["choose_logits"][0]).max())
+    print("bf16 single-plane cache: max |logit err| vs rounded-cache oracle = %.3e; rounded vs unrounded oracle = %.3e" % (worst, gap))
+    lm.close()
+    assert worst <= TOL, worst
+
+
+@pytest.mark.timeout(1100)
+def test_full_depth_8b_short_stream_matches_oracle(trunc4):
+    import paper_2412_07017_amd as pkg
+    wl = ai.preset("8b")
+    model = wl.model
+    dev = torch.device("cuda:0")
+    w_dev = ai.make_weights(model, device=dev)
+    torch.cuda.synchronize()
+    w_cpu = _host_weights(w_dev)
+    spec = ai.build_workload("8b")
+    prompt, intr = spec["prompt"][:96], spec["events"][0][1]
+    n_decode, events = 10, [(6, intr)]
+    ref = orc.run_stream(orc.Shape.of(model), w_cpu, prompt, n_decode, events, dtype=np.float32,
+                         progress=lambda j: print("oracle step", j, flush=True))
+    del w_cpu
+    lm = pkg.AsyncLM(model, w_dev, max_positions=160, stream=torch.cuda.Stream())
+    lm.prefill(0, prompt)
+    worst, n, n_gated = _compare_stream(lm, ref, {"events": events}, n_decode, events)
+    print("8b/32-layer: max |logit err| = %.3e over %d vectors, %d margin-gated ids identical" % (worst, n + 2, n_gated))
+    lm.close()
+    assert worst <= TOL, worst

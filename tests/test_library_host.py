@@ -38,13 +38,13 @@ def test_version_and_strerror(lib):
 def test_create_rejects_bad_arguments_without_touching_a_device(lib):
     h = C.c_void_p()
     assert lib.asynclm_create(C.byref(h), None, None, None) == pkg.E_INVAL
-    cfg = binding._Config(2, 256, 4, 4, 64, 688, 1024, 1e-5, 10000.0, 0, 1, 128)
+    cfg = binding._Config(2, 256, 4, 4, 64, 688, 1024, 1e-5, 10000.0, 0, 1, 128, 0)
     w = binding._Weights()
     assert lib.asynclm_create(C.byref(h), C.byref(cfg), C.byref(w), None) == pkg.E_INVAL   # null weights
     assert not h
     for field, bad in (("head_dim", 48), ("n_kv_heads", 3), ("d_model", 250), ("dtype", 7), ("max_seqs", 0),
-                       ("max_positions", 0), ("n_layers", 0), ("vocab", -1)):
-        c2 = binding._Config(2, 256, 4, 4, 64, 688, 1024, 1e-5, 10000.0, 0, 1, 128)
+                       ("max_positions", 0), ("n_layers", 0), ("vocab", -1), ("kv_format", 1), ("kv_format", 5)):
+        c2 = binding._Config(2, 256, 4, 4, 64, 688, 1024, 1e-5, 10000.0, 0, 1, 128, 0)
         setattr(c2, field, bad)
         assert lib.asynclm_create(C.byref(h), C.byref(c2), C.byref(w), None) == pkg.E_INVAL, field
 
