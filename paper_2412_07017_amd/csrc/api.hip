@@ -3,6 +3,7 @@
 #include "common.h"
 #include "launch.h"
 
+#include <algorithm>
 #include <cmath>
 #include <cstdio>
 #include <cstdlib>
@@ -29,12 +30,14 @@ struct asynclm_ctx {
     void* kv = nullptr;                 // [seq][layer][k|v][Hkv][max_pos][dh] in cfg.dtype
     float* logits = nullptr;            // [max_seqs][V]
     DecodeBuffers b{};
+    ChunkBuffers cb{};
+    bool chunk_ok = false;              // the matrix-core append path supports this model
     int32_t* token_host = nullptr;      // pinned, 1 int
 
     std::vector<int32_t> len;           // host mirror of the sequence lengths
 
     // options
-    int opt_chunk = 1, opt_graph = 1, opt_attn_split = 0;
+    int opt_chunk = 1, opt_graph = 1, opt_attn_split = 0, opt_chunk_split = 0;
 
     std::map<int, hipGraphExec_t> graphs;   // key: nsplit * 2 + with_head
 
@@ -187,9 +190,71 @@ int check_tokens(const asynclm_ctx* c, const int32_t* t, int32_t n) {
     return ASYNCLM_OK;
 }
 
+// Split-K factors of the four products of a layer (workgroups = N/32 * S, each of 4 waves).
+struct ChunkSplits { int qkv, o, gu, down; };
+
+ChunkSplits chunk_splits(const asynclm_ctx* c) {
+    if (c->opt_chunk_split > 0) return {c->opt_chunk_split, c->opt_chunk_split, c->opt_chunk_split, c->opt_chunk_split};
+    return {2, 2, 1, 4};
+}
+
+int pick_chunk_attn_split(const asynclm_ctx* c, int keys) {
+    // about 4 key tiles (128 keys) per wave, at most CHUNK_ATTN_MAX_SPLIT, a multiple of 4
+    int n = 4;
+    while (n < CHUNK_ATTN_MAX_SPLIT && n * 128 < keys) n *= 2;
+    return n;
+}
+
+// One forward pass over `rows` (2..CHUNK_MAX) tokens that are already in cb.tokens.
+hipError_t forward_chunk(asynclm_ctx* c, int seq, int rows, bool with_head) {
+    const Geom& g = c->g;
+    const ChunkBuffers& cb = c->cb;
+    hipStream_t s = c->stream;
+    const int MT = (rows + 31) / 32;
+    const ChunkSplits sp = chunk_splits(c);
+    const int nqkv = (g.Hq + 2 * g.Hkv) * g.dh, qd = g.Hq * g.dh;
+    const int asplit = pick_chunk_attn_split(c, c->len[seq] + rows);
+    hipError_t e;
+    if ((e = run(c, KC_BEGIN, [&] { return launch_begin_chunk(c->b, seq, rows, s); }))) return e;
+    if ((e = run(c, KC_CHUNK_PREP, [&] { return launch_chunk_embed(c->embed, cb, rows, g, s); }))) return e;
+    for (int l = 0; l < c->cfg.n_layers; ++l) {
+        void* kvl = kv_layer_ptr(c, l);
+        if ((e = run(c, KC_CHUNK_PREP, [&] { return launch_chunk_resid_norm(cb, l > 0, sp.down, MT, c->attn_norm[l], rows, g, s); }))) return e;
+        if ((e = run(c, KC_CHUNK_GEMM, [&] { return launch_chunk_gemm(c->wqkv[l], nqkv, g.d, cb.nrm_hi, cb.nrm_lo, cb, sp.qkv, MT, s); }))) return e;
+        if ((e = run(c, KC_CHUNK_PREP, [&] { return launch_chunk_rope_kv(cb, sp.qkv, kvl, c->b, rows, MT, g, s); }))) return e;
+        if ((e = run(c, KC_CHUNK_ATTN, [&] { return launch_chunk_attn(cb, kvl, asplit, MT, c->b, g, s); }))) return e;
+        if ((e = run(c, KC_CHUNK_GEMM, [&] { return launch_chunk_gemm(c->wo[l], g.d, qd, cb.att_hi, cb.att_lo, cb, sp.o, MT, s); }))) return e;
+        if ((e = run(c, KC_CHUNK_PREP, [&] { return launch_chunk_resid_norm(cb, true, sp.o, MT, c->ffn_norm[l], rows, g, s); }))) return e;
+        if ((e = run(c, KC_CHUNK_GEMM, [&] { return launch_chunk_gemm(c->wgate_up[l], 2 * g.F, g.d, cb.nrm_hi, cb.nrm_lo, cb, sp.gu, MT, s); }))) return e;
+        if ((e = run(c, KC_CHUNK_PREP, [&] { return launch_chunk_swiglu(cb, sp.gu, MT, rows, g, s); }))) return e;
+        if ((e = run(c, KC_CHUNK_GEMM, [&] { return launch_chunk_gemm(c->wdown[l], g.d, g.F, cb.act_hi, cb.act_lo, cb, sp.down, MT, s); }))) return e;
+    }
+    if (with_head) {
+        const int dt = c->cfg.dtype;
+        if ((e = run(c, KC_CHUNK_MISC, [&] { return launch_chunk_last_row(cb, sp.down, MT, c->b, g, s); }))) return e;
+        if ((e = run(c, KC_LMHEAD, [&] { return launch_lmhead(dt, c->lm_head, c->final_norm, c->logits + (size_t)seq * g.V, c->b, g, s); }))) return e;
+        if ((e = run(c, KC_ARGMAX, [&] { return launch_argmax(c->logits, c->b, g, s); }))) return e;
+    }
+    c->len[seq] += rows;
+    return hipSuccess;
+}
+
 // Append n >= 1 tokens to a sequence and leave logits for the token after them.
 int append_tokens(asynclm_ctx* c, int seq, const int32_t* tokens, int n) {
-    for (int i = 0; i < n; ++i) HIPCK(c, step_one_token(c, seq, tokens[i], i == n - 1));
+    const int chunk = c->chunk_ok ? std::min(c->opt_chunk, CHUNK_MAX) : 1;
+    int i = 0;
+    while (i < n) {
+        const int rows = std::min(chunk, n - i);
+        const bool last = i + rows == n;
+        if (rows == 1) {
+            HIPCK(c, step_one_token(c, seq, tokens[i], last));
+        } else {
+            // pageable source: the runtime stages the ids before the call returns
+            HIPCK(c, hipMemcpyAsync(c->cb.tokens, tokens + i, sizeof(int32_t) * rows, hipMemcpyHostToDevice, c->stream));
+            HIPCK(c, forward_chunk(c, seq, rows, last));
+        }
+        i += rows;
+    }
     return ASYNCLM_OK;
 }
 
@@ -225,16 +290,20 @@ int asynclm_create(asynclm_ctx** out, const asynclm_config* cfg, const asynclm_w
 
     Geom& g = c->g;
     g.d = cfg->d_model; g.Hq = cfg->n_q_heads; g.Hkv = cfg->n_kv_heads; g.dh = cfg->head_dim;
-    g.F = cfg->ffn; g.V = cfg->vocab; g.max_pos = cfg->max_positions; g.eps = cfg->rms_eps;
+    g.F = cfg->ffn; g.V = cfg->vocab; g.max_pos = (cfg->max_positions + 31) / 32 * 32; g.eps = cfg->rms_eps;
     g.scale = (float)(1.0 / std::sqrt((double)cfg->head_dim));
     {
         const bool pair = cfg->dtype == ASYNCLM_DTYPE_BF16 && cfg->kv_format != ASYNCLM_KV_BF16;
+        // the matrix-core append path: bf16 weights, paired cache, head_dim 128, 128-aligned inner sizes
+        c->chunk_ok = pair && g.dh == 128 && g.d % 128 == 0 && g.F % 128 == 0 && g.Hq / g.Hkv <= 4 + 4;
         const size_t plane = (size_t)g.max_pos * g.dh * g.Hkv;
         g.kv_head_stride = (size_t)g.max_pos * g.dh;
         g.kv_lo_offset = pair ? plane : 0;
         g.kv_v_offset = pair ? 2 * plane : plane;
-        g.kv_layer_stride = pair ? 4 * plane : 2 * plane;
+        g.kv_vt_offset = c->chunk_ok ? 4 * plane : 0;
+        g.kv_layer_stride = c->chunk_ok ? 6 * plane : (pair ? 4 * plane : 2 * plane);
         g.kv_seq_stride = g.kv_layer_stride * cfg->n_layers;
+        if (c->chunk_ok) c->opt_chunk = CHUNK_MAX;
     }
     c->len.assign(cfg->max_seqs, 0);
 
@@ -260,6 +329,31 @@ int asynclm_create(asynclm_ctx** out, const asynclm_config* cfg, const asynclm_w
     ALLOC(c->b.amax_v, (size_t)ARGMAX_MAX_BLOCKS);
     ALLOC(c->b.amax_i, (size_t)ARGMAX_MAX_BLOCKS);
     ALLOC(c->b.amax_counter, 1);
+    if (c->chunk_ok) {
+        ChunkBuffers& cb = c->cb;
+        const size_t M = CHUNK_MAX, qd = (size_t)g.Hq * g.dh;
+        // split-K partial planes: up to CHUNK_GEMM_MAX_SPLIT planes of the widest product
+        const size_t nmax = CHUNK_GEMM_MAX_SPLIT * std::max(std::max((size_t)2 * g.F, (size_t)(g.Hq + 2 * g.Hkv) * g.dh), (size_t)g.d);
+        cb.part_capacity = M * nmax;
+        const size_t tasks = (size_t)g.Hq * (CHUNK_MAX / 32);
+        ALLOC(cb.tokens, M);
+        ALLOC(cb.x, M * g.d);
+        ALLOC(cb.nrm_hi, M * g.d); ALLOC(cb.nrm_lo, M * g.d);
+        ALLOC(cb.att_hi, M * qd); ALLOC(cb.att_lo, M * qd);
+        ALLOC(cb.act_hi, M * g.F); ALLOC(cb.act_lo, M * g.F);
+        ALLOC(cb.q_hi, M * qd); ALLOC(cb.q_lo, M * qd);
+        ALLOC(cb.part, M * nmax);
+        ALLOC(cb.attn_o, tasks * CHUNK_ATTN_MAX_SPLIT * g.dh * 32);
+        ALLOC(cb.attn_ml, tasks * CHUNK_ATTN_MAX_SPLIT * 64);
+        // rows beyond the current chunk are multiplied into discarded columns only, but must stay finite
+        if (hipMemset(cb.tokens, 0, M * 4) || hipMemset(cb.x, 0, M * g.d * 4) || hipMemset(cb.nrm_hi, 0, M * g.d * 2) ||
+            hipMemset(cb.nrm_lo, 0, M * g.d * 2) || hipMemset(cb.att_hi, 0, M * qd * 2) || hipMemset(cb.att_lo, 0, M * qd * 2) ||
+            hipMemset(cb.act_hi, 0, M * g.F * 2) || hipMemset(cb.act_lo, 0, M * g.F * 2) || hipMemset(cb.q_hi, 0, M * qd * 2) ||
+            hipMemset(cb.q_lo, 0, M * qd * 2))
+            return bail(ASYNCLM_E_DEVICE);
+    }
+    // cache rows that were never written are read (and masked) by the chunk attention: keep them finite
+    if (hipMemset(c->kv, 0, g.kv_seq_stride * (size_t)cfg->max_seqs * elem_bytes(c)) != hipSuccess) return bail(ASYNCLM_E_DEVICE);
     float *rc = nullptr, *rs = nullptr;
     const size_t half = g.dh / 2, rope_n = (size_t)g.max_pos * half;
     ALLOC(rc, rope_n);
@@ -382,7 +476,8 @@ int asynclm_synchronize(asynclm_ctx* c) {
 
 int asynclm_set_option(asynclm_ctx* c, const char* name, int32_t value) {
     if (!c || !name) return ASYNCLM_E_INVAL;
-    if (!std::strcmp(name, "chunk")) { if (value < 1) return ASYNCLM_E_INVAL; c->opt_chunk = value; return ASYNCLM_OK; }
+    if (!std::strcmp(name, "chunk")) { if (value < 1 || value > CHUNK_MAX) return ASYNCLM_E_INVAL; c->opt_chunk = value; return ASYNCLM_OK; }
+    if (!std::strcmp(name, "chunk_split")) { if (value < 0 || value > CHUNK_GEMM_MAX_SPLIT) return ASYNCLM_E_INVAL; c->opt_chunk_split = value; return ASYNCLM_OK; }
     if (!std::strcmp(name, "graph")) { c->opt_graph = (value && c->stream) ? 1 : 0; return ASYNCLM_OK; }
     if (!std::strcmp(name, "attn_split")) { if (value < 0 || value > ATTN_MAX_SPLIT) return ASYNCLM_E_INVAL; c->opt_attn_split = value; return ASYNCLM_OK; }
     return ASYNCLM_E_INVAL;

@@ -30,9 +30,13 @@ struct Geom {
     int32_t max_pos;
     float eps;
     float scale;            // 1/sqrt(dh)
-    // K/V cache, element strides: [seq][layer][k|v][hi|lo][Hkv][max_pos][dh].  The lo plane exists
-    // only in the paired bf16 format, where a value is stored as bf16(x) + bf16(x - bf16(x)).
-    size_t kv_head_stride, kv_v_offset, kv_lo_offset /* 0: no lo plane */, kv_layer_stride, kv_seq_stride;
+    // K/V cache, element strides: [seq][layer][K | V | V^T][hi | lo][Hkv][max_pos][dh].  The lo plane
+    // exists only in the paired bf16 format, where a value is stored as bf16(x) + bf16(x - bf16(x)).
+    // V^T ([dh][max_pos] per head, same size) exists only with the append-chunk path: its PV product
+    // on the matrix cores needs 8 consecutive positions of one channel in one register quad.
+    // max_pos is the allocated row count (capacity rounded up to a multiple of 32).
+    size_t kv_head_stride, kv_v_offset, kv_lo_offset /* 0: no lo plane */, kv_vt_offset /* 0: no V^T */;
+    size_t kv_layer_stride, kv_seq_stride;
 };
 
 enum KernelClass {

@@ -208,6 +208,10 @@ __global__ __launch_bounds__(256) void k_gemv(GemvArgs a, Geom g) {
                 } else {
                     WT* vp = (WT*)a.kv_layer + g.kv_v_offset + (size_t)a.step->seq * g.kv_seq_stride + (size_t)(h - g.Hq - g.Hkv) * g.kv_head_stride + (size_t)pos * g.dh;
                     kv_store(vp + i, sa, g.kv_lo_offset); kv_store(vp + i + half, sb, g.kv_lo_offset);
+                    if (g.kv_vt_offset) {   // transposed copy [dh][max_pos] read by the append-chunk attention
+                        WT* vt = (WT*)a.kv_layer + g.kv_vt_offset + (size_t)a.step->seq * g.kv_seq_stride + (size_t)(h - g.Hq - g.Hkv) * g.kv_head_stride + pos;
+                        kv_store(vt + (size_t)i * g.max_pos, sa, g.kv_lo_offset); kv_store(vt + (size_t)(i + half) * g.max_pos, sb, g.kv_lo_offset);
+                    }
                 }
             }
         }

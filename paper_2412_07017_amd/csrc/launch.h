@@ -27,7 +27,37 @@ struct DecodeBuffers {
     const float* rope_sin;
 };
 
+constexpr int CHUNK_MAX = 64;          // rows per forward pass of the append-chunk path
+constexpr int CHUNK_ATTN_MAX_SPLIT = 32;
+constexpr int CHUNK_GEMM_MAX_SPLIT = 4;
+
+// Device buffers of the append-chunk path (bf16 models).  "hi/lo" are the two bf16 planes of a value.
+struct ChunkBuffers {
+    int32_t* tokens;          // [CHUNK_MAX]
+    float* x;                 // [CHUNK_MAX][d] residual stream
+    bf16_t *nrm_hi, *nrm_lo;  // [CHUNK_MAX][d]      normalised input of the QKV and gate/up products
+    bf16_t *att_hi, *att_lo;  // [CHUNK_MAX][Hq*dh]  attention output
+    bf16_t *act_hi, *act_lo;  // [CHUNK_MAX][F]      SwiGLU output
+    bf16_t *q_hi, *q_lo;      // [Hq][CHUNK_MAX][dh] rotated, scaled queries
+    float* part;              // split-K partial planes of the current product
+    size_t part_capacity;     // floats in `part`
+    float* attn_o;            // [tasks][split][dh][32]
+    float* attn_ml;           // [tasks][split][2][32]
+};
+
 hipError_t decode_init(int dtype, int max_k);
+hipError_t launch_begin_chunk(const DecodeBuffers& b, int seq, int rows, hipStream_t s);
+hipError_t launch_chunk_embed(const void* E, const ChunkBuffers& c, int rows, const Geom& g, hipStream_t s);
+hipError_t launch_chunk_resid_norm(const ChunkBuffers& c, bool add_partials, int S, int MT, const float* gain, int rows,
+                                   const Geom& g, hipStream_t s);
+hipError_t launch_chunk_last_row(const ChunkBuffers& c, int S, int MT, const DecodeBuffers& b, const Geom& g, hipStream_t s);
+hipError_t launch_chunk_swiglu(const ChunkBuffers& c, int S, int MT, int rows, const Geom& g, hipStream_t s);
+hipError_t launch_chunk_rope_kv(const ChunkBuffers& c, int S, void* kv_layer, const DecodeBuffers& b, int rows, int MT,
+                                const Geom& g, hipStream_t s);
+hipError_t launch_chunk_gemm(const void* W, int N, int K, const bf16_t* xhi, const bf16_t* xlo, const ChunkBuffers& c,
+                             int S, int MT, hipStream_t s);
+hipError_t launch_chunk_attn(const ChunkBuffers& c, const void* kv_layer, int nsplit, int MT, const DecodeBuffers& b,
+                             const Geom& g, hipStream_t s);
 hipError_t launch_begin_step(const DecodeBuffers& b, int seq, int forced, hipStream_t s);
 hipError_t launch_embed(int dtype, const void* E, const DecodeBuffers& b, const Geom& g, hipStream_t s);
 hipError_t launch_qkv(int dtype, const void* wqkv, const float* gain, void* kv_layer, const DecodeBuffers& b,

@@ -100,6 +100,42 @@ def test_8b_workload_on_4_layers_matches_oracle(trunc4):
     assert worst <= TOL, worst
 
 
+@pytest.mark.timeout(600)
+def test_append_chunk_sizes_agree_with_oracle_and_each_other(trunc4):
+    """The matrix-core append path for every chunk shape (ragged tails, one and two column tiles, split-K
+    factors) against the from-scratch oracle, and against the token-by-token path of the decode kernels."""
+    import paper_2412_07017_amd as pkg
+    wl, model, w_dev, w_cpu, spec = trunc4
+    toks = spec["prompt"][:203]
+    sh = orc.Shape.of(model)
+    dec = orc.CachedDecoder(sh, w_cpu, dtype=np.float32)
+    want_a = dec.prefill(toks[:150]).copy()
+    want_b = dec.inject(toks[150:]).copy()
+    outs = {}
+    for chunk, split in ((1, 0), (2, 0), (7, 0), (24, 0), (32, 1), (33, 0), (48, 2), (64, 0), (64, 4), (64, 3)):
+        lm = pkg.AsyncLM(model, w_dev, max_positions=256, stream=torch.cuda.Stream())
+        lm.set_option("chunk", chunk)
+        lm.set_option("chunk_split", split)
+        lm.prefill(0, toks[:150])
+        la = lm.logits(0)
+        lm.inject_interrupt(0, toks[150:])
+        lb = lm.logits(0)
+        assert lm.seq_len(0) == 203
+        # a decoding step after chunked appends reads the cache rows the chunk kernels wrote
+        tok = lm.decode_step(0)
+        assert tok == int(np.argmax(lb))
+        outs[(chunk, split)] = (la, lb, lm.logits(0))
+        lm.close()
+        ea, eb = float(np.abs(la - want_a).max()), float(np.abs(lb - want_b).max())
+        print("chunk %2d split %d: max |logit err| prefill %.3e inject %.3e" % (chunk, split, ea, eb))
+        assert ea <= TOL and eb <= TOL
+    dec.decode_step()
+    base = outs[(1, 0)]
+    for key, (la, lb, lc) in outs.items():
+        assert np.abs(la - base[0]).max() <= 2e-3 and np.abs(lb - base[1]).max() <= 2e-3, key
+        assert np.abs(lc - dec.logits).max() <= TOL, key
+
+
 @pytest.mark.timeout(900)
 def test_single_plane_bf16_cache_matches_oracle_with_rounded_cache(trunc4):
     """The 2-byte cache format (hi plane only) rounds K and V to bf16 when they are written.  That
