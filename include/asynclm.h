@@ -131,7 +131,7 @@ int asynclm_synchronize(asynclm_ctx *ctx);
 /* Tuning knobs; all have working defaults.  Unknown names give ASYNCLM_E_INVAL.
  *   "chunk"        rows processed per forward pass by prefill / inject (1 .. 64); 1 = token by token
  *                  through the decode kernels.  Default 64 where the matrix-core append path applies
- *                  (bf16 model, paired cache, head_dim 128, d_model and ffn multiples of 128), else 1.
+ *                  (bf16 model, paired cache, head_dim 128, d_model and ffn multiples of 256), else 1.
  *   "chunk_split"  0 = built-in split-K factors of the append path's products, 1..4 = force one
  *   "graph"        1 = replay decoding steps as a captured HIP graph, 0 = launch kernels one by one
  *   "attn_split"   0 = choose the number of sequence splits of decode attention from the length,

@@ -295,7 +295,7 @@ int asynclm_create(asynclm_ctx** out, const asynclm_config* cfg, const asynclm_w
     {
         const bool pair = cfg->dtype == ASYNCLM_DTYPE_BF16 && cfg->kv_format != ASYNCLM_KV_BF16;
         // the matrix-core append path: bf16 weights, paired cache, head_dim 128, 128-aligned inner sizes
-        c->chunk_ok = pair && g.dh == 128 && g.d % 128 == 0 && g.F % 128 == 0 && g.Hq / g.Hkv <= 4 + 4;
+        c->chunk_ok = pair && g.dh == 128 && g.d % 256 == 0 && g.F % 256 == 0 && (g.Hq * g.dh) % 256 == 0;
         const size_t plane = (size_t)g.max_pos * g.dh * g.Hkv;
         g.kv_head_stride = (size_t)g.max_pos * g.dh;
         g.kv_lo_offset = pair ? plane : 0;

@@ -154,6 +154,39 @@ __global__ void k_chunk_rope_kv(const float* __restrict__ P, int S, size_t s_str
 // partial accumulators of a workgroup are summed through LDS, the S workgroups of a row tile
 // write separate partial planes that the consumer adds in a fixed order (no atomics).
 
+// Operands of one 128-element k-block for one wave: 32 weight rows x 128 and Mpad token rows x 128 (hi, lo).
+template <int MT>
+struct GemmTile {
+    uint4 a[8];
+    uint4 bh[MT][8], bl[MT][8];
+};
+
+template <int MT>
+__device__ __forceinline__ void gemm_tile_load(GemmTile<MT>& t, const bf16_t* wrow, const bf16_t* const (&xh)[MT],
+                                               const bf16_t* const (&xl)[MT], int blk) {
+    const size_t off = (size_t)blk * 128;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) t.a[k] = load16_stream(wrow + off + k * 8);
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            t.bh[mt][k] = load16(xh[mt] + off + k * 8);
+            t.bl[mt][k] = load16(xl[mt] + off + k * 8);
+        }
+}
+
+template <int MT>
+__device__ __forceinline__ void gemm_tile_mma(const GemmTile<MT>& t, f32x16 (&acc)[MT]) {
+#pragma unroll
+    for (int k = 0; k < 8; ++k)
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+            acc[mt] = mfma_bf16(t.a[k], t.bh[mt][k], acc[mt]);
+            acc[mt] = mfma_bf16(t.a[k], t.bl[mt][k], acc[mt]);
+        }
+}
+
 template <int MT>
 __global__ __launch_bounds__(256) void k_chunk_gemm(const bf16_t* __restrict__ W, int N, int K,
                                                     const bf16_t* __restrict__ Xhi, const bf16_t* __restrict__ Xlo,
@@ -162,8 +195,9 @@ __global__ __launch_bounds__(256) void k_chunk_gemm(const bf16_t* __restrict__ W
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int i = lane & 31, gh = lane >> 5;
     const int n0 = blockIdx.x * 32, sp = blockIdx.y;
-    const int nblk = K >> 7, parts = 4 * S, part = sp * 4 + wave;
-    const int b0 = (int)((long long)nblk * part / parts), b1 = (int)((long long)nblk * (part + 1) / parts);
+    // K is split over the 4*S waves of this row tile in units of two 128-element blocks
+    const int npair = K >> 8, parts = 4 * S, part = sp * 4 + wave;
+    const int b0 = 2 * (int)((long long)npair * part / parts), b1 = 2 * (int)((long long)npair * (part + 1) / parts);
 
     const bf16_t* wrow = W + (size_t)(n0 + i) * K + gh * 64;
     const bf16_t* xh[MT]; const bf16_t* xl[MT];
@@ -178,31 +212,24 @@ __global__ __launch_bounds__(256) void k_chunk_gemm(const bf16_t* __restrict__ W
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[mt][r] = 0.f;
 
-    uint4 a_cur[8], a_nxt[8];
+    // Two register tiles in ping-pong over pairs of k-blocks: the loads of the next block are in flight
+    // while the current one is multiplied.  The body has no conditional code (a wave always owns an even
+    // number of blocks; past its end it re-reads its last block and drops it), because the compiler sinks
+    // loads into conditional users and then waits for each load right before its product.  The scheduling
+    // barriers keep the instruction scheduler from doing the same within the straight-line body.
+    GemmTile<MT> t0, t1;
     if (b0 < b1) {
-#pragma unroll
-        for (int t = 0; t < 8; ++t) a_cur[t] = load16_stream(wrow + (size_t)b0 * 128 + t * 8);
-    }
-    for (int b = b0; b < b1; ++b) {
-        const int bn = b + 1 < b1 ? b + 1 : b;      // the last trip re-reads its own block (harmless)
-#pragma unroll
-        for (int t = 0; t < 8; ++t) a_nxt[t] = load16_stream(wrow + (size_t)bn * 128 + t * 8);
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
-            uint4 bh[8], bl[8];
-#pragma unroll
-            for (int t = 0; t < 8; ++t) {
-                bh[t] = load16(xh[mt] + (size_t)b * 128 + t * 8);
-                bl[t] = load16(xl[mt] + (size_t)b * 128 + t * 8);
-            }
-#pragma unroll
-            for (int t = 0; t < 8; ++t) {
-                acc[mt] = mfma_bf16(a_cur[t], bh[t], acc[mt]);
-                acc[mt] = mfma_bf16(a_cur[t], bl[t], acc[mt]);
-            }
+        gemm_tile_load<MT>(t0, wrow, xh, xl, b0);
+        for (int b = b0; b < b1; b += 2) {
+            gemm_tile_load<MT>(t1, wrow, xh, xl, b + 1);
+            __builtin_amdgcn_sched_barrier(0);
+            gemm_tile_mma<MT>(t0, acc);
+            __builtin_amdgcn_sched_barrier(0);
+            gemm_tile_load<MT>(t0, wrow, xh, xl, min(b + 2, b1 - 1));
+            __builtin_amdgcn_sched_barrier(0);
+            gemm_tile_mma<MT>(t1, acc);
+            __builtin_amdgcn_sched_barrier(0);
         }
-#pragma unroll
-        for (int t = 0; t < 8; ++t) a_cur[t] = a_nxt[t];
     }
 
 #pragma unroll
@@ -446,7 +473,7 @@ hipError_t launch_chunk_gemm(const void* W, int N, int K, const bf16_t* xhi, con
                              int S, int MT, hipStream_t s) {
     const dim3 grid(N / 32, S), block(256);
     const size_t ps = (size_t)MT * 32 * N;
-    if (S < 1 || S > CHUNK_GEMM_MAX_SPLIT || N % 32 || K % 128 || ps * S > c.part_capacity) return hipErrorInvalidValue;
+    if (S < 1 || S > CHUNK_GEMM_MAX_SPLIT || N % 32 || K % 256 || ps * S > c.part_capacity) return hipErrorInvalidValue;
     if (MT == 1) hipLaunchKernelGGL(k_chunk_gemm<1>, grid, block, 0, s, (const bf16_t*)W, N, K, xhi, xlo, c.part, ps, N, S);
     else if (MT == 2) hipLaunchKernelGGL(k_chunk_gemm<2>, grid, block, 0, s, (const bf16_t*)W, N, K, xhi, xlo, c.part, ps, N, S);
     else return hipErrorInvalidValue;
