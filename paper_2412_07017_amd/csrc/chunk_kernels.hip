@@ -9,9 +9,16 @@
 //   A[32 x 16]: lane (i, g) holds A[i][8g .. 8g+7]        (8 bf16 = one 16-byte register quad)
 //   B[16 x 32]: lane (j, g) holds B[8g .. 8g+7][j]
 //   D[32 x 32]: lane (j, g) holds D[8b + 4g + r][j] in register 4b + r  (b, r = 0..3)
-// The k index of a product is a dummy index, so a k-block of 128 elements is mapped to the
-// eight MFMA steps as  k = 64 g + 8 t + e  (step t, lane half g, element e): every lane then
-// reads 128 contiguous bytes of its matrix row per k-block.
+// Within a k-block of 128 elements, MFMA step t, lane half g, element e is k = 16 t + 8 g + e.
+//
+// Memory access.  A wave-wide 16-byte load is cheap when its 64 lanes cover few cache lines, so:
+//  * activations (the B operand) are kept in global memory in operand order ("tiled planes"):
+//    element (row m, column k) lives at ((((m/32 * K/128 + k/128) * 8 + t) * 2 + g) * 32 + m%32) * 8 + e,
+//    and the 64 lanes of a B load read one contiguous KiB;
+//  * weights (the A operand, row-major in HBM) are loaded 4 rows x 256 contiguous bytes per
+//    instruction and transposed into operand order through a wave-private, XOR-swizzled LDS tile.
+// In the chunk attention, which is small next to the weight streaming, every lane instead reads 128
+// contiguous bytes of its own K / V^T row (k = 64 g + 8 t + e there).
 #include "common.h"
 #include "launch.h"
 
@@ -27,6 +34,12 @@ __device__ __forceinline__ f32x16 mfma_bf16(const uint4& a, const uint4& b, f32x
 __device__ __forceinline__ void split_bf16(float v, bf16_t& hi, bf16_t& lo) {
     hi = f32_to_bf16(v);
     lo = f32_to_bf16(v - __uint_as_float((uint32_t)hi << 16));
+}
+
+// offset (elements) of (row m, column k) in a tiled plane with K columns
+__device__ __forceinline__ size_t tiled_off(int m, int k, int K) {
+    const int kk = k & 127;
+    return ((((size_t)(m >> 5) * (K >> 7) + (k >> 7)) * 8 + (kk >> 4)) * 2 + ((kk >> 3) & 1)) * 256 + (size_t)(m & 31) * 8 + (kk & 7);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -49,7 +62,7 @@ __global__ __launch_bounds__(256) void k_chunk_embed(const bf16_t* __restrict__ 
     for (int i = threadIdx.x; i < d; i += 256) x[(size_t)m * d + i] = Elem<bf16_t>::load1(row + i);
 }
 
-// x[m] += sum_s P[s][m]  (if P), then RMSNorm with `gain` -> bf16 hi/lo planes [m][d].
+// x[m] += sum_s P[s][m]  (if P), then RMSNorm with `gain` -> tiled bf16 hi/lo planes.
 // One workgroup per row; P has row stride n_stride and split stride s_stride (elements).
 __global__ __launch_bounds__(256) void k_chunk_resid_norm(float* __restrict__ x, const float* __restrict__ P, int S,
                                                           size_t s_stride, int n_stride, const float* __restrict__ gain,
@@ -74,7 +87,8 @@ __global__ __launch_bounds__(256) void k_chunk_resid_norm(float* __restrict__ x,
     for (int i = tid; i < d; i += 256) {
         bf16_t hi, lo;
         split_bf16(xr[i] * sc * gain[i], hi, lo);     // xr[i] was written by this same thread
-        out_hi[(size_t)m * d + i] = hi; out_lo[(size_t)m * d + i] = lo;
+        const size_t o = tiled_off(m, i, d);
+        out_hi[o] = hi; out_lo[o] = lo;
     }
 }
 
@@ -90,7 +104,7 @@ __global__ __launch_bounds__(256) void k_chunk_last_row(const float* __restrict_
     }
 }
 
-// a[m][f] = silu(sum_s gate) * (sum_s up) -> hi/lo planes [m][F]
+// a[m][f] = silu(sum_s gate) * (sum_s up) -> tiled hi/lo planes
 __global__ __launch_bounds__(256) void k_chunk_swiglu(const float* __restrict__ P, int S, size_t s_stride, int n_stride,
                                                       int F, bf16_t* __restrict__ out_hi, bf16_t* __restrict__ out_lo) {
     const int m = blockIdx.y;
@@ -103,7 +117,8 @@ __global__ __launch_bounds__(256) void k_chunk_swiglu(const float* __restrict__ 
     }
     bf16_t hi, lo;
     split_bf16(gt / (1.f + expf(-gt)) * up, hi, lo);
-    out_hi[(size_t)m * F + f] = hi; out_lo[(size_t)m * F + f] = lo;
+    const size_t o = tiled_off(m, f, F);
+    out_hi[o] = hi; out_lo[o] = lo;
 }
 
 // Rotary embedding of q and k, K/V cache write (row-major planes and the transposed V planes),
@@ -154,7 +169,8 @@ __global__ void k_chunk_rope_kv(const float* __restrict__ P, int S, size_t s_str
 // partial accumulators of a workgroup are summed through LDS, the S workgroups of a row tile
 // write separate partial planes that the consumer adds in a fixed order (no atomics).
 
-// Operands of one 128-element k-block for one wave: 32 weight rows x 128 and Mpad token rows x 128 (hi, lo).
+// Operands of one 128-element k-block for one wave: 32 weight rows x 128 as loaded (4 rows per
+// instruction: lane l holds row 4q + l/16, 16-byte chunk l%16) and Mpad token rows x 128 in operand order.
 template <int MT>
 struct GemmTile {
     uint4 a[8];
@@ -162,28 +178,43 @@ struct GemmTile {
 };
 
 template <int MT>
-__device__ __forceinline__ void gemm_tile_load(GemmTile<MT>& t, const bf16_t* wrow, const bf16_t* const (&xh)[MT],
+__device__ __forceinline__ void gemm_tile_load(GemmTile<MT>& t, const bf16_t* wlane, size_t wstep, const bf16_t* const (&xh)[MT],
                                                const bf16_t* const (&xl)[MT], int blk) {
-    const size_t off = (size_t)blk * 128;
 #pragma unroll
-    for (int k = 0; k < 8; ++k) t.a[k] = load16_stream(wrow + off + k * 8);
+    for (int q = 0; q < 8; ++q) t.a[q] = load16_stream(wlane + (size_t)blk * 128 + q * wstep);
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
         for (int k = 0; k < 8; ++k) {
-            t.bh[mt][k] = load16(xh[mt] + off + k * 8);
-            t.bl[mt][k] = load16(xl[mt] + off + k * 8);
+            t.bh[mt][k] = load16(xh[mt] + (size_t)blk * 4096 + k * 512);
+            t.bl[mt][k] = load16(xl[mt] + (size_t)blk * 4096 + k * 512);
         }
 }
 
+// Transposes the weight tile into operand order through the wave's LDS tile, then multiplies.
+// LDS tile: 32 rows x 16 chunks of 16 bytes, chunk c of row r stored at chunk position c ^ (r & 15).
 template <int MT>
-__device__ __forceinline__ void gemm_tile_mma(const GemmTile<MT>& t, f32x16 (&acc)[MT]) {
+__device__ __forceinline__ void gemm_tile_mma(const GemmTile<MT>& t, f32x16 (&acc)[MT], uint4* lds, int lane) {
+    {
+        const int r0 = lane >> 4, c = lane & 15;
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            const int r = 4 * q + r0;
+            lds[r * 16 + (c ^ (r & 15))] = t.a[q];
+        }
+    }
+    uint4 a[8];
+    {
+        const int i = lane & 31, gh = lane >> 5;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) a[k] = lds[i * 16 + ((2 * k + gh) ^ (i & 15))];
+    }
 #pragma unroll
     for (int k = 0; k < 8; ++k)
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
-            acc[mt] = mfma_bf16(t.a[k], t.bh[mt][k], acc[mt]);
-            acc[mt] = mfma_bf16(t.a[k], t.bl[mt][k], acc[mt]);
+            acc[mt] = mfma_bf16(a[k], t.bh[mt][k], acc[mt]);
+            acc[mt] = mfma_bf16(a[k], t.bl[mt][k], acc[mt]);
         }
 }
 
@@ -191,20 +222,24 @@ template <int MT>
 __global__ __launch_bounds__(256) void k_chunk_gemm(const bf16_t* __restrict__ W, int N, int K,
                                                     const bf16_t* __restrict__ Xhi, const bf16_t* __restrict__ Xlo,
                                                     float* __restrict__ P, size_t s_stride, int n_stride, int S) {
-    __shared__ float red[4][MT][16][64];
+    // per-wave weight tiles (8 KiB each) during the product, then the four partial accumulators
+    constexpr int RED_BYTES = 4 * MT * 16 * 64 * 4, LDS_BYTES = RED_BYTES > 32768 ? RED_BYTES : 32768;
+    __shared__ uint4 lds_raw[LDS_BYTES / 16];
+    uint4 (*wt)[512] = reinterpret_cast<uint4 (*)[512]>(lds_raw);
+    float (*red)[MT][16][64] = reinterpret_cast<float (*)[MT][16][64]>(lds_raw);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int i = lane & 31, gh = lane >> 5;
     const int n0 = blockIdx.x * 32, sp = blockIdx.y;
     // K is split over the 4*S waves of this row tile in units of two 128-element blocks
     const int npair = K >> 8, parts = 4 * S, part = sp * 4 + wave;
     const int b0 = 2 * (int)((long long)npair * part / parts), b1 = 2 * (int)((long long)npair * (part + 1) / parts);
 
-    const bf16_t* wrow = W + (size_t)(n0 + i) * K + gh * 64;
+    const bf16_t* wlane = W + (size_t)(n0 + (lane >> 4)) * K + (lane & 15) * 8;   // row l/16 (+4q), chunk l%16
+    const size_t wstep = (size_t)4 * K;
     const bf16_t* xh[MT]; const bf16_t* xl[MT];
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
-        xh[mt] = Xhi + (size_t)(mt * 32 + i) * K + gh * 64;
-        xl[mt] = Xlo + (size_t)(mt * 32 + i) * K + gh * 64;
+        xh[mt] = Xhi + (size_t)mt * 32 * K + lane * 8;
+        xl[mt] = Xlo + (size_t)mt * 32 * K + lane * 8;
     }
     f32x16 acc[MT];
 #pragma unroll
@@ -219,19 +254,20 @@ __global__ __launch_bounds__(256) void k_chunk_gemm(const bf16_t* __restrict__ W
     // barriers keep the instruction scheduler from doing the same within the straight-line body.
     GemmTile<MT> t0, t1;
     if (b0 < b1) {
-        gemm_tile_load<MT>(t0, wrow, xh, xl, b0);
+        gemm_tile_load<MT>(t0, wlane, wstep, xh, xl, b0);
         for (int b = b0; b < b1; b += 2) {
-            gemm_tile_load<MT>(t1, wrow, xh, xl, b + 1);
+            gemm_tile_load<MT>(t1, wlane, wstep, xh, xl, b + 1);
             __builtin_amdgcn_sched_barrier(0);
-            gemm_tile_mma<MT>(t0, acc);
+            gemm_tile_mma<MT>(t0, acc, wt[wave], lane);
             __builtin_amdgcn_sched_barrier(0);
-            gemm_tile_load<MT>(t0, wrow, xh, xl, min(b + 2, b1 - 1));
+            gemm_tile_load<MT>(t0, wlane, wstep, xh, xl, min(b + 2, b1 - 1));
             __builtin_amdgcn_sched_barrier(0);
-            gemm_tile_mma<MT>(t1, acc);
+            gemm_tile_mma<MT>(t1, acc, wt[wave], lane);
             __builtin_amdgcn_sched_barrier(0);
         }
     }
 
+    __syncthreads();        // every wave is done with its weight tile
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
@@ -385,7 +421,7 @@ __global__ __launch_bounds__(256) void k_chunk_attn(ChunkAttnArgs a, Geom g) {
     }
 }
 
-// Merge the key splits of one task and emit the attention output as hi/lo planes [m][Hq*128].
+// Merge the key splits of one task and emit the attention output as tiled hi/lo planes (K = Hq*128).
 __global__ __launch_bounds__(256) void k_chunk_attn_combine(const float* __restrict__ part_o, const float* __restrict__ part_ml,
                                                             int nsplit, int MT, Geom g, const StepDesc* step,
                                                             bf16_t* __restrict__ out_hi, bf16_t* __restrict__ out_lo) {
@@ -420,7 +456,7 @@ __global__ __launch_bounds__(256) void k_chunk_attn_combine(const float* __restr
         if (m < rows) {
             bf16_t hi, lw;
             split_bf16(v, hi, lw);
-            const size_t o = (size_t)m * g.Hq * DH + (size_t)hq * DH + dh;
+            const size_t o = tiled_off(m, hq * DH + dh, g.Hq * DH);
             out_hi[o] = hi; out_lo[o] = lw;
         }
     }

@@ -35,9 +35,10 @@ constexpr int CHUNK_GEMM_MAX_SPLIT = 4;
 struct ChunkBuffers {
     int32_t* tokens;          // [CHUNK_MAX]
     float* x;                 // [CHUNK_MAX][d] residual stream
-    bf16_t *nrm_hi, *nrm_lo;  // [CHUNK_MAX][d]      normalised input of the QKV and gate/up products
-    bf16_t *att_hi, *att_lo;  // [CHUNK_MAX][Hq*dh]  attention output
-    bf16_t *act_hi, *act_lo;  // [CHUNK_MAX][F]      SwiGLU output
+    // inputs of the products, CHUNK_MAX rows each, stored in matrix-core operand order (tiled planes)
+    bf16_t *nrm_hi, *nrm_lo;  // d columns:     normalised input of the QKV and gate/up products
+    bf16_t *att_hi, *att_lo;  // Hq*dh columns: attention output
+    bf16_t *act_hi, *act_lo;  // F columns:     SwiGLU output
     bf16_t *q_hi, *q_lo;      // [Hq][CHUNK_MAX][dh] rotated, scaled queries
     float* part;              // split-K partial planes of the current product
     size_t part_capacity;     // floats in `part`
