@@ -41,7 +41,7 @@ def parse():
 
 
 def cpu_baseline(wl, model, w_dev, spec, seconds_budget=25.0):
-    """Times the oracle's cached decoder (fp32 numpy) on this host: decode steps on 2- and 4-layer
+    """Times the oracle's cached decoder (fp32 numpy) on this host: decode steps on 4- and 8-layer
     truncations of the same weights, extrapolated linearly in depth to the full model."""
     import numpy as np
     import torch
@@ -53,26 +53,28 @@ def cpu_baseline(wl, model, w_dev, spec, seconds_budget=25.0):
     except Exception:
         threads = os.cpu_count() or 1
     conv = lambda t: t.detach().to("cpu").to(torch.float32).numpy()
-    depth = min(4, model.n_layers)
+    depth = min(8, model.n_layers)
     w = {k: conv(w_dev[k]) for k in ("embed", "final_norm", "lm_head")}
     for k in ("attn_norm", "wqkv", "wo", "ffn_norm", "wgate_up", "wdown"):
         w[k] = [conv(t) for t in w_dev[k][:depth]]
-    P = min(64, len(spec["prompt"]))
+    P = min(256, len(spec["prompt"]))
     times = {}
     t_begin = time.perf_counter()
-    for nl in sorted({max(depth // 2, 1), depth}):
+    depths = sorted({max(depth // 2, 1), depth})
+    for nl in depths:
         sh = orc.Shape.of(ai.truncated(model, nl))
         dec = orc.CachedDecoder(sh, w, dtype=np.float32)
         dec.prefill(spec["prompt"][:P])
+        dec.decode_step()                                   # warm the BLAS threads
         n, t0 = 0, time.perf_counter()
-        while n < 4 or (time.perf_counter() - t0 < seconds_budget / 4 and n < 32):
+        while n < 4 or time.perf_counter() - t0 < seconds_budget / (2 * len(depths)):
             dec.decode_step()
             n += 1
         times[nl] = (time.perf_counter() - t0) / n
     ks = sorted(times)
     if len(ks) == 2:
-        per_layer = (times[ks[1]] - times[ks[0]]) / (ks[1] - ks[0])
-        head = max(times[ks[0]] - per_layer * ks[0], 0.0)
+        per_layer = max((times[ks[1]] - times[ks[0]]) / (ks[1] - ks[0]), 0.0)
+        head = max(times[ks[1]] - per_layer * ks[1], 0.0)
     else:
         per_layer, head = times[ks[0]] / ks[0], 0.0
     full = per_layer * model.n_layers + head
