@@ -8,7 +8,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libasynclm.so")
-SOURCES = ["api.hip", "decode_kernels.hip", "chunk_kernels.hip"]
+SOURCES = ["api.hip", "decode_kernels.hip", "decode_fused.hip", "chunk_kernels.hip"]
 
 
 def hipcc_path() -> str:

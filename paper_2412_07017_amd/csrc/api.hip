@@ -32,12 +32,17 @@ struct asynclm_ctx {
     DecodeBuffers b{};
     ChunkBuffers cb{};
     bool chunk_ok = false;              // the matrix-core append path supports this model
+    FusedPlan fused{};                  // single-kernel decoding step
+    void* layers_dev = nullptr;         // per-layer pointer table of the fused step
+    unsigned* bar = nullptr;            // its grid-barrier counters
+    unsigned long long* trace = nullptr; // its optional phase time stamps
+    bool want_trace = false;
     int32_t* token_host = nullptr;      // pinned, 1 int
 
     std::vector<int32_t> len;           // host mirror of the sequence lengths
 
     // options
-    int opt_chunk = 1, opt_graph = 1, opt_attn_split = 0, opt_chunk_split = 0;
+    int opt_chunk = 1, opt_graph = 1, opt_attn_split = 0, opt_chunk_split = 0, opt_fused = 0;
 
     std::map<int, hipGraphExec_t> graphs;   // key: nsplit * 2 + with_head
 
@@ -51,7 +56,10 @@ namespace {
 
 const char* const kClassNames[KC_COUNT] = {
     "begin_step", "embed", "qkv_rope_kvwrite", "attn_decode", "o_proj_residual", "gate_up_swiglu",
-    "down_residual", "lm_head", "argmax", "chunk_prep", "chunk_gemm", "chunk_attn", "chunk_misc"};
+    "down_residual", "lm_head", "argmax", "chunk_prep", "chunk_gemm", "chunk_attn", "chunk_misc",
+    "fused_step_kernel", "fused:qkv", "fused:qkv_barrier", "fused:attn", "fused:attn_barrier", "fused:merge",
+    "fused:merge_barrier", "fused:o_proj", "fused:o_proj_barrier", "fused:gate_up", "fused:gate_up_barrier",
+    "fused:down", "fused:down_barrier", "fused:lm_head", "fused:lm_head_barrier"};
 
 // With ASYNCLM_VERBOSE set in the environment, HIP failures are reported on stderr.
 void report_hip(const char* where, hipError_t e) {
@@ -143,6 +151,16 @@ hipError_t forward_single_graph(asynclm_ctx* c, int seq, bool with_head, int nsp
 
 hipError_t step_one_token(asynclm_ctx* c, int seq, int forced, bool with_head) {
     hipError_t e;
+    if (c->opt_fused) {
+        FusedLaunch L{};
+        L.layers_dev = c->layers_dev; L.n_layers = c->cfg.n_layers;
+        L.embed = c->embed; L.final_norm = c->final_norm; L.lm_head = c->lm_head;
+        L.seq = seq; L.forced = forced; L.with_head = with_head;
+        L.logits = c->logits + (size_t)seq * c->g.V; L.bar = c->bar; L.trace = c->want_trace ? c->trace : nullptr;
+        if ((e = launch_decode_fused(c->cfg.dtype, c->fused, L, c->b, c->g, c->stream))) return e;
+        c->len[seq] += 1;
+        return hipSuccess;
+    }
     const int nsplit = pick_nsplit(c, c->len[seq] + 1);
     if ((e = run(c, KC_BEGIN, [&] { return launch_begin_step(c->b, seq, forced, c->stream); }))) return e;
     if (c->opt_graph && !c->prof) e = forward_single_graph(c, seq, with_head, nsplit);
@@ -318,7 +336,7 @@ int asynclm_create(asynclm_ctx** out, const asynclm_config* cfg, const asynclm_w
     ALLOC(c->logits, (size_t)cfg->max_seqs * g.V);
     ALLOC(c->b.step, 1);
     ALLOC(c->b.seq_state, (size_t)cfg->max_seqs);
-    ALLOC(c->b.token_log, 1);
+    ALLOC(c->b.token_log, 2);        // [0] chosen token, [1] set when a fused step gave up at a grid barrier
     ALLOC(c->b.x, (size_t)g.d);
     ALLOC(c->b.q, (size_t)g.Hq * g.dh);
     ALLOC(c->b.o, (size_t)g.Hq * g.dh);
@@ -379,9 +397,28 @@ int asynclm_create(asynclm_ctx** out, const asynclm_config* cfg, const asynclm_w
     if (hipMemset(c->b.seq_state, 0, sizeof(SeqState) * cfg->max_seqs) != hipSuccess ||
         hipMemset(c->b.attn_counters, 0, sizeof(int32_t) * g.Hkv) != hipSuccess ||
         hipMemset(c->b.amax_counter, 0, sizeof(int32_t)) != hipSuccess ||
-        hipMemset(c->b.step, 0, sizeof(StepDesc)) != hipSuccess)
+        hipMemset(c->b.step, 0, sizeof(StepDesc)) != hipSuccess || hipMemset(c->b.token_log, 0, 2 * sizeof(int32_t)) != hipSuccess)
         return bail(ASYNCLM_E_DEVICE);
     if (hipHostMalloc((void**)&c->token_host, 64, hipHostMallocDefault) != hipSuccess) return bail(ASYNCLM_E_NOMEM);
+    // fused decoding step: pointer table, barrier counters, launch plan
+    {
+        std::vector<const void*> tab;
+        for (int l = 0; l < cfg->n_layers; ++l) {
+            tab.push_back(c->attn_norm[l]); tab.push_back(c->wqkv[l]); tab.push_back(c->wo[l]);
+            tab.push_back(c->ffn_norm[l]); tab.push_back(c->wgate_up[l]); tab.push_back(c->wdown[l]);
+            tab.push_back(kv_layer_ptr(c, l));
+        }
+        char* tabd = nullptr;
+        if ((e = dev_alloc(c, &tabd, tab.size() * sizeof(void*))) != hipSuccess) return bail(ASYNCLM_E_NOMEM);
+        c->layers_dev = tabd;
+        if ((e = dev_alloc(c, &c->bar, 4)) != hipSuccess) return bail(ASYNCLM_E_NOMEM);
+        if ((e = dev_alloc(c, &c->trace, (size_t)FUSED_TRACE_MAX)) != hipSuccess) return bail(ASYNCLM_E_NOMEM);
+        if (hipMemcpy(tabd, tab.data(), tab.size() * sizeof(void*), hipMemcpyHostToDevice) != hipSuccess ||
+            hipMemset(c->bar, 0, 4 * sizeof(unsigned)) != hipSuccess)
+            return bail(ASYNCLM_E_DEVICE);
+        if ((e = fused_init(cfg->dtype, g, &c->fused)) != hipSuccess) { report_hip("fused_init", e); return bail(ASYNCLM_E_DEVICE); }
+        c->opt_fused = c->fused.supported ? 1 : 0;
+    }
     const int max_k = g.F > g.d ? (g.F > g.Hq * g.dh ? g.F : g.Hq * g.dh) : (g.d > g.Hq * g.dh ? g.d : g.Hq * g.dh);
     if ((e = decode_init(cfg->dtype, max_k)) != hipSuccess) { report_hip("decode_init", e); return bail(ASYNCLM_E_DEVICE); }
     if ((e = hipDeviceSynchronize()) != hipSuccess) { report_hip("hipDeviceSynchronize", e); return bail(ASYNCLM_E_DEVICE); }
@@ -417,9 +454,10 @@ int asynclm_decode_step(asynclm_ctx* c, int32_t seq, int32_t forced_token, int32
     if (c->len[seq] + 1 > c->cfg.max_positions) return ASYNCLM_E_CAPACITY;
     HIPCK(c, step_one_token(c, seq, forced_token < 0 ? -1 : forced_token, true));
     if (token_out) {
-        HIPCK(c, hipMemcpyAsync(c->token_host, c->b.token_log, sizeof(int32_t), hipMemcpyDeviceToHost, c->stream));
+        HIPCK(c, hipMemcpyAsync(c->token_host, c->b.token_log, 2 * sizeof(int32_t), hipMemcpyDeviceToHost, c->stream));
         HIPCK(c, hipStreamSynchronize(c->stream));
-        *token_out = *c->token_host;
+        if (c->token_host[1]) return fail_device(c, hipErrorLaunchFailure);
+        *token_out = c->token_host[0];
     }
     return ASYNCLM_OK;
 }
@@ -439,7 +477,9 @@ int asynclm_logits(asynclm_ctx* c, int32_t seq, float* out_host, int32_t n) {
     if (!out_host || n != c->cfg.vocab) return ASYNCLM_E_INVAL;
     if (c->len[seq] == 0) return ASYNCLM_E_STATE;
     HIPCK(c, hipMemcpyAsync(out_host, c->logits + (size_t)seq * c->g.V, sizeof(float) * n, hipMemcpyDeviceToHost, c->stream));
+    HIPCK(c, hipMemcpyAsync(c->token_host, c->b.token_log, 2 * sizeof(int32_t), hipMemcpyDeviceToHost, c->stream));
     HIPCK(c, hipStreamSynchronize(c->stream));
+    if (c->token_host[1]) return fail_device(c, hipErrorLaunchFailure);
     return ASYNCLM_OK;
 }
 
@@ -478,6 +518,7 @@ int asynclm_set_option(asynclm_ctx* c, const char* name, int32_t value) {
     if (!c || !name) return ASYNCLM_E_INVAL;
     if (!std::strcmp(name, "chunk")) { if (value < 1 || value > CHUNK_MAX) return ASYNCLM_E_INVAL; c->opt_chunk = value; return ASYNCLM_OK; }
     if (!std::strcmp(name, "chunk_split")) { if (value < 0 || value > CHUNK_GEMM_MAX_SPLIT) return ASYNCLM_E_INVAL; c->opt_chunk_split = value; return ASYNCLM_OK; }
+    if (!std::strcmp(name, "fused")) { c->opt_fused = (value && c->fused.supported) ? 1 : 0; return ASYNCLM_OK; }
     if (!std::strcmp(name, "graph")) { c->opt_graph = (value && c->stream) ? 1 : 0; return ASYNCLM_OK; }
     if (!std::strcmp(name, "attn_split")) { if (value < 0 || value > ATTN_MAX_SPLIT) return ASYNCLM_E_INVAL; c->opt_attn_split = value; return ASYNCLM_OK; }
     return ASYNCLM_E_INVAL;
@@ -492,12 +533,40 @@ int asynclm_profile_step(asynclm_ctx* c, int32_t seq, int32_t forced_token, cons
     if (c->len[seq] + 1 > c->cfg.max_positions) return ASYNCLM_E_CAPACITY;
     for (hipEvent_t ev : c->prof_events) hipEventDestroy(ev);
     c->prof_events.clear(); c->prof_class.clear();
+    for (int i = 0; i < KC_COUNT; ++i) { ms_out[i] = 0.f; launches_out[i] = 0; }
+    if (c->opt_fused) {
+        // one launch: HIP events around the kernel, and the kernel's own phase time stamps (100 MHz clock)
+        const int nl = c->cfg.n_layers, n_stamps = 1 + 12 * nl + 2;
+        if (n_stamps > FUSED_TRACE_MAX) return ASYNCLM_E_INVAL;
+        hipEvent_t e0, e1;
+        HIPCK(c, hipEventCreate(&e0)); HIPCK(c, hipEventCreate(&e1));
+        c->prof_events.push_back(e0); c->prof_events.push_back(e1);
+        HIPCK(c, hipEventRecord(e0, c->stream));
+        c->want_trace = true;
+        hipError_t e = step_one_token(c, seq, forced_token, true);
+        c->want_trace = false;
+        if (e) return fail_device(c, e);
+        HIPCK(c, hipEventRecord(e1, c->stream));
+        std::vector<unsigned long long> t(n_stamps);
+        HIPCK(c, hipMemcpyAsync(t.data(), c->trace, sizeof(unsigned long long) * n_stamps, hipMemcpyDeviceToHost, c->stream));
+        HIPCK(c, hipStreamSynchronize(c->stream));
+        float ms = 0.f;
+        HIPCK(c, hipEventElapsedTime(&ms, e0, e1));
+        ms_out[KC_F_TOTAL] = ms; launches_out[KC_F_TOTAL] = 1;
+        auto add = [&](int kc, size_t i) { ms_out[kc] += (float)((double)(t[i] - t[i - 1]) * 1e-5); launches_out[kc] += 1; };
+        for (int l = 0; l < nl; ++l) {
+            const size_t b = 1 + 12 * (size_t)l;
+            for (int k = 0; k < 12; ++k) add(KC_F_QKV + k, b + k);
+        }
+        add(KC_F_HEAD, 1 + 12 * (size_t)nl); add(KC_F_HEAD_WAIT, 2 + 12 * (size_t)nl);
+        if (names_out) *names_out = kClassNames;
+        return KC_COUNT;
+    }
     c->prof = true;
     hipError_t e = step_one_token(c, seq, forced_token, true);
     c->prof = false;
     if (e) return fail_device(c, e);
     HIPCK(c, hipStreamSynchronize(c->stream));
-    for (int i = 0; i < KC_COUNT; ++i) { ms_out[i] = 0.f; launches_out[i] = 0; }
     for (size_t i = 0; i < c->prof_class.size(); ++i) {
         float ms = 0.f;
         HIPCK(c, hipEventElapsedTime(&ms, c->prof_events[2 * i], c->prof_events[2 * i + 1]));

@@ -41,7 +41,10 @@ struct Geom {
 
 enum KernelClass {
     KC_BEGIN = 0, KC_EMBED, KC_QKV, KC_ATTN, KC_OPROJ, KC_GATEUP, KC_DOWN, KC_LMHEAD, KC_ARGMAX,
-    KC_CHUNK_PREP, KC_CHUNK_GEMM, KC_CHUNK_ATTN, KC_CHUNK_MISC, KC_COUNT
+    KC_CHUNK_PREP, KC_CHUNK_GEMM, KC_CHUNK_ATTN, KC_CHUNK_MISC,
+    // phases inside the fused decoding kernel (time stamps of workgroup 0): work, then wait at the grid barrier
+    KC_F_TOTAL, KC_F_QKV, KC_F_QKV_WAIT, KC_F_ATTN, KC_F_ATTN_WAIT, KC_F_MERGE, KC_F_MERGE_WAIT, KC_F_OPROJ, KC_F_OPROJ_WAIT,
+    KC_F_GATEUP, KC_F_GATEUP_WAIT, KC_F_DOWN, KC_F_DOWN_WAIT, KC_F_HEAD, KC_F_HEAD_WAIT, KC_COUNT
 };
 
 // ---- device helpers -------------------------------------------------------------------------
@@ -78,12 +81,22 @@ template <> struct Elem<bf16_t> {
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-// 16-byte streaming load (data that is read once: weights)
+// 16-byte loads through pointers that are known to be global memory (a pointer read from a table in
+// memory is otherwise treated as generic and loaded with flat instructions, which also count as LDS
+// traffic when the wave waits for its LDS reads).
+typedef const __attribute__((address_space(1))) u32x4* global_u32x4_ptr;
+typedef const __attribute__((address_space(1))) float* global_f32_ptr;
+
+// streaming variant: data that is read once (weights)
 __device__ __forceinline__ uint4 load16_stream(const void* p) {
-    u32x4 v = __builtin_nontemporal_load((const u32x4*)p);
+    u32x4 v = __builtin_nontemporal_load((global_u32x4_ptr)(uintptr_t)p);
     return make_uint4(v.x, v.y, v.z, v.w);
 }
-__device__ __forceinline__ uint4 load16(const void* p) { return *(const uint4*)p; }
+__device__ __forceinline__ uint4 load16(const void* p) {
+    u32x4 v = *(global_u32x4_ptr)(uintptr_t)p;
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ float load_f32(const float* p) { return *(global_f32_ptr)(uintptr_t)p; }
 
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll

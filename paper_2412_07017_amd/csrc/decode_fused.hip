@@ -1,0 +1,606 @@
+// One decoding step as ONE persistent kernel (gfx950): every workgroup owns a fixed share of the rows
+// of every matrix, phases are separated by grid-wide barriers, and the first weight tiles of the next
+// phase are requested before each barrier, so that HBM keeps streaming while the workgroups wait.
+//
+// Launch: cooperative, one workgroup of 256 threads (4 waves) per compute unit.
+// Phases per layer:  QKV (+norm, rotary, K/V write) | attention partials | merge of the splits |
+//                    O (+residual) | gate/up (+norm, SwiGLU) | down (+residual);
+// then final norm + output head with a running argmax, and the argmax merge by workgroup 0.
+//
+// A wave walks its rows pair by pair ("units", see decode_device.h) in tiles of 2 rows x 4 k-steps
+// (8 loads of 16 bytes per lane = 8 KiB per wave) through a ring of four register tiles: while one
+// tile is multiplied, the next three are in flight.  The loop body has no conditional code around the
+// loads or their use (tiles past the end re-read the last tile and are multiplied by zeros), because
+// the compiler otherwise sinks the loads next to their users and the pipeline collapses.
+#include "common.h"
+#include "launch.h"
+#include "decode_device.h"
+
+#include <algorithm>
+
+namespace asynclm {
+
+constexpr unsigned BARRIER_SPIN_LIMIT = 1u << 22;   // polls before a workgroup gives up (about a second)
+constexpr int RING = 4;
+
+struct FusedLayer {
+    const float* attn_norm; const void* wqkv; const void* wo;
+    const float* ffn_norm; const void* wgate_up; const void* wdown;
+    void* kv_layer;
+};
+
+struct FusedArgs {
+    const FusedLayer* layers;
+    int32_t n_layers;
+    const void* embed; const float* final_norm; const void* lm_head;
+    Geom g;
+    SeqState* seq_state;
+    int32_t seq, forced, with_head;
+    int32_t* token_log;
+    float *x, *q, *o, *a, *part_acc, *part_ml, *logits;
+    const float *rope_cos, *rope_sin;
+    float* amax_v; int32_t* amax_i;
+    unsigned* bar;          // [0] arrivals (only grows), [1] value of [0] when this launch started, [2] error flag
+    int32_t nsplit;         // attention splits per kv head (<= gridDim.x / Hkv)
+    int32_t xs_groups;      // LDS capacity of the staged vector, in groups of EPL elements
+    unsigned long long* trace;   // optional: workgroup 0 stores the 100 MHz wall clock at every phase boundary
+};
+
+// ---------------------------------------------------------------------------------------------
+// grid barrier
+// ---------------------------------------------------------------------------------------------
+
+// Arrive.  All global stores of the workgroup made before the call are visible to every workgroup
+// that later passes grid_wait on the same target.
+__device__ __forceinline__ void grid_arrive(unsigned* bar) {
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+        atomicAdd(&bar[0], 1u);
+    }
+}
+
+// Wait until `target` arrivals have been counted.  Returns false (for the whole workgroup) when the
+// spin limit is hit or another workgroup has already given up; the caller then leaves the kernel.
+__device__ __forceinline__ bool grid_wait(unsigned* bar, unsigned target, int* s_flag, int32_t* token_log) {
+    if (threadIdx.x == 0) {
+        unsigned spins = 0;
+        int ok = 1;
+        while ((int)(__hip_atomic_load(&bar[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - target) < 0) {
+            __builtin_amdgcn_s_sleep(1);
+            if (++spins > BARRIER_SPIN_LIMIT || __hip_atomic_load(&bar[2], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) {
+                ok = 0;
+                break;
+            }
+        }
+        if (!ok) { atomicExch(&bar[2], 1u); token_log[1] = 1; }    // token_log[1]: read back by the host with the token
+        *s_flag = ok;
+    }
+    __syncthreads();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+    return *s_flag != 0;
+}
+
+// ---------------------------------------------------------------------------------------------
+// matrix-vector phase
+// ---------------------------------------------------------------------------------------------
+
+template <typename WT>
+struct Phase {
+    const WT* W;
+    int rows, K, Kg, KT, units, u0, u1;   // this wave owns units [u0, u1)
+};
+
+struct Cursor { int u, kt; };
+
+// One ring slot: a tile of weights (2 rows x 4 k-steps) plus the two values the unit's epilogue needs
+// from memory (residual pair, or rotary cos / sin).  They are requested with the tile, because a load
+// issued at epilogue time could only be waited for together with every tile load issued before it.
+struct Slot {
+    uint4 v[8];
+    float e0, e1;
+};
+
+template <typename WT, int EPI>
+__device__ __forceinline__ Phase<WT> make_phase(const void* W, int rows, int K, int units) {
+    Phase<WT> p;
+    p.W = (const WT*)W; p.rows = rows; p.K = K; p.Kg = K / Elem<WT>::EPL;
+    p.KT = (p.Kg + 255) / 256; p.units = units;
+    const long long gw = (long long)blockIdx.x * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), tw = (long long)gridDim.x * 4;
+    p.u0 = (int)(units * gw / tw); p.u1 = (int)(units * (gw + 1) / tw);
+    return p;
+}
+
+__device__ __forceinline__ void advance(Cursor& c, int KT) {
+    if (++c.kt == KT) { c.kt = 0; ++c.u; }
+}
+
+// Requests tile (c.u, c.kt): rows (rA, rB) of the unit, k-steps 4 kt .. 4 kt + 3.  Past the end of the
+// wave's range the last tile is requested again (a cache hit); addresses always stay inside W.
+template <typename WT, int EPI>
+__device__ __forceinline__ void tile_load(Slot& sl, const Phase<WT>& p, const Cursor& c, int lane, const Geom& g, const EpiOut& eo) {
+    uint4 (&v)[8] = sl.v;
+    constexpr int EPL = Elem<WT>::EPL;
+    const bool past = c.u >= p.u1;
+    const int u = past ? max(min(p.u1, p.units) - 1, 0) : c.u;
+    const int kt = past ? p.KT - 1 : c.kt;
+    int rA, rB;
+    unit_rows<EPI>(u, p.rows, g, rA, rB);
+    const WT* pa = p.W + (size_t)rA * p.K;
+    const WT* pb = p.W + (size_t)rB * p.K;
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+        const int gi = min((kt * 4 + s) * 64 + lane, p.Kg - 1);
+        v[2 * s] = load16_stream(pa + (size_t)gi * EPL);
+        v[2 * s + 1] = load16_stream(pb + (size_t)gi * EPL);
+    }
+    if (EPI == EPI_RESID) {
+        sl.e0 = load_f32(eo.res + rA); sl.e1 = load_f32(eo.res + rB);
+    } else if (EPI == EPI_QKV) {
+        const int hs = g.dh == 128 ? 6 : 5, h = u >> hs, i = u & ((1 << hs) - 1);
+        const bool rot = h < g.Hq + g.Hkv;                         // value rows are not rotated
+        const size_t ri = ((size_t)eo.pos << hs) + i;
+        const float c = load_f32(eo.rope_cos + ri), sn = load_f32(eo.rope_sin + ri);
+        sl.e0 = rot ? c : 1.f; sl.e1 = rot ? sn : 0.f;
+    } else { sl.e0 = 0.f; sl.e1 = 0.f; }
+}
+
+// Epilogue of unit u, by one lane: sa, sb are the finished dot products, e0 / e1 the slot's operands.
+template <typename WT, int EPI>
+__device__ __forceinline__ void finish_unit(int u, float sa, float sb, float e0, float e1, const EpiOut& o, const Geom& g) {
+    if (EPI == EPI_STORE) {
+        o.y[2 * u] = sa;
+        if (2 * u + 1 < o.rows) o.y[2 * u + 1] = sb;
+    } else if (EPI == EPI_RESID) {
+        o.y[2 * u] = e0 + sa;
+        if (2 * u + 1 < o.rows) o.y[2 * u + 1] = e1 + sb;
+    } else if (EPI == EPI_SWIGLU) {
+        o.y[u] = sa / (1.f + expf(-sa)) * sb;
+    } else {
+        const int hs = g.dh == 128 ? 6 : 5, half = 1 << hs;
+        const int h = u >> hs, i = u & (half - 1);
+        const float ra = sa * e0 - sb * e1, rb = sb * e0 + sa * e1;
+        const size_t seq_off = (size_t)o.seq * g.kv_seq_stride;
+        if (h < g.Hq) { o.q_out[h * g.dh + i] = ra; o.q_out[h * g.dh + i + half] = rb; }
+        else if (h < g.Hq + g.Hkv) {
+            WT* kp = (WT*)o.kv_layer + seq_off + (size_t)(h - g.Hq) * g.kv_head_stride + (size_t)o.pos * g.dh;
+            kv_store(kp + i, ra, g.kv_lo_offset); kv_store(kp + i + half, rb, g.kv_lo_offset);
+        } else {
+            const size_t head_off = seq_off + (size_t)(h - g.Hq - g.Hkv) * g.kv_head_stride;
+            WT* vp = (WT*)o.kv_layer + g.kv_v_offset + head_off + (size_t)o.pos * g.dh;
+            kv_store(vp + i, ra, g.kv_lo_offset); kv_store(vp + i + half, rb, g.kv_lo_offset);
+            if (g.kv_vt_offset) {
+                WT* vt = (WT*)o.kv_layer + g.kv_vt_offset + head_off + o.pos;
+                kv_store(vt + (size_t)i * g.max_pos, ra, g.kv_lo_offset);
+                kv_store(vt + (size_t)(i + half) * g.max_pos, rb, g.kv_lo_offset);
+            }
+        }
+    }
+}
+
+// Multiplies one tile with the staged vector.  xs: planar LDS copy of x (plane p holds elements
+// 4p..4p+3 of every group of EPL), zero beyond Kg; tiles past the end read a block of zeros.
+template <typename WT>
+__device__ __forceinline__ void tile_fma(const uint4 (&v)[8], const float4* xs, int plane_stride, int zero_group,
+                                         bool past, int kt, int lane, float& accA, float& accB) {
+    constexpr int EPL = Elem<WT>::EPL;
+    constexpr int NP = EPL / 4;
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+        const int gi = past ? zero_group + lane : (kt * 4 + s) * 64 + lane;
+        float xv[EPL], wa[EPL], wb[EPL];
+#pragma unroll
+        for (int pl = 0; pl < NP; ++pl) {
+            const float4 t = xs[pl * plane_stride + gi];
+            xv[4 * pl] = t.x; xv[4 * pl + 1] = t.y; xv[4 * pl + 2] = t.z; xv[4 * pl + 3] = t.w;
+        }
+        Elem<WT>::expand(v[2 * s], wa);
+        Elem<WT>::expand(v[2 * s + 1], wb);
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) { accA = fmaf(wa[e], xv[e], accA); accB = fmaf(wb[e], xv[e], accB); }
+    }
+}
+
+// First RING tiles of a phase; issued before the grid barrier that precedes the phase.
+template <typename WT, int EPI>
+__device__ __forceinline__ void phase_prefetch(Slot (&ring)[RING], const Phase<WT>& p, Cursor& lc, int lane, const Geom& g,
+                                               const EpiOut& eo) {
+    lc.u = p.u0; lc.kt = 0;
+#pragma unroll
+    for (int j = 0; j < RING; ++j) {
+        tile_load<WT, EPI>(ring[j], p, lc, lane, g, eo);
+        advance(lc, p.KT);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+}
+
+// Stages src[0..K) (times gain, if any) into the planar LDS layout, zero-fills the padding, and returns
+// the sum of squares of src (valid after the trailing __syncthreads).
+template <typename WT>
+__device__ __forceinline__ float stage_vector(float4* xs, int plane_stride, const float* __restrict__ src,
+                                              const float* __restrict__ gain, int K, int Kg, int KT, float* red) {
+    constexpr int NP = Elem<WT>::EPL / 4;
+    const int tid = threadIdx.x, n4 = K >> 2;
+    float ss = 0.f;
+    for (int base = 0; base < n4; base += 1024) {
+        float4 v[4], gn[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int k4 = min(base + j * 256 + tid, n4 - 1);
+            const uint4 rv = load16(src + 4 * (size_t)k4);
+            v[j] = make_float4(__uint_as_float(rv.x), __uint_as_float(rv.y), __uint_as_float(rv.z), __uint_as_float(rv.w));
+            if (gain) {
+                const uint4 rg = load16(gain + 4 * (size_t)k4);
+                gn[j] = make_float4(__uint_as_float(rg.x), __uint_as_float(rg.y), __uint_as_float(rg.z), __uint_as_float(rg.w));
+            } else gn[j] = make_float4(1.f, 1.f, 1.f, 1.f);
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int k4 = base + j * 256 + tid;
+            if (k4 < n4) {
+                ss += v[j].x * v[j].x + v[j].y * v[j].y + v[j].z * v[j].z + v[j].w * v[j].w;
+                const int grp = k4 / NP, pl = k4 - grp * NP;
+                xs[pl * plane_stride + grp] = make_float4(v[j].x * gn[j].x, v[j].y * gn[j].y, v[j].z * gn[j].z, v[j].w * gn[j].w);
+            }
+        }
+    }
+    // zeros: the tail of the last tile, and the block that tiles past the end are multiplied with
+    for (int grp = Kg + tid; grp < KT * 256; grp += 256)
+#pragma unroll
+        for (int pl = 0; pl < NP; ++pl) xs[pl * plane_stride + grp] = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (tid < 64)
+#pragma unroll
+        for (int pl = 0; pl < NP; ++pl) xs[pl * plane_stride + plane_stride - 64 + tid] = make_float4(0.f, 0.f, 0.f, 0.f);
+    ss = wave_sum(ss);
+    if ((tid & 63) == 0) red[tid >> 6] = ss;
+    __syncthreads();
+    return red[0] + red[1] + red[2] + red[3];
+}
+
+// Runs a phase whose first RING tiles are already in `ring`.  best_v / best_i: running argmax of the
+// stored values (EPI_STORE only), kept by lane 0.
+template <typename WT, int EPI>
+__device__ __forceinline__ void phase_run(Slot (&ring)[RING], const Phase<WT>& p, Cursor& lc, const float4* xs,
+                                          int plane_stride, float nscale, const EpiOut& eo, const Geom& g, int lane,
+                                          float& best_v, int& best_i) {
+    const int zero_group = plane_stride - 64;
+    const int T = (p.u1 - p.u0) * p.KT;
+    Cursor cc; cc.u = p.u0; cc.kt = 0;
+    float accA = 0.f, accB = 0.f;
+    for (int t = 0; t < T; t += RING) {
+#pragma unroll
+        for (int j = 0; j < RING; ++j) {
+            const bool past = cc.u >= p.u1;
+            tile_fma<WT>(ring[j].v, xs, plane_stride, zero_group, past, cc.kt, lane, accA, accB);
+            const float e0 = ring[j].e0, e1 = ring[j].e1;
+            __builtin_amdgcn_sched_barrier(0);
+            tile_load<WT, EPI>(ring[j], p, lc, lane, g, eo);
+            advance(lc, p.KT);
+            __builtin_amdgcn_sched_barrier(0);
+            if (!past && cc.kt == p.KT - 1) {
+                const float sa = wave_sum(accA) * nscale, sb = wave_sum(accB) * nscale;
+                if (lane == 0) {
+                    finish_unit<WT, EPI>(cc.u, sa, sb, e0, e1, eo, g);
+                    if (EPI == EPI_STORE) {
+                        amax_merge(best_v, best_i, sa, 2 * cc.u);
+                        if (2 * cc.u + 1 < p.rows) amax_merge(best_v, best_i, sb, 2 * cc.u + 1);
+                    }
+                }
+                accA = 0.f; accB = 0.f;
+            }
+            advance(cc, p.KT);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// the step
+// ---------------------------------------------------------------------------------------------
+
+#define FUSED_TRACE() do { if (a.trace && blockIdx.x == 0 && threadIdx.x == 0) a.trace[ntrace++] = wall_clock64(); } while (0)
+
+template <typename WT, int DH, int G, bool PAIR>
+__global__ __launch_bounds__(256) void k_decode_fused(FusedArgs a) {
+    int ntrace = 0;
+    constexpr int EPL = Elem<WT>::EPL;
+    extern __shared__ float4 lds4[];
+    __shared__ float red[4];
+    __shared__ int s_flag;
+    __shared__ float s_bv[4];
+    __shared__ int s_bi[4];
+
+    const Geom& g = a.g;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int nwg = gridDim.x;
+    const int plane_stride = a.xs_groups;
+    float4* xs = lds4;
+    AttnSmem<DH, G>& asm_ = *reinterpret_cast<AttnSmem<DH, G>*>(lds4);
+    float* mf = reinterpret_cast<float*>(lds4);          // merge phase scratch
+
+    unsigned target = __hip_atomic_load(&a.bar[1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const SeqState st = a.seq_state[a.seq];
+    const int pos = st.len;
+    const int token = a.forced >= 0 ? a.forced : st.next_token;
+
+    // residual stream of the new row: x = E[token]
+    {
+        const WT* erow = (const WT*)a.embed + (size_t)token * g.d;
+        for (int i = blockIdx.x * 256 + tid; i < g.d; i += nwg * 256) a.x[i] = Elem<WT>::load1(erow + i);
+    }
+
+    const int n_qkv = (g.Hq + 2 * g.Hkv) * g.dh, qd = g.Hq * g.dh;
+    Slot ring[RING];
+    Cursor lc;
+    float best_v = -INFINITY; int best_i = 0x7fffffff;
+    EpiOut eo;
+    eo.rope_cos = a.rope_cos; eo.rope_sin = a.rope_sin; eo.pos = pos; eo.seq = a.seq; eo.q_out = a.q;
+
+    Phase<WT> ph = make_phase<WT, EPI_QKV>(a.layers[0].wqkv, n_qkv, g.d, n_qkv / 2);
+    grid_arrive(a.bar);
+    phase_prefetch<WT, EPI_QKV>(ring, ph, lc, lane, g, eo);
+    target += nwg;
+    if (!grid_wait(a.bar, target, &s_flag, a.token_log)) return;
+    FUSED_TRACE();
+
+    for (int l = 0; l < a.n_layers; ++l) {
+        const FusedLayer L = a.layers[l];
+        // ---- QKV: x -> q, K/V cache row `pos`
+        {
+            const float ss = stage_vector<WT>(xs, plane_stride, a.x, L.attn_norm, g.d, ph.Kg, ph.KT, red);
+            eo.kv_layer = L.kv_layer; eo.rows = n_qkv;
+            phase_run<WT, EPI_QKV>(ring, ph, lc, xs, plane_stride, rsqrtf(ss / (float)g.d + g.eps), eo, g, lane, best_v, best_i);
+        }
+        ph = make_phase<WT, EPI_RESID>(L.wo, g.d, qd, (g.d + 1) / 2);
+        FUSED_TRACE();
+        grid_arrive(a.bar);
+        // O-projection tiles: held in registers across the attention.  Their residual operands are x, which
+        // no phase writes before the O projection itself.
+        eo.y = a.x; eo.res = a.x; eo.rows = g.d;
+        phase_prefetch<WT, EPI_RESID>(ring, ph, lc, lane, g, eo);
+        target += nwg;
+        if (!grid_wait(a.bar, target, &s_flag, a.token_log)) return;
+    FUSED_TRACE();
+
+        // ---- attention partials: workgroup = (kv head, split)
+        {
+            const int kvh = blockIdx.x % g.Hkv, split = blockIdx.x / g.Hkv, nsplit = a.nsplit;
+            if (split < nsplit) {
+                constexpr int PPW = 64 / (DH / EPL);
+                const int len = pos + 1, quantum = 4 * PPW;
+                int per = (len + nsplit - 1) / nsplit;
+                per = (per + quantum - 1) / quantum * quantum;
+                const int s0 = min(split * per, len), s1 = min(s0 + per, len);
+                const WT* Kp = (const WT*)L.kv_layer + (size_t)a.seq * g.kv_seq_stride + (size_t)kvh * g.kv_head_stride;
+                attn_partial<WT, DH, G, PAIR, (G > 4 ? 2 : 4)>(a.q, Kp, Kp + g.kv_v_offset, g.kv_lo_offset, kvh, s0, s1, g.scale, asm_);
+                for (int t = tid; t < G * DH; t += 256) {
+                    const int h = t / DH, dim = t - h * DH, hq = kvh * G + h;
+                    float M, Ls, A;
+                    attn_fold<DH, G>(asm_, h, dim, M, Ls, A);
+                    a.part_acc[((size_t)hq * nsplit + split) * DH + dim] = A;
+                    if (dim == 0) { a.part_ml[((size_t)hq * nsplit + split) * 2] = M; a.part_ml[((size_t)hq * nsplit + split) * 2 + 1] = Ls; }
+                }
+            }
+        }
+        FUSED_TRACE();
+        grid_arrive(a.bar);
+        target += nwg;
+        if (!grid_wait(a.bar, target, &s_flag, a.token_log)) return;
+    FUSED_TRACE();
+
+        // ---- merge of the splits: thread = (query head, 4 channels, one eighth of the splits)
+        {
+            constexpr int TPH = DH * 2;                     // threads per head
+            constexpr int HPW = 256 / TPH;                  // heads per workgroup
+            const int nsplit = a.nsplit;
+            const int hl = tid / TPH, within = tid - hl * TPH, d4 = within >> 3, grp = within & 7;
+            const int hq = blockIdx.x * HPW + hl;
+            const bool active = blockIdx.x * HPW < g.Hq;    // uniform per workgroup
+            if (active) {
+                for (int t = tid; t < HPW * nsplit; t += 256) {
+                    const int h2 = t / nsplit, sp = t - h2 * nsplit, hh = blockIdx.x * HPW + h2;
+                    if (hh < g.Hq) {
+                        mf[h2 * 2 * ATTN_MAX_SPLIT + sp] = a.part_ml[((size_t)hh * nsplit + sp) * 2];
+                        mf[h2 * 2 * ATTN_MAX_SPLIT + ATTN_MAX_SPLIT + sp] = a.part_ml[((size_t)hh * nsplit + sp) * 2 + 1];
+                    }
+                }
+                __syncthreads();
+                if (tid < HPW && blockIdx.x * HPW + tid < g.Hq) {
+                    float* fm = mf + tid * 2 * ATTN_MAX_SPLIT;
+                    float M = -INFINITY, Ls = 0.f;
+                    for (int sp = 0; sp < nsplit; ++sp) M = fmaxf(M, fm[sp]);
+                    for (int sp = 0; sp < nsplit; ++sp) {
+                        const float f = fm[sp] > -INFINITY ? expf(fm[sp] - M) : 0.f;
+                        Ls += fm[ATTN_MAX_SPLIT + sp] * f;
+                        fm[sp] = f;
+                    }
+                    const float inv = 1.f / Ls;
+                    for (int sp = 0; sp < nsplit; ++sp) fm[sp] *= inv;
+                }
+                __syncthreads();
+                float4 r = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (hq < g.Hq) {
+                    const float4* src = (const float4*)(a.part_acc + (size_t)hq * nsplit * DH) + d4;
+                    const float* fm = mf + hl * 2 * ATTN_MAX_SPLIT;
+#pragma unroll 4
+                    for (int sp = grp; sp < nsplit; sp += 8) {
+                        const float4 v = src[(size_t)sp * (DH / 4)];
+                        const float f = fm[sp];
+                        r.x = fmaf(v.x, f, r.x); r.y = fmaf(v.y, f, r.y); r.z = fmaf(v.z, f, r.z); r.w = fmaf(v.w, f, r.w);
+                    }
+                }
+#pragma unroll
+                for (int o = 1; o < 8; o <<= 1) {
+                    r.x += __shfl_xor(r.x, o, 64); r.y += __shfl_xor(r.y, o, 64);
+                    r.z += __shfl_xor(r.z, o, 64); r.w += __shfl_xor(r.w, o, 64);
+                }
+                if (hq < g.Hq && grp == 0) ((float4*)(a.o + (size_t)hq * DH))[d4] = r;
+            }
+        }
+        FUSED_TRACE();
+        grid_arrive(a.bar);
+        target += nwg;
+        if (!grid_wait(a.bar, target, &s_flag, a.token_log)) return;
+    FUSED_TRACE();
+
+        // ---- O projection + residual (tiles were requested before the attention)
+        {
+            stage_vector<WT>(xs, plane_stride, a.o, nullptr, qd, ph.Kg, ph.KT, red);
+            eo.y = a.x; eo.res = a.x; eo.rows = g.d;
+            phase_run<WT, EPI_RESID>(ring, ph, lc, xs, plane_stride, 1.f, eo, g, lane, best_v, best_i);
+        }
+        ph = make_phase<WT, EPI_SWIGLU>(L.wgate_up, 2 * g.F, g.d, g.F);
+        FUSED_TRACE();
+        grid_arrive(a.bar);
+        phase_prefetch<WT, EPI_SWIGLU>(ring, ph, lc, lane, g, eo);
+        target += nwg;
+        if (!grid_wait(a.bar, target, &s_flag, a.token_log)) return;
+    FUSED_TRACE();
+
+        // ---- gate/up + SwiGLU
+        {
+            const float ss = stage_vector<WT>(xs, plane_stride, a.x, L.ffn_norm, g.d, ph.Kg, ph.KT, red);
+            eo.y = a.a; eo.rows = 2 * g.F;
+            phase_run<WT, EPI_SWIGLU>(ring, ph, lc, xs, plane_stride, rsqrtf(ss / (float)g.d + g.eps), eo, g, lane, best_v, best_i);
+        }
+        ph = make_phase<WT, EPI_RESID>(L.wdown, g.d, g.F, (g.d + 1) / 2);
+        FUSED_TRACE();
+        grid_arrive(a.bar);
+        eo.y = a.x; eo.res = a.x; eo.rows = g.d;
+        phase_prefetch<WT, EPI_RESID>(ring, ph, lc, lane, g, eo);
+        target += nwg;
+        if (!grid_wait(a.bar, target, &s_flag, a.token_log)) return;
+    FUSED_TRACE();
+
+        // ---- down projection + residual
+        {
+            stage_vector<WT>(xs, plane_stride, a.a, nullptr, g.F, ph.Kg, ph.KT, red);
+            eo.y = a.x; eo.res = a.x; eo.rows = g.d;
+            phase_run<WT, EPI_RESID>(ring, ph, lc, xs, plane_stride, 1.f, eo, g, lane, best_v, best_i);
+        }
+        const bool more = l + 1 < a.n_layers;
+        if (more) ph = make_phase<WT, EPI_QKV>(a.layers[l + 1].wqkv, n_qkv, g.d, n_qkv / 2);
+        else ph = make_phase<WT, EPI_STORE>(a.lm_head, g.V, g.d, (g.V + 1) / 2);
+        FUSED_TRACE();
+        grid_arrive(a.bar);
+        if (more) phase_prefetch<WT, EPI_QKV>(ring, ph, lc, lane, g, eo);
+        else if (a.with_head) phase_prefetch<WT, EPI_STORE>(ring, ph, lc, lane, g, eo);
+        target += nwg;
+        if (!grid_wait(a.bar, target, &s_flag, a.token_log)) return;
+    FUSED_TRACE();
+    }
+
+    if (a.with_head) {
+        const float ss = stage_vector<WT>(xs, plane_stride, a.x, a.final_norm, g.d, ph.Kg, ph.KT, red);
+        eo.y = a.logits; eo.rows = g.V;
+        best_v = -INFINITY; best_i = 0x7fffffff;
+        phase_run<WT, EPI_STORE>(ring, ph, lc, xs, plane_stride, rsqrtf(ss / (float)g.d + g.eps), eo, g, lane, best_v, best_i);
+        if (lane == 0) { s_bv[wave] = best_v; s_bi[wave] = best_i; }
+        __syncthreads();
+        if (tid == 0) {
+            for (int w = 1; w < 4; ++w) amax_merge(best_v, best_i, s_bv[w], s_bi[w]);
+            a.amax_v[blockIdx.x] = best_v; a.amax_i[blockIdx.x] = best_i;
+        }
+        FUSED_TRACE();
+        grid_arrive(a.bar);
+        target += nwg;
+        if (!grid_wait(a.bar, target, &s_flag, a.token_log)) return;
+    FUSED_TRACE();
+    }
+
+    if (blockIdx.x != 0) return;
+    int next = st.next_token;
+    if (a.with_head) {
+        float bv = -INFINITY; int bi = 0x7fffffff;
+        for (int b = tid; b < nwg; b += 256) amax_merge(bv, bi, a.amax_v[b], a.amax_i[b]);
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) {
+            const float ov = __shfl_xor(bv, o, 64); const int oi = __shfl_xor(bi, o, 64);
+            amax_merge(bv, bi, ov, oi);
+        }
+        __syncthreads();
+        if (lane == 0) { s_bv[wave] = bv; s_bi[wave] = bi; }
+        __syncthreads();
+        if (tid == 0) for (int w = 1; w < 4; ++w) amax_merge(bv, bi, s_bv[w], s_bi[w]);
+        next = bi;
+    }
+    if (tid == 0) {
+        a.seq_state[a.seq].len = pos + 1;
+        a.seq_state[a.seq].next_token = next;
+        *a.token_log = token;
+        __hip_atomic_store(&a.bar[1], target, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// host side
+// ---------------------------------------------------------------------------------------------
+
+typedef void (*fused_kernel_t)(FusedArgs);
+
+static fused_kernel_t pick_kernel(int dtype, const Geom& g) {
+    const int G = g.Hq / g.Hkv;
+    const bool pair = g.kv_lo_offset != 0;
+    if (dtype == 0) {
+        if (g.dh == 64 && G == 1) return k_decode_fused<float, 64, 1, false>;
+        return nullptr;
+    }
+    if (g.dh != 128) return nullptr;
+    if (G == 4) return pair ? k_decode_fused<bf16_t, 128, 4, true> : k_decode_fused<bf16_t, 128, 4, false>;
+    if (G == 8) return pair ? k_decode_fused<bf16_t, 128, 8, true> : k_decode_fused<bf16_t, 128, 8, false>;
+    return nullptr;
+}
+
+// LDS bytes: the staged vector (largest K of any phase, padded to whole tiles plus a block of zeros).
+static size_t fused_lds_bytes(int dtype, const Geom& g, int* xs_groups) {
+    const int epl = dtype == 0 ? 4 : 8;
+    const int kmax = std::max(std::max(g.d, g.F), g.Hq * g.dh);
+    const int kg = kmax / epl, kt = (kg + 255) / 256;
+    *xs_groups = kt * 256 + 64;
+    size_t bytes = (size_t)(*xs_groups) * epl * sizeof(float);
+    const size_t attn = sizeof(float) * (size_t)(4 * 8 * 2 + 4 * 8 * g.dh);
+    return std::max(bytes, attn) + 64;
+}
+
+hipError_t fused_init(int dtype, const Geom& g, FusedPlan* plan) {
+    plan->supported = false;
+    fused_kernel_t k = pick_kernel(dtype, g);
+    if (!k) return hipSuccess;
+    int dev = 0, cus = 0, coop = 0;
+    hipError_t e;
+    if ((e = hipGetDevice(&dev))) return e;
+    if ((e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev))) return e;
+    if ((e = hipDeviceGetAttribute(&coop, hipDeviceAttributeCooperativeLaunch, dev))) return e;
+    if (!coop || cus < g.Hkv || cus > ARGMAX_MAX_BLOCKS) return hipSuccess;
+    plan->lds_bytes = fused_lds_bytes(dtype, g, &plan->xs_groups);
+    if (plan->lds_bytes > 160 * 1024) return hipSuccess;
+    if ((e = hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)plan->lds_bytes))) return e;
+    int per_cu = 0;
+    if ((e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void*)k, 256, plan->lds_bytes))) return e;
+    if (per_cu < 1) return hipSuccess;
+    plan->grid = cus;
+    plan->nsplit = std::min(cus / g.Hkv, (int)ATTN_MAX_SPLIT);
+    // the merge phase needs one workgroup per query head (two heads per workgroup at head_dim 64)
+    if (cus * (256 / (g.dh * 2)) < g.Hq) return hipSuccess;
+    plan->supported = true;
+    return hipSuccess;
+}
+
+hipError_t launch_decode_fused(int dtype, const FusedPlan& plan, const FusedLaunch& L, const DecodeBuffers& b, const Geom& g,
+                               hipStream_t s) {
+    fused_kernel_t k = pick_kernel(dtype, g);
+    if (!k || !plan.supported) return hipErrorInvalidValue;
+    FusedArgs a{};
+    a.layers = (const FusedLayer*)L.layers_dev; a.n_layers = L.n_layers;
+    a.embed = L.embed; a.final_norm = L.final_norm; a.lm_head = L.lm_head;
+    a.g = g; a.seq_state = b.seq_state; a.seq = L.seq; a.forced = L.forced; a.with_head = L.with_head ? 1 : 0;
+    a.token_log = b.token_log;
+    a.x = b.x; a.q = b.q; a.o = b.o; a.a = b.a; a.part_acc = b.part_acc; a.part_ml = b.part_ml; a.logits = L.logits;
+    a.rope_cos = b.rope_cos; a.rope_sin = b.rope_sin; a.amax_v = b.amax_v; a.amax_i = b.amax_i;
+    a.bar = L.bar; a.nsplit = plan.nsplit; a.xs_groups = plan.xs_groups; a.trace = (unsigned long long*)L.trace;
+    void* params[] = {&a};
+    return hipLaunchCooperativeKernel((const void*)k, dim3(plan.grid), dim3(256), params, (unsigned)plan.lds_bytes, s);
+}
+
+static_assert(sizeof(FusedLayer) == 7 * sizeof(void*), "FusedLayer is uploaded as 7 pointers per layer");
+
+}  // namespace asynclm

@@ -4,6 +4,7 @@
 // in the model's dtype.
 #include "common.h"
 #include "launch.h"
+#include "decode_device.h"
 
 namespace asynclm {
 
@@ -37,8 +38,6 @@ __global__ __launch_bounds__(256) void k_embed(const WT* __restrict__ E, const S
 // matrix-vector product, one row pair ("unit") per wave at a time
 // ---------------------------------------------------------------------------------------------
 
-enum { EPI_STORE = 0, EPI_RESID = 1, EPI_SWIGLU = 2, EPI_QKV = 3 };
-
 struct GemvArgs {
     const void* W;          // [rows, K] row-major
     int32_t rows, K;
@@ -55,25 +54,6 @@ struct GemvArgs {
     const StepDesc* step;
     int32_t layer;
 };
-
-// Cache write: fp32 as is; bf16 as the rounded value, plus the rounded remainder in the lo plane
-// when the cache has one.
-__device__ __forceinline__ void kv_store(float* p, float v, size_t) { *p = v; }
-__device__ __forceinline__ void kv_store(bf16_t* p, float v, size_t lo_offset) {
-    const bf16_t hi = f32_to_bf16(v);
-    *p = hi;
-    if (lo_offset) p[lo_offset] = f32_to_bf16(v - __uint_as_float((uint32_t)hi << 16));
-}
-
-template <int EPI>
-__device__ __forceinline__ void unit_rows(int u, const GemvArgs& a, const Geom& g, int& rA, int& rB) {
-    if (EPI == EPI_SWIGLU) { rA = u; rB = g.F + u; }                 // gate row, up row
-    else if (EPI == EPI_QKV) {                                        // the two halves of a rotary pair
-        const int half = g.dh >> 1;
-        const int h = u / half, i = u - h * half;
-        rA = h * g.dh + i; rB = rA + half;
-    } else { rA = 2 * u; rB = min(2 * u + 1, a.rows - 1); }
-}
 
 template <typename WT, int EPI, int NU>
 __global__ __launch_bounds__(256) void k_gemv(GemvArgs a, Geom g) {
@@ -95,7 +75,7 @@ __global__ __launch_bounds__(256) void k_gemv(GemvArgs a, Geom g) {
 #pragma unroll
         for (int j = 0; j < NU; ++j) {
             int u = min(u_base + wave * NU + j, a.units - 1), rA, rB;
-            unit_rows<EPI>(u, a, g, rA, rB);
+            unit_rows<EPI>(u, a.rows, g, rA, rB);
 #pragma unroll
             for (int s = 0; s < PRE; ++s) {
                 int gi = min(lane + s * 64, Kg - 1);
@@ -128,7 +108,7 @@ __global__ __launch_bounds__(256) void k_gemv(GemvArgs a, Geom g) {
 #pragma unroll
         for (int j = 0; j < NU; ++j) {
             uu[j] = u_base + (it * 4 + wave) * NU + j;
-            unit_rows<EPI>(min(uu[j], a.units - 1), a, g, rA[j], rB[j]);
+            unit_rows<EPI>(min(uu[j], a.units - 1), a.rows, g, rA[j], rB[j]);
             accA[j] = 0.f; accB[j] = 0.f;
         }
         int g0 = lane;
@@ -185,35 +165,11 @@ __global__ __launch_bounds__(256) void k_gemv(GemvArgs a, Geom g) {
         for (int j = 0; j < NU; ++j) {
             const float sa = wave_sum(accA[j]) * nscale, sb = wave_sum(accB[j]) * nscale;
             if (lane != 0 || uu[j] >= a.units) continue;
-            if (EPI == EPI_STORE) {
-                a.y[rA[j]] = sa;
-                if (2 * uu[j] + 1 < a.rows) a.y[rB[j]] = sb;
-            } else if (EPI == EPI_RESID) {
-                a.y[rA[j]] = a.res[rA[j]] + sa;
-                if (2 * uu[j] + 1 < a.rows) a.y[rB[j]] = a.res[rB[j]] + sb;
-            } else if (EPI == EPI_SWIGLU) {
-                a.y[uu[j]] = sa / (1.f + expf(-sa)) * sb;
-            } else {
-                const int half = g.dh >> 1;
-                const int h = uu[j] / half, i = uu[j] - h * half;
-                const int pos = a.step->pos;
-                if (h < g.Hq + g.Hkv) {
-                    const float c = a.rope_cos[(size_t)pos * half + i], s = a.rope_sin[(size_t)pos * half + i];
-                    const float ra = sa * c - sb * s, rb = sb * c + sa * s;
-                    if (h < g.Hq) { a.q_out[h * g.dh + i] = ra; a.q_out[h * g.dh + i + half] = rb; }
-                    else {
-                        WT* kp = (WT*)a.kv_layer + (size_t)a.step->seq * g.kv_seq_stride + (size_t)(h - g.Hq) * g.kv_head_stride + (size_t)pos * g.dh;
-                        kv_store(kp + i, ra, g.kv_lo_offset); kv_store(kp + i + half, rb, g.kv_lo_offset);
-                    }
-                } else {
-                    WT* vp = (WT*)a.kv_layer + g.kv_v_offset + (size_t)a.step->seq * g.kv_seq_stride + (size_t)(h - g.Hq - g.Hkv) * g.kv_head_stride + (size_t)pos * g.dh;
-                    kv_store(vp + i, sa, g.kv_lo_offset); kv_store(vp + i + half, sb, g.kv_lo_offset);
-                    if (g.kv_vt_offset) {   // transposed copy [dh][max_pos] read by the append-chunk attention
-                        WT* vt = (WT*)a.kv_layer + g.kv_vt_offset + (size_t)a.step->seq * g.kv_seq_stride + (size_t)(h - g.Hq - g.Hkv) * g.kv_head_stride + pos;
-                        kv_store(vt + (size_t)i * g.max_pos, sa, g.kv_lo_offset); kv_store(vt + (size_t)(i + half) * g.max_pos, sb, g.kv_lo_offset);
-                    }
-                }
-            }
+            EpiOut eo;
+            eo.y = a.y; eo.res = a.res; eo.q_out = a.q_out; eo.kv_layer = a.kv_layer;
+            eo.rope_cos = a.rope_cos; eo.rope_sin = a.rope_sin; eo.rows = a.rows;
+            if (EPI == EPI_QKV) { eo.pos = a.step->pos; eo.seq = a.step->seq; }
+            gemv_finish<WT, EPI>(uu[j], sa, sb, eo, g);
         }
     }
 }
@@ -236,13 +192,12 @@ struct AttnArgs {
 template <typename KVT, int DH, int G, bool PAIR>
 __global__ __launch_bounds__(256) void k_attn_decode(AttnArgs a, Geom g) {
     constexpr int EPL = Elem<KVT>::EPL;
-    constexpr int LPR = DH / EPL;       // lanes that cover one cached row
-    constexpr int PPW = 64 / LPR;       // positions per wave-wide load
-    __shared__ float s_m[4][G], s_l[4][G], s_acc[4][G][DH];
+    constexpr int PPW = 64 / (DH / EPL);        // positions per wave-wide load
+    __shared__ AttnSmem<DH, G> sm;
     __shared__ int s_last;
+    float (&s_acc)[4][G][DH] = sm.acc;
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int sub = lane / LPR, c = lane % LPR;
+    const int tid = threadIdx.x;
     const int kvh = blockIdx.x, split = blockIdx.y, nsplit = a.nsplit;
     const int len = a.step->pos + 1;
     // split boundaries: equal shares rounded up to whole workgroup iterations
@@ -253,101 +208,12 @@ __global__ __launch_bounds__(256) void k_attn_decode(AttnArgs a, Geom g) {
 
     const KVT* Kp = (const KVT*)a.kv_layer + (size_t)a.step->seq * g.kv_seq_stride + (size_t)kvh * g.kv_head_stride;
     const KVT* Vp = Kp + g.kv_v_offset;
+    attn_partial<KVT, DH, G, PAIR>(a.q, Kp, Vp, g.kv_lo_offset, kvh, s0, s1, g.scale, sm);
 
-    float qr[G][EPL];
-#pragma unroll
-    for (int h = 0; h < G; ++h)
-#pragma unroll
-        for (int e = 0; e < EPL; ++e) qr[h][e] = a.q[(kvh * G + h) * DH + c * EPL + e] * g.scale;
-
-    float m[G], l[G], acc[G][EPL];
-#pragma unroll
-    for (int h = 0; h < G; ++h) {
-        m[h] = -INFINITY; l[h] = 0.f;
-#pragma unroll
-        for (int e = 0; e < EPL; ++e) acc[h][e] = 0.f;
-    }
-
-    // UN position groups per trip: all their K/V loads are issued before the first is used
-    constexpr int UN = 4;
-    for (int p0 = s0 + wave * PPW; p0 < s1; p0 += 4 * PPW * UN) {
-        uint4 kr[UN], vr[UN], krl[PAIR ? UN : 1], vrl[PAIR ? UN : 1];
-#pragma unroll
-        for (int u = 0; u < UN; ++u) {
-            const int p = p0 + u * 4 * PPW + sub;
-            const int pc = p < s1 ? p : s1 - 1;
-            kr[u] = load16(Kp + (size_t)pc * DH + c * EPL);
-            vr[u] = load16(Vp + (size_t)pc * DH + c * EPL);
-            if (PAIR) {
-                krl[u] = load16(Kp + g.kv_lo_offset + (size_t)pc * DH + c * EPL);
-                vrl[u] = load16(Vp + g.kv_lo_offset + (size_t)pc * DH + c * EPL);
-            }
-        }
-#pragma unroll
-        for (int u = 0; u < UN; ++u) {
-            const bool valid = p0 + u * 4 * PPW + sub < s1;
-            float kf[EPL], vf[EPL];
-            Elem<KVT>::expand(kr[u], kf);
-            Elem<KVT>::expand(vr[u], vf);
-            if (PAIR) {
-                float kl[EPL], vl[EPL];
-                Elem<KVT>::expand(krl[u], kl);
-                Elem<KVT>::expand(vrl[u], vl);
-#pragma unroll
-                for (int e = 0; e < EPL; ++e) { kf[e] += kl[e]; vf[e] += vl[e]; }
-            }
-#pragma unroll
-            for (int h = 0; h < G; ++h) {
-                float s = 0.f;
-#pragma unroll
-                for (int e = 0; e < EPL; ++e) s = fmaf(qr[h][e], kf[e], s);
-#pragma unroll
-                for (int o = 1; o < LPR; o <<= 1) s += __shfl_xor(s, o, 64);
-                if (!valid) s = -INFINITY;
-                float mx = s;
-#pragma unroll
-                for (int o = LPR; o < 64; o <<= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
-                // group u = 0 always holds the valid position p0, so m is finite from then on
-                const float mn = fmaxf(m[h], mx);
-                const float corr = expf(m[h] - mn);     // exp(-inf) = 0 on the very first group
-                const float pr = expf(s - mn);
-                l[h] = l[h] * corr + pr;
-#pragma unroll
-                for (int e = 0; e < EPL; ++e) acc[h][e] = fmaf(pr, vf[e], acc[h][e] * corr);
-                m[h] = mn;
-            }
-        }
-    }
-
-    // fold the PPW position groups of the wave (they share m)
-#pragma unroll
-    for (int h = 0; h < G; ++h) {
-#pragma unroll
-        for (int o = LPR; o < 64; o <<= 1) {
-            l[h] += __shfl_xor(l[h], o, 64);
-#pragma unroll
-            for (int e = 0; e < EPL; ++e) acc[h][e] += __shfl_xor(acc[h][e], o, 64);
-        }
-        if (sub == 0) {
-            if (c == 0) { s_m[wave][h] = m[h]; s_l[wave][h] = l[h]; }
-#pragma unroll
-            for (int e = 0; e < EPL; ++e) s_acc[wave][h][c * EPL + e] = acc[h][e];
-        }
-    }
-    __syncthreads();
-
-    // fold the four waves; a wave without positions has m = -inf, l = 0
     for (int t = tid; t < G * DH; t += 256) {
         const int h = t / DH, dim = t - h * DH;
-        float M = fmaxf(fmaxf(s_m[0][h], s_m[1][h]), fmaxf(s_m[2][h], s_m[3][h]));
-        float L = 0.f, A = 0.f;
-        if (M > -INFINITY) {
-#pragma unroll
-            for (int w = 0; w < 4; ++w) {
-                const float f = expf(s_m[w][h] - M);
-                L += s_l[w][h] * f; A += s_acc[w][h][dim] * f;
-            }
-        }
+        float M, L, A;
+        attn_fold<DH, G>(sm, h, dim, M, L, A);
         const int hq = kvh * G + h;
         if (nsplit == 1) {
             a.o[hq * DH + dim] = A / L;
@@ -409,10 +275,6 @@ __global__ __launch_bounds__(256) void k_attn_decode(AttnArgs a, Geom g) {
 // ---------------------------------------------------------------------------------------------
 // greedy argmax over the vocabulary: per-block (max, lowest index), last block merges
 // ---------------------------------------------------------------------------------------------
-
-__device__ __forceinline__ void amax_merge(float& bv, int& bi, float v, int i) {
-    if (v > bv || (v == bv && i < bi)) { bv = v; bi = i; }
-}
 
 __global__ __launch_bounds__(256) void k_argmax(const float* __restrict__ logits_base, int V, const StepDesc* step,
                                                 SeqState* st, float* part_v, int32_t* part_i, int32_t* counter) {

@@ -46,6 +46,28 @@ struct ChunkBuffers {
     float* attn_ml;           // [tasks][split][2][32]
 };
 
+// Fused (persistent, single-kernel) decoding step.
+struct FusedPlan {
+    bool supported;
+    int grid;           // workgroups = compute units
+    int nsplit;         // attention splits per kv head
+    int xs_groups;      // LDS capacity of the staged vector
+    size_t lds_bytes;
+};
+struct FusedLaunch {
+    const void* layers_dev;     // device array, 7 pointers per layer: attn_norm, wqkv, wo, ffn_norm, wgate_up, wdown, kv_layer
+    int n_layers;
+    const void* embed; const float* final_norm; const void* lm_head;
+    int seq, forced; bool with_head;
+    float* logits;              // of this sequence
+    unsigned* bar;              // 3 counters, zero at create
+    void* trace;                // optional device buffer of 64-bit time stamps (FUSED_TRACE_MAX entries)
+};
+constexpr int FUSED_TRACE_MAX = 4096;
+hipError_t fused_init(int dtype, const Geom& g, FusedPlan* plan);
+hipError_t launch_decode_fused(int dtype, const FusedPlan& plan, const FusedLaunch& L, const DecodeBuffers& b, const Geom& g,
+                               hipStream_t s);
+
 hipError_t decode_init(int dtype, int max_k);
 hipError_t launch_begin_chunk(const DecodeBuffers& b, int seq, int rows, hipStream_t s);
 hipError_t launch_chunk_embed(const void* E, const ChunkBuffers& c, int rows, const Geom& g, hipStream_t s);

@@ -43,11 +43,14 @@ def test_weights_identical_on_device_and_host(tiny):
             assert np.array_equal(w_dev[k][l].cpu().numpy(), w_cpu[k][l])
 
 
-@pytest.mark.parametrize("graph", [0, 1])
-def test_teacher_forced_stream_matches_oracle(tiny, graph):
+@pytest.mark.parametrize("mode", ["fused", "graph", "plain"])
+def test_teacher_forced_stream_matches_oracle(tiny, mode):
+    """The same stream through the single persistent kernel, the captured graph of per-operation kernels,
+    and plain launches of those kernels."""
     pkg, wl, spec, w_cpu, w_dev, stream, ref = tiny
     lm = _new(tiny)
-    lm.set_option("graph", graph)
+    lm.set_option("fused", 1 if mode == "fused" else 0)
+    lm.set_option("graph", 1 if mode == "graph" else 0)
     lm.prefill(0, spec["prompt"])
     ev = {n: t for n, t in spec["events"]}
     worst = 0.0
@@ -112,6 +115,7 @@ def test_attention_split_count_does_not_change_logits(tiny, nsplit):
     pkg, wl, spec, w_cpu, w_dev, stream, ref = tiny
     s = ref["stream"]
     lm = _new(tiny)
+    lm.set_option("fused", 0)                 # the split count is a knob of the per-operation attention kernel
     lm.set_option("attn_split", nsplit)
     lm.prefill(0, s[:97])
     want = orc.full_logits(orc.Shape.of(wl.model), w_cpu, s[:97])[-1]
