@@ -149,6 +149,13 @@ int asynclm_set_option(asynclm_ctx *ctx, const char *name, int32_t value);
 int asynclm_profile_step(asynclm_ctx *ctx, int32_t seq, int32_t forced_token, const char *const **names_out,
                          float *ms_out, int32_t *launches_out, int32_t cap);
 
+/* Raw time stamps of the last asynclm_profile_step that ran as the fused kernel: out_host[i * n_workgroups + w]
+ * is the 100 MHz device clock of workgroup w at phase boundary i (per layer: end of QKV, barrier passed, end of
+ * attention, barrier, end of merge, barrier, end of O, barrier, end of gate/up, barrier, end of down, barrier;
+ * stamp 0 is the first barrier, the last two are the output head and its barrier).  Call with out_host = NULL
+ * to get the sizes; cap is the capacity of out_host in elements. */
+int asynclm_profile_trace(asynclm_ctx *ctx, uint64_t *out_host, int32_t cap, int32_t *n_stamps, int32_t *n_workgroups);
+
 /* Text for an error code; never NULL. */
 const char *asynclm_strerror(int code);
 

@@ -13,7 +13,7 @@ KV_AUTO, KV_BF16 = 0, 1
 API_SYMBOLS = [
     "asynclm_create", "asynclm_destroy", "asynclm_prefill", "asynclm_decode_step",
     "asynclm_inject_interrupt", "asynclm_logits", "asynclm_logits_device", "asynclm_seq_len",
-    "asynclm_reset", "asynclm_synchronize", "asynclm_set_option", "asynclm_profile_step",
+    "asynclm_reset", "asynclm_synchronize", "asynclm_set_option", "asynclm_profile_step", "asynclm_profile_trace",
     "asynclm_strerror", "asynclm_version",
 ]
 
@@ -78,6 +78,7 @@ def load_library():
     lib.asynclm_synchronize.argtypes = [p]
     lib.asynclm_set_option.argtypes = [p, C.c_char_p, i32]
     lib.asynclm_profile_step.argtypes = [p, i32, i32, C.POINTER(C.POINTER(C.c_char_p)), C.POINTER(C.c_float), C.POINTER(i32), i32]
+    lib.asynclm_profile_trace.argtypes = [p, C.POINTER(C.c_uint64), i32, C.POINTER(i32), C.POINTER(i32)]
     lib.asynclm_strerror.argtypes = [C.c_int]
     lib.asynclm_strerror.restype = C.c_char_p
     lib.asynclm_version.restype = C.c_char_p
@@ -173,6 +174,15 @@ class AsyncLM:
 
     def set_option(self, name: str, value: int) -> None:
         self._check(self._lib.asynclm_set_option(self._h, name.encode(), int(value)), "asynclm_set_option")
+
+    def profile_trace(self) -> "np.ndarray":
+        ns, nw = C.c_int32(), C.c_int32()
+        self._check(self._lib.asynclm_profile_trace(self._h, None, 0, C.byref(ns), C.byref(nw)), "asynclm_profile_trace")
+        out = np.zeros((ns.value, nw.value), dtype=np.uint64)
+        if out.size:
+            self._check(self._lib.asynclm_profile_trace(self._h, out.ctypes.data_as(C.POINTER(C.c_uint64)), out.size,
+                                                        C.byref(ns), C.byref(nw)), "asynclm_profile_trace")
+        return out
 
     def profile_step(self, seq: int, forced_token: int) -> Dict[str, Dict[str, float]]:
         cap = 64

@@ -37,6 +37,8 @@ struct asynclm_ctx {
     unsigned* bar = nullptr;            // its grid-barrier counters
     unsigned long long* trace = nullptr; // its optional phase time stamps
     bool want_trace = false;
+    std::vector<unsigned long long> last_trace;  // raw stamps [stamp][workgroup] of the last profiled fused step
+    int last_trace_stamps = 0;
     int32_t* token_host = nullptr;      // pinned, 1 int
 
     std::vector<int32_t> len;           // host mirror of the sequence lengths
@@ -411,13 +413,14 @@ int asynclm_create(asynclm_ctx** out, const asynclm_config* cfg, const asynclm_w
         char* tabd = nullptr;
         if ((e = dev_alloc(c, &tabd, tab.size() * sizeof(void*))) != hipSuccess) return bail(ASYNCLM_E_NOMEM);
         c->layers_dev = tabd;
-        if ((e = dev_alloc(c, &c->bar, 4)) != hipSuccess) return bail(ASYNCLM_E_NOMEM);
-        if ((e = dev_alloc(c, &c->trace, (size_t)FUSED_TRACE_MAX)) != hipSuccess) return bail(ASYNCLM_E_NOMEM);
+        if ((e = dev_alloc(c, &c->bar, (size_t)FUSED_BAR_WORDS)) != hipSuccess) return bail(ASYNCLM_E_NOMEM);
+        
         if (hipMemcpy(tabd, tab.data(), tab.size() * sizeof(void*), hipMemcpyHostToDevice) != hipSuccess ||
-            hipMemset(c->bar, 0, 4 * sizeof(unsigned)) != hipSuccess)
+            hipMemset(c->bar, 0, FUSED_BAR_WORDS * sizeof(unsigned)) != hipSuccess)
             return bail(ASYNCLM_E_DEVICE);
         if ((e = fused_init(cfg->dtype, g, &c->fused)) != hipSuccess) { report_hip("fused_init", e); return bail(ASYNCLM_E_DEVICE); }
         c->opt_fused = c->fused.supported ? 1 : 0;
+        if (c->fused.supported && (e = dev_alloc(c, &c->trace, (size_t)FUSED_TRACE_MAX * c->fused.grid)) != hipSuccess) return bail(ASYNCLM_E_NOMEM);
     }
     const int max_k = g.F > g.d ? (g.F > g.Hq * g.dh ? g.F : g.Hq * g.dh) : (g.d > g.Hq * g.dh ? g.d : g.Hq * g.dh);
     if ((e = decode_init(cfg->dtype, max_k)) != hipSuccess) { report_hip("decode_init", e); return bail(ASYNCLM_E_DEVICE); }
@@ -547,9 +550,14 @@ int asynclm_profile_step(asynclm_ctx* c, int32_t seq, int32_t forced_token, cons
         c->want_trace = false;
         if (e) return fail_device(c, e);
         HIPCK(c, hipEventRecord(e1, c->stream));
-        std::vector<unsigned long long> t(n_stamps);
-        HIPCK(c, hipMemcpyAsync(t.data(), c->trace, sizeof(unsigned long long) * n_stamps, hipMemcpyDeviceToHost, c->stream));
+        // stamps [i][workgroup]; a phase lasts from the latest start to the latest finish over the workgroups,
+        // a barrier from the latest arrival to the latest release
+        const size_t nw = (size_t)c->fused.grid;
+        std::vector<unsigned long long> raw((size_t)n_stamps * nw), t(n_stamps);
+        HIPCK(c, hipMemcpyAsync(raw.data(), c->trace, sizeof(unsigned long long) * raw.size(), hipMemcpyDeviceToHost, c->stream));
         HIPCK(c, hipStreamSynchronize(c->stream));
+        for (int i = 0; i < n_stamps; ++i) t[i] = *std::max_element(raw.begin() + i * nw, raw.begin() + (i + 1) * nw);
+        c->last_trace = raw; c->last_trace_stamps = n_stamps;
         float ms = 0.f;
         HIPCK(c, hipEventElapsedTime(&ms, e0, e1));
         ms_out[KC_F_TOTAL] = ms; launches_out[KC_F_TOTAL] = 1;
@@ -575,6 +583,17 @@ int asynclm_profile_step(asynclm_ctx* c, int32_t seq, int32_t forced_token, cons
     }
     if (names_out) *names_out = kClassNames;
     return KC_COUNT;
+}
+
+int asynclm_profile_trace(asynclm_ctx* c, uint64_t* out_host, int32_t cap, int32_t* n_stamps, int32_t* n_workgroups) {
+    if (!c || !n_stamps || !n_workgroups) return ASYNCLM_E_INVAL;
+    *n_stamps = c->last_trace_stamps;
+    *n_workgroups = c->last_trace_stamps ? (int32_t)(c->last_trace.size() / c->last_trace_stamps) : 0;
+    if (out_host) {
+        if ((size_t)cap < c->last_trace.size()) return ASYNCLM_E_INVAL;
+        for (size_t i = 0; i < c->last_trace.size(); ++i) out_host[i] = c->last_trace[i];
+    }
+    return ASYNCLM_OK;
 }
 
 const char* asynclm_strerror(int code) {

@@ -40,41 +40,55 @@ struct FusedArgs {
     float *x, *q, *o, *a, *part_acc, *part_ml, *logits;
     const float *rope_cos, *rope_sin;
     float* amax_v; int32_t* amax_i;
-    unsigned* bar;          // [0] arrivals (only grows), [1] value of [0] when this launch started, [2] error flag
+    unsigned* bar;          // grid barrier state (see grid_arrive)
     int32_t nsplit;         // attention splits per kv head (<= gridDim.x / Hkv)
     int32_t xs_groups;      // LDS capacity of the staged vector, in groups of EPL elements
-    unsigned long long* trace;   // optional: workgroup 0 stores the 100 MHz wall clock at every phase boundary
+    int32_t done_cap;       // units one wave can park in LDS before its epilogues run
+    unsigned long long* trace;   // optional [stamp][workgroup]: the 100 MHz wall clock at every phase boundary
 };
 
 // ---------------------------------------------------------------------------------------------
 // grid barrier
 // ---------------------------------------------------------------------------------------------
 
-// Arrive.  All global stores of the workgroup made before the call are visible to every workgroup
-// that later passes grid_wait on the same target.
-__device__ __forceinline__ void grid_arrive(unsigned* bar) {
+// One flag per workgroup instead of one shared counter: arrivals are plain stores to different
+// addresses (an atomic counter would serialise the 256 arrivals at the memory side), and a waiting
+// workgroup reads all flags with one load per lane.  bar[0] = epoch of the last barrier of the previous
+// launch, bar[1] = error flag, bar[BAR_FLAGS + w] = last epoch workgroup w has reached.
+constexpr int BAR_FLAGS = 8;
+
+// Arrive at barrier `epoch`.  All global stores of the workgroup made before the call are visible to
+// every workgroup that later passes grid_wait(epoch).
+__device__ __forceinline__ void grid_arrive(unsigned* bar, unsigned epoch) {
     __syncthreads();
     if (threadIdx.x == 0) {
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
-        atomicAdd(&bar[0], 1u);
+        __hip_atomic_store(&bar[BAR_FLAGS + blockIdx.x], epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
 }
 
-// Wait until `target` arrivals have been counted.  Returns false (for the whole workgroup) when the
+// Wait until every workgroup has arrived at `epoch`.  Returns false (for the whole workgroup) when the
 // spin limit is hit or another workgroup has already given up; the caller then leaves the kernel.
-__device__ __forceinline__ bool grid_wait(unsigned* bar, unsigned target, int* s_flag, int32_t* token_log) {
-    if (threadIdx.x == 0) {
+__device__ __forceinline__ bool grid_wait(unsigned* bar, unsigned epoch, int* s_flag, int32_t* token_log) {
+    if (threadIdx.x < 64) {
+        const int lane = threadIdx.x, nwg = gridDim.x;
         unsigned spins = 0;
         int ok = 1;
-        while ((int)(__hip_atomic_load(&bar[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - target) < 0) {
+        for (;;) {
+            bool mine = true;
+            for (int w = lane; w < nwg; w += 64)
+                mine = mine && (int)(__hip_atomic_load(&bar[BAR_FLAGS + w], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - epoch) >= 0;
+            if (__all(mine)) break;
             __builtin_amdgcn_s_sleep(1);
-            if (++spins > BARRIER_SPIN_LIMIT || __hip_atomic_load(&bar[2], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) {
+            if (++spins > BARRIER_SPIN_LIMIT || __hip_atomic_load(&bar[1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) {
                 ok = 0;
                 break;
             }
         }
-        if (!ok) { atomicExch(&bar[2], 1u); token_log[1] = 1; }    // token_log[1]: read back by the host with the token
-        *s_flag = ok;
+        if (lane == 0) {
+            if (!ok) { atomicExch(&bar[1], 1u); token_log[1] = 1; }    // token_log[1]: read back by the host with the token
+            *s_flag = ok;
+        }
     }
     __syncthreads();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
@@ -257,12 +271,16 @@ __device__ __forceinline__ float stage_vector(float4* xs, int plane_stride, cons
     return red[0] + red[1] + red[2] + red[3];
 }
 
-// Runs a phase whose first RING tiles are already in `ring`.  best_v / best_i: running argmax of the
-// stored values (EPI_STORE only), kept by lane 0.
+// Runs a phase whose first RING tiles are already in `ring`.  The loop only parks each finished unit
+// (two dot products and the slot's epilogue operands) in the wave's LDS area `done`; the epilogues, with
+// their global stores, run after the loop, one unit per lane.  Keeping every global memory instruction
+// of the loop unconditional lets the compiler count the outstanding loads exactly, so a tile is waited
+// for while the three younger ones stay in flight.
+// best_v / best_i: argmax of the stored values (EPI_STORE only), valid in every lane afterwards.
 template <typename WT, int EPI>
 __device__ __forceinline__ void phase_run(Slot (&ring)[RING], const Phase<WT>& p, Cursor& lc, const float4* xs,
                                           int plane_stride, float nscale, const EpiOut& eo, const Geom& g, int lane,
-                                          float& best_v, int& best_i) {
+                                          float4* done, float& best_v, int& best_i) {
     const int zero_group = plane_stride - 64;
     const int T = (p.u1 - p.u0) * p.KT;
     Cursor cc; cc.u = p.u0; cc.kt = 0;
@@ -279,16 +297,26 @@ __device__ __forceinline__ void phase_run(Slot (&ring)[RING], const Phase<WT>& p
             __builtin_amdgcn_sched_barrier(0);
             if (!past && cc.kt == p.KT - 1) {
                 const float sa = wave_sum(accA) * nscale, sb = wave_sum(accB) * nscale;
-                if (lane == 0) {
-                    finish_unit<WT, EPI>(cc.u, sa, sb, e0, e1, eo, g);
-                    if (EPI == EPI_STORE) {
-                        amax_merge(best_v, best_i, sa, 2 * cc.u);
-                        if (2 * cc.u + 1 < p.rows) amax_merge(best_v, best_i, sb, 2 * cc.u + 1);
-                    }
-                }
+                if (lane == 0) done[cc.u - p.u0] = make_float4(sa, sb, e0, e1);
                 accA = 0.f; accB = 0.f;
             }
             advance(cc, p.KT);
+        }
+    }
+    for (int ul = lane; ul < p.u1 - p.u0; ul += 64) {
+        const float4 r = done[ul];          // written by lane 0 of this same wave
+        const int u = p.u0 + ul;
+        finish_unit<WT, EPI>(u, r.x, r.y, r.z, r.w, eo, g);
+        if (EPI == EPI_STORE) {
+            amax_merge(best_v, best_i, r.x, 2 * u);
+            if (2 * u + 1 < p.rows) amax_merge(best_v, best_i, r.y, 2 * u + 1);
+        }
+    }
+    if (EPI == EPI_STORE) {
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) {
+            const float ov = __shfl_xor(best_v, o, 64); const int oi = __shfl_xor(best_i, o, 64);
+            amax_merge(best_v, best_i, ov, oi);
         }
     }
 }
@@ -297,7 +325,7 @@ __device__ __forceinline__ void phase_run(Slot (&ring)[RING], const Phase<WT>& p
 // the step
 // ---------------------------------------------------------------------------------------------
 
-#define FUSED_TRACE() do { if (a.trace && blockIdx.x == 0 && threadIdx.x == 0) a.trace[ntrace++] = wall_clock64(); } while (0)
+#define FUSED_TRACE() do { if (a.trace && threadIdx.x == 0) a.trace[(size_t)(ntrace++) * gridDim.x + blockIdx.x] = wall_clock64(); } while (0)
 
 template <typename WT, int DH, int G, bool PAIR>
 __global__ __launch_bounds__(256) void k_decode_fused(FusedArgs a) {
@@ -316,8 +344,9 @@ __global__ __launch_bounds__(256) void k_decode_fused(FusedArgs a) {
     float4* xs = lds4;
     AttnSmem<DH, G>& asm_ = *reinterpret_cast<AttnSmem<DH, G>*>(lds4);
     float* mf = reinterpret_cast<float*>(lds4);          // merge phase scratch
+    float4* done = lds4 + (size_t)plane_stride * (EPL / 4) + (size_t)wave * a.done_cap;   // finished units of this wave
 
-    unsigned target = __hip_atomic_load(&a.bar[1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    unsigned target = __hip_atomic_load(&a.bar[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // epoch counter
     const SeqState st = a.seq_state[a.seq];
     const int pos = st.len;
     const int token = a.forced >= 0 ? a.forced : st.next_token;
@@ -336,9 +365,9 @@ __global__ __launch_bounds__(256) void k_decode_fused(FusedArgs a) {
     eo.rope_cos = a.rope_cos; eo.rope_sin = a.rope_sin; eo.pos = pos; eo.seq = a.seq; eo.q_out = a.q;
 
     Phase<WT> ph = make_phase<WT, EPI_QKV>(a.layers[0].wqkv, n_qkv, g.d, n_qkv / 2);
-    grid_arrive(a.bar);
+    grid_arrive(a.bar, target + 1);
     phase_prefetch<WT, EPI_QKV>(ring, ph, lc, lane, g, eo);
-    target += nwg;
+    target += 1;
     if (!grid_wait(a.bar, target, &s_flag, a.token_log)) return;
     FUSED_TRACE();
 
@@ -348,16 +377,16 @@ __global__ __launch_bounds__(256) void k_decode_fused(FusedArgs a) {
         {
             const float ss = stage_vector<WT>(xs, plane_stride, a.x, L.attn_norm, g.d, ph.Kg, ph.KT, red);
             eo.kv_layer = L.kv_layer; eo.rows = n_qkv;
-            phase_run<WT, EPI_QKV>(ring, ph, lc, xs, plane_stride, rsqrtf(ss / (float)g.d + g.eps), eo, g, lane, best_v, best_i);
+            phase_run<WT, EPI_QKV>(ring, ph, lc, xs, plane_stride, rsqrtf(ss / (float)g.d + g.eps), eo, g, lane, done, best_v, best_i);
         }
         ph = make_phase<WT, EPI_RESID>(L.wo, g.d, qd, (g.d + 1) / 2);
         FUSED_TRACE();
-        grid_arrive(a.bar);
+        grid_arrive(a.bar, target + 1);
         // O-projection tiles: held in registers across the attention.  Their residual operands are x, which
         // no phase writes before the O projection itself.
         eo.y = a.x; eo.res = a.x; eo.rows = g.d;
         phase_prefetch<WT, EPI_RESID>(ring, ph, lc, lane, g, eo);
-        target += nwg;
+        target += 1;
         if (!grid_wait(a.bar, target, &s_flag, a.token_log)) return;
     FUSED_TRACE();
 
@@ -382,8 +411,8 @@ __global__ __launch_bounds__(256) void k_decode_fused(FusedArgs a) {
             }
         }
         FUSED_TRACE();
-        grid_arrive(a.bar);
-        target += nwg;
+        grid_arrive(a.bar, target + 1);
+        target += 1;
         if (!grid_wait(a.bar, target, &s_flag, a.token_log)) return;
     FUSED_TRACE();
 
@@ -437,8 +466,8 @@ __global__ __launch_bounds__(256) void k_decode_fused(FusedArgs a) {
             }
         }
         FUSED_TRACE();
-        grid_arrive(a.bar);
-        target += nwg;
+        grid_arrive(a.bar, target + 1);
+        target += 1;
         if (!grid_wait(a.bar, target, &s_flag, a.token_log)) return;
     FUSED_TRACE();
 
@@ -446,13 +475,13 @@ __global__ __launch_bounds__(256) void k_decode_fused(FusedArgs a) {
         {
             stage_vector<WT>(xs, plane_stride, a.o, nullptr, qd, ph.Kg, ph.KT, red);
             eo.y = a.x; eo.res = a.x; eo.rows = g.d;
-            phase_run<WT, EPI_RESID>(ring, ph, lc, xs, plane_stride, 1.f, eo, g, lane, best_v, best_i);
+            phase_run<WT, EPI_RESID>(ring, ph, lc, xs, plane_stride, 1.f, eo, g, lane, done, best_v, best_i);
         }
         ph = make_phase<WT, EPI_SWIGLU>(L.wgate_up, 2 * g.F, g.d, g.F);
         FUSED_TRACE();
-        grid_arrive(a.bar);
+        grid_arrive(a.bar, target + 1);
         phase_prefetch<WT, EPI_SWIGLU>(ring, ph, lc, lane, g, eo);
-        target += nwg;
+        target += 1;
         if (!grid_wait(a.bar, target, &s_flag, a.token_log)) return;
     FUSED_TRACE();
 
@@ -460,14 +489,14 @@ __global__ __launch_bounds__(256) void k_decode_fused(FusedArgs a) {
         {
             const float ss = stage_vector<WT>(xs, plane_stride, a.x, L.ffn_norm, g.d, ph.Kg, ph.KT, red);
             eo.y = a.a; eo.rows = 2 * g.F;
-            phase_run<WT, EPI_SWIGLU>(ring, ph, lc, xs, plane_stride, rsqrtf(ss / (float)g.d + g.eps), eo, g, lane, best_v, best_i);
+            phase_run<WT, EPI_SWIGLU>(ring, ph, lc, xs, plane_stride, rsqrtf(ss / (float)g.d + g.eps), eo, g, lane, done, best_v, best_i);
         }
         ph = make_phase<WT, EPI_RESID>(L.wdown, g.d, g.F, (g.d + 1) / 2);
         FUSED_TRACE();
-        grid_arrive(a.bar);
+        grid_arrive(a.bar, target + 1);
         eo.y = a.x; eo.res = a.x; eo.rows = g.d;
         phase_prefetch<WT, EPI_RESID>(ring, ph, lc, lane, g, eo);
-        target += nwg;
+        target += 1;
         if (!grid_wait(a.bar, target, &s_flag, a.token_log)) return;
     FUSED_TRACE();
 
@@ -475,16 +504,16 @@ __global__ __launch_bounds__(256) void k_decode_fused(FusedArgs a) {
         {
             stage_vector<WT>(xs, plane_stride, a.a, nullptr, g.F, ph.Kg, ph.KT, red);
             eo.y = a.x; eo.res = a.x; eo.rows = g.d;
-            phase_run<WT, EPI_RESID>(ring, ph, lc, xs, plane_stride, 1.f, eo, g, lane, best_v, best_i);
+            phase_run<WT, EPI_RESID>(ring, ph, lc, xs, plane_stride, 1.f, eo, g, lane, done, best_v, best_i);
         }
         const bool more = l + 1 < a.n_layers;
         if (more) ph = make_phase<WT, EPI_QKV>(a.layers[l + 1].wqkv, n_qkv, g.d, n_qkv / 2);
         else ph = make_phase<WT, EPI_STORE>(a.lm_head, g.V, g.d, (g.V + 1) / 2);
         FUSED_TRACE();
-        grid_arrive(a.bar);
+        grid_arrive(a.bar, target + 1);
         if (more) phase_prefetch<WT, EPI_QKV>(ring, ph, lc, lane, g, eo);
         else if (a.with_head) phase_prefetch<WT, EPI_STORE>(ring, ph, lc, lane, g, eo);
-        target += nwg;
+        target += 1;
         if (!grid_wait(a.bar, target, &s_flag, a.token_log)) return;
     FUSED_TRACE();
     }
@@ -493,7 +522,7 @@ __global__ __launch_bounds__(256) void k_decode_fused(FusedArgs a) {
         const float ss = stage_vector<WT>(xs, plane_stride, a.x, a.final_norm, g.d, ph.Kg, ph.KT, red);
         eo.y = a.logits; eo.rows = g.V;
         best_v = -INFINITY; best_i = 0x7fffffff;
-        phase_run<WT, EPI_STORE>(ring, ph, lc, xs, plane_stride, rsqrtf(ss / (float)g.d + g.eps), eo, g, lane, best_v, best_i);
+        phase_run<WT, EPI_STORE>(ring, ph, lc, xs, plane_stride, rsqrtf(ss / (float)g.d + g.eps), eo, g, lane, done, best_v, best_i);
         if (lane == 0) { s_bv[wave] = best_v; s_bi[wave] = best_i; }
         __syncthreads();
         if (tid == 0) {
@@ -501,8 +530,8 @@ __global__ __launch_bounds__(256) void k_decode_fused(FusedArgs a) {
             a.amax_v[blockIdx.x] = best_v; a.amax_i[blockIdx.x] = best_i;
         }
         FUSED_TRACE();
-        grid_arrive(a.bar);
-        target += nwg;
+        grid_arrive(a.bar, target + 1);
+        target += 1;
         if (!grid_wait(a.bar, target, &s_flag, a.token_log)) return;
     FUSED_TRACE();
     }
@@ -527,7 +556,7 @@ __global__ __launch_bounds__(256) void k_decode_fused(FusedArgs a) {
         a.seq_state[a.seq].len = pos + 1;
         a.seq_state[a.seq].next_token = next;
         *a.token_log = token;
-        __hip_atomic_store(&a.bar[1], target, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(&a.bar[0], target, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
 }
 
@@ -550,15 +579,19 @@ static fused_kernel_t pick_kernel(int dtype, const Geom& g) {
     return nullptr;
 }
 
-// LDS bytes: the staged vector (largest K of any phase, padded to whole tiles plus a block of zeros).
-static size_t fused_lds_bytes(int dtype, const Geom& g, int* xs_groups) {
+// LDS bytes: the staged vector (largest K of any phase, padded to whole tiles plus a block of zeros),
+// which the attention phases reuse, then per wave one float4 per unit of its largest phase.
+static size_t fused_lds_bytes(int dtype, const Geom& g, int grid, int* xs_groups, int* done_cap) {
     const int epl = dtype == 0 ? 4 : 8;
     const int kmax = std::max(std::max(g.d, g.F), g.Hq * g.dh);
     const int kg = kmax / epl, kt = (kg + 255) / 256;
     *xs_groups = kt * 256 + 64;
     size_t bytes = (size_t)(*xs_groups) * epl * sizeof(float);
     const size_t attn = sizeof(float) * (size_t)(4 * 8 * 2 + 4 * 8 * g.dh);
-    return std::max(bytes, attn) + 64;
+    bytes = std::max(bytes, attn);
+    const int units_max = std::max(std::max((g.Hq + 2 * g.Hkv) * g.dh / 2, g.F), (g.V + 1) / 2);
+    *done_cap = (units_max + grid * 4 - 1) / (grid * 4) + 1;
+    return bytes + (size_t)4 * (*done_cap) * sizeof(float4);
 }
 
 hipError_t fused_init(int dtype, const Geom& g, FusedPlan* plan) {
@@ -571,7 +604,7 @@ hipError_t fused_init(int dtype, const Geom& g, FusedPlan* plan) {
     if ((e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev))) return e;
     if ((e = hipDeviceGetAttribute(&coop, hipDeviceAttributeCooperativeLaunch, dev))) return e;
     if (!coop || cus < g.Hkv || cus > ARGMAX_MAX_BLOCKS) return hipSuccess;
-    plan->lds_bytes = fused_lds_bytes(dtype, g, &plan->xs_groups);
+    plan->lds_bytes = fused_lds_bytes(dtype, g, cus, &plan->xs_groups, &plan->done_cap);
     if (plan->lds_bytes > 160 * 1024) return hipSuccess;
     if ((e = hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)plan->lds_bytes))) return e;
     int per_cu = 0;
@@ -596,7 +629,7 @@ hipError_t launch_decode_fused(int dtype, const FusedPlan& plan, const FusedLaun
     a.token_log = b.token_log;
     a.x = b.x; a.q = b.q; a.o = b.o; a.a = b.a; a.part_acc = b.part_acc; a.part_ml = b.part_ml; a.logits = L.logits;
     a.rope_cos = b.rope_cos; a.rope_sin = b.rope_sin; a.amax_v = b.amax_v; a.amax_i = b.amax_i;
-    a.bar = L.bar; a.nsplit = plan.nsplit; a.xs_groups = plan.xs_groups; a.trace = (unsigned long long*)L.trace;
+    a.bar = L.bar; a.nsplit = plan.nsplit; a.xs_groups = plan.xs_groups; a.done_cap = plan.done_cap; a.trace = (unsigned long long*)L.trace;
     void* params[] = {&a};
     return hipLaunchCooperativeKernel((const void*)k, dim3(plan.grid), dim3(256), params, (unsigned)plan.lds_bytes, s);
 }

@@ -52,6 +52,7 @@ struct FusedPlan {
     int grid;           // workgroups = compute units
     int nsplit;         // attention splits per kv head
     int xs_groups;      // LDS capacity of the staged vector
+    int done_cap;       // finished units a wave can park in LDS
     size_t lds_bytes;
 };
 struct FusedLaunch {
@@ -60,10 +61,11 @@ struct FusedLaunch {
     const void* embed; const float* final_norm; const void* lm_head;
     int seq, forced; bool with_head;
     float* logits;              // of this sequence
-    unsigned* bar;              // 3 counters, zero at create
-    void* trace;                // optional device buffer of 64-bit time stamps (FUSED_TRACE_MAX entries)
+    unsigned* bar;              // FUSED_BAR_WORDS words, zero at create
+    void* trace;                // optional device buffer of 64-bit time stamps [FUSED_TRACE_MAX][grid]
 };
 constexpr int FUSED_TRACE_MAX = 4096;
+constexpr int FUSED_BAR_WORDS = 8 + 1024;   // barrier header + one flag per workgroup
 hipError_t fused_init(int dtype, const Geom& g, FusedPlan* plan);
 hipError_t launch_decode_fused(int dtype, const FusedPlan& plan, const FusedLaunch& L, const DecodeBuffers& b, const Geom& g,
                                hipStream_t s);
