@@ -85,32 +85,89 @@ __device__ __forceinline__ void amax_merge(float& bv, int& bi, float v, int i) {
     if (v > bv || (v == bv && i < bi)) { bv = v; bi = i; }
 }
 
-// LDS of one attention workgroup
-template <int DH, int G>
-struct AttnSmem {
-    float m[4][G], l[4][G], acc[4][G][DH];
-};
+// ---------------------------------------------------------------------------------------------
+// split-sequence decode attention of one workgroup (256 threads)
+// ---------------------------------------------------------------------------------------------
 
-// Positions [s0, s1) of one kv head for its G query heads, by one workgroup of 4 waves.
-// q: [Hq*DH] rotated, unscaled.  Kp / Vp: row-major planes of this kv head (row = position).
-// After the call (it ends with a __syncthreads) sm.m / sm.l / sm.acc hold the per-wave online-softmax
-// state; attn_fold turns them into the workgroup's (M, L, A[dim]).
-template <typename KVT, int DH, int G, bool PAIR, int UN = 4>
-__device__ __forceinline__ void attn_partial(const float* __restrict__ q, const KVT* __restrict__ Kp,
-                                             const KVT* __restrict__ Vp, size_t lo_offset, int kvh, int s0, int s1,
-                                             float scale, AttnSmem<DH, G>& sm) {
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float v) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, true));
+}
+
+// Sum over groups of N consecutive lanes (N = 8, 16 or 32); every lane of a group gets the total.
+// Lane exchanges inside a row of 16 are DPP modifiers of the add (no LDS traffic).
+template <int N>
+__device__ __forceinline__ float group_sum(float v) {
+    v += dpp_move<0xB1>(v);                 // quad_perm [1,0,3,2]
+    v += dpp_move<0x4E>(v);                 // quad_perm [2,3,0,1]
+    v += dpp_move<0x141>(v);                // row_half_mirror: the other quad of each 8 lanes
+    if (N >= 16) v += dpp_move<0x140>(v);   // row_mirror: the other half of the row
+    if (N >= 32) v += __shfl_xor(v, 16, 64);
+    return v;
+}
+
+__device__ __forceinline__ float wave_max_all(float v) {
+    v = fmaxf(v, dpp_move<0xB1>(v)); v = fmaxf(v, dpp_move<0x4E>(v));
+    v = fmaxf(v, dpp_move<0x141>(v)); v = fmaxf(v, dpp_move<0x140>(v));
+    float r0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 0));
+    float r1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 16));
+    float r2 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 32));
+    float r3 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 48));
+    return fmaxf(fmaxf(r0, r1), fmaxf(r2, r3));
+}
+
+__device__ __forceinline__ float wave_sum_all(float v) {
+    v += dpp_move<0xB1>(v); v += dpp_move<0x4E>(v); v += dpp_move<0x141>(v); v += dpp_move<0x140>(v);
+    float r0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 0));
+    float r1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 16));
+    float r2 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 32));
+    float r3 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 48));
+    return (r0 + r1) + (r2 + r3);
+}
+
+constexpr int ATTN_CHUNK = 256;     // positions whose scores are held in LDS at a time (one per thread)
+
+// LDS floats the attention of one workgroup needs
+template <typename KVT, int DH, int G>
+__host__ __device__ constexpr int attn_lds_floats() {
+    return ATTN_CHUNK * G + 4 * G + 4 * (64 / (DH / Elem<KVT>::EPL)) * G * DH;
+}
+
+// Positions [s0, s1) of one kv head for its G query heads.
+// q: [Hq*DH] rotated, unscaled.  Kp / Vp: row-major planes of this kv head (row = position); lo_offset: distance
+// to the lo planes (PAIR).  Three passes per chunk of up to ATTN_CHUNK positions:
+//   1. scores: a group of LPR lanes covers one cached key (16 bytes per lane), the G heads reuse the load,
+//      dot products are reduced inside the group with DPP adds, and land in LDS;
+//   2. softmax statistics of the chunk, one position per thread (running max m and sum l are replicated);
+//   3. P V: the same lane groups walk the values, the probabilities come from LDS.
+// On return (after a __syncthreads) lds holds NPART = 4 * PPW partial accumulators [part][G][DH] starting at
+// attn_part_offset, all relative to the same maximum; m_out[h], l_out[h] are valid in every thread.
+template <typename KVT, int DH, int G, bool PAIR>
+__device__ __forceinline__ void attn_split(const float* __restrict__ q, const KVT* __restrict__ Kp,
+                                           const KVT* __restrict__ Vp, size_t lo_offset, int kvh, int s0, int s1,
+                                           float scale, float* lds, float (&m_out)[G], float (&l_out)[G]) {
     constexpr int EPL = Elem<KVT>::EPL;
     constexpr int LPR = DH / EPL;       // lanes that cover one cached row
     constexpr int PPW = 64 / LPR;       // positions per wave-wide load
+    constexpr int PPR = 4 * PPW;        // positions per workgroup-wide round
+    constexpr int UN = 4;               // rounds whose loads are issued together
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int sub = lane / LPR, c = lane % LPR;
+    float* sc = lds;                            // [ATTN_CHUNK][G] scores, then probabilities
+    float* wred = lds + ATTN_CHUNK * G;         // [4][G] per-wave partial max / sum
+    float* part = wred + 4 * G;                 // [4 * PPW][G][DH]
 
     float qr[G][EPL];
 #pragma unroll
-    for (int h = 0; h < G; ++h)
+    for (int h = 0; h < G; ++h) {
+        const float* qp = q + (kvh * G + h) * DH + c * EPL;
 #pragma unroll
-        for (int e = 0; e < EPL; ++e) qr[h][e] = q[(kvh * G + h) * DH + c * EPL + e] * scale;
-
+        for (int e4 = 0; e4 < EPL; e4 += 4) {
+            const uint4 t = load16(qp + e4);
+            qr[h][e4] = __uint_as_float(t.x) * scale; qr[h][e4 + 1] = __uint_as_float(t.y) * scale;
+            qr[h][e4 + 2] = __uint_as_float(t.z) * scale; qr[h][e4 + 3] = __uint_as_float(t.w) * scale;
+        }
+    }
     float m[G], l[G], acc[G][EPL];
 #pragma unroll
     for (int h = 0; h < G; ++h) {
@@ -119,86 +176,118 @@ __device__ __forceinline__ void attn_partial(const float* __restrict__ q, const 
         for (int e = 0; e < EPL; ++e) acc[h][e] = 0.f;
     }
 
-    // UN position groups per trip: all their K/V loads are issued before the first is used
-    for (int p0 = s0 + wave * PPW; p0 < s1; p0 += 4 * PPW * UN) {
-        uint4 kr[UN], vr[UN], krl[PAIR ? UN : 1], vrl[PAIR ? UN : 1];
+    for (int c0 = s0; c0 < s1; c0 += ATTN_CHUNK) {
+        const int c1 = min(c0 + ATTN_CHUNK, s1), nc = c1 - c0;
+        // ---- 1. scores
+        for (int r0 = 0; r0 < nc; r0 += PPR * UN) {
+            uint4 kr[UN], krl[PAIR ? UN : 1];
 #pragma unroll
-        for (int u = 0; u < UN; ++u) {
-            const int p = p0 + u * 4 * PPW + sub;
-            const int pc = p < s1 ? p : s1 - 1;
-            kr[u] = load16(Kp + (size_t)pc * DH + c * EPL);
-            vr[u] = load16(Vp + (size_t)pc * DH + c * EPL);
-            if (PAIR) {
-                krl[u] = load16(Kp + lo_offset + (size_t)pc * DH + c * EPL);
-                vrl[u] = load16(Vp + lo_offset + (size_t)pc * DH + c * EPL);
+            for (int u = 0; u < UN; ++u) {
+                const int p = min(c0 + r0 + u * PPR + wave * PPW + sub, s1 - 1);
+                kr[u] = load16(Kp + (size_t)p * DH + c * EPL);
+                if (PAIR) krl[u] = load16(Kp + lo_offset + (size_t)p * DH + c * EPL);
+            }
+#pragma unroll
+            for (int u = 0; u < UN; ++u) {
+                const int pl = r0 + u * PPR + wave * PPW + sub;      // position within the chunk
+                float kf[EPL];
+                Elem<KVT>::expand(kr[u], kf);
+                if (PAIR) {
+                    float kl[EPL];
+                    Elem<KVT>::expand(krl[u], kl);
+#pragma unroll
+                    for (int e = 0; e < EPL; ++e) kf[e] += kl[e];
+                }
+#pragma unroll
+                for (int h = 0; h < G; ++h) {
+                    float s = 0.f;
+#pragma unroll
+                    for (int e = 0; e < EPL; ++e) s = fmaf(qr[h][e], kf[e], s);
+                    s = group_sum<LPR>(s);
+                    if (c == 0 && pl < ATTN_CHUNK) sc[pl * G + h] = pl < nc ? s : -INFINITY;
+                }
             }
         }
+        __syncthreads();
+        // ---- 2. statistics: thread t owns position c0 + t
+        float sv[G], corr[G];
 #pragma unroll
-        for (int u = 0; u < UN; ++u) {
-            const bool valid = p0 + u * 4 * PPW + sub < s1;
-            float kf[EPL], vf[EPL];
-            Elem<KVT>::expand(kr[u], kf);
-            Elem<KVT>::expand(vr[u], vf);
-            if (PAIR) {
-                float kl[EPL], vl[EPL];
-                Elem<KVT>::expand(krl[u], kl);
-                Elem<KVT>::expand(vrl[u], vl);
+        for (int h = 0; h < G; ++h) {
+            sv[h] = tid < nc ? sc[tid * G + h] : -INFINITY;
+            const float wm = wave_max_all(sv[h]);
+            if (lane == 0) wred[wave * G + h] = wm;
+        }
+        __syncthreads();
 #pragma unroll
-                for (int e = 0; e < EPL; ++e) { kf[e] += kl[e]; vf[e] += vl[e]; }
+        for (int h = 0; h < G; ++h) {
+            const float cm = fmaxf(fmaxf(wred[h], wred[G + h]), fmaxf(wred[2 * G + h], wred[3 * G + h]));
+            const float mn = fmaxf(m[h], cm);            // finite: the chunk is not empty
+            corr[h] = expf(m[h] - mn);                   // exp(-inf) = 0 for the first chunk
+            m[h] = mn;
+            sv[h] = expf(sv[h] - mn);                    // 0 for threads without a position
+        }
+        __syncthreads();                                  // every thread has read wred
+#pragma unroll
+        for (int h = 0; h < G; ++h) {
+            if (tid < nc) sc[tid * G + h] = sv[h];
+            const float ws = wave_sum_all(sv[h]);
+            if (lane == 0) wred[wave * G + h] = ws;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int h = 0; h < G; ++h) {
+            l[h] = l[h] * corr[h] + ((wred[h] + wred[G + h]) + (wred[2 * G + h] + wred[3 * G + h]));
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) acc[h][e] *= corr[h];
+        }
+        // ---- 3. P V
+        for (int r0 = 0; r0 < nc; r0 += PPR * UN) {
+            uint4 vr[UN], vrl[PAIR ? UN : 1];
+#pragma unroll
+            for (int u = 0; u < UN; ++u) {
+                const int p = min(c0 + r0 + u * PPR + wave * PPW + sub, s1 - 1);
+                vr[u] = load16(Vp + (size_t)p * DH + c * EPL);
+                if (PAIR) vrl[u] = load16(Vp + lo_offset + (size_t)p * DH + c * EPL);
             }
 #pragma unroll
-            for (int h = 0; h < G; ++h) {
-                float s = 0.f;
+            for (int u = 0; u < UN; ++u) {
+                const int pl = r0 + u * PPR + wave * PPW + sub;
+                float vf[EPL];
+                Elem<KVT>::expand(vr[u], vf);
+                if (PAIR) {
+                    float vl[EPL];
+                    Elem<KVT>::expand(vrl[u], vl);
 #pragma unroll
-                for (int e = 0; e < EPL; ++e) s = fmaf(qr[h][e], kf[e], s);
+                    for (int e = 0; e < EPL; ++e) vf[e] += vl[e];
+                }
 #pragma unroll
-                for (int o = 1; o < LPR; o <<= 1) s += __shfl_xor(s, o, 64);
-                if (!valid) s = -INFINITY;
-                float mx = s;
+                for (int h = 0; h < G; ++h) {
+                    const float pr = pl < nc ? sc[pl * G + h] : 0.f;
 #pragma unroll
-                for (int o = LPR; o < 64; o <<= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
-                // group u = 0 always holds the valid position p0, so m is finite from then on
-                const float mn = fmaxf(m[h], mx);
-                const float corr = expf(m[h] - mn);     // exp(-inf) = 0 on the very first group
-                const float pr = expf(s - mn);
-                l[h] = l[h] * corr + pr;
-#pragma unroll
-                for (int e = 0; e < EPL; ++e) acc[h][e] = fmaf(pr, vf[e], acc[h][e] * corr);
-                m[h] = mn;
+                    for (int e = 0; e < EPL; ++e) acc[h][e] = fmaf(pr, vf[e], acc[h][e]);
+                }
             }
         }
+        __syncthreads();                                  // sc and wred are rewritten by the next chunk
     }
-
-    // fold the PPW position groups of the wave (they share m)
 #pragma unroll
     for (int h = 0; h < G; ++h) {
+        m_out[h] = m[h]; l_out[h] = l[h];
 #pragma unroll
-        for (int o = LPR; o < 64; o <<= 1) {
-            l[h] += __shfl_xor(l[h], o, 64);
-#pragma unroll
-            for (int e = 0; e < EPL; ++e) acc[h][e] += __shfl_xor(acc[h][e], o, 64);
-        }
-        if (sub == 0) {
-            if (c == 0) { sm.m[wave][h] = m[h]; sm.l[wave][h] = l[h]; }
-#pragma unroll
-            for (int e = 0; e < EPL; ++e) sm.acc[wave][h][c * EPL + e] = acc[h][e];
-        }
+        for (int e = 0; e < EPL; ++e) part[((wave * PPW + sub) * G + h) * DH + c * EPL + e] = acc[h][e];
     }
     __syncthreads();
 }
 
-// Fold the four waves for (query head h of the group, channel dim); a wave without positions has m = -inf.
-template <int DH, int G>
-__device__ __forceinline__ void attn_fold(const AttnSmem<DH, G>& sm, int h, int dim, float& M, float& L, float& A) {
-    M = fmaxf(fmaxf(sm.m[0][h], sm.m[1][h]), fmaxf(sm.m[2][h], sm.m[3][h]));
-    L = 0.f; A = 0.f;
-    if (M > -INFINITY) {
+// Sum of the workgroup's partial accumulators for (head h of the group, channel dim).
+template <typename KVT, int DH, int G>
+__device__ __forceinline__ float attn_gather(const float* lds, int h, int dim) {
+    constexpr int NPART = 4 * (64 / (DH / Elem<KVT>::EPL));
+    const float* part = lds + ATTN_CHUNK * G + 4 * G;
+    float a = 0.f;
 #pragma unroll
-        for (int w = 0; w < 4; ++w) {
-            const float f = expf(sm.m[w][h] - M);
-            L += sm.l[w][h] * f; A += sm.acc[w][h][dim] * f;
-        }
-    }
+    for (int i = 0; i < NPART; ++i) a += part[(i * G + h) * DH + dim];
+    return a;
 }
 
 }  // namespace asynclm

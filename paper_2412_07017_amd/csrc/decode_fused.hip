@@ -342,7 +342,7 @@ __global__ __launch_bounds__(256) void k_decode_fused(FusedArgs a) {
     const int nwg = gridDim.x;
     const int plane_stride = a.xs_groups;
     float4* xs = lds4;
-    AttnSmem<DH, G>& asm_ = *reinterpret_cast<AttnSmem<DH, G>*>(lds4);
+    float* attn_lds = reinterpret_cast<float*>(lds4);    // the attention reuses the staged-vector area
     float* mf = reinterpret_cast<float*>(lds4);          // merge phase scratch
     float4* done = lds4 + (size_t)plane_stride * (EPL / 4) + (size_t)wave * a.done_cap;   // finished units of this wave
 
@@ -400,15 +400,19 @@ __global__ __launch_bounds__(256) void k_decode_fused(FusedArgs a) {
                 per = (per + quantum - 1) / quantum * quantum;
                 const int s0 = min(split * per, len), s1 = min(s0 + per, len);
                 const WT* Kp = (const WT*)L.kv_layer + (size_t)a.seq * g.kv_seq_stride + (size_t)kvh * g.kv_head_stride;
-                attn_partial<WT, DH, G, PAIR, (G > 4 ? 2 : 4)>(a.q, Kp, Kp + g.kv_v_offset, g.kv_lo_offset, kvh, s0, s1, g.scale, asm_);
+                float mh[G], lh[G];
+                attn_split<WT, DH, G, PAIR>(a.q, Kp, Kp + g.kv_v_offset, g.kv_lo_offset, kvh, s0, s1, g.scale, attn_lds, mh, lh);
                 for (int t = tid; t < G * DH; t += 256) {
                     const int h = t / DH, dim = t - h * DH, hq = kvh * G + h;
-                    float M, Ls, A;
-                    attn_fold<DH, G>(asm_, h, dim, M, Ls, A);
+                    const float A = attn_gather<WT, DH, G>(attn_lds, h, dim);
+                    float M = mh[0], Ls = lh[0];
+#pragma unroll
+                    for (int hh = 1; hh < G; ++hh) if (hh == h) { M = mh[hh]; Ls = lh[hh]; }
                     a.part_acc[((size_t)hq * nsplit + split) * DH + dim] = A;
                     if (dim == 0) { a.part_ml[((size_t)hq * nsplit + split) * 2] = M; a.part_ml[((size_t)hq * nsplit + split) * 2 + 1] = Ls; }
                 }
             }
+            __syncthreads();            // LDS is reused by the next phase
         }
         FUSED_TRACE();
         grid_arrive(a.bar, target + 1);
@@ -587,7 +591,8 @@ static size_t fused_lds_bytes(int dtype, const Geom& g, int grid, int* xs_groups
     const int kg = kmax / epl, kt = (kg + 255) / 256;
     *xs_groups = kt * 256 + 64;
     size_t bytes = (size_t)(*xs_groups) * epl * sizeof(float);
-    const size_t attn = sizeof(float) * (size_t)(4 * 8 * 2 + 4 * 8 * g.dh);
+    const int G = g.Hq / g.Hkv, ppw = 64 / (g.dh / epl);
+    const size_t attn = sizeof(float) * (size_t)(ATTN_CHUNK * G + 4 * G + 4 * ppw * G * g.dh);
     bytes = std::max(bytes, attn);
     const int units_max = std::max(std::max((g.Hq + 2 * g.Hkv) * g.dh / 2, g.F), (g.V + 1) / 2);
     *done_cap = (units_max + grid * 4 - 1) / (grid * 4) + 1;

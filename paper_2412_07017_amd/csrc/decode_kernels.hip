@@ -193,14 +193,13 @@ template <typename KVT, int DH, int G, bool PAIR>
 __global__ __launch_bounds__(256) void k_attn_decode(AttnArgs a, Geom g) {
     constexpr int EPL = Elem<KVT>::EPL;
     constexpr int PPW = 64 / (DH / EPL);        // positions per wave-wide load
-    __shared__ AttnSmem<DH, G> sm;
+    extern __shared__ float lds[];
     __shared__ int s_last;
-    float (&s_acc)[4][G][DH] = sm.acc;
 
     const int tid = threadIdx.x;
     const int kvh = blockIdx.x, split = blockIdx.y, nsplit = a.nsplit;
     const int len = a.step->pos + 1;
-    // split boundaries: equal shares rounded up to whole workgroup iterations
+    // split boundaries: equal shares rounded up to whole workgroup rounds
     const int quantum = 4 * PPW;
     int per = (len + nsplit - 1) / nsplit;
     per = (per + quantum - 1) / quantum * quantum;
@@ -208,12 +207,15 @@ __global__ __launch_bounds__(256) void k_attn_decode(AttnArgs a, Geom g) {
 
     const KVT* Kp = (const KVT*)a.kv_layer + (size_t)a.step->seq * g.kv_seq_stride + (size_t)kvh * g.kv_head_stride;
     const KVT* Vp = Kp + g.kv_v_offset;
-    attn_partial<KVT, DH, G, PAIR>(a.q, Kp, Vp, g.kv_lo_offset, kvh, s0, s1, g.scale, sm);
+    float mh[G], lh[G];
+    attn_split<KVT, DH, G, PAIR>(a.q, Kp, Vp, g.kv_lo_offset, kvh, s0, s1, g.scale, lds, mh, lh);
 
     for (int t = tid; t < G * DH; t += 256) {
         const int h = t / DH, dim = t - h * DH;
-        float M, L, A;
-        attn_fold<DH, G>(sm, h, dim, M, L, A);
+        const float A = attn_gather<KVT, DH, G>(lds, h, dim);
+        float M = mh[0], L = lh[0];
+#pragma unroll
+        for (int hh = 1; hh < G; ++hh) if (hh == h) { M = mh[hh]; L = lh[hh]; }
         const int hq = kvh * G + h;
         if (nsplit == 1) {
             a.o[hq * DH + dim] = A / L;
@@ -235,7 +237,8 @@ __global__ __launch_bounds__(256) void k_attn_decode(AttnArgs a, Geom g) {
     if (!s_last) return;
     __threadfence();
     // weights of the splits: f_s = exp(m_s - M) / L, staged in LDS (reuses the wave buffers)
-    float* s_f = &s_acc[0][0][0];                 // [G][ATTN_MAX_SPLIT] factors
+    __syncthreads();                              // the partial accumulators in LDS have been read
+    float* s_f = lds;                             // [G][ATTN_MAX_SPLIT] factors
     float* s_lv = s_f + G * ATTN_MAX_SPLIT;       // [G][ATTN_MAX_SPLIT] partial sums
     for (int t = tid; t < G * nsplit; t += 256) {
         const int h = t / nsplit, sp = t - h * nsplit;
@@ -431,13 +434,22 @@ hipError_t launch_lmhead(int dtype, const void* wout, const float* gain, float* 
 template <typename KVT, int DH, bool PAIR>
 static hipError_t launch_attn_t(const AttnArgs& a, const Geom& g, hipStream_t s) {
     const dim3 grid(g.Hkv, a.nsplit), block(256);
+#define ATTN_CASE(GG)                                                                                                   \
+    case GG: {                                                                                                          \
+        const size_t lds = sizeof(float) * attn_lds_floats<KVT, DH, GG>();                                              \
+        if (lds > 48 * 1024) {                                                                                          \
+            hipError_t e = hipFuncSetAttribute((const void*)(k_attn_decode<KVT, DH, GG, PAIR>),                         \
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);                   \
+            if (e) return e;                                                                                            \
+        }                                                                                                               \
+        hipLaunchKernelGGL((k_attn_decode<KVT, DH, GG, PAIR>), grid, block, lds, s, a, g);                              \
+        break;                                                                                                          \
+    }
     switch (g.Hq / g.Hkv) {
-        case 1: hipLaunchKernelGGL((k_attn_decode<KVT, DH, 1, PAIR>), grid, block, 0, s, a, g); break;
-        case 2: hipLaunchKernelGGL((k_attn_decode<KVT, DH, 2, PAIR>), grid, block, 0, s, a, g); break;
-        case 4: hipLaunchKernelGGL((k_attn_decode<KVT, DH, 4, PAIR>), grid, block, 0, s, a, g); break;
-        case 8: hipLaunchKernelGGL((k_attn_decode<KVT, DH, 8, PAIR>), grid, block, 0, s, a, g); break;
+        ATTN_CASE(1) ATTN_CASE(2) ATTN_CASE(4) ATTN_CASE(8)
         default: return hipErrorInvalidValue;
     }
+#undef ATTN_CASE
     return hipGetLastError();
 }
 
