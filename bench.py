@@ -37,6 +37,7 @@ def parse():
     ap.add_argument("--layers", type=int, default=0, help="truncate the model (0 = full depth); for experiments only")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--chunk", type=int, default=0, help="override the library's rows per forward pass for prefill/inject")
+    ap.add_argument("--fused", type=int, default=-1, help="1/0: force the single-kernel / per-operation decoding step (default: library's choice)")
     return ap.parse_args()
 
 
@@ -116,6 +117,8 @@ def main():
     lm = pkg.AsyncLM(model, w_dev, max_positions=max_pos, stream=stream)
     if args.chunk:
         lm.set_option("chunk", args.chunk)
+    if args.fused >= 0:
+        lm.set_option("fused", args.fused)
     t0 = time.perf_counter()
     lm.prefill(0, spec["prompt"])
     lm.synchronize()
@@ -168,13 +171,19 @@ def main():
         for name, d in p.items():
             c = classes.setdefault(name, {"ms": 0.0, "launches": 0})
             c["ms"] += d["ms"]; c["launches"] += d["launches"]
-    gu = classes["gate_up_swiglu"]
-    gu_ms = gu["ms"] / gu["launches"]
     eb = model.elem_bytes
-    gu_bytes = 2 * model.ffn * model.d_model * eb + 4 * model.d_model * 2 + 4 * model.ffn
-    roofline = {"bound": "hbm", "kernel": "gate_up_swiglu (k_gemv)", "achieved": gu_bytes / (gu_ms * 1e-3) / 1e9,
+    if "fused_step_kernel" in classes:
+        # the whole step is one kernel: its algorithmic bytes are those of the step
+        fk = classes["fused_step_kernel"]
+        k_ms, k_bytes, k_name = fk["ms"] / fk["launches"], bytes_step, "k_decode_fused (whole decoding step)"
+    else:
+        gu = classes["gate_up_swiglu"]
+        k_ms = gu["ms"] / gu["launches"]
+        k_bytes = 2 * model.ffn * model.d_model * eb + 4 * model.d_model * 2 + 4 * model.ffn
+        k_name = "gate_up_swiglu (k_gemv)"
+    roofline = {"bound": "hbm", "kernel": k_name, "achieved": k_bytes / (k_ms * 1e-3) / 1e9,
                 "peak": HBM_PEAK / 1e9, "unit": "GB/s", "traffic": None,
-                "bytes_per_launch": gu_bytes, "ms_per_launch": gu_ms}
+                "bytes_per_launch": k_bytes, "ms_per_launch": k_ms}
     roofline["frac"] = roofline["achieved"] / roofline["peak"]
     per_class = {k: {"ms_per_step": v["ms"] / 5, "launches_per_step": v["launches"] // 5} for k, v in classes.items()}
     lm.synchronize()

@@ -133,8 +133,8 @@ int asynclm_synchronize(asynclm_ctx *ctx);
  *                  through the decode kernels.  Default 64 where the matrix-core append path applies
  *                  (bf16 model, paired cache, head_dim 128, d_model and ffn multiples of 256), else 1.
  *   "chunk_split"  0 = built-in split-K factors of the append path's products, 1..4 = force one
- *   "fused"        1 = run a decoding step as one persistent cooperative kernel (default where the
- *                  device and the model shape allow it), 0 = one kernel per operation
+ *   "fused"        1 = run a decoding step as one persistent cooperative kernel (where the device and the
+ *                  model shape allow it; ignored otherwise), 0 = one kernel per operation (default)
  *   "graph"        (per-operation kernels only) 1 = replay decoding steps as a captured HIP graph,
  *                  0 = launch kernels one by one
  *   "attn_split"   0 = choose the number of sequence splits of decode attention from the length,

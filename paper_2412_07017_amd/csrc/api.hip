@@ -100,15 +100,24 @@ void* kv_layer_ptr(const asynclm_ctx* c, int layer) {
     return (char*)c->kv + (size_t)layer * c->g.kv_layer_stride * elem_bytes(c);
 }
 
-int pick_nsplit(const asynclm_ctx* c, int len_after) {
-    if (c->opt_attn_split > 0) return c->opt_attn_split < ATTN_MAX_SPLIT ? c->opt_attn_split : ATTN_MAX_SPLIT;
-    int want = (len_after + 63) / 64, n = 1;
-    while (n < want && n < ATTN_MAX_SPLIT) n *= 2;
-    return n;
+// Attention splits for a context of len_after tokens.  Up to 2048 tokens: at most MERGE_MAX_SPLIT splits, which
+// the O projection merges while it stages its input (no merge step at all).  Longer: up to ATTN_MAX_SPLIT
+// splits with a merge step of their own.
+struct SplitPlan { int nsplit; bool merge_in_oproj; };
+
+SplitPlan pick_nsplit(const asynclm_ctx* c, int len_after) {
+    if (c->opt_attn_split > 0) {
+        const int n = c->opt_attn_split < ATTN_MAX_SPLIT ? c->opt_attn_split : ATTN_MAX_SPLIT;
+        return {n, n <= 8};
+    }
+    const int want = (len_after + 63) / 64, cap = len_after <= 2048 ? 8 : ATTN_MAX_SPLIT;
+    int n = 1;
+    while (n < want && n < cap) n *= 2;
+    return {n, cap == 8};
 }
 
 // One forward pass of a single row whose token/position are already in the step descriptor.
-hipError_t forward_single(asynclm_ctx* c, int seq, bool with_head, int nsplit) {
+hipError_t forward_single(asynclm_ctx* c, int seq, bool with_head, SplitPlan sp) {
     const int dt = c->cfg.dtype;
     const Geom& g = c->g;
     hipStream_t s = c->stream;
@@ -117,8 +126,8 @@ hipError_t forward_single(asynclm_ctx* c, int seq, bool with_head, int nsplit) {
     for (int l = 0; l < c->cfg.n_layers; ++l) {
         void* kvl = kv_layer_ptr(c, l);
         if ((e = run(c, KC_QKV, [&] { return launch_qkv(dt, c->wqkv[l], c->attn_norm[l], kvl, c->b, g, s); }))) return e;
-        if ((e = run(c, KC_ATTN, [&] { return launch_attn_decode(dt, kvl, nsplit, c->b, g, s); }))) return e;
-        if ((e = run(c, KC_OPROJ, [&] { return launch_oproj(dt, c->wo[l], c->b, g, s); }))) return e;
+        if ((e = run(c, KC_ATTN, [&] { return launch_attn_decode(dt, kvl, sp.nsplit, sp.merge_in_oproj, c->b, g, s); }))) return e;
+        if ((e = run(c, KC_OPROJ, [&] { return launch_oproj(dt, c->wo[l], sp.merge_in_oproj ? sp.nsplit : 0, c->b, g, s); }))) return e;
         if ((e = run(c, KC_GATEUP, [&] { return launch_gateup(dt, c->wgate_up[l], c->ffn_norm[l], c->b, g, s); }))) return e;
         if ((e = run(c, KC_DOWN, [&] { return launch_down(dt, c->wdown[l], c->b, g, s); }))) return e;
     }
@@ -131,14 +140,14 @@ hipError_t forward_single(asynclm_ctx* c, int seq, bool with_head, int nsplit) {
 }
 
 // The same pass, replayed from a captured graph (one graph per split count / head flag / sequence).
-hipError_t forward_single_graph(asynclm_ctx* c, int seq, bool with_head, int nsplit) {
-    const int key = ((seq * (ATTN_MAX_SPLIT + 1) + nsplit) << 1) | (with_head ? 1 : 0);
+hipError_t forward_single_graph(asynclm_ctx* c, int seq, bool with_head, SplitPlan sp) {
+    const int key = ((((seq * (ATTN_MAX_SPLIT + 1) + sp.nsplit) << 1) | (sp.merge_in_oproj ? 1 : 0)) << 1) | (with_head ? 1 : 0);
     auto it = c->graphs.find(key);
     if (it == c->graphs.end()) {
         hipError_t e;
         hipGraph_t graph = nullptr;
         if ((e = hipStreamBeginCapture(c->stream, hipStreamCaptureModeRelaxed))) return e;
-        e = forward_single(c, seq, with_head, nsplit);
+        e = forward_single(c, seq, with_head, sp);
         hipError_t e2 = hipStreamEndCapture(c->stream, &graph);
         if (e) { if (graph) hipGraphDestroy(graph); return e; }
         if (e2) return e2;
@@ -158,15 +167,21 @@ hipError_t step_one_token(asynclm_ctx* c, int seq, int forced, bool with_head) {
         L.layers_dev = c->layers_dev; L.n_layers = c->cfg.n_layers;
         L.embed = c->embed; L.final_norm = c->final_norm; L.lm_head = c->lm_head;
         L.seq = seq; L.forced = forced; L.with_head = with_head;
+        {
+            SplitPlan sp = pick_nsplit(c, c->len[seq] + 1);
+            if (!sp.merge_in_oproj) sp.nsplit = c->fused.nsplit;          // long context: every workgroup takes a split
+            if (sp.nsplit > c->fused.nsplit) sp.nsplit = c->fused.nsplit;
+            L.nsplit = sp.nsplit; L.merge_in_stage = sp.merge_in_oproj;
+        }
         L.logits = c->logits + (size_t)seq * c->g.V; L.bar = c->bar; L.trace = c->want_trace ? c->trace : nullptr;
         if ((e = launch_decode_fused(c->cfg.dtype, c->fused, L, c->b, c->g, c->stream))) return e;
         c->len[seq] += 1;
         return hipSuccess;
     }
-    const int nsplit = pick_nsplit(c, c->len[seq] + 1);
+    const SplitPlan sp = pick_nsplit(c, c->len[seq] + 1);
     if ((e = run(c, KC_BEGIN, [&] { return launch_begin_step(c->b, seq, forced, c->stream); }))) return e;
-    if (c->opt_graph && !c->prof) e = forward_single_graph(c, seq, with_head, nsplit);
-    else e = forward_single(c, seq, with_head, nsplit);
+    if (c->opt_graph && !c->prof) e = forward_single_graph(c, seq, with_head, sp);
+    else e = forward_single(c, seq, with_head, sp);
     if (e) return e;
     c->len[seq] += 1;
     return hipSuccess;
@@ -419,7 +434,7 @@ int asynclm_create(asynclm_ctx** out, const asynclm_config* cfg, const asynclm_w
             hipMemset(c->bar, 0, FUSED_BAR_WORDS * sizeof(unsigned)) != hipSuccess)
             return bail(ASYNCLM_E_DEVICE);
         if ((e = fused_init(cfg->dtype, g, &c->fused)) != hipSuccess) { report_hip("fused_init", e); return bail(ASYNCLM_E_DEVICE); }
-        c->opt_fused = c->fused.supported ? 1 : 0;
+        c->opt_fused = 0;      // opt-in (set_option "fused"): the per-operation kernels are currently faster
         if (c->fused.supported && (e = dev_alloc(c, &c->trace, (size_t)FUSED_TRACE_MAX * c->fused.grid)) != hipSuccess) return bail(ASYNCLM_E_NOMEM);
     }
     const int max_k = g.F > g.d ? (g.F > g.Hq * g.dh ? g.F : g.Hq * g.dh) : (g.d > g.Hq * g.dh ? g.d : g.Hq * g.dh);

@@ -290,4 +290,111 @@ __device__ __forceinline__ float attn_gather(const float* lds, int h, int dim) {
     return a;
 }
 
+// ---------------------------------------------------------------------------------------------
+// staging of the input vector of a matrix-vector product
+// ---------------------------------------------------------------------------------------------
+
+constexpr int MERGE_MAX_SPLIT = 8;      // attention splits that the O projection can merge while staging
+
+// Where the vector comes from: a plain fp32 vector x (times an optional gain), or - when x is null - the
+// attention output formed on the fly from the per-split partial accumulators:
+//   o[h][dim] = sum_s f[h][s] * part_acc[h][s][dim],   f[h][s] = exp(m[h][s] - M[h]) / L[h].
+struct VecSource {
+    const float* x;
+    const float* gain;
+    const float* part_acc;  // [Hq][nsplit][DH]
+    const float* part_ml;   // [Hq][nsplit][2]
+    int nsplit, DH, Hq;
+};
+
+__device__ __forceinline__ float4 as_float4(const uint4& v) {
+    return make_float4(__uint_as_float(v.x), __uint_as_float(v.y), __uint_as_float(v.z), __uint_as_float(v.w));
+}
+
+// Stages K elements into the planar LDS layout (plane p of group grp holds elements 4p..4p+3 of the group of
+// EPL elements; planes are plane_stride float4 apart) and returns the sum of squares of the unscaled vector
+// (valid after the trailing __syncthreads).  With `pad`, groups [Kg, 256 KT) and the last 64 groups of each
+// plane are zero-filled.
+// All loads of a batch are issued before the first is used.
+template <typename WT>
+__device__ __forceinline__ float stage_vector(float4* xs, int plane_stride, const VecSource& src, int K, int Kg, int KT,
+                                              bool pad, float* red) {
+    constexpr int NP = Elem<WT>::EPL / 4;
+    const int tid = threadIdx.x, n4 = K >> 2;
+    float ss = 0.f;
+    if (src.x) {
+        for (int base = 0; base < n4; base += 1024) {
+            float4 v[4], gn[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int k4 = min(base + j * 256 + tid, n4 - 1);
+                v[j] = as_float4(load16(src.x + 4 * (size_t)k4));
+                gn[j] = src.gain ? as_float4(load16(src.gain + 4 * (size_t)k4)) : make_float4(1.f, 1.f, 1.f, 1.f);
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int k4 = base + j * 256 + tid;
+                if (k4 < n4) {
+                    ss += v[j].x * v[j].x + v[j].y * v[j].y + v[j].z * v[j].z + v[j].w * v[j].w;
+                    const int grp = k4 / NP, pl = k4 - grp * NP;
+                    xs[pl * plane_stride + grp] = make_float4(v[j].x * gn[j].x, v[j].y * gn[j].y, v[j].z * gn[j].z, v[j].w * gn[j].w);
+                }
+            }
+        }
+    } else {
+        // every thread merges the splits of its own elements: statistics and partials of a batch are all
+        // requested before the first is used, so a batch costs one memory round trip
+        const int ns = src.nsplit;
+        for (int base = 0; base < n4; base += 512) {
+            float4 raw[2][MERGE_MAX_SPLIT];
+            float ms[2][MERGE_MAX_SPLIT], ls[2][MERGE_MAX_SPLIT];
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const int kc = min(base + j * 256 + tid, n4 - 1);
+                const int h = 4 * kc / src.DH, dim = 4 * kc - h * src.DH;
+                const float* pm = src.part_ml + (size_t)h * ns * 2;
+                const float* pa = src.part_acc + (size_t)h * ns * src.DH + dim;
+#pragma unroll
+                for (int s = 0; s < MERGE_MAX_SPLIT; ++s) {
+                    const int sc = min(s, ns - 1);
+                    ms[j][s] = load_f32(pm + 2 * sc); ls[j][s] = load_f32(pm + 2 * sc + 1);
+                    raw[j][s] = as_float4(load16(pa + (size_t)sc * src.DH));
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const int k4 = base + j * 256 + tid;
+                float M = -INFINITY, L = 0.f;
+#pragma unroll
+                for (int s = 0; s < MERGE_MAX_SPLIT; ++s) if (s < ns) M = fmaxf(M, ms[j][s]);
+                float4 r = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+                for (int s = 0; s < MERGE_MAX_SPLIT; ++s) {
+                    const float w = (s < ns && ms[j][s] > -INFINITY) ? expf(ms[j][s] - M) : 0.f;
+                    L += ls[j][s] * w;
+                    r.x = fmaf(raw[j][s].x, w, r.x); r.y = fmaf(raw[j][s].y, w, r.y);
+                    r.z = fmaf(raw[j][s].z, w, r.z); r.w = fmaf(raw[j][s].w, w, r.w);
+                }
+                const float inv = 1.f / L;
+                if (k4 < n4) {
+                    const int grp = k4 / NP, pl = k4 - grp * NP;
+                    xs[pl * plane_stride + grp] = make_float4(r.x * inv, r.y * inv, r.z * inv, r.w * inv);
+                }
+            }
+        }
+    }
+    if (pad) {
+        for (int grp = Kg + tid; grp < KT * 256; grp += 256)
+#pragma unroll
+            for (int pl = 0; pl < NP; ++pl) xs[pl * plane_stride + grp] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (tid < 64)
+#pragma unroll
+            for (int pl = 0; pl < NP; ++pl) xs[pl * plane_stride + plane_stride - 64 + tid] = make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+    ss = wave_sum(ss);
+    if ((tid & 63) == 0) red[tid >> 6] = ss;
+    __syncthreads();
+    return red[0] + red[1] + red[2] + red[3];
+}
+
 }  // namespace asynclm

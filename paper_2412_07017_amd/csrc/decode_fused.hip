@@ -42,6 +42,7 @@ struct FusedArgs {
     float* amax_v; int32_t* amax_i;
     unsigned* bar;          // grid barrier state (see grid_arrive)
     int32_t nsplit;         // attention splits per kv head (<= gridDim.x / Hkv)
+    int32_t merge_in_stage; // 1: the O projection merges the splits while staging (nsplit <= MERGE_MAX_SPLIT), no merge phase
     int32_t xs_groups;      // LDS capacity of the staged vector, in groups of EPL elements
     int32_t done_cap;       // units one wave can park in LDS before its epilogues run
     unsigned long long* trace;   // optional [stamp][workgroup]: the 100 MHz wall clock at every phase boundary
@@ -228,49 +229,6 @@ __device__ __forceinline__ void phase_prefetch(Slot (&ring)[RING], const Phase<W
     __builtin_amdgcn_sched_barrier(0);
 }
 
-// Stages src[0..K) (times gain, if any) into the planar LDS layout, zero-fills the padding, and returns
-// the sum of squares of src (valid after the trailing __syncthreads).
-template <typename WT>
-__device__ __forceinline__ float stage_vector(float4* xs, int plane_stride, const float* __restrict__ src,
-                                              const float* __restrict__ gain, int K, int Kg, int KT, float* red) {
-    constexpr int NP = Elem<WT>::EPL / 4;
-    const int tid = threadIdx.x, n4 = K >> 2;
-    float ss = 0.f;
-    for (int base = 0; base < n4; base += 1024) {
-        float4 v[4], gn[4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int k4 = min(base + j * 256 + tid, n4 - 1);
-            const uint4 rv = load16(src + 4 * (size_t)k4);
-            v[j] = make_float4(__uint_as_float(rv.x), __uint_as_float(rv.y), __uint_as_float(rv.z), __uint_as_float(rv.w));
-            if (gain) {
-                const uint4 rg = load16(gain + 4 * (size_t)k4);
-                gn[j] = make_float4(__uint_as_float(rg.x), __uint_as_float(rg.y), __uint_as_float(rg.z), __uint_as_float(rg.w));
-            } else gn[j] = make_float4(1.f, 1.f, 1.f, 1.f);
-        }
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int k4 = base + j * 256 + tid;
-            if (k4 < n4) {
-                ss += v[j].x * v[j].x + v[j].y * v[j].y + v[j].z * v[j].z + v[j].w * v[j].w;
-                const int grp = k4 / NP, pl = k4 - grp * NP;
-                xs[pl * plane_stride + grp] = make_float4(v[j].x * gn[j].x, v[j].y * gn[j].y, v[j].z * gn[j].z, v[j].w * gn[j].w);
-            }
-        }
-    }
-    // zeros: the tail of the last tile, and the block that tiles past the end are multiplied with
-    for (int grp = Kg + tid; grp < KT * 256; grp += 256)
-#pragma unroll
-        for (int pl = 0; pl < NP; ++pl) xs[pl * plane_stride + grp] = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (tid < 64)
-#pragma unroll
-        for (int pl = 0; pl < NP; ++pl) xs[pl * plane_stride + plane_stride - 64 + tid] = make_float4(0.f, 0.f, 0.f, 0.f);
-    ss = wave_sum(ss);
-    if ((tid & 63) == 0) red[tid >> 6] = ss;
-    __syncthreads();
-    return red[0] + red[1] + red[2] + red[3];
-}
-
 // Runs a phase whose first RING tiles are already in `ring`.  The loop only parks each finished unit
 // (two dot products and the slot's epilogue operands) in the wave's LDS area `done`; the epilogues, with
 // their global stores, run after the loop, one unit per lane.  Keeping every global memory instruction
@@ -375,7 +333,7 @@ __global__ __launch_bounds__(256) void k_decode_fused(FusedArgs a) {
         const FusedLayer L = a.layers[l];
         // ---- QKV: x -> q, K/V cache row `pos`
         {
-            const float ss = stage_vector<WT>(xs, plane_stride, a.x, L.attn_norm, g.d, ph.Kg, ph.KT, red);
+            const float ss = stage_vector<WT>(xs, plane_stride, VecSource{a.x, L.attn_norm}, g.d, ph.Kg, ph.KT, true, red);
             eo.kv_layer = L.kv_layer; eo.rows = n_qkv;
             phase_run<WT, EPI_QKV>(ring, ph, lc, xs, plane_stride, rsqrtf(ss / (float)g.d + g.eps), eo, g, lane, done, best_v, best_i);
         }
@@ -421,7 +379,7 @@ __global__ __launch_bounds__(256) void k_decode_fused(FusedArgs a) {
     FUSED_TRACE();
 
         // ---- merge of the splits: thread = (query head, 4 channels, one eighth of the splits)
-        {
+        if (!a.merge_in_stage) {
             constexpr int TPH = DH * 2;                     // threads per head
             constexpr int HPW = 256 / TPH;                  // heads per workgroup
             const int nsplit = a.nsplit;
@@ -470,14 +428,18 @@ __global__ __launch_bounds__(256) void k_decode_fused(FusedArgs a) {
             }
         }
         FUSED_TRACE();
-        grid_arrive(a.bar, target + 1);
-        target += 1;
-        if (!grid_wait(a.bar, target, &s_flag, a.token_log)) return;
-    FUSED_TRACE();
+        if (!a.merge_in_stage) {
+            grid_arrive(a.bar, target + 1);
+            target += 1;
+            if (!grid_wait(a.bar, target, &s_flag, a.token_log)) return;
+        }
+        FUSED_TRACE();
 
         // ---- O projection + residual (tiles were requested before the attention)
         {
-            stage_vector<WT>(xs, plane_stride, a.o, nullptr, qd, ph.Kg, ph.KT, red);
+            VecSource vs{a.o, nullptr};
+            if (a.merge_in_stage) { vs.x = nullptr; vs.part_acc = a.part_acc; vs.part_ml = a.part_ml; vs.nsplit = a.nsplit; vs.DH = DH; vs.Hq = g.Hq; }
+            stage_vector<WT>(xs, plane_stride, vs, qd, ph.Kg, ph.KT, true, red);
             eo.y = a.x; eo.res = a.x; eo.rows = g.d;
             phase_run<WT, EPI_RESID>(ring, ph, lc, xs, plane_stride, 1.f, eo, g, lane, done, best_v, best_i);
         }
@@ -491,7 +453,7 @@ __global__ __launch_bounds__(256) void k_decode_fused(FusedArgs a) {
 
         // ---- gate/up + SwiGLU
         {
-            const float ss = stage_vector<WT>(xs, plane_stride, a.x, L.ffn_norm, g.d, ph.Kg, ph.KT, red);
+            const float ss = stage_vector<WT>(xs, plane_stride, VecSource{a.x, L.ffn_norm}, g.d, ph.Kg, ph.KT, true, red);
             eo.y = a.a; eo.rows = 2 * g.F;
             phase_run<WT, EPI_SWIGLU>(ring, ph, lc, xs, plane_stride, rsqrtf(ss / (float)g.d + g.eps), eo, g, lane, done, best_v, best_i);
         }
@@ -506,7 +468,7 @@ __global__ __launch_bounds__(256) void k_decode_fused(FusedArgs a) {
 
         // ---- down projection + residual
         {
-            stage_vector<WT>(xs, plane_stride, a.a, nullptr, g.F, ph.Kg, ph.KT, red);
+            stage_vector<WT>(xs, plane_stride, VecSource{a.a, nullptr}, g.F, ph.Kg, ph.KT, true, red);
             eo.y = a.x; eo.res = a.x; eo.rows = g.d;
             phase_run<WT, EPI_RESID>(ring, ph, lc, xs, plane_stride, 1.f, eo, g, lane, done, best_v, best_i);
         }
@@ -523,7 +485,7 @@ __global__ __launch_bounds__(256) void k_decode_fused(FusedArgs a) {
     }
 
     if (a.with_head) {
-        const float ss = stage_vector<WT>(xs, plane_stride, a.x, a.final_norm, g.d, ph.Kg, ph.KT, red);
+        const float ss = stage_vector<WT>(xs, plane_stride, VecSource{a.x, a.final_norm}, g.d, ph.Kg, ph.KT, true, red);
         eo.y = a.logits; eo.rows = g.V;
         best_v = -INFINITY; best_i = 0x7fffffff;
         phase_run<WT, EPI_STORE>(ring, ph, lc, xs, plane_stride, rsqrtf(ss / (float)g.d + g.eps), eo, g, lane, done, best_v, best_i);
@@ -634,7 +596,9 @@ hipError_t launch_decode_fused(int dtype, const FusedPlan& plan, const FusedLaun
     a.token_log = b.token_log;
     a.x = b.x; a.q = b.q; a.o = b.o; a.a = b.a; a.part_acc = b.part_acc; a.part_ml = b.part_ml; a.logits = L.logits;
     a.rope_cos = b.rope_cos; a.rope_sin = b.rope_sin; a.amax_v = b.amax_v; a.amax_i = b.amax_i;
-    a.bar = L.bar; a.nsplit = plan.nsplit; a.xs_groups = plan.xs_groups; a.done_cap = plan.done_cap; a.trace = (unsigned long long*)L.trace;
+    a.bar = L.bar; a.nsplit = L.nsplit; a.merge_in_stage = L.merge_in_stage ? 1 : 0;
+    if (L.nsplit < 1 || L.nsplit > plan.nsplit || (L.merge_in_stage && L.nsplit > MERGE_MAX_SPLIT)) return hipErrorInvalidValue;
+    a.xs_groups = plan.xs_groups; a.done_cap = plan.done_cap; a.trace = (unsigned long long*)L.trace;
     void* params[] = {&a};
     return hipLaunchCooperativeKernel((const void*)k, dim3(plan.grid), dim3(256), params, (unsigned)plan.lds_bytes, s);
 }

@@ -53,6 +53,8 @@ struct GemvArgs {
     const float* rope_sin;
     const StepDesc* step;
     int32_t layer;
+    // merged attention output as input vector (x == nullptr): see VecSource
+    const float* part_acc; const float* part_ml; int32_t merge_nsplit, merge_dh, merge_hq;
 };
 
 template <typename WT, int EPI, int NU>
@@ -86,21 +88,9 @@ __global__ __launch_bounds__(256) void k_gemv(GemvArgs a, Geom g) {
     }
 
     // ---- stage x (times the norm gain) into LDS, planar so that lanes read consecutive 16 B
-    float ss = 0.f;
-    for (int k4 = tid; k4 < K / 4; k4 += 256) {
-        float4 v = ((const float4*)a.x)[k4];
-        ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
-        if (a.gain) {
-            float4 gn = ((const float4*)a.gain)[k4];
-            v.x *= gn.x; v.y *= gn.y; v.z *= gn.z; v.w *= gn.w;
-        }
-        const int grp = k4 / NP, pl = k4 - grp * NP;
-        ((float4*)xs)[pl * Kg + grp] = v;
-    }
-    ss = wave_sum(ss);
-    if (lane == 0) red[wave] = ss;
-    __syncthreads();
-    const float nscale = a.gain ? rsqrtf((red[0] + red[1] + red[2] + red[3]) / (float)K + g.eps) : 1.f;
+    VecSource vs{a.x, a.gain, a.part_acc, a.part_ml, a.merge_nsplit, a.merge_dh, a.merge_hq};
+    const float ssq = stage_vector<WT>((float4*)xs, Kg, vs, K, Kg, 0, false, red);
+    const float nscale = a.gain ? rsqrtf(ssq / (float)K + g.eps) : 1.f;
 
     for (int it = 0; it < iters; ++it) {
         int rA[NU], rB[NU], uu[NU];
@@ -187,6 +177,7 @@ struct AttnArgs {
     float* part_ml;         // [Hq][nsplit][2]
     int32_t* counters;      // [Hkv], zero between launches
     int32_t nsplit;
+    int32_t defer_merge;    // 1: leave the partials to the O projection (no merge here, even for one split)
 };
 
 template <typename KVT, int DH, int G, bool PAIR>
@@ -217,14 +208,14 @@ __global__ __launch_bounds__(256) void k_attn_decode(AttnArgs a, Geom g) {
 #pragma unroll
         for (int hh = 1; hh < G; ++hh) if (hh == h) { M = mh[hh]; L = lh[hh]; }
         const int hq = kvh * G + h;
-        if (nsplit == 1) {
+        if (nsplit == 1 && !a.defer_merge) {
             a.o[hq * DH + dim] = A / L;
         } else {
             a.part_acc[((size_t)hq * nsplit + split) * DH + dim] = A;
             if (dim == 0) { a.part_ml[((size_t)hq * nsplit + split) * 2] = M; a.part_ml[((size_t)hq * nsplit + split) * 2 + 1] = L; }
         }
     }
-    if (nsplit == 1) return;
+    if (nsplit == 1 || a.defer_merge) return;
 
     // the workgroup that finishes last for this kv head merges the splits, in split order
     __threadfence();
@@ -361,7 +352,7 @@ static hipError_t set_lds_t(int bytes) {
 
 hipError_t decode_init(int dtype, int max_k) {
     const int bytes = max_k * (int)sizeof(float);
-    if (bytes <= 64 * 1024) return hipSuccess;
+    if (bytes <= 48 * 1024) return hipSuccess;
     hipError_t e;
     if (dtype == 0) {
         if ((e = set_lds_t<float, EPI_STORE>(bytes))) return e;
@@ -402,10 +393,15 @@ hipError_t launch_qkv(int dtype, const void* wqkv, const float* gain, void* kv_l
     return launch_gemv(dtype, EPI_QKV, a, g, s);
 }
 
-hipError_t launch_oproj(int dtype, const void* wo, const DecodeBuffers& b, const Geom& g, hipStream_t s) {
+hipError_t launch_oproj(int dtype, const void* wo, int merge_nsplit, const DecodeBuffers& b, const Geom& g, hipStream_t s) {
     GemvArgs a{};
     a.W = wo; a.rows = g.d; a.K = g.Hq * g.dh; a.units = (a.rows + 1) / 2;
     a.x = b.o; a.gain = nullptr; a.y = b.x; a.res = b.x; a.step = b.step;
+    if (merge_nsplit > 0) {
+        if (merge_nsplit > MERGE_MAX_SPLIT) return hipErrorInvalidValue;
+        a.x = nullptr; a.part_acc = b.part_acc; a.part_ml = b.part_ml;
+        a.merge_nsplit = merge_nsplit; a.merge_dh = g.dh; a.merge_hq = g.Hq;
+    }
     return launch_gemv(dtype, EPI_RESID, a, g, s);
 }
 
@@ -453,8 +449,10 @@ static hipError_t launch_attn_t(const AttnArgs& a, const Geom& g, hipStream_t s)
     return hipGetLastError();
 }
 
-hipError_t launch_attn_decode(int dtype, const void* kv_layer, int nsplit, const DecodeBuffers& b, const Geom& g, hipStream_t s) {
+hipError_t launch_attn_decode(int dtype, const void* kv_layer, int nsplit, bool merge_in_oproj, const DecodeBuffers& b,
+                              const Geom& g, hipStream_t s) {
     AttnArgs a{};
+    a.defer_merge = merge_in_oproj ? 1 : 0;
     a.q = b.q; a.kv_layer = kv_layer; a.step = b.step; a.o = b.o;
     a.part_acc = b.part_acc; a.part_ml = b.part_ml; a.counters = b.attn_counters; a.nsplit = nsplit;
     if (dtype == 0) return g.dh == 64 ? launch_attn_t<float, 64, false>(a, g, s) : launch_attn_t<float, 128, false>(a, g, s);

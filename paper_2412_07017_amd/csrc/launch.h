@@ -50,7 +50,7 @@ struct ChunkBuffers {
 struct FusedPlan {
     bool supported;
     int grid;           // workgroups = compute units
-    int nsplit;         // attention splits per kv head
+    int nsplit;         // largest number of attention splits per kv head
     int xs_groups;      // LDS capacity of the staged vector
     int done_cap;       // finished units a wave can park in LDS
     size_t lds_bytes;
@@ -60,6 +60,7 @@ struct FusedLaunch {
     int n_layers;
     const void* embed; const float* final_norm; const void* lm_head;
     int seq, forced; bool with_head;
+    int nsplit; bool merge_in_stage;   // attention splits of this step; merged by the O projection's staging if set
     float* logits;              // of this sequence
     unsigned* bar;              // FUSED_BAR_WORDS words, zero at create
     void* trace;                // optional device buffer of 64-bit time stamps [FUSED_TRACE_MAX][grid]
@@ -87,9 +88,10 @@ hipError_t launch_begin_step(const DecodeBuffers& b, int seq, int forced, hipStr
 hipError_t launch_embed(int dtype, const void* E, const DecodeBuffers& b, const Geom& g, hipStream_t s);
 hipError_t launch_qkv(int dtype, const void* wqkv, const float* gain, void* kv_layer, const DecodeBuffers& b,
                       const Geom& g, hipStream_t s);
-hipError_t launch_attn_decode(int dtype, const void* kv_layer, int nsplit, const DecodeBuffers& b, const Geom& g,
-                              hipStream_t s);
-hipError_t launch_oproj(int dtype, const void* wo, const DecodeBuffers& b, const Geom& g, hipStream_t s);
+// merge_in_oproj: the attention only leaves per-split partials and the O projection merges them (nsplit <= 8)
+hipError_t launch_attn_decode(int dtype, const void* kv_layer, int nsplit, bool merge_in_oproj, const DecodeBuffers& b,
+                              const Geom& g, hipStream_t s);
+hipError_t launch_oproj(int dtype, const void* wo, int merge_nsplit, const DecodeBuffers& b, const Geom& g, hipStream_t s);
 hipError_t launch_gateup(int dtype, const void* wgu, const float* gain, const DecodeBuffers& b, const Geom& g,
                          hipStream_t s);
 hipError_t launch_down(int dtype, const void* wd, const DecodeBuffers& b, const Geom& g, hipStream_t s);
