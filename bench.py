@@ -37,6 +37,7 @@ def parse():
     ap.add_argument("--layers", type=int, default=0, help="truncate the model (0 = full depth); for experiments only")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--chunk", type=int, default=0, help="override the library's rows per forward pass for prefill/inject")
+    ap.add_argument("--opt", action="append", default=[], help="library option name=value (repeatable), for experiments")
     ap.add_argument("--fused", type=int, default=-1, help="1/0: force the single-kernel / per-operation decoding step (default: library's choice)")
     return ap.parse_args()
 
@@ -119,6 +120,9 @@ def main():
         lm.set_option("chunk", args.chunk)
     if args.fused >= 0:
         lm.set_option("fused", args.fused)
+    for kv in args.opt:
+        k, v = kv.split("=")
+        lm.set_option(k, int(v))
     t0 = time.perf_counter()
     lm.prefill(0, spec["prompt"])
     lm.synchronize()

@@ -536,6 +536,7 @@ int asynclm_set_option(asynclm_ctx* c, const char* name, int32_t value) {
     if (!c || !name) return ASYNCLM_E_INVAL;
     if (!std::strcmp(name, "chunk")) { if (value < 1 || value > CHUNK_MAX) return ASYNCLM_E_INVAL; c->opt_chunk = value; return ASYNCLM_OK; }
     if (!std::strcmp(name, "chunk_split")) { if (value < 0 || value > CHUNK_GEMM_MAX_SPLIT) return ASYNCLM_E_INVAL; c->opt_chunk_split = value; return ASYNCLM_OK; }
+    if (!std::strcmp(name, "gemv_grid")) { if (value < 1 || value > 4096) return ASYNCLM_E_INVAL; decode_set_gemv_grid(value); return ASYNCLM_OK; }
     if (!std::strcmp(name, "fused")) { c->opt_fused = (value && c->fused.supported) ? 1 : 0; return ASYNCLM_OK; }
     if (!std::strcmp(name, "graph")) { c->opt_graph = (value && c->stream) ? 1 : 0; return ASYNCLM_OK; }
     if (!std::strcmp(name, "attn_split")) { if (value < 0 || value > ATTN_MAX_SPLIT) return ASYNCLM_E_INVAL; c->opt_attn_split = value; return ASYNCLM_OK; }

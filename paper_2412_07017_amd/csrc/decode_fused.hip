@@ -21,7 +21,6 @@
 namespace asynclm {
 
 constexpr unsigned BARRIER_SPIN_LIMIT = 1u << 22;   // polls before a workgroup gives up (about a second)
-constexpr int RING = 4;
 
 struct FusedLayer {
     const float* attn_norm; const void* wqkv; const void* wo;
@@ -99,185 +98,6 @@ __device__ __forceinline__ bool grid_wait(unsigned* bar, unsigned epoch, int* s_
 // ---------------------------------------------------------------------------------------------
 // matrix-vector phase
 // ---------------------------------------------------------------------------------------------
-
-template <typename WT>
-struct Phase {
-    const WT* W;
-    int rows, K, Kg, KT, units, u0, u1;   // this wave owns units [u0, u1)
-};
-
-struct Cursor { int u, kt; };
-
-// One ring slot: a tile of weights (2 rows x 4 k-steps) plus the two values the unit's epilogue needs
-// from memory (residual pair, or rotary cos / sin).  They are requested with the tile, because a load
-// issued at epilogue time could only be waited for together with every tile load issued before it.
-struct Slot {
-    uint4 v[8];
-    float e0, e1;
-};
-
-template <typename WT, int EPI>
-__device__ __forceinline__ Phase<WT> make_phase(const void* W, int rows, int K, int units) {
-    Phase<WT> p;
-    p.W = (const WT*)W; p.rows = rows; p.K = K; p.Kg = K / Elem<WT>::EPL;
-    p.KT = (p.Kg + 255) / 256; p.units = units;
-    const long long gw = (long long)blockIdx.x * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), tw = (long long)gridDim.x * 4;
-    p.u0 = (int)(units * gw / tw); p.u1 = (int)(units * (gw + 1) / tw);
-    return p;
-}
-
-__device__ __forceinline__ void advance(Cursor& c, int KT) {
-    if (++c.kt == KT) { c.kt = 0; ++c.u; }
-}
-
-// Requests tile (c.u, c.kt): rows (rA, rB) of the unit, k-steps 4 kt .. 4 kt + 3.  Past the end of the
-// wave's range the last tile is requested again (a cache hit); addresses always stay inside W.
-template <typename WT, int EPI>
-__device__ __forceinline__ void tile_load(Slot& sl, const Phase<WT>& p, const Cursor& c, int lane, const Geom& g, const EpiOut& eo) {
-    uint4 (&v)[8] = sl.v;
-    constexpr int EPL = Elem<WT>::EPL;
-    const bool past = c.u >= p.u1;
-    const int u = past ? max(min(p.u1, p.units) - 1, 0) : c.u;
-    const int kt = past ? p.KT - 1 : c.kt;
-    int rA, rB;
-    unit_rows<EPI>(u, p.rows, g, rA, rB);
-    const WT* pa = p.W + (size_t)rA * p.K;
-    const WT* pb = p.W + (size_t)rB * p.K;
-#pragma unroll
-    for (int s = 0; s < 4; ++s) {
-        const int gi = min((kt * 4 + s) * 64 + lane, p.Kg - 1);
-        v[2 * s] = load16_stream(pa + (size_t)gi * EPL);
-        v[2 * s + 1] = load16_stream(pb + (size_t)gi * EPL);
-    }
-    if (EPI == EPI_RESID) {
-        sl.e0 = load_f32(eo.res + rA); sl.e1 = load_f32(eo.res + rB);
-    } else if (EPI == EPI_QKV) {
-        const int hs = g.dh == 128 ? 6 : 5, h = u >> hs, i = u & ((1 << hs) - 1);
-        const bool rot = h < g.Hq + g.Hkv;                         // value rows are not rotated
-        const size_t ri = ((size_t)eo.pos << hs) + i;
-        const float c = load_f32(eo.rope_cos + ri), sn = load_f32(eo.rope_sin + ri);
-        sl.e0 = rot ? c : 1.f; sl.e1 = rot ? sn : 0.f;
-    } else { sl.e0 = 0.f; sl.e1 = 0.f; }
-}
-
-// Epilogue of unit u, by one lane: sa, sb are the finished dot products, e0 / e1 the slot's operands.
-template <typename WT, int EPI>
-__device__ __forceinline__ void finish_unit(int u, float sa, float sb, float e0, float e1, const EpiOut& o, const Geom& g) {
-    if (EPI == EPI_STORE) {
-        o.y[2 * u] = sa;
-        if (2 * u + 1 < o.rows) o.y[2 * u + 1] = sb;
-    } else if (EPI == EPI_RESID) {
-        o.y[2 * u] = e0 + sa;
-        if (2 * u + 1 < o.rows) o.y[2 * u + 1] = e1 + sb;
-    } else if (EPI == EPI_SWIGLU) {
-        o.y[u] = sa / (1.f + expf(-sa)) * sb;
-    } else {
-        const int hs = g.dh == 128 ? 6 : 5, half = 1 << hs;
-        const int h = u >> hs, i = u & (half - 1);
-        const float ra = sa * e0 - sb * e1, rb = sb * e0 + sa * e1;
-        const size_t seq_off = (size_t)o.seq * g.kv_seq_stride;
-        if (h < g.Hq) { o.q_out[h * g.dh + i] = ra; o.q_out[h * g.dh + i + half] = rb; }
-        else if (h < g.Hq + g.Hkv) {
-            WT* kp = (WT*)o.kv_layer + seq_off + (size_t)(h - g.Hq) * g.kv_head_stride + (size_t)o.pos * g.dh;
-            kv_store(kp + i, ra, g.kv_lo_offset); kv_store(kp + i + half, rb, g.kv_lo_offset);
-        } else {
-            const size_t head_off = seq_off + (size_t)(h - g.Hq - g.Hkv) * g.kv_head_stride;
-            WT* vp = (WT*)o.kv_layer + g.kv_v_offset + head_off + (size_t)o.pos * g.dh;
-            kv_store(vp + i, ra, g.kv_lo_offset); kv_store(vp + i + half, rb, g.kv_lo_offset);
-            if (g.kv_vt_offset) {
-                WT* vt = (WT*)o.kv_layer + g.kv_vt_offset + head_off + o.pos;
-                kv_store(vt + (size_t)i * g.max_pos, ra, g.kv_lo_offset);
-                kv_store(vt + (size_t)(i + half) * g.max_pos, rb, g.kv_lo_offset);
-            }
-        }
-    }
-}
-
-// Multiplies one tile with the staged vector.  xs: planar LDS copy of x (plane p holds elements
-// 4p..4p+3 of every group of EPL), zero beyond Kg; tiles past the end read a block of zeros.
-template <typename WT>
-__device__ __forceinline__ void tile_fma(const uint4 (&v)[8], const float4* xs, int plane_stride, int zero_group,
-                                         bool past, int kt, int lane, float& accA, float& accB) {
-    constexpr int EPL = Elem<WT>::EPL;
-    constexpr int NP = EPL / 4;
-#pragma unroll
-    for (int s = 0; s < 4; ++s) {
-        const int gi = past ? zero_group + lane : (kt * 4 + s) * 64 + lane;
-        float xv[EPL], wa[EPL], wb[EPL];
-#pragma unroll
-        for (int pl = 0; pl < NP; ++pl) {
-            const float4 t = xs[pl * plane_stride + gi];
-            xv[4 * pl] = t.x; xv[4 * pl + 1] = t.y; xv[4 * pl + 2] = t.z; xv[4 * pl + 3] = t.w;
-        }
-        Elem<WT>::expand(v[2 * s], wa);
-        Elem<WT>::expand(v[2 * s + 1], wb);
-#pragma unroll
-        for (int e = 0; e < EPL; ++e) { accA = fmaf(wa[e], xv[e], accA); accB = fmaf(wb[e], xv[e], accB); }
-    }
-}
-
-// First RING tiles of a phase; issued before the grid barrier that precedes the phase.
-template <typename WT, int EPI>
-__device__ __forceinline__ void phase_prefetch(Slot (&ring)[RING], const Phase<WT>& p, Cursor& lc, int lane, const Geom& g,
-                                               const EpiOut& eo) {
-    lc.u = p.u0; lc.kt = 0;
-#pragma unroll
-    for (int j = 0; j < RING; ++j) {
-        tile_load<WT, EPI>(ring[j], p, lc, lane, g, eo);
-        advance(lc, p.KT);
-    }
-    __builtin_amdgcn_sched_barrier(0);
-}
-
-// Runs a phase whose first RING tiles are already in `ring`.  The loop only parks each finished unit
-// (two dot products and the slot's epilogue operands) in the wave's LDS area `done`; the epilogues, with
-// their global stores, run after the loop, one unit per lane.  Keeping every global memory instruction
-// of the loop unconditional lets the compiler count the outstanding loads exactly, so a tile is waited
-// for while the three younger ones stay in flight.
-// best_v / best_i: argmax of the stored values (EPI_STORE only), valid in every lane afterwards.
-template <typename WT, int EPI>
-__device__ __forceinline__ void phase_run(Slot (&ring)[RING], const Phase<WT>& p, Cursor& lc, const float4* xs,
-                                          int plane_stride, float nscale, const EpiOut& eo, const Geom& g, int lane,
-                                          float4* done, float& best_v, int& best_i) {
-    const int zero_group = plane_stride - 64;
-    const int T = (p.u1 - p.u0) * p.KT;
-    Cursor cc; cc.u = p.u0; cc.kt = 0;
-    float accA = 0.f, accB = 0.f;
-    for (int t = 0; t < T; t += RING) {
-#pragma unroll
-        for (int j = 0; j < RING; ++j) {
-            const bool past = cc.u >= p.u1;
-            tile_fma<WT>(ring[j].v, xs, plane_stride, zero_group, past, cc.kt, lane, accA, accB);
-            const float e0 = ring[j].e0, e1 = ring[j].e1;
-            __builtin_amdgcn_sched_barrier(0);
-            tile_load<WT, EPI>(ring[j], p, lc, lane, g, eo);
-            advance(lc, p.KT);
-            __builtin_amdgcn_sched_barrier(0);
-            if (!past && cc.kt == p.KT - 1) {
-                const float sa = wave_sum(accA) * nscale, sb = wave_sum(accB) * nscale;
-                if (lane == 0) done[cc.u - p.u0] = make_float4(sa, sb, e0, e1);
-                accA = 0.f; accB = 0.f;
-            }
-            advance(cc, p.KT);
-        }
-    }
-    for (int ul = lane; ul < p.u1 - p.u0; ul += 64) {
-        const float4 r = done[ul];          // written by lane 0 of this same wave
-        const int u = p.u0 + ul;
-        finish_unit<WT, EPI>(u, r.x, r.y, r.z, r.w, eo, g);
-        if (EPI == EPI_STORE) {
-            amax_merge(best_v, best_i, r.x, 2 * u);
-            if (2 * u + 1 < p.rows) amax_merge(best_v, best_i, r.y, 2 * u + 1);
-        }
-    }
-    if (EPI == EPI_STORE) {
-#pragma unroll
-        for (int o = 32; o > 0; o >>= 1) {
-            const float ov = __shfl_xor(best_v, o, 64); const int oi = __shfl_xor(best_i, o, 64);
-            amax_merge(best_v, best_i, ov, oi);
-        }
-    }
-}
 
 // ---------------------------------------------------------------------------------------------
 // the step

@@ -42,7 +42,7 @@ struct GemvArgs {
     const void* W;          // [rows, K] row-major
     int32_t rows, K;
     int32_t units;          // row pairs to compute
-    int32_t units_per_wg;   // multiple of 4 * NU
+    int32_t done_cap;       // finished row pairs a wave can park in LDS
     const float* x;         // [K] fp32 input vector
     const float* gain;      // [K] RMSNorm gain, or nullptr for no normalisation
     float* y;               // output (meaning depends on the epilogue)
@@ -57,111 +57,33 @@ struct GemvArgs {
     const float* part_acc; const float* part_ml; int32_t merge_nsplit, merge_dh, merge_hq;
 };
 
-template <typename WT, int EPI, int NU>
+// Every wave owns a contiguous share of the row pairs and streams them through a ring of four register
+// tiles (decode_device.h); the first tiles are requested before the input vector is staged.
+template <typename WT, int EPI>
 __global__ __launch_bounds__(256) void k_gemv(GemvArgs a, Geom g) {
     constexpr int EPL = Elem<WT>::EPL;
-    constexpr int NP = EPL / 4;       // LDS planes: element k lives in plane (k % EPL) / 4
-    constexpr int PRE = 2;            // k-steps of the first unit set fetched before x is staged
-    extern __shared__ float xs[];
+    extern __shared__ float4 lds4[];
     __shared__ float red[4];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int K = a.K, Kg = K / EPL;
-    const WT* W = (const WT*)a.W;
-    const int u_base = blockIdx.x * a.units_per_wg;
-    const int iters = a.units_per_wg / (4 * NU);
+    Phase<WT> ph = make_phase<WT, EPI>(a.W, a.rows, a.K, a.units);
+    const int plane_stride = ph.KT * 256 + 64;
+    float4* done = lds4 + (size_t)plane_stride * (EPL / 4) + (size_t)wave * a.done_cap;
 
-    // ---- issue the first weight loads; they do not depend on the activations
-    uint4 pre[NU][2][PRE];
-    {
-#pragma unroll
-        for (int j = 0; j < NU; ++j) {
-            int u = min(u_base + wave * NU + j, a.units - 1), rA, rB;
-            unit_rows<EPI>(u, a.rows, g, rA, rB);
-#pragma unroll
-            for (int s = 0; s < PRE; ++s) {
-                int gi = min(lane + s * 64, Kg - 1);
-                pre[j][0][s] = load16_stream(W + (size_t)rA * K + (size_t)gi * EPL);
-                pre[j][1][s] = load16_stream(W + (size_t)rB * K + (size_t)gi * EPL);
-            }
-        }
-    }
+    Slot ring[RING];
+    Cursor lc;
+    phase_prefetch_w<WT, EPI>(ring, ph, lane, g);
+    EpiOut eo;
+    eo.y = a.y; eo.res = a.res; eo.q_out = a.q_out; eo.kv_layer = a.kv_layer;
+    eo.rope_cos = a.rope_cos; eo.rope_sin = a.rope_sin; eo.rows = a.rows; eo.pos = 0; eo.seq = 0;
+    if (EPI == EPI_QKV) { eo.pos = a.step->pos; eo.seq = a.step->seq; }
+    phase_prefetch_e<WT, EPI>(ring, ph, lc, g, eo);
 
-    // ---- stage x (times the norm gain) into LDS, planar so that lanes read consecutive 16 B
     VecSource vs{a.x, a.gain, a.part_acc, a.part_ml, a.merge_nsplit, a.merge_dh, a.merge_hq};
-    const float ssq = stage_vector<WT>((float4*)xs, Kg, vs, K, Kg, 0, false, red);
-    const float nscale = a.gain ? rsqrtf(ssq / (float)K + g.eps) : 1.f;
-
-    for (int it = 0; it < iters; ++it) {
-        int rA[NU], rB[NU], uu[NU];
-        float accA[NU], accB[NU];
-#pragma unroll
-        for (int j = 0; j < NU; ++j) {
-            uu[j] = u_base + (it * 4 + wave) * NU + j;
-            unit_rows<EPI>(min(uu[j], a.units - 1), a.rows, g, rA[j], rB[j]);
-            accA[j] = 0.f; accB[j] = 0.f;
-        }
-        int g0 = lane;
-        if (it == 0) {
-#pragma unroll
-            for (int s = 0; s < PRE; ++s) {
-                const int gi = lane + s * 64;
-                if (gi < Kg) {
-                    float xv[EPL];
-#pragma unroll
-                    for (int p = 0; p < NP; ++p) {
-                        float4 t = ((const float4*)xs)[p * Kg + gi];
-                        xv[4 * p] = t.x; xv[4 * p + 1] = t.y; xv[4 * p + 2] = t.z; xv[4 * p + 3] = t.w;
-                    }
-#pragma unroll
-                    for (int j = 0; j < NU; ++j) {
-                        float wa[EPL], wb[EPL];
-                        Elem<WT>::expand(pre[j][0][s], wa);
-                        Elem<WT>::expand(pre[j][1][s], wb);
-#pragma unroll
-                        for (int e = 0; e < EPL; ++e) { accA[j] = fmaf(wa[e], xv[e], accA[j]); accB[j] = fmaf(wb[e], xv[e], accB[j]); }
-                    }
-                }
-            }
-            g0 = lane + PRE * 64;
-        }
-        const WT* pA[NU]; const WT* pB[NU];
-#pragma unroll
-        for (int j = 0; j < NU; ++j) { pA[j] = W + (size_t)rA[j] * K; pB[j] = W + (size_t)rB[j] * K; }
-#pragma unroll 4
-        for (int gi = g0; gi < Kg; gi += 64) {
-            uint4 va[NU], vb[NU];
-#pragma unroll
-            for (int j = 0; j < NU; ++j) {
-                va[j] = load16_stream(pA[j] + (size_t)gi * EPL);
-                vb[j] = load16_stream(pB[j] + (size_t)gi * EPL);
-            }
-            float xv[EPL];
-#pragma unroll
-            for (int p = 0; p < NP; ++p) {
-                float4 t = ((const float4*)xs)[p * Kg + gi];
-                xv[4 * p] = t.x; xv[4 * p + 1] = t.y; xv[4 * p + 2] = t.z; xv[4 * p + 3] = t.w;
-            }
-#pragma unroll
-            for (int j = 0; j < NU; ++j) {
-                float wa[EPL], wb[EPL];
-                Elem<WT>::expand(va[j], wa);
-                Elem<WT>::expand(vb[j], wb);
-#pragma unroll
-                for (int e = 0; e < EPL; ++e) { accA[j] = fmaf(wa[e], xv[e], accA[j]); accB[j] = fmaf(wb[e], xv[e], accB[j]); }
-            }
-        }
-#pragma unroll
-        for (int j = 0; j < NU; ++j) {
-            const float sa = wave_sum(accA[j]) * nscale, sb = wave_sum(accB[j]) * nscale;
-            if (lane != 0 || uu[j] >= a.units) continue;
-            EpiOut eo;
-            eo.y = a.y; eo.res = a.res; eo.q_out = a.q_out; eo.kv_layer = a.kv_layer;
-            eo.rope_cos = a.rope_cos; eo.rope_sin = a.rope_sin; eo.rows = a.rows;
-            if (EPI == EPI_QKV) { eo.pos = a.step->pos; eo.seq = a.step->seq; }
-            gemv_finish<WT, EPI>(uu[j], sa, sb, eo, g);
-        }
-    }
+    const float ssq = stage_vector<WT>(lds4, plane_stride, vs, a.K, ph.Kg, ph.KT, true, red);
+    const float nscale = a.gain ? rsqrtf(ssq / (float)a.K + g.eps) : 1.f;
+    float best_v = -INFINITY; int best_i = 0x7fffffff;
+    phase_run<WT, EPI>(ring, ph, lc, lds4, plane_stride, nscale, eo, g, lane, done, best_v, best_i);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -320,18 +242,16 @@ __global__ __launch_bounds__(256) void k_argmax(const float* __restrict__ logits
 // launchers
 // ---------------------------------------------------------------------------------------------
 
+static int g_gemv_grid = 256;       // workgroups per matrix-vector kernel; decode_init sets it to the number of compute units
+
 template <typename WT, int EPI>
 static hipError_t launch_gemv_t(const GemvArgs& a0, const Geom& g, hipStream_t s) {
-    constexpr int NU = 2;
     GemvArgs a = a0;
-    // units per workgroup: enough workgroups to cover the chip several times, few enough that
-    // staging x is amortised over many rows
-    int upw = 4 * NU;
-    while (upw < 64 && (a.units + upw * 2 - 1) / (upw * 2) >= 1024) upw *= 2;
-    a.units_per_wg = upw;
-    const int grid = (a.units + upw - 1) / upw;
-    const size_t lds = (size_t)a.K * sizeof(float);
-    hipLaunchKernelGGL((k_gemv<WT, EPI, NU>), dim3(grid), dim3(256), lds, s, a, g);
+    const int grid = g_gemv_grid;
+    a.done_cap = (a.units + grid * 4 - 1) / (grid * 4) + 1;
+    const int kg = a.K / Elem<WT>::EPL, kt = (kg + 255) / 256;
+    const size_t lds = (size_t)(kt * 256 + 64) * Elem<WT>::EPL * sizeof(float) + (size_t)4 * a.done_cap * sizeof(float4);
+    hipLaunchKernelGGL((k_gemv<WT, EPI>), dim3(grid), dim3(256), lds, s, a, g);
     return hipGetLastError();
 }
 
@@ -347,11 +267,18 @@ static hipError_t launch_gemv_w(int epi, const GemvArgs& a, const Geom& g, hipSt
 
 template <typename WT, int EPI>
 static hipError_t set_lds_t(int bytes) {
-    return hipFuncSetAttribute((const void*)(k_gemv<WT, EPI, 2>), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    return hipFuncSetAttribute((const void*)(k_gemv<WT, EPI>), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
 }
 
+void decode_set_gemv_grid(int grid) { g_gemv_grid = grid; }
+
 hipError_t decode_init(int dtype, int max_k) {
-    const int bytes = max_k * (int)sizeof(float);
+    {   // one workgroup per compute unit measured best: every workgroup stages the whole input vector
+        int dev = 0, cus = 0;
+        if (hipGetDevice(&dev) == hipSuccess && hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0)
+            g_gemv_grid = cus;
+    }
+    const int bytes = (max_k + 8 * 256 + 64 * 8) * (int)sizeof(float) + 64 * 1024;     // staged vector, padding, parked units
     if (bytes <= 48 * 1024) return hipSuccess;
     hipError_t e;
     if (dtype == 0) {

@@ -72,6 +72,7 @@ hipError_t launch_decode_fused(int dtype, const FusedPlan& plan, const FusedLaun
                                hipStream_t s);
 
 hipError_t decode_init(int dtype, int max_k);
+void decode_set_gemv_grid(int grid);
 hipError_t launch_begin_chunk(const DecodeBuffers& b, int seq, int rows, hipStream_t s);
 hipError_t launch_chunk_embed(const void* E, const ChunkBuffers& c, int rows, const Geom& g, hipStream_t s);
 hipError_t launch_chunk_resid_norm(const ChunkBuffers& c, bool add_partials, int S, int MT, const float* gain, int rows,
