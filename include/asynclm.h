@@ -111,6 +111,21 @@ int asynclm_decode_step(asynclm_ctx *ctx, int32_t seq, int32_t forced_token, int
  * token after the block.  Legal between any two decoding steps of a non-empty sequence. */
 int asynclm_inject_interrupt(asynclm_ctx *ctx, int32_t seq, const int32_t *tokens, int32_t k);
 
+/* One batched iteration over several sequences with ONE pass over the weights (Sec. 5.3: the interrupts that are
+ * queued when a step ends are appended to the just-generated tokens and processed in the next forward pass).
+ * For i in [0, nseq): sequence seqs[i] (all distinct, non-empty) gets the rows
+ *     [chosen token] ++ intr_tokens[intr_offsets[i] .. intr_offsets[i+1])
+ * where the chosen token is forced[i] if forced != NULL and forced[i] >= 0, else the greedy argmax of the
+ * sequence's current logits (device side).  All rows of all sequences go through the layers together (each
+ * row attends to its own sequence only); afterwards every sequence has valid logits for its next token.
+ * seqs, forced, intr_tokens, intr_offsets (nseq + 1 ascending entries; NULL = no interrupts) are host pointers.
+ * tokens_out (host, may be NULL): tokens_out[i] receives the token chosen for seqs[i]; NULL avoids the stream
+ * synchronisation.  More rows than one pass holds (96) are processed in several passes.
+ * Everything is validated before any state changes (ASYNCLM_E_INVAL / _STATE / _CAPACITY as for the
+ * single-sequence calls; a sequence may appear only once). */
+int asynclm_step_batch(asynclm_ctx *ctx, int32_t nseq, const int32_t *seqs, const int32_t *forced,
+                       const int32_t *intr_tokens, const int32_t *intr_offsets, int32_t *tokens_out);
+
 /* Copy the current next-token logits of `seq` (fp32) to out_host[0..n); n must equal vocab.
  * Synchronises the stream. */
 int asynclm_logits(asynclm_ctx *ctx, int32_t seq, float *out_host, int32_t n);
@@ -129,10 +144,11 @@ int asynclm_reset(asynclm_ctx *ctx, int32_t seq);
 int asynclm_synchronize(asynclm_ctx *ctx);
 
 /* Tuning knobs; all have working defaults.  Unknown names give ASYNCLM_E_INVAL.
- *   "chunk"        rows processed per forward pass by prefill / inject (1 .. 64); 1 = token by token
- *                  through the decode kernels.  Default 64 where the matrix-core append path applies
- *                  (bf16 model, paired cache, head_dim 128, d_model and ffn multiples of 256), else 1.
- *   "chunk_split"  0 = built-in split-K factors of the append path's products, 1..4 = force one
+ *   "chunk"        rows processed per forward pass by prefill / inject (1 .. 96); 1 = token by token
+ *                  through the decode kernels.  Default 96 where the matrix-core append path applies
+ *                  (bf16 model, paired cache, head_dim 128, d_model and ffn multiples of 128), else 1.
+ *   "chunk_split"  0 = split-K factors of the append path's products chosen from the shapes and the number
+ *                  of compute units, 1..8 = force one
  *   "fused"        1 = run a decoding step as one persistent cooperative kernel (where the device and the
  *                  model shape allow it; ignored otherwise), 0 = one kernel per operation (default)
  *   "graph"        (per-operation kernels only) 1 = replay decoding steps as a captured HIP graph,

@@ -12,7 +12,7 @@ KV_AUTO, KV_BF16 = 0, 1
 
 API_SYMBOLS = [
     "asynclm_create", "asynclm_destroy", "asynclm_prefill", "asynclm_decode_step",
-    "asynclm_inject_interrupt", "asynclm_logits", "asynclm_logits_device", "asynclm_seq_len",
+    "asynclm_inject_interrupt", "asynclm_step_batch", "asynclm_logits", "asynclm_logits_device", "asynclm_seq_len",
     "asynclm_reset", "asynclm_synchronize", "asynclm_set_option", "asynclm_profile_step", "asynclm_profile_trace",
     "asynclm_strerror", "asynclm_version",
 ]
@@ -150,6 +150,29 @@ class AsyncLM:
     def inject_interrupt(self, seq: int, tokens) -> None:
         t = _tok(tokens)
         self._check(self._lib.asynclm_inject_interrupt(self._h, seq, t.ctypes.data_as(C.POINTER(C.c_int32)), len(t)), "asynclm_inject_interrupt")
+
+    def step_batch(self, seqs, forced=None, interrupts=None, want_tokens: bool = True):
+        """interrupts: None, or one token list (possibly empty) per sequence."""
+        sq = _tok(seqs)
+        n = len(sq)
+        p32 = C.POINTER(C.c_int32)
+        fo = _tok(forced) if forced is not None else None
+        if fo is not None and len(fo) != n:
+            raise ValueError("forced needs one entry per sequence")
+        off = toks = None
+        if interrupts is not None:
+            if len(interrupts) != n:
+                raise ValueError("interrupts needs one entry per sequence")
+            lens = [len(x) for x in interrupts]
+            off = np.ascontiguousarray(np.concatenate([[0], np.cumsum(lens)]).astype(np.int32))
+            toks = _tok(np.concatenate([np.asarray(x, dtype=np.int32).reshape(-1) for x in interrupts]) if sum(lens) else [])
+        out = np.full(n, -1, dtype=np.int32)
+        self._check(self._lib.asynclm_step_batch(
+            self._h, n, sq.ctypes.data_as(p32), fo.ctypes.data_as(p32) if fo is not None else None,
+            toks.ctypes.data_as(p32) if toks is not None and len(toks) else None,
+            off.ctypes.data_as(p32) if off is not None else None,
+            out.ctypes.data_as(p32) if want_tokens else None), "asynclm_step_batch")
+        return out if want_tokens else None
 
     def logits(self, seq: int) -> "np.ndarray":
         out = np.empty(self.vocab, dtype=np.float32)

@@ -14,11 +14,42 @@
 
 using namespace asynclm;
 
+// Host-side builder of the row table of one pass.
+struct PassBuilder {
+    ChunkTable t{};
+    int G = 1, max_keys = 0;
+    void clear() { t.rows = t.ngroups = t.ntasks = t.nhead = 0; max_keys = 0; }
+    int tiles_of(int n) const { return (G * n + 31) / 32; }
+    bool fits(int n) const { return t.rows + n <= CHUNK_MAX && t.ntasks + tiles_of(n) <= CHUNK_MAX_TASKS; }
+    // Appends a group of n rows to sequence `seq` (length before: pos0).  forced: see ChunkGroup; `rest` holds the
+    // tokens of the rows that are not chosen on the device (n of them if forced == -2, else n - 1).
+    void add(int seq, int pos0, int n, int forced, const int32_t* rest, bool want_head) {
+        const int row0 = t.rows;
+        for (int r = 0; r < n; ++r) {
+            ChunkRow& R = t.row[row0 + r];
+            R = ChunkRow{};
+            R.token = forced == -2 ? rest[r] : (r == 0 ? 0 : rest[r - 1]);
+            R.seq = seq; R.pos = pos0 + r; R.row0 = row0; R.n = n;
+        }
+        ChunkGroup& Gp = t.group[t.ngroups++];
+        Gp = ChunkGroup{};
+        Gp.seq = seq; Gp.row0 = row0; Gp.n = n; Gp.pos0 = pos0; Gp.forced = forced; Gp.head = want_head ? t.nhead++ : -1;
+        for (int tile = 0; tile < tiles_of(n); ++tile) {
+            ChunkTask& T = t.task[t.ntasks++];
+            T = ChunkTask{};
+            T.seq = seq; T.row0 = row0; T.n = n; T.pos0 = pos0; T.tile = tile;
+        }
+        t.rows += n;
+        max_keys = std::max(max_keys, pos0 + n);
+    }
+};
+
+
 struct asynclm_ctx {
     asynclm_config cfg{};
     Geom g{};
     hipStream_t stream = nullptr;
-    int device = 0;
+    int device = 0, n_cu = 0;
     bool poisoned = false;
     hipError_t last_hip = hipSuccess;
 
@@ -42,6 +73,8 @@ struct asynclm_ctx {
     int32_t* token_host = nullptr;      // pinned, 1 int
 
     std::vector<int32_t> len;           // host mirror of the sequence lengths
+    PassBuilder pass;                   // row table of the append-chunk pass being built
+    int32_t* chosen_host = nullptr;     // pinned, CHUNK_MAX ints
 
     // options
     int opt_chunk = 1, opt_graph = 1, opt_attn_split = 0, opt_chunk_split = 0, opt_fused = 0;
@@ -228,49 +261,78 @@ int check_tokens(const asynclm_ctx* c, const int32_t* t, int32_t n) {
 // Split-K factors of the four products of a layer (workgroups = N/32 * S, each of 4 waves).
 struct ChunkSplits { int qkv, o, gu, down; };
 
-ChunkSplits chunk_splits(const asynclm_ctx* c) {
-    if (c->opt_chunk_split > 0) return {c->opt_chunk_split, c->opt_chunk_split, c->opt_chunk_split, c->opt_chunk_split};
-    return {2, 2, 1, 4};
+// A product with N output rows and K columns runs N/128 * S workgroups, one per compute unit at a time:
+// S = the split that comes closest to one workgroup per unit, with at least two 128-column blocks per workgroup.
+int pick_gemm_split(const asynclm_ctx* c, int N, int K) {
+    const int tiles = N / 128, nblk = K / 128;
+    int s = (c->n_cu + tiles / 2) / tiles;
+    s = std::min(s, std::min(CHUNK_GEMM_MAX_SPLIT, std::max(1, nblk / 2)));
+    s = std::max(s, 1);
+    if (c->opt_chunk_split > 0) s = std::min(c->opt_chunk_split, std::max(1, nblk));
+    return s;
 }
 
-int pick_chunk_attn_split(const asynclm_ctx* c, int keys) {
-    // about 4 key tiles (128 keys) per wave, at most CHUNK_ATTN_MAX_SPLIT, a multiple of 4
-    int n = 4;
-    while (n < CHUNK_ATTN_MAX_SPLIT && n * 128 < keys) n *= 2;
+ChunkSplits chunk_splits(const asynclm_ctx* c) {
+    const Geom& g = c->g;
+    return {pick_gemm_split(c, (g.Hq + 2 * g.Hkv) * g.dh, g.d), pick_gemm_split(c, g.d, g.Hq * g.dh),
+            pick_gemm_split(c, 2 * g.F, g.d), pick_gemm_split(c, g.d, g.F)};
+}
+
+// Key splits of the chunk attention: about two 32-key tiles per wave, a multiple of 4, within the capacity
+// of the partial-result buffers.
+int pick_chunk_attn_split(const asynclm_ctx* c, int max_keys, int ntasks) {
+    const int tiles = (max_keys + 31) / 32;
+    int n = ((tiles + 1) / 2 + 3) / 4 * 4;
+    n = std::max(4, std::min(n, CHUNK_ATTN_MAX_SPLIT));
+    while (n > 4 && (long long)ntasks * c->g.Hkv * n > CHUNK_ATTN_MAX_UNITS) n -= 4;
     return n;
 }
 
-// One forward pass over `rows` (2..CHUNK_MAX) tokens that are already in cb.tokens.
-hipError_t forward_chunk(asynclm_ctx* c, int seq, int rows, bool with_head) {
+// One forward pass over the rows of `pb` (1..CHUNK_MAX rows in any number of groups).  Groups that want logits
+// get them from the single-row head kernels (one group) or from one more product on the matrix cores (several).
+hipError_t forward_chunk(asynclm_ctx* c, const PassBuilder& pb) {
     const Geom& g = c->g;
     const ChunkBuffers& cb = c->cb;
     hipStream_t s = c->stream;
-    const int MT = (rows + 31) / 32;
+    const ChunkTable& t = pb.t;
+    const int rows = t.rows, MT = (rows + 31) / 32;
     const ChunkSplits sp = chunk_splits(c);
     const int nqkv = (g.Hq + 2 * g.Hkv) * g.dh, qd = g.Hq * g.dh;
-    const int asplit = pick_chunk_attn_split(c, c->len[seq] + rows);
+    const int asplit = pick_chunk_attn_split(c, pb.max_keys, t.ntasks);
+    const int dt = c->cfg.dtype;
     hipError_t e;
-    if ((e = run(c, KC_BEGIN, [&] { return launch_begin_chunk(c->b, seq, rows, s); }))) return e;
+    // pageable source: the runtime stages the table before the call returns
+    if ((e = hipMemcpyAsync(cb.tab, &t, sizeof(ChunkTable), hipMemcpyHostToDevice, s))) return e;
+    if ((e = run(c, KC_BEGIN, [&] { return launch_begin_chunk(cb, c->b, t.ngroups, s); }))) return e;
     if ((e = run(c, KC_CHUNK_PREP, [&] { return launch_chunk_embed(c->embed, cb, rows, g, s); }))) return e;
     for (int l = 0; l < c->cfg.n_layers; ++l) {
         void* kvl = kv_layer_ptr(c, l);
         if ((e = run(c, KC_CHUNK_PREP, [&] { return launch_chunk_resid_norm(cb, l > 0, sp.down, MT, c->attn_norm[l], rows, g, s); }))) return e;
         if ((e = run(c, KC_CHUNK_GEMM, [&] { return launch_chunk_gemm(c->wqkv[l], nqkv, g.d, cb.nrm_hi, cb.nrm_lo, cb, sp.qkv, MT, s); }))) return e;
         if ((e = run(c, KC_CHUNK_PREP, [&] { return launch_chunk_rope_kv(cb, sp.qkv, kvl, c->b, rows, MT, g, s); }))) return e;
-        if ((e = run(c, KC_CHUNK_ATTN, [&] { return launch_chunk_attn(cb, kvl, asplit, MT, c->b, g, s); }))) return e;
+        if ((e = run(c, KC_CHUNK_ATTN, [&] { return launch_chunk_attn(cb, kvl, asplit, t.ntasks, g, s); }))) return e;
         if ((e = run(c, KC_CHUNK_GEMM, [&] { return launch_chunk_gemm(c->wo[l], g.d, qd, cb.att_hi, cb.att_lo, cb, sp.o, MT, s); }))) return e;
         if ((e = run(c, KC_CHUNK_PREP, [&] { return launch_chunk_resid_norm(cb, true, sp.o, MT, c->ffn_norm[l], rows, g, s); }))) return e;
         if ((e = run(c, KC_CHUNK_GEMM, [&] { return launch_chunk_gemm(c->wgate_up[l], 2 * g.F, g.d, cb.nrm_hi, cb.nrm_lo, cb, sp.gu, MT, s); }))) return e;
         if ((e = run(c, KC_CHUNK_PREP, [&] { return launch_chunk_swiglu(cb, sp.gu, MT, rows, g, s); }))) return e;
         if ((e = run(c, KC_CHUNK_GEMM, [&] { return launch_chunk_gemm(c->wdown[l], g.d, g.F, cb.act_hi, cb.act_lo, cb, sp.down, MT, s); }))) return e;
     }
-    if (with_head) {
-        const int dt = c->cfg.dtype;
-        if ((e = run(c, KC_CHUNK_MISC, [&] { return launch_chunk_last_row(cb, sp.down, MT, c->b, g, s); }))) return e;
-        if ((e = run(c, KC_LMHEAD, [&] { return launch_lmhead(dt, c->lm_head, c->final_norm, c->logits + (size_t)seq * g.V, c->b, g, s); }))) return e;
-        if ((e = run(c, KC_ARGMAX, [&] { return launch_argmax(c->logits, c->b, g, s); }))) return e;
+    const bool head_on_mfma = t.nhead > 1 && g.V % 128 == 0 && (size_t)((t.nhead + 31) / 32) * 32 * g.V <= cb.part_capacity;
+    if (head_on_mfma) {
+        const int MTh = (t.nhead + 31) / 32;
+        if ((e = run(c, KC_CHUNK_MISC, [&] { return launch_chunk_head_rows(cb, sp.down, MT, c->final_norm, t.ngroups, g, s); }))) return e;
+        if ((e = run(c, KC_LMHEAD, [&] { return launch_chunk_gemm(c->lm_head, g.V, g.d, cb.nrm_hi, cb.nrm_lo, cb, 1, MTh, s); }))) return e;
+        if ((e = run(c, KC_ARGMAX, [&] { return launch_chunk_logits(cb, MTh, c->logits, c->b, t.ngroups, g, s); }))) return e;
+    } else {
+        for (int gi = 0; gi < t.ngroups; ++gi) {
+            if (t.group[gi].head < 0) continue;
+            const int seq = t.group[gi].seq;
+            if ((e = run(c, KC_CHUNK_MISC, [&] { return launch_chunk_last_row(cb, sp.down, MT, gi, c->b, g, s); }))) return e;
+            if ((e = run(c, KC_LMHEAD, [&] { return launch_lmhead(dt, c->lm_head, c->final_norm, c->logits + (size_t)seq * g.V, c->b, g, s); }))) return e;
+            if ((e = run(c, KC_ARGMAX, [&] { return launch_argmax(c->logits, c->b, g, s); }))) return e;
+        }
     }
-    c->len[seq] += rows;
+    for (int gi = 0; gi < t.ngroups; ++gi) c->len[t.group[gi].seq] = t.group[gi].pos0 + t.group[gi].n;
     return hipSuccess;
 }
 
@@ -284,9 +346,10 @@ int append_tokens(asynclm_ctx* c, int seq, const int32_t* tokens, int n) {
         if (rows == 1) {
             HIPCK(c, step_one_token(c, seq, tokens[i], last));
         } else {
-            // pageable source: the runtime stages the ids before the call returns
-            HIPCK(c, hipMemcpyAsync(c->cb.tokens, tokens + i, sizeof(int32_t) * rows, hipMemcpyHostToDevice, c->stream));
-            HIPCK(c, forward_chunk(c, seq, rows, last));
+            PassBuilder& pb = c->pass;
+            pb.clear();
+            pb.add(seq, c->len[seq], rows, -2, tokens + i, last);
+            HIPCK(c, forward_chunk(c, pb));
         }
         i += rows;
     }
@@ -315,6 +378,9 @@ int asynclm_create(asynclm_ctx** out, const asynclm_config* cfg, const asynclm_w
     c->stream = (hipStream_t)hip_stream;
     if (!c->stream) c->opt_graph = 0;   // the null stream cannot be captured
     if ((e0 = hipGetDevice(&c->device)) != hipSuccess) { report_hip("hipGetDevice", e0); delete c; return ASYNCLM_E_DEVICE; }
+    if ((e0 = hipDeviceGetAttribute(&c->n_cu, hipDeviceAttributeMultiprocessorCount, c->device)) != hipSuccess || c->n_cu < 1) {
+        report_hip("hipDeviceGetAttribute", e0); delete c; return ASYNCLM_E_DEVICE;
+    }
 
     c->embed = w->embed; c->final_norm = w->final_norm; c->lm_head = w->lm_head;
     for (int l = 0; l < cfg->n_layers; ++l) {
@@ -330,7 +396,7 @@ int asynclm_create(asynclm_ctx** out, const asynclm_config* cfg, const asynclm_w
     {
         const bool pair = cfg->dtype == ASYNCLM_DTYPE_BF16 && cfg->kv_format != ASYNCLM_KV_BF16;
         // the matrix-core append path: bf16 weights, paired cache, head_dim 128, 128-aligned inner sizes
-        c->chunk_ok = pair && g.dh == 128 && g.d % 256 == 0 && g.F % 256 == 0 && (g.Hq * g.dh) % 256 == 0;
+        c->chunk_ok = pair && g.dh == 128 && g.d % 128 == 0 && g.F % 128 == 0 && g.d <= 8192;
         const size_t plane = (size_t)g.max_pos * g.dh * g.Hkv;
         g.kv_head_stride = (size_t)g.max_pos * g.dh;
         g.kv_lo_offset = pair ? plane : 0;
@@ -368,23 +434,27 @@ int asynclm_create(asynclm_ctx** out, const asynclm_config* cfg, const asynclm_w
         ChunkBuffers& cb = c->cb;
         const size_t M = CHUNK_MAX, qd = (size_t)g.Hq * g.dh;
         // split-K partial planes: up to CHUNK_GEMM_MAX_SPLIT planes of the widest product
-        const size_t nmax = CHUNK_GEMM_MAX_SPLIT * std::max(std::max((size_t)2 * g.F, (size_t)(g.Hq + 2 * g.Hkv) * g.dh), (size_t)g.d);
+        const size_t nmax = std::max((size_t)g.V, CHUNK_GEMM_MAX_SPLIT * std::max(std::max((size_t)2 * g.F, (size_t)(g.Hq + 2 * g.Hkv) * g.dh), (size_t)g.d));
         cb.part_capacity = M * nmax;
-        const size_t tasks = (size_t)g.Hq * (CHUNK_MAX / 32);
-        ALLOC(cb.tokens, M);
+        if ((e = chunk_init()) != hipSuccess) { report_hip("chunk_init", e); return bail(ASYNCLM_E_DEVICE); }
+        cb.q_cols = (g.Hq / g.Hkv) * CHUNK_MAX + 32;
+        const size_t qn = (size_t)g.Hkv * cb.q_cols * g.dh;
+        c->pass.G = g.Hq / g.Hkv;
+        ALLOC(cb.tab, 1);
+        ALLOC(cb.chosen, M);
         ALLOC(cb.x, M * g.d);
         ALLOC(cb.nrm_hi, M * g.d); ALLOC(cb.nrm_lo, M * g.d);
         ALLOC(cb.att_hi, M * qd); ALLOC(cb.att_lo, M * qd);
         ALLOC(cb.act_hi, M * g.F); ALLOC(cb.act_lo, M * g.F);
-        ALLOC(cb.q_hi, M * qd); ALLOC(cb.q_lo, M * qd);
+        ALLOC(cb.q_hi, qn); ALLOC(cb.q_lo, qn);
         ALLOC(cb.part, M * nmax);
-        ALLOC(cb.attn_o, tasks * CHUNK_ATTN_MAX_SPLIT * g.dh * 32);
-        ALLOC(cb.attn_ml, tasks * CHUNK_ATTN_MAX_SPLIT * 64);
+        ALLOC(cb.attn_o, (size_t)CHUNK_ATTN_MAX_UNITS * g.dh * 32);
+        ALLOC(cb.attn_ml, (size_t)CHUNK_ATTN_MAX_UNITS * 64);
         // rows beyond the current chunk are multiplied into discarded columns only, but must stay finite
-        if (hipMemset(cb.tokens, 0, M * 4) || hipMemset(cb.x, 0, M * g.d * 4) || hipMemset(cb.nrm_hi, 0, M * g.d * 2) ||
+        if (hipMemset(cb.tab, 0, sizeof(ChunkTable)) || hipMemset(cb.chosen, 0, M * 4) || hipMemset(cb.x, 0, M * g.d * 4) || hipMemset(cb.nrm_hi, 0, M * g.d * 2) ||
             hipMemset(cb.nrm_lo, 0, M * g.d * 2) || hipMemset(cb.att_hi, 0, M * qd * 2) || hipMemset(cb.att_lo, 0, M * qd * 2) ||
-            hipMemset(cb.act_hi, 0, M * g.F * 2) || hipMemset(cb.act_lo, 0, M * g.F * 2) || hipMemset(cb.q_hi, 0, M * qd * 2) ||
-            hipMemset(cb.q_lo, 0, M * qd * 2))
+            hipMemset(cb.act_hi, 0, M * g.F * 2) || hipMemset(cb.act_lo, 0, M * g.F * 2) || hipMemset(cb.q_hi, 0, qn * 2) ||
+            hipMemset(cb.q_lo, 0, qn * 2))
             return bail(ASYNCLM_E_DEVICE);
     }
     // cache rows that were never written are read (and masked) by the chunk attention: keep them finite
@@ -417,6 +487,7 @@ int asynclm_create(asynclm_ctx** out, const asynclm_config* cfg, const asynclm_w
         hipMemset(c->b.step, 0, sizeof(StepDesc)) != hipSuccess || hipMemset(c->b.token_log, 0, 2 * sizeof(int32_t)) != hipSuccess)
         return bail(ASYNCLM_E_DEVICE);
     if (hipHostMalloc((void**)&c->token_host, 64, hipHostMallocDefault) != hipSuccess) return bail(ASYNCLM_E_NOMEM);
+    if (hipHostMalloc((void**)&c->chosen_host, sizeof(int32_t) * CHUNK_MAX, hipHostMallocDefault) != hipSuccess) return bail(ASYNCLM_E_NOMEM);
     // fused decoding step: pointer table, barrier counters, launch plan
     {
         std::vector<const void*> tab;
@@ -451,6 +522,7 @@ int asynclm_destroy(asynclm_ctx* c) {
     for (hipEvent_t ev : c->prof_events) hipEventDestroy(ev);
     for (void* p : c->allocs) hipFree(p);
     if (c->token_host) hipHostFree(c->token_host);
+    if (c->chosen_host) hipHostFree(c->chosen_host);
     delete c;
     return ASYNCLM_OK;
 }
@@ -487,6 +559,97 @@ int asynclm_inject_interrupt(asynclm_ctx* c, int32_t seq, const int32_t* tokens,
     if (c->len[seq] == 0) return ASYNCLM_E_STATE;
     if ((int64_t)c->len[seq] + k > c->cfg.max_positions) return ASYNCLM_E_CAPACITY;
     return append_tokens(c, seq, tokens, k);
+}
+
+int asynclm_step_batch(asynclm_ctx* c, int32_t nseq, const int32_t* seqs, const int32_t* forced, const int32_t* intr_tokens,
+                       const int32_t* intr_offsets, int32_t* tokens_out) {
+    if (!c) return ASYNCLM_E_INVAL;
+    if (c->poisoned) return ASYNCLM_E_DEVICE;
+    if (nseq < 1 || nseq > c->cfg.max_seqs || !seqs) return ASYNCLM_E_INVAL;
+    // everything is checked before anything is enqueued
+    {
+        std::vector<char> seen(c->cfg.max_seqs, 0);
+        for (int i = 0; i < nseq; ++i) {
+            const int q = seqs[i];
+            if (q < 0 || q >= c->cfg.max_seqs || seen[q]) return ASYNCLM_E_INVAL;
+            seen[q] = 1;
+            if (forced && forced[i] >= c->cfg.vocab) return ASYNCLM_E_INVAL;
+            if (intr_offsets && intr_offsets[i + 1] < intr_offsets[i]) return ASYNCLM_E_INVAL;
+        }
+        if (intr_offsets && intr_offsets[0] < 0) return ASYNCLM_E_INVAL;
+        if (intr_offsets && intr_offsets[nseq] > intr_offsets[0] && !intr_tokens) return ASYNCLM_E_INVAL;
+        if (intr_offsets)
+            for (int j = intr_offsets[0]; j < intr_offsets[nseq]; ++j)
+                if (intr_tokens[j] < 0 || intr_tokens[j] >= c->cfg.vocab) return ASYNCLM_E_INVAL;
+        for (int i = 0; i < nseq; ++i)
+            if (c->len[seqs[i]] == 0) return ASYNCLM_E_STATE;
+        for (int i = 0; i < nseq; ++i) {
+            const int64_t k = intr_offsets ? intr_offsets[i + 1] - intr_offsets[i] : 0;
+            if ((int64_t)c->len[seqs[i]] + 1 + k > c->cfg.max_positions) return ASYNCLM_E_CAPACITY;
+        }
+    }
+    auto forced_of = [&](int i) { return forced && forced[i] >= 0 ? forced[i] : -1; };
+    if (nseq == 1 && (!intr_offsets || intr_offsets[1] == intr_offsets[0]))
+        return asynclm_decode_step(c, seqs[0], forced_of(0), tokens_out);      // one row: the single-row kernels
+
+    if (!c->chunk_ok) {
+        // models outside the matrix-core append path: the same result sequence by sequence through the single-row kernels
+        for (int i = 0; i < nseq; ++i) {
+            const int k = intr_offsets ? intr_offsets[i + 1] - intr_offsets[i] : 0;
+            HIPCK(c, step_one_token(c, seqs[i], forced_of(i), k == 0));
+            if (tokens_out) {
+                HIPCK(c, hipMemcpyAsync(c->token_host, c->b.token_log, 2 * sizeof(int32_t), hipMemcpyDeviceToHost, c->stream));
+                HIPCK(c, hipStreamSynchronize(c->stream));
+                if (c->token_host[1]) return fail_device(c, hipErrorLaunchFailure);
+                tokens_out[i] = c->token_host[0];
+            }
+            if (k > 0) {
+                const int r = append_tokens(c, seqs[i], intr_tokens + intr_offsets[i], k);
+                if (r) return r;
+            }
+        }
+        return ASYNCLM_OK;
+    }
+
+    // One weight pass per CHUNK_MAX rows: groups are packed in the order given; a group that does not fit is
+    // continued in the next pass (its later rows see its earlier ones through the cache).
+    PassBuilder& pb = c->pass;
+    std::vector<int> owner;                 // group of the current pass -> index i whose token it chooses, or -1
+    auto flush = [&]() -> int {
+        if (pb.t.rows == 0) return ASYNCLM_OK;
+        const int ng = pb.t.ngroups;
+        HIPCK(c, forward_chunk(c, pb));
+        if (tokens_out) {
+            HIPCK(c, hipMemcpyAsync(c->chosen_host, c->cb.chosen, sizeof(int32_t) * ng, hipMemcpyDeviceToHost, c->stream));
+            HIPCK(c, hipStreamSynchronize(c->stream));
+            for (int gi = 0; gi < ng; ++gi)
+                if (owner[gi] >= 0) tokens_out[owner[gi]] = c->chosen_host[gi];
+        }
+        pb.clear();
+        owner.clear();
+        return ASYNCLM_OK;
+    };
+    pb.clear();
+    for (int i = 0; i < nseq; ++i) {
+        const int q = seqs[i];
+        const int k = intr_offsets ? intr_offsets[i + 1] - intr_offsets[i] : 0;
+        const int32_t* it = k ? intr_tokens + intr_offsets[i] : nullptr;
+        int done = 0;                       // rows of this sequence already placed (the chosen token is row 0)
+        const int total = 1 + k;
+        while (done < total) {
+            int space = CHUNK_MAX - pb.t.rows;
+            if (space == 0 || !pb.fits(1)) { const int r = flush(); if (r) return r; space = CHUNK_MAX; }
+            int n = std::min(space, total - done);
+            while (n > 1 && !pb.fits(n)) --n;
+            const int pos0 = c->len[q];     // rows placed by earlier passes are already counted
+            if (done == 0) pb.add(q, pos0, n, forced_of(i), it, done + n == total);
+            else pb.add(q, pos0, n, -2, it + (done - 1), done + n == total);
+            owner.push_back(done == 0 ? i : -1);
+            done += n;
+            if (done < total) { const int r = flush(); if (r) return r; }
+        }
+    }
+    return flush();
 }
 
 int asynclm_logits(asynclm_ctx* c, int32_t seq, float* out_host, int32_t n) {

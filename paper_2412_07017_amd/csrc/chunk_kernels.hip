@@ -46,20 +46,93 @@ __device__ __forceinline__ size_t tiled_off(int m, int k, int K) {
 // bookkeeping and small row-wise kernels
 // ---------------------------------------------------------------------------------------------
 
-__global__ void k_begin_chunk(StepDesc* step, SeqState* st, int32_t seq, int32_t rows) {
-    if (threadIdx.x == 0 && blockIdx.x == 0) {
-        const int32_t len = st[seq].len;
-        step->token = -1; step->pos = len; step->seq = seq; step->rows = rows;
-        st[seq].len = len + rows;
+// Resolves the tokens that are chosen on the device (first row of a group), records them, moves the
+// sequence lengths, and fills the step descriptor that the single-row head kernels read.
+__global__ void k_begin_chunk(ChunkTable* tab, StepDesc* step, SeqState* st, int32_t* chosen) {
+    const int ng = tab->ngroups;
+    for (int gi = threadIdx.x; gi < ng; gi += blockDim.x) {
+        const ChunkGroup G = tab->group[gi];
+        if (G.forced != -2) {
+            const int32_t tok = G.forced >= 0 ? G.forced : st[G.seq].next_token;
+            tab->row[G.row0].token = tok;
+            chosen[gi] = tok;
+        }
+        st[G.seq].len = G.pos0 + G.n;
+    }
+    if (threadIdx.x == 0) {
+        step->token = -1; step->pos = tab->group[0].pos0; step->seq = tab->group[0].seq; step->rows = tab->rows;
     }
 }
 
 // x[m][:] = E[token_m][:]   (one workgroup per row)
-__global__ __launch_bounds__(256) void k_chunk_embed(const bf16_t* __restrict__ E, const int32_t* __restrict__ tokens,
+__global__ __launch_bounds__(256) void k_chunk_embed(const bf16_t* __restrict__ E, const ChunkTable* __restrict__ tab,
                                                      float* __restrict__ x, int d) {
     const int m = blockIdx.x;
-    const bf16_t* row = E + (size_t)tokens[m] * d;
+    const bf16_t* row = E + (size_t)tab->row[m].token * d;
     for (int i = threadIdx.x; i < d; i += 256) x[(size_t)m * d + i] = Elem<bf16_t>::load1(row + i);
+}
+
+constexpr int ROW_VEC_MAX = 8;      // float4 groups per thread of a row kernel: d <= 8192
+
+// One row by one workgroup: v = x[m] + sum_s P[s][row pm] (S <= CHUNK_GEMM_MAX_SPLIT planes; all loads of the
+// row are issued before the first use), returns the sum of squares over the workgroup.  Thread tid owns the
+// float4 groups tid + 256 u.
+__device__ __forceinline__ float row_gather(const float* __restrict__ xr, const float* __restrict__ Pr, int S,
+                                            size_t s_stride, int d4, int tid, float4 (&v)[ROW_VEC_MAX], float* red) {
+    const float4* x4 = reinterpret_cast<const float4*>(xr);
+    float ss = 0.f;
+#pragma unroll
+    for (int hf = 0; hf < 2; ++hf) {
+        constexpr int HU = ROW_VEC_MAX / 2;
+        if (hf * HU * 256 < d4) {                               // uniform: the upper half only for d > 4096
+            float4 p[HU][CHUNK_GEMM_MAX_SPLIT];
+#pragma unroll
+            for (int u = 0; u < HU; ++u) {
+                const int i4 = min(tid + 256 * (hf * HU + u), d4 - 1);      // past the end: a repeated load, dropped below
+                v[hf * HU + u] = x4[i4];
+#pragma unroll
+                for (int s = 0; s < CHUNK_GEMM_MAX_SPLIT; ++s)
+                    p[u][s] = Pr ? reinterpret_cast<const float4*>(Pr + (size_t)min(s, S - 1) * s_stride)[i4] : make_float4(0.f, 0.f, 0.f, 0.f);
+            }
+#pragma unroll
+            for (int u = 0; u < HU; ++u) {
+                float4& w = v[hf * HU + u];
+#pragma unroll
+                for (int s = 0; s < CHUNK_GEMM_MAX_SPLIT; ++s) {
+                    const float k = s < S ? 1.f : 0.f;
+                    w.x += k * p[u][s].x; w.y += k * p[u][s].y; w.z += k * p[u][s].z; w.w += k * p[u][s].w;
+                }
+                if (tid + 256 * (hf * HU + u) < d4) ss += w.x * w.x + w.y * w.y + w.z * w.z + w.w * w.w;
+            }
+        } else {
+#pragma unroll
+            for (int u = 0; u < HU; ++u) v[hf * HU + u] = make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+    }
+    ss = wave_sum(ss);
+    __syncthreads();
+    if ((tid & 63) == 0) red[tid >> 6] = ss;
+    __syncthreads();
+    return red[0] + red[1] + red[2] + red[3];
+}
+
+// v * sc * gain -> tiled bf16 hi/lo planes at row `mo`
+__device__ __forceinline__ void row_emit(const float4 (&v)[ROW_VEC_MAX], float sc, const float* __restrict__ gain, int d,
+                                         int tid, int mo, bf16_t* __restrict__ out_hi, bf16_t* __restrict__ out_lo) {
+    const int d4 = d >> 2;
+#pragma unroll
+    for (int u = 0; u < ROW_VEC_MAX; ++u) {
+        const int i4 = tid + 256 * u;
+        if (i4 < d4) {
+            const float4 gn = reinterpret_cast<const float4*>(gain)[i4];
+            bf16_t h0, l0, h1, l1, h2, l2, h3, l3;
+            split_bf16(v[u].x * sc * gn.x, h0, l0); split_bf16(v[u].y * sc * gn.y, h1, l1);
+            split_bf16(v[u].z * sc * gn.z, h2, l2); split_bf16(v[u].w * sc * gn.w, h3, l3);
+            const size_t o = tiled_off(mo, 4 * i4, d);       // 4 consecutive columns stay inside one 8-element group
+            *reinterpret_cast<uint2*>(out_hi + o) = make_uint2(h0 | ((uint32_t)h1 << 16), h2 | ((uint32_t)h3 << 16));
+            *reinterpret_cast<uint2*>(out_lo + o) = make_uint2(l0 | ((uint32_t)l1 << 16), l2 | ((uint32_t)l3 << 16));
+        }
+    }
 }
 
 // x[m] += sum_s P[s][m]  (if P), then RMSNorm with `gain` -> tiled bf16 hi/lo planes.
@@ -69,38 +142,76 @@ __global__ __launch_bounds__(256) void k_chunk_resid_norm(float* __restrict__ x,
                                                           float eps, int d, bf16_t* __restrict__ out_hi,
                                                           bf16_t* __restrict__ out_lo) {
     __shared__ float red[4];
-    const int m = blockIdx.x, tid = threadIdx.x;
+    const int m = blockIdx.x, tid = threadIdx.x, d4 = d >> 2;
     float* xr = x + (size_t)m * d;
-    float ss = 0.f;
-    for (int i = tid; i < d; i += 256) {
-        float v = xr[i];
-        if (P) {
-            for (int s = 0; s < S; ++s) v += P[s * s_stride + (size_t)m * n_stride + i];
-            xr[i] = v;
-        }
-        ss += v * v;
+    float4 v[ROW_VEC_MAX];
+    const float ss = row_gather(xr, P ? P + (size_t)m * n_stride : nullptr, S, s_stride, d4, tid, v, red);
+    if (P) {
+#pragma unroll
+        for (int u = 0; u < ROW_VEC_MAX; ++u)
+            if (tid + 256 * u < d4) reinterpret_cast<float4*>(xr)[tid + 256 * u] = v[u];
     }
-    ss = wave_sum(ss);
-    if ((tid & 63) == 0) red[tid >> 6] = ss;
-    __syncthreads();
-    const float sc = rsqrtf((red[0] + red[1] + red[2] + red[3]) / (float)d + eps);
-    for (int i = tid; i < d; i += 256) {
-        bf16_t hi, lo;
-        split_bf16(xr[i] * sc * gain[i], hi, lo);     // xr[i] was written by this same thread
-        const size_t o = tiled_off(m, i, d);
-        out_hi[o] = hi; out_lo[o] = lo;
-    }
+    row_emit(v, rsqrtf(ss / (float)d + eps), gain, d, tid, m, out_hi, out_lo);
 }
 
-// Row `row` only: out[:] = x[row] + sum_s P[s][row]  (residual stream handed to the output head)
+// Last row of group `group` only: out[:] = x[row] + sum_s P[s][row]  (residual stream handed to the
+// single-row output head); the step descriptor gets the group's sequence.
 __global__ __launch_bounds__(256) void k_chunk_last_row(const float* __restrict__ x, const float* __restrict__ P, int S,
-                                                        size_t s_stride, int n_stride, int d, const StepDesc* step,
-                                                        float* __restrict__ out) {
-    const int row = step->rows - 1;
+                                                        size_t s_stride, int n_stride, int d, const ChunkTable* __restrict__ tab,
+                                                        int group, StepDesc* step, float* __restrict__ out) {
+    const ChunkGroup G = tab->group[group];
+    const int row = G.row0 + G.n - 1;
+    if (blockIdx.x == 0 && threadIdx.x == 0) step->seq = G.seq;
     for (int i = blockIdx.x * 256 + threadIdx.x; i < d; i += gridDim.x * 256) {
         float v = x[(size_t)row * d + i];
         for (int s = 0; s < S; ++s) v += P[s * s_stride + (size_t)row * n_stride + i];
         out[i] = v;
+    }
+}
+
+// Workgroup = group: if the group wants logits, its last row (residual + down-projection partials), normalised
+// with the final gain, becomes row `head` of the tiled planes that feed the output-head product.
+__global__ __launch_bounds__(256) void k_chunk_head_rows(const float* __restrict__ x, const float* __restrict__ P, int S,
+                                                         size_t s_stride, int n_stride, const float* __restrict__ gain,
+                                                         float eps, int d, const ChunkTable* __restrict__ tab,
+                                                         bf16_t* __restrict__ out_hi, bf16_t* __restrict__ out_lo) {
+    __shared__ float red[4];
+    const ChunkGroup G = tab->group[blockIdx.x];
+    if (G.head < 0) return;
+    const int row = G.row0 + G.n - 1, tid = threadIdx.x, d4 = d >> 2;
+    float4 v[ROW_VEC_MAX];
+    const float ss = row_gather(x + (size_t)row * d, P + (size_t)row * n_stride, S, s_stride, d4, tid, v, red);
+    row_emit(v, rsqrtf(ss / (float)d + eps), gain, d, tid, G.head, out_hi, out_lo);
+}
+
+// Workgroup = group that wants logits: row `head` of the output-head product -> logits of its sequence,
+// greedy argmax (lowest index on ties) -> next_token.
+__global__ __launch_bounds__(1024) void k_chunk_logits(const float* __restrict__ P, int V, const ChunkTable* __restrict__ tab,
+                                                       float* __restrict__ logits_base, SeqState* st) {
+    __shared__ float sv[16];
+    __shared__ int si[16];
+    const ChunkGroup G = tab->group[blockIdx.x];
+    if (G.head < 0) return;
+    const float* src = P + (size_t)G.head * V;
+    float* dst = logits_base + (size_t)G.seq * V;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    float bv = -INFINITY; int bi = 0x7fffffff;
+    for (int i = tid; i < V; i += 1024) {
+        const float v = src[i];
+        dst[i] = v;
+        if (v > bv) { bv = v; bi = i; }             // i ascends: the first maximum is kept
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        const float ov = __shfl_xor(bv, o, 64); const int oi = __shfl_xor(bi, o, 64);
+        if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
+    }
+    if (lane == 0) { sv[wave] = bv; si[wave] = bi; }
+    __syncthreads();
+    if (tid == 0) {
+        for (int w = 1; w < 16; ++w)
+            if (sv[w] > bv || (sv[w] == bv && si[w] < bi)) { bv = sv[w]; bi = si[w]; }
+        st[G.seq].next_token = bi;
     }
 }
 
@@ -121,15 +232,17 @@ __global__ __launch_bounds__(256) void k_chunk_swiglu(const float* __restrict__ 
     out_hi[o] = hi; out_lo[o] = lo;
 }
 
-// Rotary embedding of q and k, K/V cache write (row-major planes and the transposed V planes),
-// scaled q as hi/lo planes [Hq][Mpad][dh].  grid (heads = Hq + 2 Hkv, rows), dh/2 threads.
+// Rotary embedding of q and k, K/V cache write (row-major planes and the transposed V planes), scaled q
+// as hi/lo planes [Hkv][q_cols][dh] with the columns of a group ordered [q head in the kv group][row].
+// grid (heads = Hq + 2 Hkv, rows), dh/2 threads.
 __global__ void k_chunk_rope_kv(const float* __restrict__ P, int S, size_t s_stride, int n_stride, Geom g,
-                                const StepDesc* step, const float* __restrict__ rope_cos,
+                                const ChunkTable* __restrict__ tab, const float* __restrict__ rope_cos,
                                 const float* __restrict__ rope_sin, bf16_t* __restrict__ kv_layer,
-                                bf16_t* __restrict__ q_hi, bf16_t* __restrict__ q_lo, int Mpad) {
+                                bf16_t* __restrict__ q_hi, bf16_t* __restrict__ q_lo, int q_cols) {
     const int h = blockIdx.x, m = blockIdx.y, i = threadIdx.x, half = g.dh >> 1;
-    const int pos = step->pos + m;
-    const size_t seq_off = (size_t)step->seq * g.kv_seq_stride;
+    const ChunkRow R = tab->row[m];
+    const int pos = R.pos;
+    const size_t seq_off = (size_t)R.seq * g.kv_seq_stride;
     float a = 0.f, b = 0.f;
     for (int s = 0; s < S; ++s) {
         const float* p = P + s * s_stride + (size_t)m * n_stride + h * g.dh;
@@ -143,7 +256,8 @@ __global__ void k_chunk_rope_kv(const float* __restrict__ P, int S, size_t s_str
     bf16_t ahi, alo, bhi, blo;
     if (h < g.Hq) {
         split_bf16(a * g.scale, ahi, alo); split_bf16(b * g.scale, bhi, blo);
-        const size_t o = ((size_t)h * Mpad + m) * g.dh;
+        const int G = g.Hq / g.Hkv, kvh = h / G, gq = h - kvh * G;
+        const size_t o = ((size_t)kvh * q_cols + (size_t)G * R.row0 + (size_t)gq * R.n + (m - R.row0)) * g.dh;
         q_hi[o + i] = ahi; q_lo[o + i] = alo; q_hi[o + i + half] = bhi; q_lo[o + i + half] = blo;
         return;
     }
@@ -162,59 +276,79 @@ __global__ void k_chunk_rope_kv(const float* __restrict__ P, int S, size_t s_str
 }
 
 // ---------------------------------------------------------------------------------------------
-// skinny GEMM on the matrix cores:  P[s][m][n] = sum_{k in slice} X[m][k] W[n][k]
+// skinny GEMM on the matrix cores:  P[s][m][n] = sum_{k in slice s} X[m][k] W[n][k]
 // ---------------------------------------------------------------------------------------------
-// Workgroup = 4 waves on the same 32 weight rows; the 4*S waves of a row tile split K into
-// contiguous runs of 128-element blocks.  A wave keeps the whole 32 x Mpad accumulator; the four
-// partial accumulators of a workgroup are summed through LDS, the S workgroups of a row tile
-// write separate partial planes that the consumer adds in a fixed order (no atomics).
+// Workgroup = 4 waves on 128 weight rows (32 per wave) and one contiguous run of 128-element k-blocks
+// (the S workgroups of a row tile split K and write separate partial planes that the consumer adds in
+// a fixed order: no atomics, results are bit-reproducible).
+//  * weights stream from HBM through a register ring of GEMM_RING tiles per wave (one tile = the wave's
+//    32 rows x 128 columns, loaded 4 rows x 256 contiguous bytes per instruction), are transposed into
+//    operand order through a wave-private XOR-swizzled LDS tile and multiplied;
+//  * the activations of a k-block (all rows, hi and lo planes: MT x 16 KiB) are shared by the four waves
+//    through a double-buffered LDS tile that the workgroup fills one block ahead.
+// The loop body has no conditional code: past the end of its run a workgroup re-reads its last block
+// (cache hits) against activations replaced by zeros.  The compiler sinks loads into conditional users
+// and then waits for each load right before its product; the scheduling barriers keep the instruction
+// scheduler from doing the same within the straight-line body.
 
-// Operands of one 128-element k-block for one wave: 32 weight rows x 128 as loaded (4 rows per
-// instruction: lane l holds row 4q + l/16, 16-byte chunk l%16) and Mpad token rows x 128 in operand order.
-template <int MT>
-struct GemmTile {
-    uint4 a[8];
-    uint4 bh[MT][8], bl[MT][8];
-};
+constexpr int GEMM_RING = 4;
 
 template <int MT>
-__device__ __forceinline__ void gemm_tile_load(GemmTile<MT>& t, const bf16_t* wlane, size_t wstep, const bf16_t* const (&xh)[MT],
-                                               const bf16_t* const (&xl)[MT], int blk) {
+struct BStage { uint4 v[MT][4]; };
+
+__device__ __forceinline__ void gemm_a_load(uint4 (&a)[8], const bf16_t* wlane, size_t wstep, int blk) {
 #pragma unroll
-    for (int q = 0; q < 8; ++q) t.a[q] = load16_stream(wlane + (size_t)blk * 128 + q * wstep);
+    for (int q = 0; q < 8; ++q) a[q] = load16_stream(wlane + (size_t)blk * 128 + q * wstep);
+}
+
+// thread tid stages chunks tid and tid + 256 of the 512 16-byte chunks of each 8 KiB plane tile
+template <int MT>
+__device__ __forceinline__ void gemm_b_load(BStage<MT>& st, const bf16_t* xh, const bf16_t* xl, int nblk, int blk) {
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+        const size_t base = ((size_t)mt * nblk + blk) * 4096;
+        st.v[mt][0] = load16(xh + base); st.v[mt][1] = load16(xh + base + 2048);
+        st.v[mt][2] = load16(xl + base); st.v[mt][3] = load16(xl + base + 2048);
+    }
+}
+
+template <int MT>
+__device__ __forceinline__ void gemm_b_store(const BStage<MT>& st, uint4* buf, int tid, bool live) {
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-        for (int k = 0; k < 8; ++k) {
-            t.bh[mt][k] = load16(xh[mt] + (size_t)blk * 4096 + k * 512);
-            t.bl[mt][k] = load16(xl[mt] + (size_t)blk * 4096 + k * 512);
+        for (int h = 0; h < 4; ++h) {
+            uint4 v = st.v[mt][h];
+            v.x = live ? v.x : 0u; v.y = live ? v.y : 0u; v.z = live ? v.z : 0u; v.w = live ? v.w : 0u;
+            buf[(mt * 2 + (h >> 1)) * 512 + (h & 1) * 256 + tid] = v;
         }
 }
 
-// Transposes the weight tile into operand order through the wave's LDS tile, then multiplies.
-// LDS tile: 32 rows x 16 chunks of 16 bytes, chunk c of row r stored at chunk position c ^ (r & 15).
+// Transposes the weight tile into operand order through the wave's LDS tile (32 rows x 16 chunks of
+// 16 bytes, chunk c of row r stored at chunk position c ^ (r & 15)), then multiplies it with the
+// activation tile in `bt` ([mt][hi | lo][k-step][lane]).
 template <int MT>
-__device__ __forceinline__ void gemm_tile_mma(const GemmTile<MT>& t, f32x16 (&acc)[MT], uint4* lds, int lane) {
+__device__ __forceinline__ void gemm_tile_mma(const uint4 (&ta)[8], f32x16 (&acc)[MT], uint4* at, const uint4* bt, int lane) {
     {
         const int r0 = lane >> 4, c = lane & 15;
 #pragma unroll
         for (int q = 0; q < 8; ++q) {
             const int r = 4 * q + r0;
-            lds[r * 16 + (c ^ (r & 15))] = t.a[q];
+            at[r * 16 + (c ^ (r & 15))] = ta[q];
         }
     }
     uint4 a[8];
     {
         const int i = lane & 31, gh = lane >> 5;
 #pragma unroll
-        for (int k = 0; k < 8; ++k) a[k] = lds[i * 16 + ((2 * k + gh) ^ (i & 15))];
+        for (int k = 0; k < 8; ++k) a[k] = at[i * 16 + ((2 * k + gh) ^ (i & 15))];
     }
 #pragma unroll
     for (int k = 0; k < 8; ++k)
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
-            acc[mt] = mfma_bf16(a[k], t.bh[mt][k], acc[mt]);
-            acc[mt] = mfma_bf16(a[k], t.bl[mt][k], acc[mt]);
+            acc[mt] = mfma_bf16(a[k], bt[(mt * 2 + 0) * 512 + k * 64 + lane], acc[mt]);
+            acc[mt] = mfma_bf16(a[k], bt[(mt * 2 + 1) * 512 + k * 64 + lane], acc[mt]);
         }
 }
 
@@ -222,88 +356,82 @@ template <int MT>
 __global__ __launch_bounds__(256) void k_chunk_gemm(const bf16_t* __restrict__ W, int N, int K,
                                                     const bf16_t* __restrict__ Xhi, const bf16_t* __restrict__ Xlo,
                                                     float* __restrict__ P, size_t s_stride, int n_stride, int S) {
-    // per-wave weight tiles (8 KiB each) during the product, then the four partial accumulators
-    constexpr int RED_BYTES = 4 * MT * 16 * 64 * 4, LDS_BYTES = RED_BYTES > 32768 ? RED_BYTES : 32768;
-    __shared__ uint4 lds_raw[LDS_BYTES / 16];
-    uint4 (*wt)[512] = reinterpret_cast<uint4 (*)[512]>(lds_raw);
-    float (*red)[MT][16][64] = reinterpret_cast<float (*)[MT][16][64]>(lds_raw);
+    extern __shared__ uint4 gemm_lds[];             // [4 waves][512] weight tiles, then [2][MT][2][512] activation tiles
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int n0 = blockIdx.x * 32, sp = blockIdx.y;
-    // K is split over the 4*S waves of this row tile in units of two 128-element blocks
-    const int npair = K >> 8, parts = 4 * S, part = sp * 4 + wave;
-    const int b0 = 2 * (int)((long long)npair * part / parts), b1 = 2 * (int)((long long)npair * (part + 1) / parts);
+    uint4* at = gemm_lds + wave * 512;
+    uint4* bt = gemm_lds + 2048;
+    constexpr int BT = MT * 2 * 512;                // chunks in one activation buffer
+    const int n0 = blockIdx.x * 128 + wave * 32, sp = blockIdx.y;
+    const int nblk = K >> 7;
+    const int b0 = (int)((long long)nblk * sp / S), b1 = (int)((long long)nblk * (sp + 1) / S);
+    const int nb = b1 - b0, last = b1 - 1;
 
     const bf16_t* wlane = W + (size_t)(n0 + (lane >> 4)) * K + (lane & 15) * 8;   // row l/16 (+4q), chunk l%16
     const size_t wstep = (size_t)4 * K;
-    const bf16_t* xh[MT]; const bf16_t* xl[MT];
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-        xh[mt] = Xhi + (size_t)mt * 32 * K + lane * 8;
-        xl[mt] = Xlo + (size_t)mt * 32 * K + lane * 8;
-    }
+    const bf16_t* xh = Xhi + tid * 8;
+    const bf16_t* xl = Xlo + tid * 8;
+
     f32x16 acc[MT];
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[mt][r] = 0.f;
 
-    // Two register tiles in ping-pong over pairs of k-blocks: the loads of the next block are in flight
-    // while the current one is multiplied.  The body has no conditional code (a wave always owns an even
-    // number of blocks; past its end it re-reads its last block and drops it), because the compiler sinks
-    // loads into conditional users and then waits for each load right before its product.  The scheduling
-    // barriers keep the instruction scheduler from doing the same within the straight-line body.
-    GemmTile<MT> t0, t1;
-    if (b0 < b1) {
-        gemm_tile_load<MT>(t0, wlane, wstep, xh, xl, b0);
-        for (int b = b0; b < b1; b += 2) {
-            gemm_tile_load<MT>(t1, wlane, wstep, xh, xl, b + 1);
-            __builtin_amdgcn_sched_barrier(0);
-            gemm_tile_mma<MT>(t0, acc, wt[wave], lane);
-            __builtin_amdgcn_sched_barrier(0);
-            gemm_tile_load<MT>(t0, wlane, wstep, xh, xl, min(b + 2, b1 - 1));
-            __builtin_amdgcn_sched_barrier(0);
-            gemm_tile_mma<MT>(t1, acc, wt[wave], lane);
-            __builtin_amdgcn_sched_barrier(0);
+    if (nb > 0) {
+        // Waits are in issue order, so the activation loads of block t+2 are issued before the weight loads of
+        // block t+3: waiting for the activations of block t+1 (to store them) then leaves two weight tiles in flight.
+        uint4 ring[GEMM_RING][8];
+        BStage<MT> st[2];
+        gemm_b_load<MT>(st[0], xh, xl, nblk, b0);
+        gemm_b_load<MT>(st[1], xh, xl, nblk, min(b0 + 1, last));
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int u = 0; u < GEMM_RING - 1; ++u) gemm_a_load(ring[u], wlane, wstep, min(b0 + u, last));
+        gemm_b_store<MT>(st[0], bt, tid, true);
+        __syncthreads();
+        for (int t = 0; t < nb; t += GEMM_RING) {
+#pragma unroll
+            for (int u = 0; u < GEMM_RING; ++u) {
+                const int tt = b0 + t + u;                  // this block (past the end: zeros)
+                gemm_b_load<MT>(st[u & 1], xh, xl, nblk, min(tt + 2, last));
+                __builtin_amdgcn_sched_barrier(0);
+                gemm_a_load(ring[(u + GEMM_RING - 1) % GEMM_RING], wlane, wstep, min(tt + GEMM_RING - 1, last));
+                __builtin_amdgcn_sched_barrier(0);
+                gemm_tile_mma<MT>(ring[u], acc, at, bt + (u & 1) * BT, lane);
+                __builtin_amdgcn_sched_barrier(0);
+                gemm_b_store<MT>(st[(u + 1) & 1], bt + ((u + 1) & 1) * BT, tid, tt + 1 <= last);
+                __syncthreads();
+            }
         }
     }
 
-    __syncthreads();        // every wave is done with its weight tile
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) red[wave][mt][r][lane] = acc[mt][r];
-    __syncthreads();
-    // thread -> (token column j, four consecutive weight rows): coalesced 16-byte stores
-    const int j = tid >> 3, q = tid & 7, b = q >> 1, g2 = q & 1;
+    // lane (j, g) holds D[8b + 4g + r][j] in register 4b + r: four consecutive weight rows of token row j
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
-        float4 v;
-        float* vp = &v.x;
+        float* prow = P + sp * s_stride + (size_t)(mt * 32 + (lane & 31)) * n_stride + n0 + 4 * (lane >> 5);
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const int idx = 4 * b + r, ln = j + 32 * g2;
-            vp[r] = red[0][mt][idx][ln] + red[1][mt][idx][ln] + red[2][mt][idx][ln] + red[3][mt][idx][ln];
-        }
-        *(float4*)(P + sp * s_stride + (size_t)(mt * 32 + j) * n_stride + n0 + 4 * q) = v;
+        for (int b = 0; b < 4; ++b)
+            *(float4*)(prow + 8 * b) = make_float4(acc[mt][4 * b], acc[mt][4 * b + 1], acc[mt][4 * b + 2], acc[mt][4 * b + 3]);
     }
 }
 
 // ---------------------------------------------------------------------------------------------
 // causal chunk attention on the matrix cores (head_dim 128, paired bf16 cache)
 // ---------------------------------------------------------------------------------------------
-// One wave = one (kv head, tile of 32 query rows, key split).  Query rows of a kv head are ordered
-// [q head within the group][row m], padded to Mpad rows per head.  Per 32-key tile the wave forms
-// S^T = K Q^T (keys along D rows), does the online softmax per query column, and accumulates
-// O^T += V^T P^T from the transposed V planes.  Key rows are permuted so that the D registers of a
-// lane hold 16 consecutive keys, which makes P directly usable as the next B operand.
+// One wave = one (task, kv head, key split); a task is a tile of 32 query columns of one group, the columns
+// of a group being (q head within the kv group, row) pairs, so a single-row group of a 4:1 model fills
+// 4 columns and a 24-row group three tiles.  Per 32-key tile the wave loads K and V^T (both planes) at once,
+// forms S^T = K Q^T (keys along D rows), does the online softmax per query column, and accumulates
+// O^T += V^T P^T.  Key rows are permuted so that the D registers of a lane hold 16 consecutive keys, which
+// makes P directly usable as the next B operand.
 
 struct ChunkAttnArgs {
-    const bf16_t* q_hi; const bf16_t* q_lo;     // [Hq][Mpad][128], scaled by 1/sqrt(dh)
+    const bf16_t* q_hi; const bf16_t* q_lo;     // [Hkv][q_cols][128], scaled by 1/sqrt(dh)
     const bf16_t* kv_layer;
-    const StepDesc* step;
-    float* part_o;      // [task][split][128][32]
-    float* part_ml;     // [task][split][2][32]
-    int32_t nsplit, MT;
+    const ChunkTable* tab;
+    float* part_o;      // [unit][128][32]
+    float* part_ml;     // [unit][2][32]
+    int32_t nsplit, q_cols;
 };
 
 __global__ __launch_bounds__(256) void k_chunk_attn(ChunkAttnArgs a, Geom g) {
@@ -311,64 +439,69 @@ __global__ __launch_bounds__(256) void k_chunk_attn(ChunkAttnArgs a, Geom g) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int i = lane & 31, gh = lane >> 5;
     const int G = g.Hq / g.Hkv;
-    const int task = blockIdx.x, split = blockIdx.y * 4 + wave;
-    const int tiles_q = G * a.MT;
-    const int kvh = task / tiles_q, qt = task - kvh * tiles_q;
-    const int hq = kvh * G + qt / a.MT, m0 = (qt % a.MT) * 32;
-    const int Mpad = a.MT * 32;
-    const int pos0 = a.step->pos, rows = a.step->rows;
-    const int Lk = pos0 + rows;                           // keys 0 .. Lk-1 exist
+    const int kvh = blockIdx.x % g.Hkv, split = blockIdx.y * 4 + wave;
+    const ChunkTask T = a.tab->task[blockIdx.x / g.Hkv];
+    const int Lk = T.pos0 + T.n;                           // keys 0 .. Lk-1 exist
     const int ntile = (Lk + 31) >> 5;
     const int tps = (ntile + a.nsplit - 1) / a.nsplit;
     const int t0 = split * tps, t1 = min(ntile, t0 + tps);
 
-    const size_t seq_off = (size_t)a.step->seq * g.kv_seq_stride + (size_t)kvh * g.kv_head_stride;
+    const size_t seq_off = (size_t)T.seq * g.kv_seq_stride + (size_t)kvh * g.kv_head_stride;
     const bf16_t* Kp = a.kv_layer + seq_off;
     const bf16_t* Vt = a.kv_layer + g.kv_vt_offset + seq_off;
     const size_t lo = g.kv_lo_offset;
 
+    // this lane's query column: (q head gq, row r) of the group; columns past the group are computed and dropped
+    const int col = 32 * T.tile + i;
+    const int gq = min(col / T.n, G - 1), r = col - (col / T.n) * T.n;
+    const int qpos = T.pos0 + r;
+    (void)gq;
+
     // B operand of S^T = K Q^T: lane (j, g) holds q[j][64 g + 8 t + e]
     uint4 qh[8], ql[8];
     {
-        const bf16_t* qp = a.q_hi + ((size_t)hq * Mpad + m0 + i) * DH + gh * 64;
-        const bf16_t* qq = a.q_lo + ((size_t)hq * Mpad + m0 + i) * DH + gh * 64;
+        const size_t qo = ((size_t)kvh * a.q_cols + (size_t)G * T.row0 + col) * DH + gh * 64;
 #pragma unroll
-        for (int t = 0; t < 8; ++t) { qh[t] = load16(qp + t * 8); ql[t] = load16(qq + t * 8); }
+        for (int t = 0; t < 8; ++t) { qh[t] = load16(a.q_hi + qo + t * 8); ql[t] = load16(a.q_lo + qo + t * 8); }
     }
-    const int qpos = pos0 + m0 + i;                        // position of this lane's query column
     const int krow = (i >> 3) * 4 + (i & 3) + 16 * ((i >> 2) & 1);   // key (within a tile) held in A row i
 
     f32x16 o[4];
 #pragma unroll
     for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) o[dt][r] = 0.f;
+        for (int r2 = 0; r2 < 16; ++r2) o[dt][r2] = 0.f;
     float mrun = -INFINITY, lrun = 0.f;
 
     for (int tile = t0; tile < t1; ++tile) {
         const int key0 = tile * 32;
-        if (key0 > pos0 + m0 + 31) break;                   // beyond the causal limit of every row
-        f32x16 s;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) s[r] = 0.f;
+        uint4 kh[8], kl[8], vh[4][2], vl[4][2];
         {
             const bf16_t* kp = Kp + (size_t)(key0 + krow) * DH + gh * 64;
-            uint4 kh[8], kl[8];
 #pragma unroll
             for (int t = 0; t < 8; ++t) { kh[t] = load16(kp + t * 8); kl[t] = load16(kp + lo + t * 8); }
 #pragma unroll
-            for (int t = 0; t < 8; ++t) {
-                s = mfma_bf16(kh[t], qh[t], s);
-                s = mfma_bf16(kl[t], qh[t], s);
-                s = mfma_bf16(kh[t], ql[t], s);
+            for (int dt = 0; dt < 4; ++dt) {
+                const bf16_t* vp = Vt + (size_t)(dt * 32 + i) * g.max_pos + key0 + 16 * gh;
+#pragma unroll
+                for (int t = 0; t < 2; ++t) { vh[dt][t] = load16(vp + 8 * t); vl[dt][t] = load16(vp + lo + 8 * t); }
             }
         }
-        // register r of lane (j, g) is key key0 + 16 g + r for query column j
+        f32x16 s;
+#pragma unroll
+        for (int r2 = 0; r2 < 16; ++r2) s[r2] = 0.f;
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+            s = mfma_bf16(kh[t], qh[t], s);
+            s = mfma_bf16(kl[t], qh[t], s);
+            s = mfma_bf16(kh[t], ql[t], s);
+        }
+        // register r2 of lane (j, g) is key key0 + 16 g + r2 for query column j
         float mx = -INFINITY;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            if (key0 + 16 * gh + r > qpos) s[r] = -INFINITY;
-            mx = fmaxf(mx, s[r]);
+        for (int r2 = 0; r2 < 16; ++r2) {
+            if (key0 + 16 * gh + r2 > qpos) s[r2] = -INFINITY;
+            mx = fmaxf(mx, s[r2]);
         }
         mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
         const float mnew = fmaxf(mrun, mx);
@@ -379,10 +512,10 @@ __global__ __launch_bounds__(256) void k_chunk_attn(ChunkAttnArgs a, Geom g) {
         {
             bf16_t hi[16], lw[16];
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const float p = expf(s[r] - msafe);
+            for (int r2 = 0; r2 < 16; ++r2) {
+                const float p = expf(s[r2] - msafe);
                 psum += p;
-                split_bf16(p, hi[r], lw[r]);
+                split_bf16(p, hi[r2], lw[r2]);
             }
 #pragma unroll
             for (int t = 0; t < 2; ++t) {
@@ -397,66 +530,89 @@ __global__ __launch_bounds__(256) void k_chunk_attn(ChunkAttnArgs a, Geom g) {
 #pragma unroll
         for (int dt = 0; dt < 4; ++dt) {
 #pragma unroll
-            for (int r = 0; r < 16; ++r) o[dt][r] *= corr;
-            const bf16_t* vp = Vt + (size_t)(dt * 32 + i) * g.max_pos + key0 + 16 * gh;
+            for (int r2 = 0; r2 < 16; ++r2) o[dt][r2] *= corr;
 #pragma unroll
             for (int t = 0; t < 2; ++t) {
-                const uint4 vh = load16(vp + 8 * t), vl = load16(vp + lo + 8 * t);
-                o[dt] = mfma_bf16(vh, ph[t], o[dt]);
-                o[dt] = mfma_bf16(vl, ph[t], o[dt]);
-                o[dt] = mfma_bf16(vh, pl[t], o[dt]);
+                o[dt] = mfma_bf16(vh[dt][t], ph[t], o[dt]);
+                o[dt] = mfma_bf16(vl[dt][t], ph[t], o[dt]);
+                o[dt] = mfma_bf16(vh[dt][t], pl[t], o[dt]);
             }
         }
     }
     lrun += __shfl_xor(lrun, 32, 64);
 
-    float* po = a.part_o + ((size_t)task * a.nsplit + split) * DH * 32;
+    const size_t unit = (size_t)blockIdx.x * a.nsplit + split;
+    float* po = a.part_o + unit * DH * 32;
 #pragma unroll
     for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) po[(size_t)(dt * 32 + 8 * (r >> 2) + 4 * gh + (r & 3)) * 32 + i] = o[dt][r];
+        for (int r2 = 0; r2 < 16; ++r2) po[(size_t)(dt * 32 + 8 * (r2 >> 2) + 4 * gh + (r2 & 3)) * 32 + i] = o[dt][r2];
     if (gh == 0) {
-        float* pm = a.part_ml + ((size_t)task * a.nsplit + split) * 64;
+        float* pm = a.part_ml + unit * 64;
         pm[i] = mrun; pm[32 + i] = lrun;
     }
 }
 
-// Merge the key splits of one task and emit the attention output as tiled hi/lo planes (K = Hq*128).
+// Merge the key splits of one (task, kv head) and emit the attention output as tiled hi/lo planes
+// (K = Hq*128).  grid (tasks * Hkv, 4): workgroup y handles channels 32 y .. 32 y + 31.
 __global__ __launch_bounds__(256) void k_chunk_attn_combine(const float* __restrict__ part_o, const float* __restrict__ part_ml,
-                                                            int nsplit, int MT, Geom g, const StepDesc* step,
+                                                            int nsplit, Geom g, const ChunkTable* __restrict__ tab,
                                                             bf16_t* __restrict__ out_hi, bf16_t* __restrict__ out_lo) {
     constexpr int DH = 128;
-    __shared__ float f[ATTN_MAX_SPLIT][32];
-    const int task = blockIdx.x, tid = threadIdx.x;
-    const int G = g.Hq / g.Hkv, tiles_q = G * MT;
-    const int kvh = task / tiles_q, qt = task - kvh * tiles_q;
-    const int hq = kvh * G + qt / MT, m0 = (qt % MT) * 32;
-    const float* ml = part_ml + (size_t)task * nsplit * 64;
+    __shared__ float f[CHUNK_ATTN_MAX_SPLIT][32];
+    const int tid = threadIdx.x;
+    const int G = g.Hq / g.Hkv;
+    const int kvh = blockIdx.x % g.Hkv;
+    const ChunkTask T = tab->task[blockIdx.x / g.Hkv];
+    const float* ml = part_ml + (size_t)blockIdx.x * nsplit * 64;
     if (tid < 32) {
+        float ms[CHUNK_ATTN_MAX_SPLIT], ls[CHUNK_ATTN_MAX_SPLIT];
+#pragma unroll
+        for (int s = 0; s < CHUNK_ATTN_MAX_SPLIT; ++s) {
+            const int sc = min(s, nsplit - 1);
+            ms[s] = ml[sc * 64 + tid]; ls[s] = ml[sc * 64 + 32 + tid];
+        }
         float M = -INFINITY, L = 0.f;
-        for (int s = 0; s < nsplit; ++s) M = fmaxf(M, ml[s * 64 + tid]);
-        for (int s = 0; s < nsplit; ++s) {
-            const float ms = ml[s * 64 + tid];
-            const float w = ms > -INFINITY ? expf(ms - M) : 0.f;
-            L += ml[s * 64 + 32 + tid] * w;
-            f[s][tid] = w;
+#pragma unroll
+        for (int s = 0; s < CHUNK_ATTN_MAX_SPLIT; ++s) if (s < nsplit) M = fmaxf(M, ms[s]);
+#pragma unroll
+        for (int s = 0; s < CHUNK_ATTN_MAX_SPLIT; ++s) {
+            const float w = (s < nsplit && ms[s] > -INFINITY) ? expf(ms[s] - M) : 0.f;
+            L += ls[s] * w;
+            ms[s] = w;
         }
         const float inv = L > 0.f ? 1.f / L : 0.f;
-        for (int s = 0; s < nsplit; ++s) f[s][tid] *= inv;
+#pragma unroll
+        for (int s = 0; s < CHUNK_ATTN_MAX_SPLIT; ++s) f[s][tid] = ms[s] * inv;
     }
     __syncthreads();
-    const int rows = step->rows;
-    const float* po = part_o + (size_t)task * nsplit * DH * 32;
-    for (int e = tid; e < DH * 32; e += 256) {
-        const int dh = e >> 5, j = e & 31;
-        float v = 0.f;
-#pragma unroll 4
-        for (int s = 0; s < nsplit; ++s) v = fmaf(po[(size_t)s * DH * 32 + e], f[s][j], v);
-        const int m = m0 + j;
-        if (m < rows) {
+    const int j = tid & 31, dl = tid >> 5;                 // column, channel within a run of 8
+    const float* po = part_o + (size_t)blockIdx.x * nsplit * DH * 32 + (size_t)(blockIdx.y * 32 + dl) * 32 + j;
+    float v[4] = {0.f, 0.f, 0.f, 0.f};
+    for (int s = 0; s < nsplit; s += 4) {
+        float p[4][4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int sc = min(s + k, nsplit - 1);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) p[k][u] = po[(size_t)sc * DH * 32 + u * 8 * 32];
+        }
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const float w = s + k < nsplit ? f[min(s + k, CHUNK_ATTN_MAX_SPLIT - 1)][j] : 0.f;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) v[u] = fmaf(p[k][u], w, v[u]);
+        }
+    }
+    const int col = 32 * T.tile + j;
+    if (col < G * T.n) {
+        const int gq = col / T.n, r = col - gq * T.n;
+        const int m = T.row0 + r, hq = kvh * G + gq;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
             bf16_t hi, lw;
-            split_bf16(v, hi, lw);
-            const size_t o = tiled_off(m, hq * DH + dh, g.Hq * DH);
+            split_bf16(v[u], hi, lw);
+            const size_t o = tiled_off(m, hq * DH + blockIdx.y * 32 + dl + 8 * u, g.Hq * DH);
             out_hi[o] = hi; out_lo[o] = lw;
         }
     }
@@ -466,27 +622,46 @@ __global__ __launch_bounds__(256) void k_chunk_attn_combine(const float* __restr
 // launchers
 // ---------------------------------------------------------------------------------------------
 
-hipError_t launch_begin_chunk(const DecodeBuffers& b, int seq, int rows, hipStream_t s) {
-    hipLaunchKernelGGL(k_begin_chunk, dim3(1), dim3(64), 0, s, b.step, b.seq_state, seq, rows);
+hipError_t launch_begin_chunk(const ChunkBuffers& c, const DecodeBuffers& b, int ngroups, hipStream_t s) {
+    (void)ngroups;
+    hipLaunchKernelGGL(k_begin_chunk, dim3(1), dim3(128), 0, s, c.tab, b.step, b.seq_state, c.chosen);
     return hipGetLastError();
 }
 
 hipError_t launch_chunk_embed(const void* E, const ChunkBuffers& c, int rows, const Geom& g, hipStream_t s) {
-    hipLaunchKernelGGL(k_chunk_embed, dim3(rows), dim3(256), 0, s, (const bf16_t*)E, c.tokens, c.x, g.d);
+    hipLaunchKernelGGL(k_chunk_embed, dim3(rows), dim3(256), 0, s, (const bf16_t*)E, c.tab, c.x, g.d);
     return hipGetLastError();
 }
 
+static bool row_kernel_ok(const Geom& g, int S) { return g.d % 4 == 0 && g.d <= ROW_VEC_MAX * 1024 && S >= 1 && S <= CHUNK_GEMM_MAX_SPLIT; }
+
 hipError_t launch_chunk_resid_norm(const ChunkBuffers& c, bool add_partials, int S, int MT, const float* gain,
                                    int rows, const Geom& g, hipStream_t s) {
+    if (!row_kernel_ok(g, S)) return hipErrorInvalidValue;
     hipLaunchKernelGGL(k_chunk_resid_norm, dim3(rows), dim3(256), 0, s, c.x, add_partials ? c.part : nullptr, S,
                        (size_t)MT * 32 * g.d, g.d, gain, g.eps, g.d, c.nrm_hi, c.nrm_lo);
     return hipGetLastError();
 }
 
-hipError_t launch_chunk_last_row(const ChunkBuffers& c, int S, int MT, const DecodeBuffers& b, const Geom& g,
+hipError_t launch_chunk_last_row(const ChunkBuffers& c, int S, int MT, int group, const DecodeBuffers& b, const Geom& g,
                                  hipStream_t s) {
     hipLaunchKernelGGL(k_chunk_last_row, dim3((g.d + 255) / 256), dim3(256), 0, s, c.x, c.part, S, (size_t)MT * 32 * g.d,
-                       g.d, g.d, b.step, b.x);
+                       g.d, g.d, c.tab, group, b.step, b.x);
+    return hipGetLastError();
+}
+
+hipError_t launch_chunk_head_rows(const ChunkBuffers& c, int S, int MT, const float* gain, int ngroups, const Geom& g,
+                                  hipStream_t s) {
+    if (!row_kernel_ok(g, S)) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(k_chunk_head_rows, dim3(ngroups), dim3(256), 0, s, c.x, c.part, S, (size_t)MT * 32 * g.d, g.d, gain,
+                       g.eps, g.d, c.tab, c.nrm_hi, c.nrm_lo);
+    return hipGetLastError();
+}
+
+hipError_t launch_chunk_logits(const ChunkBuffers& c, int MT_head, float* logits_base, const DecodeBuffers& b, int ngroups,
+                               const Geom& g, hipStream_t s) {
+    (void)MT_head;
+    hipLaunchKernelGGL(k_chunk_logits, dim3(ngroups), dim3(1024), 0, s, c.part, g.V, c.tab, logits_base, b.seq_state);
     return hipGetLastError();
 }
 
@@ -500,32 +675,43 @@ hipError_t launch_chunk_rope_kv(const ChunkBuffers& c, int S, void* kv_layer, co
                                 const Geom& g, hipStream_t s) {
     const int n_qkv = (g.Hq + 2 * g.Hkv) * g.dh;
     hipLaunchKernelGGL(k_chunk_rope_kv, dim3(g.Hq + 2 * g.Hkv, rows), dim3(g.dh / 2), 0, s, c.part, S, (size_t)MT * 32 * n_qkv,
-                       n_qkv, g, b.step, b.rope_cos, b.rope_sin, (bf16_t*)kv_layer, c.q_hi, c.q_lo,
-                       MT * 32);
+                       n_qkv, g, c.tab, b.rope_cos, b.rope_sin, (bf16_t*)kv_layer, c.q_hi, c.q_lo, c.q_cols);
     return hipGetLastError();
+}
+
+static size_t gemm_lds_bytes(int MT) { return (size_t)(2048 + 2 * MT * 2 * 512) * 16; }
+
+hipError_t chunk_init() {
+    hipError_t e;
+    if ((e = hipFuncSetAttribute((const void*)k_chunk_gemm<1>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)gemm_lds_bytes(1)))) return e;
+    if ((e = hipFuncSetAttribute((const void*)k_chunk_gemm<2>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)gemm_lds_bytes(2)))) return e;
+    if ((e = hipFuncSetAttribute((const void*)k_chunk_gemm<3>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)gemm_lds_bytes(3)))) return e;
+    return hipSuccess;
 }
 
 hipError_t launch_chunk_gemm(const void* W, int N, int K, const bf16_t* xhi, const bf16_t* xlo, const ChunkBuffers& c,
                              int S, int MT, hipStream_t s) {
-    const dim3 grid(N / 32, S), block(256);
-    const size_t ps = (size_t)MT * 32 * N;
-    if (S < 1 || S > CHUNK_GEMM_MAX_SPLIT || N % 32 || K % 256 || ps * S > c.part_capacity) return hipErrorInvalidValue;
-    if (MT == 1) hipLaunchKernelGGL(k_chunk_gemm<1>, grid, block, 0, s, (const bf16_t*)W, N, K, xhi, xlo, c.part, ps, N, S);
-    else if (MT == 2) hipLaunchKernelGGL(k_chunk_gemm<2>, grid, block, 0, s, (const bf16_t*)W, N, K, xhi, xlo, c.part, ps, N, S);
+    const dim3 grid(N / 128, S), block(256);
+    const size_t ps = (size_t)MT * 32 * N, lds = gemm_lds_bytes(MT);
+    if (S < 1 || S > CHUNK_GEMM_MAX_SPLIT || S > K / 128 || N % 128 || K % 128 || ps * S > c.part_capacity) return hipErrorInvalidValue;
+    if (MT == 1) hipLaunchKernelGGL(k_chunk_gemm<1>, grid, block, lds, s, (const bf16_t*)W, N, K, xhi, xlo, c.part, ps, N, S);
+    else if (MT == 2) hipLaunchKernelGGL(k_chunk_gemm<2>, grid, block, lds, s, (const bf16_t*)W, N, K, xhi, xlo, c.part, ps, N, S);
+    else if (MT == 3) hipLaunchKernelGGL(k_chunk_gemm<3>, grid, block, lds, s, (const bf16_t*)W, N, K, xhi, xlo, c.part, ps, N, S);
     else return hipErrorInvalidValue;
     return hipGetLastError();
 }
 
-hipError_t launch_chunk_attn(const ChunkBuffers& c, const void* kv_layer, int nsplit, int MT, const DecodeBuffers& b,
-                             const Geom& g, hipStream_t s) {
+hipError_t launch_chunk_attn(const ChunkBuffers& c, const void* kv_layer, int nsplit, int ntasks, const Geom& g, hipStream_t s) {
+    if (nsplit < 4 || nsplit % 4 || nsplit > CHUNK_ATTN_MAX_SPLIT || ntasks < 1 || ntasks > CHUNK_MAX_TASKS ||
+        (long long)ntasks * g.Hkv * nsplit > CHUNK_ATTN_MAX_UNITS)
+        return hipErrorInvalidValue;
     ChunkAttnArgs a{};
-    a.q_hi = c.q_hi; a.q_lo = c.q_lo; a.kv_layer = (const bf16_t*)kv_layer; a.step = b.step;
-    a.part_o = c.attn_o; a.part_ml = c.attn_ml; a.nsplit = nsplit; a.MT = MT;
-    const int tasks = g.Hkv * (g.Hq / g.Hkv) * MT;
-    hipLaunchKernelGGL(k_chunk_attn, dim3(tasks, nsplit / 4), dim3(256), 0, s, a, g);
+    a.q_hi = c.q_hi; a.q_lo = c.q_lo; a.kv_layer = (const bf16_t*)kv_layer; a.tab = c.tab;
+    a.part_o = c.attn_o; a.part_ml = c.attn_ml; a.nsplit = nsplit; a.q_cols = c.q_cols;
+    hipLaunchKernelGGL(k_chunk_attn, dim3(ntasks * g.Hkv, nsplit / 4), dim3(256), 0, s, a, g);
     hipError_t e = hipGetLastError();
     if (e) return e;
-    hipLaunchKernelGGL(k_chunk_attn_combine, dim3(tasks), dim3(256), 0, s, c.attn_o, c.attn_ml, nsplit, MT, g, b.step,
+    hipLaunchKernelGGL(k_chunk_attn_combine, dim3(ntasks * g.Hkv, 4), dim3(256), 0, s, c.attn_o, c.attn_ml, nsplit, g, c.tab,
                        c.att_hi, c.att_lo);
     return hipGetLastError();
 }

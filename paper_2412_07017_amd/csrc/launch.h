@@ -27,23 +27,46 @@ struct DecodeBuffers {
     const float* rope_sin;
 };
 
-constexpr int CHUNK_MAX = 64;          // rows per forward pass of the append-chunk path
+constexpr int CHUNK_MAX = 96;          // rows per forward pass of the append-chunk path
+constexpr int CHUNK_MAX_TASKS = 128;   // attention tiles (32 query columns of one group) per pass
 constexpr int CHUNK_ATTN_MAX_SPLIT = 32;
-constexpr int CHUNK_GEMM_MAX_SPLIT = 4;
+constexpr int CHUNK_ATTN_MAX_UNITS = 4096;   // (task, kv head, key split) partial results per pass
+constexpr int CHUNK_GEMM_MAX_SPLIT = 8;
+
+// What one pass of the append-chunk path processes: rows, grouped by sequence.  A group is a run of
+// consecutive rows appended to one sequence: [chosen token] ++ [interrupt tokens], or plain tokens.
+// The host fills the table; k_begin_chunk resolves the tokens that are chosen on the device.
+struct ChunkRow { int32_t token, seq, pos, row0, n, pad0, pad1, pad2; };          // row0, n: its group
+struct ChunkGroup {
+    int32_t seq, row0, n, pos0;
+    int32_t forced;     // first row: >= 0 this token, -1 greedy argmax of the sequence's logits, -2 already in the row table
+    int32_t head;       // row of this group in the output-head product, -1: no logits wanted
+    int32_t pad0, pad1;
+};
+struct ChunkTask { int32_t seq, row0, n, pos0, tile, pad0, pad1, pad2; };         // query columns 32 tile .. 32 tile + 31 of a group
+struct ChunkTable {
+    int32_t rows, ngroups, ntasks, nhead;
+    ChunkRow row[CHUNK_MAX];
+    ChunkGroup group[CHUNK_MAX];
+    ChunkTask task[CHUNK_MAX_TASKS];
+};
 
 // Device buffers of the append-chunk path (bf16 models).  "hi/lo" are the two bf16 planes of a value.
 struct ChunkBuffers {
-    int32_t* tokens;          // [CHUNK_MAX]
+    ChunkTable* tab;
+    int32_t* chosen;          // [CHUNK_MAX] token chosen for the first row of each group
     float* x;                 // [CHUNK_MAX][d] residual stream
     // inputs of the products, CHUNK_MAX rows each, stored in matrix-core operand order (tiled planes)
-    bf16_t *nrm_hi, *nrm_lo;  // d columns:     normalised input of the QKV and gate/up products
+    bf16_t *nrm_hi, *nrm_lo;  // d columns:     normalised input of the QKV, gate/up and output-head products
     bf16_t *att_hi, *att_lo;  // Hq*dh columns: attention output
     bf16_t *act_hi, *act_lo;  // F columns:     SwiGLU output
-    bf16_t *q_hi, *q_lo;      // [Hq][CHUNK_MAX][dh] rotated, scaled queries
+    // rotated, scaled queries [Hkv][q_cols][dh]: the columns of a group are [q head within the kv group][row]
+    bf16_t *q_hi, *q_lo;
+    int q_cols;               // G * CHUNK_MAX + 32 (a tile may read up to 31 columns past its group)
     float* part;              // split-K partial planes of the current product
     size_t part_capacity;     // floats in `part`
-    float* attn_o;            // [tasks][split][dh][32]
-    float* attn_ml;           // [tasks][split][2][32]
+    float* attn_o;            // [unit][dh][32]      unit = (task * Hkv + kv head) * nsplit + split
+    float* attn_ml;           // [unit][2][32]
 };
 
 // Fused (persistent, single-kernel) decoding step.
@@ -73,18 +96,26 @@ hipError_t launch_decode_fused(int dtype, const FusedPlan& plan, const FusedLaun
 
 hipError_t decode_init(int dtype, int max_k);
 void decode_set_gemv_grid(int grid);
-hipError_t launch_begin_chunk(const DecodeBuffers& b, int seq, int rows, hipStream_t s);
+hipError_t chunk_init();
+hipError_t launch_begin_chunk(const ChunkBuffers& c, const DecodeBuffers& b, int ngroups, hipStream_t s);
 hipError_t launch_chunk_embed(const void* E, const ChunkBuffers& c, int rows, const Geom& g, hipStream_t s);
 hipError_t launch_chunk_resid_norm(const ChunkBuffers& c, bool add_partials, int S, int MT, const float* gain, int rows,
                                    const Geom& g, hipStream_t s);
-hipError_t launch_chunk_last_row(const ChunkBuffers& c, int S, int MT, const DecodeBuffers& b, const Geom& g, hipStream_t s);
+// residual stream of the last row of group `group` -> the single-row path's x (and its sequence -> the step descriptor)
+hipError_t launch_chunk_last_row(const ChunkBuffers& c, int S, int MT, int group, const DecodeBuffers& b, const Geom& g,
+                                 hipStream_t s);
+// last rows of all groups that want logits: residual + final norm -> rows 0..nhead-1 of the nrm planes
+hipError_t launch_chunk_head_rows(const ChunkBuffers& c, int S, int MT, const float* gain, int ngroups, const Geom& g,
+                                  hipStream_t s);
+// rows of the head product -> logits of their sequences, greedy argmax -> next_token
+hipError_t launch_chunk_logits(const ChunkBuffers& c, int MT_head, float* logits_base, const DecodeBuffers& b, int ngroups,
+                               const Geom& g, hipStream_t s);
 hipError_t launch_chunk_swiglu(const ChunkBuffers& c, int S, int MT, int rows, const Geom& g, hipStream_t s);
 hipError_t launch_chunk_rope_kv(const ChunkBuffers& c, int S, void* kv_layer, const DecodeBuffers& b, int rows, int MT,
                                 const Geom& g, hipStream_t s);
 hipError_t launch_chunk_gemm(const void* W, int N, int K, const bf16_t* xhi, const bf16_t* xlo, const ChunkBuffers& c,
                              int S, int MT, hipStream_t s);
-hipError_t launch_chunk_attn(const ChunkBuffers& c, const void* kv_layer, int nsplit, int MT, const DecodeBuffers& b,
-                             const Geom& g, hipStream_t s);
+hipError_t launch_chunk_attn(const ChunkBuffers& c, const void* kv_layer, int nsplit, int ntasks, const Geom& g, hipStream_t s);
 hipError_t launch_begin_step(const DecodeBuffers& b, int seq, int forced, hipStream_t s);
 hipError_t launch_embed(int dtype, const void* E, const DecodeBuffers& b, const Geom& g, hipStream_t s);
 hipError_t launch_qkv(int dtype, const void* wqkv, const float* gain, void* kv_layer, const DecodeBuffers& b,

@@ -102,7 +102,7 @@ def test_8b_workload_on_4_layers_matches_oracle(trunc4):
 
 @pytest.mark.timeout(600)
 def test_append_chunk_sizes_agree_with_oracle_and_each_other(trunc4):
-    """The matrix-core append path for every chunk shape (ragged tails, one and two column tiles, split-K
+    """The matrix-core append path for every chunk shape (ragged tails, one to three column tiles, split-K
     factors) against the from-scratch oracle, and against the token-by-token path of the decode kernels."""
     import paper_2412_07017_amd as pkg
     wl, model, w_dev, w_cpu, spec = trunc4
@@ -112,7 +112,7 @@ def test_append_chunk_sizes_agree_with_oracle_and_each_other(trunc4):
     want_a = dec.prefill(toks[:150]).copy()
     want_b = dec.inject(toks[150:]).copy()
     outs = {}
-    for chunk, split in ((1, 0), (2, 0), (7, 0), (24, 0), (32, 1), (33, 0), (48, 2), (64, 0), (64, 4), (64, 3)):
+    for chunk, split in ((1, 0), (2, 0), (7, 0), (24, 0), (32, 1), (33, 0), (48, 2), (64, 0), (64, 4), (64, 3), (65, 0), (96, 0), (96, 8), (24, 5)):
         lm = pkg.AsyncLM(model, w_dev, max_positions=256, stream=torch.cuda.Stream())
         lm.set_option("chunk", chunk)
         lm.set_option("chunk_split", split)
@@ -178,5 +178,60 @@ def test_full_depth_8b_short_stream_matches_oracle(trunc4):
     lm.prefill(0, prompt)
     worst, n, n_gated = _compare_stream(lm, ref, {"events": events}, n_decode, events)
     print("8b/32-layer: max |logit err| = %.3e over %d vectors, %d margin-gated ids identical" % (worst, n + 2, n_gated))
+    lm.close()
+    assert worst <= TOL, worst
+
+
+@pytest.mark.timeout(900)
+def test_step_batch_ragged_sequences_match_independent_oracle_sequences(trunc4):
+    """asynclm_step_batch on the matrix-core path: six sequences of ragged length share every weight pass; rows
+    are [chosen token] ++ [interrupt tokens] per sequence (Sec. 5.3).  Covers single-row groups, interrupts
+    of 16-32 tokens, one interrupt that is longer than a pass (continued in the next pass), greedy choice on
+    the device and the output head on the matrix cores, against one independent oracle decoder per sequence."""
+    import paper_2412_07017_amd as pkg
+    wl, model, w_dev, w_cpu, spec = trunc4
+    V = model.vocab
+    sh = orc.Shape.of(model)
+    lens = (37, 64, 150, 200, 97, 256)
+    prompts = [ai.uniform_tokens(ai.MASTER_SEED, 911, n, V, sub=i) for i, n in enumerate(lens)]
+    tk = lambda n, sub: ai.uniform_tokens(ai.MASTER_SEED, 912, n, V, sub=sub)
+    plan = [{}, {2: tk(24, 0)}, {0: tk(16, 1), 5: tk(32, 2)}, {}, {1: tk(120, 3)}, {3: tk(31, 4), 4: tk(17, 5), 0: tk(20, 6)}, {}, {}]
+    decs = [orc.CachedDecoder(sh, w_cpu, dtype=np.float32) for _ in prompts]
+    for d, p in zip(decs, prompts):
+        d.prefill(p)
+    lm = pkg.AsyncLM(model, w_dev, max_positions=512, max_seqs=6, stream=torch.cuda.Stream())
+    for s, p in enumerate(prompts):
+        lm.prefill(s, p)
+    worst, gated = 0.0, 0
+    order = [3, 0, 5, 1, 4, 2]
+    for t, ev in enumerate(plan):
+        margins = [orc.top2_margin(d.logits) for d in decs]
+        chosen = []
+        for s, d in enumerate(decs):
+            chosen.append(d.decode_step())
+            if s in ev:
+                d.inject(ev[s])
+        intr = [ev.get(s, []) for s in order]
+        if t % 2 == 0:
+            got = lm.step_batch(order, None, intr)                      # greedy on the device
+            for i, s in enumerate(order):
+                if margins[s] > MARGIN:
+                    assert got[i] == chosen[s], (t, s)
+                    gated += 1
+                assert got[i] == chosen[s], "near tie in the reference stream: pick another seed"
+        else:
+            got = lm.step_batch(order, [chosen[s] for s in order], intr)
+            assert list(got) == [chosen[s] for s in order]
+        for s, d in enumerate(decs):
+            got_l = lm.logits(s)
+            assert np.isfinite(got_l).all()
+            worst = max(worst, float(np.abs(got_l - d.logits).max()))
+            assert lm.seq_len(s) == d.length
+    print("step_batch 8b/4-layer, 6 sequences: max |logit err| = %.3e, %d margin-gated ids identical" % (worst, gated))
+    # the same sequences continue correctly through the single-sequence calls (they read the rows the batch wrote)
+    for s, d in enumerate(decs):
+        tok = d.decode_step()
+        assert lm.decode_step(s, forced_token=tok) == tok
+        worst = max(worst, float(np.abs(lm.logits(s) - d.logits).max()))
     lm.close()
     assert worst <= TOL, worst

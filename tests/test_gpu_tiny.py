@@ -184,3 +184,72 @@ def test_results_are_deterministic(tiny):
         outs.append(lm.logits(0))
         lm.close()
     assert np.array_equal(outs[0], outs[1])
+
+
+def _batch_reference(sh, w_cpu, prompts, plan, dtype):
+    """Oracle of a batched run: one cached decoder per sequence, stepped independently (Sec. 5.3: a step
+    appends [chosen token] ++ [queued interrupt tokens] to the sequence).  plan[t] = {seq: tokens}."""
+    decs = [orc.CachedDecoder(sh, w_cpu, dtype=dtype) for _ in prompts]
+    for d, p in zip(decs, prompts):
+        d.prefill(p)
+    choose, chosen, after = [], [], []
+    for ev in plan:
+        choose.append([d.logits.copy() for d in decs])
+        toks = []
+        for s, d in enumerate(decs):
+            toks.append(d.decode_step())
+            if s in ev:
+                d.inject(ev[s])
+        chosen.append(toks)
+        after.append([d.logits.copy() for d in decs])
+    return choose, chosen, after
+
+
+def test_step_batch_matches_independent_oracle_sequences(tiny):
+    """asynclm_step_batch on the fp32 preset (sequence-by-sequence fallback of models outside the matrix-core
+    append path): three sequences, interrupts riding with the chosen token, greedy and forced choices."""
+    pkg, wl, spec, w_cpu, w_dev, stream, ref = tiny
+    V = wl.model.vocab
+    prompts = [ai.uniform_tokens(ai.MASTER_SEED, 901, n, V, sub=i) for i, n in enumerate((5, 17, 33))]
+    plan = [{}, {1: ai.uniform_tokens(ai.MASTER_SEED, 902, 6, V)}, {0: ai.uniform_tokens(ai.MASTER_SEED, 902, 3, V, sub=1),
+            2: ai.uniform_tokens(ai.MASTER_SEED, 902, 9, V, sub=2)}, {}, {}]
+    choose, chosen, after = _batch_reference(orc.Shape.of(wl.model), w_cpu, prompts, plan, np.float64)
+    lm = _new(tiny, max_seqs=3)
+    for s, p in enumerate(prompts):
+        lm.prefill(s, p)
+    worst = 0.0
+    for t, ev in enumerate(plan):
+        intr = [ev.get(s, []) for s in range(3)]
+        if t % 2 == 0:      # greedy on the device
+            got = lm.step_batch([0, 1, 2], None, intr)
+            for s in range(3):
+                if orc.top2_margin(choose[t][s]) > MARGIN:
+                    assert got[s] == chosen[t][s]
+                if got[s] != chosen[t][s]:
+                    pytest.skip("near tie in the reference stream")
+        else:
+            got = lm.step_batch([2, 0, 1], [chosen[t][2], chosen[t][0], chosen[t][1]], [intr[2], intr[0], intr[1]])
+            assert list(got) == [chosen[t][2], chosen[t][0], chosen[t][1]]
+        for s in range(3):
+            worst = max(worst, float(np.abs(lm.logits(s) - after[t][s]).max()))
+    assert [lm.seq_len(s) for s in range(3)] == [5 + 5 + 3, 17 + 5 + 6, 33 + 5 + 9]
+    lm.close()
+    assert worst <= TOL, worst
+
+
+def test_step_batch_rejects_bad_arguments_without_changing_state(tiny):
+    pkg, wl, spec, w_cpu, w_dev, stream, ref = tiny
+    lm = _new(tiny, max_seqs=3, max_positions=40)
+    lm.prefill(0, spec["prompt"][:30])
+    lm.prefill(1, spec["prompt"][:10])
+    before = lm.logits(0).copy()
+    for args, code in ((([0, 0], None, None), pkg.E_INVAL), (([0, 3], None, None), pkg.E_INVAL),
+                       (([0, 2], None, None), pkg.E_STATE), (([0, 1], [0, wl.model.vocab], None), pkg.E_INVAL),
+                       (([1, 0], None, [[1], list(range(10))]), pkg.E_CAPACITY),
+                       (([0, 1], None, [[], [wl.model.vocab]]), pkg.E_INVAL)):
+        with pytest.raises(pkg.AsyncLMError) as ei:
+            lm.step_batch(*args)
+        assert ei.value.code == code, args
+    assert lm.seq_len(0) == 30 and lm.seq_len(1) == 10
+    assert np.array_equal(lm.logits(0), before)
+    lm.close()
