@@ -33,7 +33,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=4)
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--workload", default="8b", choices=["tiny", "8b", "8b-long", "70b"])
+    ap.add_argument("--workload", default="8b", choices=["tiny", "8b", "8b-long", "8b-ragged16", "70b"])
     ap.add_argument("--layers", type=int, default=0, help="truncate the model (0 = full depth); for experiments only")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--chunk", type=int, default=0, help="override the library's rows per forward pass for prefill/inject")
@@ -89,11 +89,92 @@ def cpu_baseline(wl, model, w_dev, spec, seconds_budget=25.0):
     }
 
 
+def bench_ragged(args):
+    """The 16-sequence preset: every step is one asynclm_step_batch call (one pass over the weights for all
+    sequences; the interrupts that arrived after the previous token ride with the chosen tokens).  A bench
+    "step" is one such batched step; value = generated tokens per second summed over the sequences."""
+    import numpy as np
+    import torch
+    import asynclm_inputs as ai
+    import paper_2412_07017_amd as pkg
+    wl = ai.preset(args.workload)
+    model = wl.model if not args.layers else ai.truncated(wl.model, args.layers)
+    spec = ai.build_workload(args.workload)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    t0 = time.perf_counter()
+    w_dev = ai.make_weights(model, device=dev)
+    torch.cuda.synchronize()
+    t_weights = time.perf_counter() - t0
+    stream = torch.cuda.Stream(device=dev)
+    ns = wl.n_seqs
+    n_steps = min(args.warmup + args.steps, spec["n_decode"])
+    grow = [n_steps + sum(len(t) for ev in spec["step_events"][:n_steps] for s, t in ev if s == q) for q in range(ns)]
+    max_pos = max(len(p) + g for p, g in zip(spec["prompts"], grow)) + 8
+    lm = pkg.AsyncLM(model, w_dev, max_positions=max_pos, max_seqs=ns, stream=stream)
+    for kv in args.opt:
+        k, v = kv.split("=")
+        lm.set_option(k, int(v))
+    t0 = time.perf_counter()
+    for q, p in enumerate(spec["prompts"]):
+        lm.prefill(q, p)
+    lm.synchronize()
+    t_prefill = time.perf_counter() - t0
+    seqs = list(range(ns))
+
+    def step(t):
+        ev = dict(spec["step_events"][t])
+        return lm.step_batch(seqs, None, [ev.get(q, []) for q in seqs])
+
+    for t in range(args.warmup):
+        step(t)
+    lm.synchronize()
+    len_start = sum(lm.seq_len(q) for q in seqs)
+    rows = 0
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    e0.record(stream)
+    for t in range(args.warmup, n_steps):
+        step(t)
+        rows += ns + sum(len(x) for _, x in spec["step_events"][t])
+    e1.record(stream)
+    lm.synchronize()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    len_end = sum(lm.seq_len(q) for q in seqs)
+    timed = n_steps - args.warmup
+    ms_step = e0.elapsed_time(e1) / timed
+    bytes_step = model.weight_bytes_per_step() + (len_start + len_end) / 2.0 * model.kv_bytes_per_position() + ns * 4 * model.vocab
+    ach = bytes_step / (ms_step * 1e-3)
+    out = {
+        "metric": "decode tokens/s @ batch 1 (% HBM roofline); us per k-token interrupt inject",
+        "value": timed * ns / wall, "unit": "tokens/s", "n_gpus": 1, "steps": timed, "warmup": args.warmup,
+        "ms_per_step": wall * 1e3 / timed, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32 accumulate over %s weights and K/V" % model.dtype, "data": "synthetic",
+        "config": {"workload": "%s: %d layers, d %d, %dq/%dkv heads x %d, ffn %d, vocab %d, %s; %d sequences, contexts %d..%d "
+                               "tokens; step = one batched step (chosen tokens + the interrupts of 16-32 tokens that arrived, "
+                               "p = 0.05 per sequence and step) in one pass over the weights"
+                               % (wl.name, model.n_layers, model.d_model, model.n_q_heads, model.n_kv_heads, model.head_dim,
+                                  model.ffn, model.vocab, model.dtype, ns, min(map(len, spec["prompts"])), max(map(len, spec["prompts"]))),
+                   "context_tokens_total": [len_start, len_end], "rows_per_step": rows / timed, "seed": ai.MASTER_SEED},
+        "batch_ms_per_step": ms_step, "batch_hbm_frac": ach / HBM_PEAK, "batch_bytes_per_step": bytes_step,
+        "prefill_s": t_prefill, "weights_s": t_weights,
+        "roofline": {"bound": "hbm", "kernel": "whole batched step (all kernels of one pass)", "achieved": ach / 1e9,
+                     "peak": HBM_PEAK / 1e9, "unit": "GB/s", "frac": ach / HBM_PEAK, "traffic": None,
+                     "bytes_per_launch": bytes_step, "ms_per_launch": ms_step},
+    }
+    lm.close()
+    print(json.dumps(out))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (--gpus must be 1)", file=sys.stderr)
         sys.exit(2)
+    if args.workload == "8b-ragged16":
+        return bench_ragged(args)
     import numpy as np
     import torch
     import asynclm_inputs as ai

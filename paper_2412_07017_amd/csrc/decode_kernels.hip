@@ -6,6 +6,8 @@
 #include "launch.h"
 #include "decode_device.h"
 
+#include <algorithm>
+
 namespace asynclm {
 
 // ---------------------------------------------------------------------------------------------
@@ -149,41 +151,51 @@ __global__ __launch_bounds__(256) void k_attn_decode(AttnArgs a, Geom g) {
     __syncthreads();
     if (!s_last) return;
     __threadfence();
-    // weights of the splits: f_s = exp(m_s - M) / L, staged in LDS (reuses the wave buffers)
+    // weights of the splits: f_s = exp(m_s - M) / L, one wave per head at a time, lane = split
     __syncthreads();                              // the partial accumulators in LDS have been read
     float* s_f = lds;                             // [G][ATTN_MAX_SPLIT] factors
-    float* s_lv = s_f + G * ATTN_MAX_SPLIT;       // [G][ATTN_MAX_SPLIT] partial sums
-    for (int t = tid; t < G * nsplit; t += 256) {
-        const int h = t / nsplit, sp = t - h * nsplit;
-        const float* ml = a.part_ml + ((size_t)(kvh * G + h) * nsplit + sp) * 2;
-        s_f[h * ATTN_MAX_SPLIT + sp] = ml[0];
-        s_lv[h * ATTN_MAX_SPLIT + sp] = ml[1];
-    }
-    __syncthreads();
-    if (tid < G) {
-        float M = -INFINITY, L = 0.f;
-        for (int sp = 0; sp < nsplit; ++sp) M = fmaxf(M, s_f[tid * ATTN_MAX_SPLIT + sp]);
-        for (int sp = 0; sp < nsplit; ++sp) {
-            const float ms = s_f[tid * ATTN_MAX_SPLIT + sp];
+    {
+        const int lane = tid & 63, wave = tid >> 6;
+        for (int h = wave; h < G; h += 4) {
+            const float* ml = a.part_ml + (size_t)(kvh * G + h) * nsplit * 2;
+            const float ms = lane < nsplit ? ml[lane * 2] : -INFINITY;
+            const float ls = lane < nsplit ? ml[lane * 2 + 1] : 0.f;
+            const float M = wave_max_all(ms);
             const float f = ms > -INFINITY ? expf(ms - M) : 0.f;
-            L += s_lv[tid * ATTN_MAX_SPLIT + sp] * f;
-            s_f[tid * ATTN_MAX_SPLIT + sp] = f;
+            const float L = wave_sum_all(ls * f);
+            s_f[h * ATTN_MAX_SPLIT + lane] = f / L;
         }
-        const float inv = 1.f / L;
-        for (int sp = 0; sp < nsplit; ++sp) s_f[tid * ATTN_MAX_SPLIT + sp] *= inv;
     }
     __syncthreads();
-    for (int t = tid; t < G * DH / 4; t += 256) {
-        const int h = t / (DH / 4), d4 = t - h * (DH / 4), hq = kvh * G + h;
-        const float4* src = (const float4*)(a.part_acc + (size_t)hq * nsplit * DH) + d4;
-        float4 r = make_float4(0.f, 0.f, 0.f, 0.f);
-#pragma unroll 8
-        for (int sp = 0; sp < nsplit; ++sp) {
-            const float4 v = src[(size_t)sp * (DH / 4)];
-            const float f = s_f[h * ATTN_MAX_SPLIT + sp];
-            r.x = fmaf(v.x, f, r.x); r.y = fmaf(v.y, f, r.y); r.z = fmaf(v.z, f, r.z); r.w = fmaf(v.w, f, r.w);
+    // thread = (output float4, half of the splits); the two halves meet in LDS
+    {
+        constexpr int NO = G * DH / 4;            // output float4s of this kv head
+        float4* s_half = reinterpret_cast<float4*>(lds + G * ATTN_MAX_SPLIT);
+        for (int base = 0; base < NO; base += 128) {
+            const int t = base + (tid & 127), half = tid >> 7;
+            const int tc = min(t, NO - 1);
+            const int h = tc / (DH / 4), d4 = tc - h * (DH / 4), hq = kvh * G + h;
+            const float4* src = (const float4*)(a.part_acc + (size_t)hq * nsplit * DH) + d4;
+            const int per = (nsplit + 1) / 2, sp0 = half * per, sp1 = min(nsplit, sp0 + per);
+            float4 r = make_float4(0.f, 0.f, 0.f, 0.f);
+            for (int sp = sp0; sp < sp1; sp += 8) {
+                float4 v[8];
+#pragma unroll
+                for (int k = 0; k < 8; ++k) v[k] = src[(size_t)min(sp + k, sp1 - 1) * (DH / 4)];
+#pragma unroll
+                for (int k = 0; k < 8; ++k) {
+                    const float f = sp + k < sp1 ? s_f[h * ATTN_MAX_SPLIT + min(sp + k, ATTN_MAX_SPLIT - 1)] : 0.f;
+                    r.x = fmaf(v[k].x, f, r.x); r.y = fmaf(v[k].y, f, r.y); r.z = fmaf(v[k].z, f, r.z); r.w = fmaf(v[k].w, f, r.w);
+                }
+            }
+            if (half == 1) s_half[tid & 127] = r;
+            __syncthreads();
+            if (half == 0 && t < NO) {
+                const float4 o2 = s_half[tid];
+                ((float4*)(a.o + (size_t)hq * DH))[d4] = make_float4(r.x + o2.x, r.y + o2.y, r.z + o2.z, r.w + o2.w);
+            }
+            __syncthreads();
         }
-        ((float4*)(a.o + (size_t)hq * DH))[d4] = r;
     }
     if (tid == 0) a.counters[kvh] = 0;
 }
@@ -243,6 +255,7 @@ __global__ __launch_bounds__(256) void k_argmax(const float* __restrict__ logits
 // ---------------------------------------------------------------------------------------------
 
 static int g_gemv_grid = 256;       // workgroups per matrix-vector kernel; decode_init sets it to the number of compute units
+static size_t g_gemv_lds_limit = 48 * 1024;   // dynamic LDS a matrix-vector kernel may ask for (raised by decode_init)
 
 template <typename WT, int EPI>
 static hipError_t launch_gemv_t(const GemvArgs& a0, const Geom& g, hipStream_t s) {
@@ -251,6 +264,7 @@ static hipError_t launch_gemv_t(const GemvArgs& a0, const Geom& g, hipStream_t s
     a.done_cap = (a.units + grid * 4 - 1) / (grid * 4) + 1;
     const int kg = a.K / Elem<WT>::EPL, kt = (kg + 255) / 256;
     const size_t lds = (size_t)(kt * 256 + 64) * Elem<WT>::EPL * sizeof(float) + (size_t)4 * a.done_cap * sizeof(float4);
+    if (lds > g_gemv_lds_limit) return hipErrorInvalidValue;
     hipLaunchKernelGGL((k_gemv<WT, EPI>), dim3(grid), dim3(256), lds, s, a, g);
     return hipGetLastError();
 }
@@ -278,8 +292,10 @@ hipError_t decode_init(int dtype, int max_k) {
         if (hipGetDevice(&dev) == hipSuccess && hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0)
             g_gemv_grid = cus;
     }
-    const int bytes = (max_k + 8 * 256 + 64 * 8) * (int)sizeof(float) + 64 * 1024;     // staged vector, padding, parked units
+    // staged vector with its padding + parked units (16 KiB cover 256 units per wave), within the 160 KiB of a compute unit
+    const int bytes = std::min((max_k + 8 * 256 + 64 * 8) * (int)sizeof(float) + 16 * 1024, 160 * 1024);
     if (bytes <= 48 * 1024) return hipSuccess;
+    g_gemv_lds_limit = (size_t)bytes;
     hipError_t e;
     if (dtype == 0) {
         if ((e = set_lds_t<float, EPI_STORE>(bytes))) return e;

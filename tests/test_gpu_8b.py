@@ -136,6 +136,32 @@ def test_append_chunk_sizes_agree_with_oracle_and_each_other(trunc4):
         assert np.abs(lc - dec.logits).max() <= TOL, key
 
 
+@pytest.mark.timeout(600)
+def test_decode_attention_split_counts_agree_with_oracle(trunc4):
+    """Decode attention with forced split counts: up to 8 splits are merged by the O projection, more by the
+    last workgroup of each kv head (the long-context path), on the grouped-query bf16 shape."""
+    import paper_2412_07017_amd as pkg
+    wl, model, w_dev, w_cpu, spec = trunc4
+    toks = spec["prompt"][:300]
+    dec = orc.CachedDecoder(orc.Shape.of(model), w_cpu, dtype=np.float32)
+    dec.prefill(toks)
+    want0 = dec.logits.copy()
+    t1 = dec.decode_step()
+    want1 = dec.logits.copy()
+    for nsplit in (1, 3, 8, 9, 24, 64):
+        lm = pkg.AsyncLM(model, w_dev, max_positions=320, stream=torch.cuda.Stream())
+        lm.set_option("chunk", 1)                 # the prompt goes through the decode kernels too
+        lm.set_option("attn_split", nsplit)
+        lm.prefill(0, toks[:280])
+        lm.inject_interrupt(0, toks[280:])
+        e0 = float(np.abs(lm.logits(0) - want0).max())
+        assert lm.decode_step(0, forced_token=t1) == t1
+        e1 = float(np.abs(lm.logits(0) - want1).max())
+        lm.close()
+        print("attn_split %2d: max |logit err| %.3e %.3e" % (nsplit, e0, e1))
+        assert e0 <= TOL and e1 <= TOL, nsplit
+
+
 @pytest.mark.timeout(900)
 def test_single_plane_bf16_cache_matches_oracle_with_rounded_cache(trunc4):
     """The 2-byte cache format (hi plane only) rounds K and V to bf16 when they are written.  That

@@ -110,7 +110,7 @@ def test_inject_equals_prefill_of_concatenation_on_device(tiny):
         x.close()
 
 
-@pytest.mark.parametrize("nsplit", [1, 2, 4, 64])
+@pytest.mark.parametrize("nsplit", [1, 2, 4, 16, 33, 64])
 def test_attention_split_count_does_not_change_logits(tiny, nsplit):
     pkg, wl, spec, w_cpu, w_dev, stream, ref = tiny
     s = ref["stream"]
