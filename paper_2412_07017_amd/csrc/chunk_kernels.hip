@@ -269,9 +269,9 @@ __global__ void k_chunk_rope_kv(const float* __restrict__ P, int S, size_t s_str
         const int vh = h - g.Hq - g.Hkv;
         bf16_t* vp = kv_layer + g.kv_v_offset + seq_off + (size_t)vh * g.kv_head_stride + (size_t)pos * g.dh;
         vp[i] = ahi; vp[i + half] = bhi; vp[g.kv_lo_offset + i] = alo; vp[g.kv_lo_offset + i + half] = blo;
-        bf16_t* vt = kv_layer + g.kv_vt_offset + seq_off + (size_t)vh * g.kv_head_stride + pos;   // [dh][max_pos]
-        vt[(size_t)i * g.max_pos] = ahi; vt[(size_t)(i + half) * g.max_pos] = bhi;
-        vt[g.kv_lo_offset + (size_t)i * g.max_pos] = alo; vt[g.kv_lo_offset + (size_t)(i + half) * g.max_pos] = blo;
+        bf16_t* vt = kv_layer + g.kv_vt_offset + seq_off + (size_t)vh * g.kv_head_stride;
+        const size_t oa = vt_tile_off(pos, i), ob = vt_tile_off(pos, i + half);
+        vt[oa] = ahi; vt[ob] = bhi; vt[g.kv_lo_offset + oa] = alo; vt[g.kv_lo_offset + ob] = blo;
     }
 }
 
@@ -434,10 +434,105 @@ struct ChunkAttnArgs {
     int32_t nsplit, q_cols;
 };
 
+// K tile (32 keys x 128 channels, one plane) as loaded: instruction q covers rows 4q .. 4q+3, lane l holds
+// row 4q + l/16, 16-byte chunk l%16 (1 KiB contiguous per instruction).
+__device__ __forceinline__ void attn_k_load(uint4 (&kh)[8], uint4 (&kl)[8], const bf16_t* Kp, size_t lo, int key0, int lane) {
+    const bf16_t* p = Kp + (size_t)(key0 + (lane >> 4)) * 128 + (lane & 15) * 8;
+#pragma unroll
+    for (int q = 0; q < 8; ++q) { kh[q] = load16(p + q * 512); kl[q] = load16(p + lo + q * 512); }
+}
+
+// V^T tile (both planes) in operand order: instruction (dt, t) is one contiguous KiB in lane order.
+__device__ __forceinline__ void attn_v_load(uint4 (&vh)[8], uint4 (&vl)[8], const bf16_t* Vt, size_t lo, int tile, int lane) {
+    const bf16_t* p = Vt + ((size_t)tile * 8 * 64 + lane) * 8;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) { vh[k] = load16(p + k * 512); vl[k] = load16(p + lo + k * 512); }
+}
+
+// chunk position of 16-byte chunk c of row r in the wave's LDS tile (conflict-free for the row-wise writes and
+// for the reads of the permuted key rows)
+__device__ __forceinline__ int attn_k_slot(int r, int c) { return r * 16 + (c ^ ((r & 7) | ((r >> 1) & 8))); }
+
+struct AttnState {
+    f32x16 o[4];
+    float mrun, lrun;
+};
+
+// One 32-key tile: K goes through the wave's LDS tile (attn_stage_k) into A-operand order (key rows permuted so
+// that the D registers of a lane hold 16 consecutive keys), then S^T = K Q^T, online softmax, O^T += V^T P^T.
+__device__ __forceinline__ void attn_stage_k(const uint4 (&kh)[8], const uint4 (&kl)[8], uint4* kt, int lane) {
+    const int r0 = lane >> 4, c = lane & 15;
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+        kt[attn_k_slot(4 * q + r0, c)] = kh[q];
+        kt[512 + attn_k_slot(4 * q + r0, c)] = kl[q];
+    }
+}
+
+__device__ __forceinline__ void attn_tile(AttnState& st, const uint4 (&vh)[8], const uint4 (&vl)[8], const uint4 (&qh)[8],
+                                          const uint4 (&ql)[8], const uint4* kt, int key0, int qpos, int lane) {
+    const int i = lane & 31, gh = lane >> 5;
+    const int krow = (i >> 3) * 4 + (i & 3) + 16 * ((i >> 2) & 1);   // key (within the tile) held in A row i
+    f32x16 s;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) s[r] = 0.f;
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+        const uint4 ah = kt[attn_k_slot(krow, 2 * t + gh)], al = kt[512 + attn_k_slot(krow, 2 * t + gh)];
+        s = mfma_bf16(ah, qh[t], s);
+        s = mfma_bf16(al, qh[t], s);
+        s = mfma_bf16(ah, ql[t], s);
+    }
+    // register r of lane (j, g) is key key0 + 16 g + r for query column j
+    float mx = -INFINITY;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        if (key0 + 16 * gh + r > qpos) s[r] = -INFINITY;
+        mx = fmaxf(mx, s[r]);
+    }
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    const float mnew = fmaxf(st.mrun, mx);
+    const float msafe = mnew == -INFINITY ? 0.f : mnew;
+    const float corr = expf(st.mrun - msafe);
+    float psum = 0.f;
+    uint4 ph[2], pl[2];
+    {
+        bf16_t hi[16], lw[16];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const float p = expf(s[r] - msafe);
+            psum += p;
+            split_bf16(p, hi[r], lw[r]);
+        }
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            ph[t] = make_uint4(hi[8 * t] | ((uint32_t)hi[8 * t + 1] << 16), hi[8 * t + 2] | ((uint32_t)hi[8 * t + 3] << 16),
+                               hi[8 * t + 4] | ((uint32_t)hi[8 * t + 5] << 16), hi[8 * t + 6] | ((uint32_t)hi[8 * t + 7] << 16));
+            pl[t] = make_uint4(lw[8 * t] | ((uint32_t)lw[8 * t + 1] << 16), lw[8 * t + 2] | ((uint32_t)lw[8 * t + 3] << 16),
+                               lw[8 * t + 4] | ((uint32_t)lw[8 * t + 5] << 16), lw[8 * t + 6] | ((uint32_t)lw[8 * t + 7] << 16));
+        }
+    }
+    st.lrun = st.lrun * corr + psum;
+    st.mrun = mnew;
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) st.o[dt][r] *= corr;
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            st.o[dt] = mfma_bf16(vh[dt * 2 + t], ph[t], st.o[dt]);
+            st.o[dt] = mfma_bf16(vl[dt * 2 + t], ph[t], st.o[dt]);
+            st.o[dt] = mfma_bf16(vh[dt * 2 + t], pl[t], st.o[dt]);
+        }
+    }
+}
+
 __global__ __launch_bounds__(256) void k_chunk_attn(ChunkAttnArgs a, Geom g) {
     constexpr int DH = 128;
+    extern __shared__ uint4 attn_lds[];                    // [4 waves][hi | lo][512 chunks] K tiles
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int i = lane & 31, gh = lane >> 5;
+    uint4* kt = attn_lds + wave * 1024;
     const int G = g.Hq / g.Hkv;
     const int kvh = blockIdx.x % g.Hkv, split = blockIdx.y * 4 + wave;
     const ChunkTask T = a.tab->task[blockIdx.x / g.Hkv];
@@ -451,105 +546,58 @@ __global__ __launch_bounds__(256) void k_chunk_attn(ChunkAttnArgs a, Geom g) {
     const bf16_t* Vt = a.kv_layer + g.kv_vt_offset + seq_off;
     const size_t lo = g.kv_lo_offset;
 
-    // this lane's query column: (q head gq, row r) of the group; columns past the group are computed and dropped
+    // this lane's query column: (q head, row r) of the group; columns past the group are computed and dropped
     const int col = 32 * T.tile + i;
-    const int gq = min(col / T.n, G - 1), r = col - (col / T.n) * T.n;
-    const int qpos = T.pos0 + r;
-    (void)gq;
+    const int qpos = T.pos0 + col % T.n;
 
-    // B operand of S^T = K Q^T: lane (j, g) holds q[j][64 g + 8 t + e]
-    uint4 qh[8], ql[8];
-    {
-        const size_t qo = ((size_t)kvh * a.q_cols + (size_t)G * T.row0 + col) * DH + gh * 64;
-#pragma unroll
-        for (int t = 0; t < 8; ++t) { qh[t] = load16(a.q_hi + qo + t * 8); ql[t] = load16(a.q_lo + qo + t * 8); }
-    }
-    const int krow = (i >> 3) * 4 + (i & 3) + 16 * ((i >> 2) & 1);   // key (within a tile) held in A row i
-
-    f32x16 o[4];
+    AttnState st;
 #pragma unroll
     for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
-        for (int r2 = 0; r2 < 16; ++r2) o[dt][r2] = 0.f;
-    float mrun = -INFINITY, lrun = 0.f;
+        for (int r = 0; r < 16; ++r) st.o[dt][r] = 0.f;
+    st.mrun = -INFINITY; st.lrun = 0.f;
 
-    for (int tile = t0; tile < t1; ++tile) {
-        const int key0 = tile * 32;
-        uint4 kh[8], kl[8], vh[4][2], vl[4][2];
+    if (t0 < t1) {
+        // B operand of S^T = K Q^T: lane (j, g) holds q[j][16 t + 8 g + e]
+        uint4 qh[8], ql[8];
         {
-            const bf16_t* kp = Kp + (size_t)(key0 + krow) * DH + gh * 64;
+            const size_t qo = ((size_t)kvh * a.q_cols + (size_t)G * T.row0 + col) * DH + gh * 8;
 #pragma unroll
-            for (int t = 0; t < 8; ++t) { kh[t] = load16(kp + t * 8); kl[t] = load16(kp + lo + t * 8); }
-#pragma unroll
-            for (int dt = 0; dt < 4; ++dt) {
-                const bf16_t* vp = Vt + (size_t)(dt * 32 + i) * g.max_pos + key0 + 16 * gh;
-#pragma unroll
-                for (int t = 0; t < 2; ++t) { vh[dt][t] = load16(vp + 8 * t); vl[dt][t] = load16(vp + lo + 8 * t); }
-            }
+            for (int t = 0; t < 8; ++t) { qh[t] = load16(a.q_hi + qo + t * 16); ql[t] = load16(a.q_lo + qo + t * 16); }
         }
-        f32x16 s;
-#pragma unroll
-        for (int r2 = 0; r2 < 16; ++r2) s[r2] = 0.f;
-#pragma unroll
-        for (int t = 0; t < 8; ++t) {
-            s = mfma_bf16(kh[t], qh[t], s);
-            s = mfma_bf16(kl[t], qh[t], s);
-            s = mfma_bf16(kh[t], ql[t], s);
-        }
-        // register r2 of lane (j, g) is key key0 + 16 g + r2 for query column j
-        float mx = -INFINITY;
-#pragma unroll
-        for (int r2 = 0; r2 < 16; ++r2) {
-            if (key0 + 16 * gh + r2 > qpos) s[r2] = -INFINITY;
-            mx = fmaxf(mx, s[r2]);
-        }
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-        const float mnew = fmaxf(mrun, mx);
-        const float msafe = mnew == -INFINITY ? 0.f : mnew;
-        const float corr = expf(mrun - msafe);
-        float psum = 0.f;
-        uint4 ph[2], pl[2];
-        {
-            bf16_t hi[16], lw[16];
-#pragma unroll
-            for (int r2 = 0; r2 < 16; ++r2) {
-                const float p = expf(s[r2] - msafe);
-                psum += p;
-                split_bf16(p, hi[r2], lw[r2]);
-            }
-#pragma unroll
-            for (int t = 0; t < 2; ++t) {
-                ph[t] = make_uint4(hi[8 * t] | ((uint32_t)hi[8 * t + 1] << 16), hi[8 * t + 2] | ((uint32_t)hi[8 * t + 3] << 16),
-                                   hi[8 * t + 4] | ((uint32_t)hi[8 * t + 5] << 16), hi[8 * t + 6] | ((uint32_t)hi[8 * t + 7] << 16));
-                pl[t] = make_uint4(lw[8 * t] | ((uint32_t)lw[8 * t + 1] << 16), lw[8 * t + 2] | ((uint32_t)lw[8 * t + 3] << 16),
-                                   lw[8 * t + 4] | ((uint32_t)lw[8 * t + 5] << 16), lw[8 * t + 6] | ((uint32_t)lw[8 * t + 7] << 16));
-            }
-        }
-        lrun = lrun * corr + psum;
-        mrun = mnew;
-#pragma unroll
-        for (int dt = 0; dt < 4; ++dt) {
-#pragma unroll
-            for (int r2 = 0; r2 < 16; ++r2) o[dt][r2] *= corr;
-#pragma unroll
-            for (int t = 0; t < 2; ++t) {
-                o[dt] = mfma_bf16(vh[dt][t], ph[t], o[dt]);
-                o[dt] = mfma_bf16(vl[dt][t], ph[t], o[dt]);
-                o[dt] = mfma_bf16(vh[dt][t], pl[t], o[dt]);
-            }
+        // Once K of a tile is staged in LDS its registers take K of the next tile (clamped to the last one), and the V
+        // registers take the next tile's V as soon as the P V product has used them, so the next tile's loads are in
+        // flight while a tile is multiplied.  No conditional code around loads or their uses (the compiler would
+        // sink the loads next to the uses).
+        uint4 kh[8], kl[8], vh[8], vl[8];
+        __builtin_amdgcn_sched_barrier(0);          // issue order q, K, V: the waits in the loop count on it
+        attn_k_load(kh, kl, Kp, lo, t0 * 32, lane);
+        __builtin_amdgcn_sched_barrier(0);
+        attn_v_load(vh, vl, Vt, lo, t0, lane);
+        __builtin_amdgcn_sched_barrier(0);
+        for (int tile = t0; tile < t1; ++tile) {
+            const int n1 = min(tile + 1, t1 - 1);
+            attn_stage_k(kh, kl, kt, lane);
+            __builtin_amdgcn_sched_barrier(0);
+            attn_k_load(kh, kl, Kp, lo, n1 * 32, lane);
+            __builtin_amdgcn_sched_barrier(0);
+            attn_tile(st, vh, vl, qh, ql, kt, tile * 32, qpos, lane);
+            __builtin_amdgcn_sched_barrier(0);
+            attn_v_load(vh, vl, Vt, lo, n1, lane);
+            __builtin_amdgcn_sched_barrier(0);
         }
     }
-    lrun += __shfl_xor(lrun, 32, 64);
+    st.lrun += __shfl_xor(st.lrun, 32, 64);
 
     const size_t unit = (size_t)blockIdx.x * a.nsplit + split;
     float* po = a.part_o + unit * DH * 32;
 #pragma unroll
     for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
-        for (int r2 = 0; r2 < 16; ++r2) po[(size_t)(dt * 32 + 8 * (r2 >> 2) + 4 * gh + (r2 & 3)) * 32 + i] = o[dt][r2];
+        for (int r2 = 0; r2 < 16; ++r2) po[(size_t)(dt * 32 + 8 * (r2 >> 2) + 4 * gh + (r2 & 3)) * 32 + i] = st.o[dt][r2];
     if (gh == 0) {
         float* pm = a.part_ml + unit * 64;
-        pm[i] = mrun; pm[32 + i] = lrun;
+        pm[i] = st.mrun; pm[32 + i] = st.lrun;
     }
 }
 
@@ -679,12 +727,15 @@ hipError_t launch_chunk_rope_kv(const ChunkBuffers& c, int S, void* kv_layer, co
     return hipGetLastError();
 }
 
+constexpr int ATTN_LDS_BYTES = 4 * 1024 * 16;       // k_chunk_attn: per wave one K tile, two planes
+
 static size_t gemm_lds_bytes(int MT) { return (size_t)(2048 + 2 * MT * 2 * 512) * 16; }
 
 hipError_t chunk_init() {
     hipError_t e;
     if ((e = hipFuncSetAttribute((const void*)k_chunk_gemm<1>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)gemm_lds_bytes(1)))) return e;
     if ((e = hipFuncSetAttribute((const void*)k_chunk_gemm<2>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)gemm_lds_bytes(2)))) return e;
+    if ((e = hipFuncSetAttribute((const void*)k_chunk_attn, hipFuncAttributeMaxDynamicSharedMemorySize, ATTN_LDS_BYTES))) return e;
     if ((e = hipFuncSetAttribute((const void*)k_chunk_gemm<3>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)gemm_lds_bytes(3)))) return e;
     return hipSuccess;
 }
@@ -708,7 +759,7 @@ hipError_t launch_chunk_attn(const ChunkBuffers& c, const void* kv_layer, int ns
     ChunkAttnArgs a{};
     a.q_hi = c.q_hi; a.q_lo = c.q_lo; a.kv_layer = (const bf16_t*)kv_layer; a.tab = c.tab;
     a.part_o = c.attn_o; a.part_ml = c.attn_ml; a.nsplit = nsplit; a.q_cols = c.q_cols;
-    hipLaunchKernelGGL(k_chunk_attn, dim3(ntasks * g.Hkv, nsplit / 4), dim3(256), 0, s, a, g);
+    hipLaunchKernelGGL(k_chunk_attn, dim3(ntasks * g.Hkv, nsplit / 4), dim3(256), ATTN_LDS_BYTES, s, a, g);
     hipError_t e = hipGetLastError();
     if (e) return e;
     hipLaunchKernelGGL(k_chunk_attn_combine, dim3(ntasks * g.Hkv, 4), dim3(256), 0, s, c.attn_o, c.attn_ml, nsplit, g, c.tab,

@@ -32,12 +32,20 @@ struct Geom {
     float scale;            // 1/sqrt(dh)
     // K/V cache, element strides: [seq][layer][K | V | V^T][hi | lo][Hkv][max_pos][dh].  The lo plane
     // exists only in the paired bf16 format, where a value is stored as bf16(x) + bf16(x - bf16(x)).
-    // V^T ([dh][max_pos] per head, same size) exists only with the append-chunk path: its PV product
+    // V^T (same size per head, laid out by vt_tile_off) exists only with the append-chunk path: its PV product
     // on the matrix cores needs 8 consecutive positions of one channel in one register quad.
     // max_pos is the allocated row count (capacity rounded up to a multiple of 32).
     size_t kv_head_stride, kv_v_offset, kv_lo_offset /* 0: no lo plane */, kv_vt_offset /* 0: no V^T */;
     size_t kv_layer_stride, kv_seq_stride;
 };
+
+// Offset (elements, relative to the head's plane) of value (pos, channel) in the transposed V planes (head_dim 128).
+// Per tile of 32 positions the 128 x 32 block is stored in matrix-core A-operand order of the P V product:
+// [tile][channel / 32][position bit 3][position bit 4][channel % 32][position % 8], so the 64 lanes of a wave read
+// one contiguous KiB per instruction.
+__host__ __device__ inline size_t vt_tile_off(int pos, int ch) {
+    return ((((size_t)(pos >> 5) * 4 + (ch >> 5)) * 2 + ((pos >> 3) & 1)) * 64 + ((pos >> 4) & 1) * 32 + (ch & 31)) * 8 + (pos & 7);
+}
 
 enum KernelClass {
     KC_BEGIN = 0, KC_EMBED, KC_QKV, KC_ATTN, KC_OPROJ, KC_GATEUP, KC_DOWN, KC_LMHEAD, KC_ARGMAX,

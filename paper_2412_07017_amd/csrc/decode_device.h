@@ -44,43 +44,6 @@ struct EpiOut {
     int32_t pos, seq;       // QKV: position and sequence of the row being processed
 };
 
-// Called by one lane with the two finished dot products of unit u.
-template <typename WT, int EPI>
-__device__ __forceinline__ void gemv_finish(int u, float sa, float sb, const EpiOut& o, const Geom& g) {
-    if (EPI == EPI_STORE) {
-        o.y[2 * u] = sa;
-        if (2 * u + 1 < o.rows) o.y[2 * u + 1] = sb;
-    } else if (EPI == EPI_RESID) {
-        o.y[2 * u] = o.res[2 * u] + sa;
-        if (2 * u + 1 < o.rows) o.y[2 * u + 1] = o.res[2 * u + 1] + sb;
-    } else if (EPI == EPI_SWIGLU) {
-        o.y[u] = sa / (1.f + expf(-sa)) * sb;
-    } else {
-        const int hs = g.dh == 128 ? 6 : 5, half = 1 << hs;
-        const int h = u >> hs, i = u & (half - 1);
-        const int pos = o.pos;
-        const size_t seq_off = (size_t)o.seq * g.kv_seq_stride;
-        if (h < g.Hq + g.Hkv) {
-            const float c = o.rope_cos[(size_t)pos * half + i], s = o.rope_sin[(size_t)pos * half + i];
-            const float ra = sa * c - sb * s, rb = sb * c + sa * s;
-            if (h < g.Hq) { o.q_out[h * g.dh + i] = ra; o.q_out[h * g.dh + i + half] = rb; }
-            else {
-                WT* kp = (WT*)o.kv_layer + seq_off + (size_t)(h - g.Hq) * g.kv_head_stride + (size_t)pos * g.dh;
-                kv_store(kp + i, ra, g.kv_lo_offset); kv_store(kp + i + half, rb, g.kv_lo_offset);
-            }
-        } else {
-            const size_t head_off = seq_off + (size_t)(h - g.Hq - g.Hkv) * g.kv_head_stride;
-            WT* vp = (WT*)o.kv_layer + g.kv_v_offset + head_off + (size_t)pos * g.dh;
-            kv_store(vp + i, sa, g.kv_lo_offset); kv_store(vp + i + half, sb, g.kv_lo_offset);
-            if (g.kv_vt_offset) {   // transposed copy [dh][max_pos] read by the append-chunk attention
-                WT* vt = (WT*)o.kv_layer + g.kv_vt_offset + head_off + pos;
-                kv_store(vt + (size_t)i * g.max_pos, sa, g.kv_lo_offset);
-                kv_store(vt + (size_t)(i + half) * g.max_pos, sb, g.kv_lo_offset);
-            }
-        }
-    }
-}
-
 __device__ __forceinline__ void amax_merge(float& bv, int& bi, float v, int i) {
     if (v > bv || (v == bv && i < bi)) { bv = v; bi = i; }
 }
@@ -503,9 +466,9 @@ __device__ __forceinline__ void finish_unit(int u, float sa, float sb, float e0,
             WT* vp = (WT*)o.kv_layer + g.kv_v_offset + head_off + (size_t)o.pos * g.dh;
             kv_store(vp + i, ra, g.kv_lo_offset); kv_store(vp + i + half, rb, g.kv_lo_offset);
             if (g.kv_vt_offset) {
-                WT* vt = (WT*)o.kv_layer + g.kv_vt_offset + head_off + o.pos;
-                kv_store(vt + (size_t)i * g.max_pos, ra, g.kv_lo_offset);
-                kv_store(vt + (size_t)(i + half) * g.max_pos, rb, g.kv_lo_offset);
+                WT* vt = (WT*)o.kv_layer + g.kv_vt_offset + head_off;
+                kv_store(vt + vt_tile_off(o.pos, i), ra, g.kv_lo_offset);
+                kv_store(vt + vt_tile_off(o.pos, i + half), rb, g.kv_lo_offset);
             }
         }
     }
