@@ -38,8 +38,27 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--chunk", type=int, default=0, help="override the library's rows per forward pass for prefill/inject")
     ap.add_argument("--opt", action="append", default=[], help="library option name=value (repeatable), for experiments")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run three plain device copies of 1 GiB (torch copy kernel) so that a counter run can be scaled by them")
     ap.add_argument("--fused", type=int, default=-1, help="1/0: force the single-kernel / per-operation decoding step (default: library's choice)")
     return ap.parse_args()
+
+
+def recorded_traffic(model):
+    """HBM bytes per launch of the gate/up kernel from the committed hardware-counter record, or None when the
+    record is for another shape or the kernel's sources have changed since the counters were taken."""
+    import hashlib
+    path = os.path.join(ROOT, "paper_2412_07017_amd", "traffic_gate_up.json")
+    try:
+        rec = json.load(open(path))
+        h = hashlib.sha256()
+        for f in rec["source_files"]:
+            h.update(open(os.path.join(ROOT, f), "rb").read())
+        if h.hexdigest() != rec["sources_sha256"] or (model.d_model, model.ffn, model.dtype) != (4096, 14336, "bf16"):
+            return None
+        return float(rec["fetch_bytes_per_launch"] + rec["write_bytes_per_launch"])
+    except (OSError, KeyError, ValueError):
+        return None
 
 
 def cpu_baseline(wl, model, w_dev, spec, seconds_budget=25.0):
@@ -267,7 +286,8 @@ def main():
         k_bytes = 2 * model.ffn * model.d_model * eb + 4 * model.d_model * 2 + 4 * model.ffn
         k_name = "gate_up_swiglu (k_gemv)"
     roofline = {"bound": "hbm", "kernel": k_name, "achieved": k_bytes / (k_ms * 1e-3) / 1e9,
-                "peak": HBM_PEAK / 1e9, "unit": "GB/s", "traffic": None,
+                "peak": HBM_PEAK / 1e9, "unit": "GB/s",
+                "traffic": recorded_traffic(model) if "fused_step_kernel" not in classes else None,
                 "bytes_per_launch": k_bytes, "ms_per_launch": k_ms}
     roofline["frac"] = roofline["achieved"] / roofline["peak"]
     per_class = {k: {"ms_per_step": v["ms"] / 5, "launches_per_step": v["launches"] // 5} for k, v in classes.items()}
@@ -291,6 +311,13 @@ def main():
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, model, w_dev, spec)
+    if args.copy_calibration:
+        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        out["copy_calibration_bytes"] = int(src.numel() * 4)
     lm.close()
     print(json.dumps(out))
 

@@ -8,6 +8,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libasynclm.so")
+PROBE = os.path.join(HERE, "traffic_probe")      # stand-alone C-ABI consumer for hardware-counter runs
 SOURCES = ["api.hip", "decode_kernels.hip", "decode_fused.hip", "chunk_kernels.hip"]
 
 
@@ -31,6 +32,16 @@ def build_library(verbose: bool = False) -> str:
         print(res.stderr)
     if res.returncode != 0:
         raise RuntimeError("hipcc failed")
+    cmd = [hipcc_path(), "--offload-arch=gfx950", "-O2", "-std=c++17", "-Wno-unused-command-line-argument",
+           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+           os.path.join(CSRC, "traffic_probe.hip"), "-o", PROBE, "-L", HERE, "-lasynclm", "-Wl,-rpath,$ORIGIN"]
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if verbose or res.returncode != 0:
+        print(" ".join(cmd))
+        print(res.stdout)
+        print(res.stderr)
+    if res.returncode != 0:
+        raise RuntimeError("hipcc failed (traffic_probe)")
     return LIB
 
 
