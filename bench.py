@@ -214,7 +214,7 @@ def main():
     t_weights = time.perf_counter() - t0
 
     stream = torch.cuda.Stream(device=dev)
-    max_pos = wl.prompt_len + n_blocks * (block + k_intr) + 64
+    max_pos = wl.prompt_len + n_blocks * (block + k_intr) + 3 * (k_intr + 1) + 64
     lm = pkg.AsyncLM(model, w_dev, max_positions=max_pos, stream=stream)
     if args.chunk:
         lm.set_option("chunk", args.chunk)
@@ -255,6 +255,19 @@ def main():
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     len_end = lm.seq_len(0)
+
+    # Sec. 5.3 merged form: the interrupt rides with the next chosen token in ONE forward pass
+    # (asynclm_step_batch on one sequence); its cost beyond a plain decoding step is the price of the interrupt.
+    merged_ms = []
+    for j in range(3):
+        m0, m1 = ev(), ev()
+        m0.record(stream)
+        lm.step_batch([0], None, [intr[j % len(intr)]])
+        m1.record(stream)
+        lm.synchronize()
+        if j:
+            merged_ms.append(m0.elapsed_time(m1))
+    torch.cuda.synchronize()
 
     dec_ms = [a.elapsed_time(b) for a, b, c in rec]
     inj_ms = [b.elapsed_time(c) for a, b, c in rec]
@@ -306,6 +319,8 @@ def main():
         "decode_tokens_per_s": decode_tok_s, "decode_ms_per_token": ms_dec_step,
         "decode_hbm_frac": decode_frac, "decode_bytes_per_token": bytes_step,
         "inject_us": ms_inject * 1e3, "inject_tokens": k_intr, "inject_in_decode_steps": ms_inject / ms_dec_step,
+        "merged_step_us": float(np.mean(merged_ms)) * 1e3,
+        "merged_inject_extra_in_decode_steps": float(np.mean(merged_ms)) / ms_dec_step - 1.0,
         "prefill_s": t_prefill, "weights_s": t_weights,
         "roofline": roofline, "kernel_classes": per_class,
     }

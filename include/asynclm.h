@@ -154,7 +154,10 @@ int asynclm_synchronize(asynclm_ctx *ctx);
  *   "graph"        (per-operation kernels only) 1 = replay decoding steps as a captured HIP graph,
  *                  0 = launch kernels one by one
  *   "attn_split"   0 = choose the number of sequence splits of decode attention from the length,
- *                  n > 0 = always use n */
+ *                  n > 0 = always use n
+ *   "attn_mfma_min" context length from which a decoding step runs its attention on the matrix cores (the
+ *                  append path's attention kernel with a one-row group; models with the append path only);
+ *                  0 = never.  Default 4096. */
 int asynclm_set_option(asynclm_ctx *ctx, const char *name, int32_t value);
 
 /* Per-kernel-class GPU time of ONE decoding step (forced token), measured with HIP events around

@@ -77,7 +77,7 @@ struct asynclm_ctx {
     int32_t* chosen_host = nullptr;     // pinned, CHUNK_MAX ints
 
     // options
-    int opt_chunk = 1, opt_graph = 1, opt_attn_split = 0, opt_chunk_split = 0, opt_fused = 0;
+    int opt_chunk = 1, opt_graph = 1, opt_attn_split = 0, opt_chunk_split = 0, opt_fused = 0, opt_attn_mfma_min = 4096;
 
     std::map<int, hipGraphExec_t> graphs;   // key: nsplit * 2 + with_head
 
@@ -136,17 +136,25 @@ void* kv_layer_ptr(const asynclm_ctx* c, int layer) {
 // Attention splits for a context of len_after tokens.  Up to 2048 tokens: at most MERGE_MAX_SPLIT splits, which
 // the O projection merges while it stages its input (no merge step at all).  Longer: up to ATTN_MAX_SPLIT
 // splits with a merge step of their own.
-struct SplitPlan { int nsplit; bool merge_in_oproj; };
+struct SplitPlan { int nsplit; bool merge_in_oproj; bool mfma; };
 
 SplitPlan pick_nsplit(const asynclm_ctx* c, int len_after) {
+    if (c->chunk_ok && c->opt_attn_mfma_min > 0 && len_after >= c->opt_attn_mfma_min) {
+        // long contexts: the chunk attention (matrix cores) with about two 32-key tiles per wave
+        const int tiles = (len_after + 31) / 32;
+        int n = ((tiles + 1) / 2 + 3) / 4 * 4;
+        n = std::max(4, std::min(n, CHUNK_ATTN_MAX_SPLIT));
+        if (c->opt_attn_split > 0) n = std::max(4, std::min((c->opt_attn_split + 3) / 4 * 4, CHUNK_ATTN_MAX_SPLIT));
+        return {n, false, true};
+    }
     if (c->opt_attn_split > 0) {
         const int n = c->opt_attn_split < ATTN_MAX_SPLIT ? c->opt_attn_split : ATTN_MAX_SPLIT;
-        return {n, n <= 8};
+        return {n, n <= 8, false};
     }
     const int want = (len_after + 63) / 64, cap = len_after <= 2048 ? 8 : ATTN_MAX_SPLIT;
     int n = 1;
     while (n < want && n < cap) n *= 2;
-    return {n, cap == 8};
+    return {n, cap == 8, false};
 }
 
 // One forward pass of a single row whose token/position are already in the step descriptor.
@@ -159,7 +167,8 @@ hipError_t forward_single(asynclm_ctx* c, int seq, bool with_head, SplitPlan sp)
     for (int l = 0; l < c->cfg.n_layers; ++l) {
         void* kvl = kv_layer_ptr(c, l);
         if ((e = run(c, KC_QKV, [&] { return launch_qkv(dt, c->wqkv[l], c->attn_norm[l], kvl, c->b, g, s); }))) return e;
-        if ((e = run(c, KC_ATTN, [&] { return launch_attn_decode(dt, kvl, sp.nsplit, sp.merge_in_oproj, c->b, g, s); }))) return e;
+        if (sp.mfma) { if ((e = run(c, KC_ATTN, [&] { return launch_decode_attn_mfma(c->cb, kvl, sp.nsplit, c->b, g, s); }))) return e; }
+        else if ((e = run(c, KC_ATTN, [&] { return launch_attn_decode(dt, kvl, sp.nsplit, sp.merge_in_oproj, c->b, g, s); }))) return e;
         if ((e = run(c, KC_OPROJ, [&] { return launch_oproj(dt, c->wo[l], sp.merge_in_oproj ? sp.nsplit : 0, c->b, g, s); }))) return e;
         if ((e = run(c, KC_GATEUP, [&] { return launch_gateup(dt, c->wgate_up[l], c->ffn_norm[l], c->b, g, s); }))) return e;
         if ((e = run(c, KC_DOWN, [&] { return launch_down(dt, c->wdown[l], c->b, g, s); }))) return e;
@@ -174,7 +183,7 @@ hipError_t forward_single(asynclm_ctx* c, int seq, bool with_head, SplitPlan sp)
 
 // The same pass, replayed from a captured graph (one graph per split count / head flag / sequence).
 hipError_t forward_single_graph(asynclm_ctx* c, int seq, bool with_head, SplitPlan sp) {
-    const int key = ((((seq * (ATTN_MAX_SPLIT + 1) + sp.nsplit) << 1) | (sp.merge_in_oproj ? 1 : 0)) << 1) | (with_head ? 1 : 0);
+    const int key = (((((seq * (ATTN_MAX_SPLIT + 1) + sp.nsplit) << 1) | (sp.merge_in_oproj ? 1 : 0)) << 1 | (sp.mfma ? 1 : 0)) << 1) | (with_head ? 1 : 0);
     auto it = c->graphs.find(key);
     if (it == c->graphs.end()) {
         hipError_t e;
@@ -702,6 +711,7 @@ int asynclm_set_option(asynclm_ctx* c, const char* name, int32_t value) {
     if (!std::strcmp(name, "gemv_grid")) { if (value < 1 || value > 4096) return ASYNCLM_E_INVAL; decode_set_gemv_grid(value); return ASYNCLM_OK; }
     if (!std::strcmp(name, "fused")) { c->opt_fused = (value && c->fused.supported) ? 1 : 0; return ASYNCLM_OK; }
     if (!std::strcmp(name, "graph")) { c->opt_graph = (value && c->stream) ? 1 : 0; return ASYNCLM_OK; }
+    if (!std::strcmp(name, "attn_mfma_min")) { if (value < 0) return ASYNCLM_E_INVAL; c->opt_attn_mfma_min = value; return ASYNCLM_OK; }
     if (!std::strcmp(name, "attn_split")) { if (value < 0 || value > ATTN_MAX_SPLIT) return ASYNCLM_E_INVAL; c->opt_attn_split = value; return ASYNCLM_OK; }
     return ASYNCLM_E_INVAL;
 }

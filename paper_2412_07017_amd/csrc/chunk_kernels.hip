@@ -602,10 +602,12 @@ __global__ __launch_bounds__(256) void k_chunk_attn(ChunkAttnArgs a, Geom g) {
 }
 
 // Merge the key splits of one (task, kv head) and emit the attention output as tiled hi/lo planes
-// (K = Hq*128).  grid (tasks * Hkv, 4): workgroup y handles channels 32 y .. 32 y + 31.
+// (K = Hq*128), or as an fp32 vector for single-row decoding.  grid (tasks * Hkv, 4): workgroup y handles
+// channels 32 y .. 32 y + 31.
 __global__ __launch_bounds__(256) void k_chunk_attn_combine(const float* __restrict__ part_o, const float* __restrict__ part_ml,
                                                             int nsplit, Geom g, const ChunkTable* __restrict__ tab,
-                                                            bf16_t* __restrict__ out_hi, bf16_t* __restrict__ out_lo) {
+                                                            bf16_t* __restrict__ out_hi, bf16_t* __restrict__ out_lo,
+                                                            float* __restrict__ out_f32) {
     constexpr int DH = 128;
     __shared__ float f[CHUNK_ATTN_MAX_SPLIT][32];
     const int tid = threadIdx.x;
@@ -658,11 +660,35 @@ __global__ __launch_bounds__(256) void k_chunk_attn_combine(const float* __restr
         const int m = T.row0 + r, hq = kvh * G + gq;
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-            bf16_t hi, lw;
-            split_bf16(v[u], hi, lw);
-            const size_t o = tiled_off(m, hq * DH + blockIdx.y * 32 + dl + 8 * u, g.Hq * DH);
-            out_hi[o] = hi; out_lo[o] = lw;
+            const int ch = blockIdx.y * 32 + dl + 8 * u;
+            if (out_f32) {                                  // single-row decoding: fp32 vector [Hq][dh] (m is 0)
+                out_f32[hq * DH + ch] = v[u];
+            } else {
+                bf16_t hi, lw;
+                split_bf16(v[u], hi, lw);
+                const size_t o = tiled_off(m, hq * DH + ch, g.Hq * DH);
+                out_hi[o] = hi; out_lo[o] = lw;
+            }
         }
+    }
+}
+
+// Single-row decoding through the chunk attention (long contexts): the rotated fp32 query of the step becomes
+// the hi/lo query planes of a one-row group (columns = the q heads of each kv head), and the row table gets the
+// group's only task.  grid = Hq, block = dh.
+__global__ void k_decode_attn_prep(const float* __restrict__ q, const StepDesc* __restrict__ step, Geom g,
+                                   ChunkTable* tab, bf16_t* __restrict__ q_hi, bf16_t* __restrict__ q_lo, int q_cols) {
+    const int hq = blockIdx.x, i = threadIdx.x;
+    const int G = g.Hq / g.Hkv, kvh = hq / G, gq = hq - kvh * G;
+    bf16_t hi, lo;
+    split_bf16(q[hq * g.dh + i] * g.scale, hi, lo);
+    const size_t o = ((size_t)kvh * q_cols + gq) * g.dh + i;
+    q_hi[o] = hi; q_lo[o] = lo;
+    if (hq == 0 && i == 0) {
+        ChunkTask T{};
+        T.seq = step->seq; T.row0 = 0; T.n = 1; T.pos0 = step->pos; T.tile = 0;
+        tab->task[0] = T;
+        tab->ntasks = 1;
     }
 }
 
@@ -752,7 +778,8 @@ hipError_t launch_chunk_gemm(const void* W, int N, int K, const bf16_t* xhi, con
     return hipGetLastError();
 }
 
-hipError_t launch_chunk_attn(const ChunkBuffers& c, const void* kv_layer, int nsplit, int ntasks, const Geom& g, hipStream_t s) {
+static hipError_t chunk_attn_launch(const ChunkBuffers& c, const void* kv_layer, int nsplit, int ntasks, const Geom& g,
+                                    float* out_f32, hipStream_t s) {
     if (nsplit < 4 || nsplit % 4 || nsplit > CHUNK_ATTN_MAX_SPLIT || ntasks < 1 || ntasks > CHUNK_MAX_TASKS ||
         (long long)ntasks * g.Hkv * nsplit > CHUNK_ATTN_MAX_UNITS)
         return hipErrorInvalidValue;
@@ -763,8 +790,21 @@ hipError_t launch_chunk_attn(const ChunkBuffers& c, const void* kv_layer, int ns
     hipError_t e = hipGetLastError();
     if (e) return e;
     hipLaunchKernelGGL(k_chunk_attn_combine, dim3(ntasks * g.Hkv, 4), dim3(256), 0, s, c.attn_o, c.attn_ml, nsplit, g, c.tab,
-                       c.att_hi, c.att_lo);
+                       c.att_hi, c.att_lo, out_f32);
     return hipGetLastError();
+}
+
+hipError_t launch_chunk_attn(const ChunkBuffers& c, const void* kv_layer, int nsplit, int ntasks, const Geom& g, hipStream_t s) {
+    return chunk_attn_launch(c, kv_layer, nsplit, ntasks, g, nullptr, s);
+}
+
+hipError_t launch_decode_attn_mfma(const ChunkBuffers& c, const void* kv_layer, int nsplit, const DecodeBuffers& b, const Geom& g,
+                                   hipStream_t s) {
+    if (g.dh != 128) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(k_decode_attn_prep, dim3(g.Hq), dim3(g.dh), 0, s, b.q, b.step, g, c.tab, c.q_hi, c.q_lo, c.q_cols);
+    hipError_t e = hipGetLastError();
+    if (e) return e;
+    return chunk_attn_launch(c, kv_layer, nsplit, 1, g, b.o, s);
 }
 
 }  // namespace asynclm

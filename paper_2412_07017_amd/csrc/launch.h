@@ -29,7 +29,7 @@ struct DecodeBuffers {
 
 constexpr int CHUNK_MAX = 96;          // rows per forward pass of the append-chunk path
 constexpr int CHUNK_MAX_TASKS = 128;   // attention tiles (32 query columns of one group) per pass
-constexpr int CHUNK_ATTN_MAX_SPLIT = 32;
+constexpr int CHUNK_ATTN_MAX_SPLIT = 64;
 constexpr int CHUNK_ATTN_MAX_UNITS = 4096;   // (task, kv head, key split) partial results per pass
 constexpr int CHUNK_GEMM_MAX_SPLIT = 8;
 
@@ -116,6 +116,9 @@ hipError_t launch_chunk_rope_kv(const ChunkBuffers& c, int S, void* kv_layer, co
 hipError_t launch_chunk_gemm(const void* W, int N, int K, const bf16_t* xhi, const bf16_t* xlo, const ChunkBuffers& c,
                              int S, int MT, hipStream_t s);
 hipError_t launch_chunk_attn(const ChunkBuffers& c, const void* kv_layer, int nsplit, int ntasks, const Geom& g, hipStream_t s);
+// single-row decoding attention on the matrix cores (long contexts): b.q -> b.o through the chunk attention
+hipError_t launch_decode_attn_mfma(const ChunkBuffers& c, const void* kv_layer, int nsplit, const DecodeBuffers& b, const Geom& g,
+                                   hipStream_t s);
 hipError_t launch_begin_step(const DecodeBuffers& b, int seq, int forced, hipStream_t s);
 hipError_t launch_embed(int dtype, const void* E, const DecodeBuffers& b, const Geom& g, hipStream_t s);
 hipError_t launch_qkv(int dtype, const void* wqkv, const float* gain, void* kv_layer, const DecodeBuffers& b,
