@@ -126,6 +126,13 @@ int asynclm_inject_interrupt(asynclm_ctx *ctx, int32_t seq, const int32_t *token
 int asynclm_step_batch(asynclm_ctx *ctx, int32_t nseq, const int32_t *seqs, const int32_t *forced,
                        const int32_t *intr_tokens, const int32_t *intr_offsets, int32_t *tokens_out);
 
+/* Device half of the token monitor (Sec. 5.1: the monitor keeps tokens such as the interrupt marker out of the
+ * next-token distribution): every later greedy choice of `seq` skips the n <= 31 token ids in `ids` (host pointer;
+ * n = 0 clears the list).  Applies to the tokens chosen by asynclm_decode_step and asynclm_step_batch when no token
+ * is forced, starting with the very next one; the logits themselves are returned unmasked.  The list survives
+ * asynclm_reset. */
+int asynclm_set_banned_tokens(asynclm_ctx *ctx, int32_t seq, const int32_t *ids, int32_t n);
+
 /* Copy the current next-token logits of `seq` (fp32) to out_host[0..n); n must equal vocab.
  * Synchronises the stream. */
 int asynclm_logits(asynclm_ctx *ctx, int32_t seq, float *out_host, int32_t n);

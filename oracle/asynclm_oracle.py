@@ -93,9 +93,14 @@ def softmax_rows(s: np.ndarray) -> np.ndarray:
     return e / np.sum(e, axis=-1, keepdims=True)
 
 
-def greedy(logits: np.ndarray) -> int:
-    """Index of the maximum; the lowest index wins ties."""
-    return int(np.argmax(logits))
+def greedy(logits: np.ndarray, banned: Sequence[int] = ()) -> int:
+    """Index of the maximum; the lowest index wins ties.  `banned` ids are not eligible (the token
+    monitor of Sec. 5.1 removes tokens such as the interrupt marker from the next-token distribution)."""
+    if len(banned) == 0:
+        return int(np.argmax(logits))
+    masked = np.array(logits, dtype=np.float64, copy=True)
+    masked[np.asarray(list(banned), dtype=np.int64)] = -np.inf
+    return int(np.argmax(masked))
 
 
 def round_to_bf16(x: np.ndarray) -> np.ndarray:
@@ -261,11 +266,11 @@ class CachedDecoder:
             raise RuntimeError("inject on an empty sequence")
         return self.append(tokens)
 
-    def decode_step(self, forced: Optional[int] = None) -> int:
-        """Choose the next token (greedy unless forced), append it, run one forward."""
+    def decode_step(self, forced: Optional[int] = None, banned: Sequence[int] = ()) -> int:
+        """Choose the next token (greedy over the ids not in `banned`, unless forced), append it, run one forward."""
         if self.logits is None:
             raise RuntimeError("decode on an empty sequence")
-        tok = greedy(self.logits) if forced is None else int(forced)
+        tok = greedy(self.logits, banned) if forced is None else int(forced)
         self.append([tok])
         return tok
 

@@ -12,7 +12,7 @@ KV_AUTO, KV_BF16 = 0, 1
 
 API_SYMBOLS = [
     "asynclm_create", "asynclm_destroy", "asynclm_prefill", "asynclm_decode_step",
-    "asynclm_inject_interrupt", "asynclm_step_batch", "asynclm_logits", "asynclm_logits_device", "asynclm_seq_len",
+    "asynclm_inject_interrupt", "asynclm_step_batch", "asynclm_set_banned_tokens", "asynclm_logits", "asynclm_logits_device", "asynclm_seq_len",
     "asynclm_reset", "asynclm_synchronize", "asynclm_set_option", "asynclm_profile_step", "asynclm_profile_trace",
     "asynclm_strerror", "asynclm_version",
 ]
@@ -173,6 +173,11 @@ class AsyncLM:
             off.ctypes.data_as(p32) if off is not None else None,
             out.ctypes.data_as(p32) if want_tokens else None), "asynclm_step_batch")
         return out if want_tokens else None
+
+    def set_banned_tokens(self, seq: int, ids) -> None:
+        t = _tok(ids)
+        self._check(self._lib.asynclm_set_banned_tokens(self._h, seq, t.ctypes.data_as(C.POINTER(C.c_int32)) if len(t) else None,
+                                                        len(t)), "asynclm_set_banned_tokens")
 
     def logits(self, seq: int) -> "np.ndarray":
         out = np.empty(self.vocab, dtype=np.float32)

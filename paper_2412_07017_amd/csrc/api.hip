@@ -73,6 +73,8 @@ struct asynclm_ctx {
     int32_t* token_host = nullptr;      // pinned, 1 int
 
     std::vector<int32_t> len;           // host mirror of the sequence lengths
+    std::vector<int32_t> nban;          // host mirror of the number of banned token ids per sequence
+    std::vector<char> choice_stale;     // the ban list changed after the sequence's greedy token was computed
     PassBuilder pass;                   // row table of the append-chunk pass being built
     int32_t* chosen_host = nullptr;     // pinned, CHUNK_MAX ints
 
@@ -202,9 +204,18 @@ hipError_t forward_single_graph(asynclm_ctx* c, int seq, bool with_head, SplitPl
     return hipGraphLaunch(it->second, c->stream);
 }
 
+// The greedy token of a sequence is computed when a forward pass ends; if the ban list changed since, it is
+// recomputed from the (unchanged) logits before it is used.
+hipError_t refresh_choice(asynclm_ctx* c, int seq) {
+    if (!c->choice_stale[seq]) return hipSuccess;
+    c->choice_stale[seq] = 0;
+    return launch_argmax(c->logits, c->b, c->g, c->stream, seq);
+}
+
 hipError_t step_one_token(asynclm_ctx* c, int seq, int forced, bool with_head) {
     hipError_t e;
-    if (c->opt_fused) {
+    if (forced < 0 && (e = refresh_choice(c, seq))) return e;
+    if (c->opt_fused && c->nban[seq] == 0) {      // the single-kernel step has no token mask
         FusedLaunch L{};
         L.layers_dev = c->layers_dev; L.n_layers = c->cfg.n_layers;
         L.embed = c->embed; L.final_norm = c->final_norm; L.lm_head = c->lm_head;
@@ -416,6 +427,8 @@ int asynclm_create(asynclm_ctx** out, const asynclm_config* cfg, const asynclm_w
         if (c->chunk_ok) c->opt_chunk = CHUNK_MAX;
     }
     c->len.assign(cfg->max_seqs, 0);
+    c->nban.assign(cfg->max_seqs, 0);
+    c->choice_stale.assign(cfg->max_seqs, 0);
 
     auto bail = [&](int code) { asynclm_destroy(c); return code; };
     hipError_t e;
@@ -439,6 +452,7 @@ int asynclm_create(asynclm_ctx** out, const asynclm_config* cfg, const asynclm_w
     ALLOC(c->b.amax_v, (size_t)ARGMAX_MAX_BLOCKS);
     ALLOC(c->b.amax_i, (size_t)ARGMAX_MAX_BLOCKS);
     ALLOC(c->b.amax_counter, 1);
+    ALLOC(c->b.banned, (size_t)cfg->max_seqs * (1 + BAN_MAX));
     if (c->chunk_ok) {
         ChunkBuffers& cb = c->cb;
         const size_t M = CHUNK_MAX, qd = (size_t)g.Hq * g.dh;
@@ -493,6 +507,7 @@ int asynclm_create(asynclm_ctx** out, const asynclm_config* cfg, const asynclm_w
     if (hipMemset(c->b.seq_state, 0, sizeof(SeqState) * cfg->max_seqs) != hipSuccess ||
         hipMemset(c->b.attn_counters, 0, sizeof(int32_t) * g.Hkv) != hipSuccess ||
         hipMemset(c->b.amax_counter, 0, sizeof(int32_t)) != hipSuccess ||
+        hipMemset(c->b.banned, 0, sizeof(int32_t) * cfg->max_seqs * (1 + BAN_MAX)) != hipSuccess ||
         hipMemset(c->b.step, 0, sizeof(StepDesc)) != hipSuccess || hipMemset(c->b.token_log, 0, 2 * sizeof(int32_t)) != hipSuccess)
         return bail(ASYNCLM_E_DEVICE);
     if (hipHostMalloc((void**)&c->token_host, 64, hipHostMallocDefault) != hipSuccess) return bail(ASYNCLM_E_NOMEM);
@@ -622,6 +637,8 @@ int asynclm_step_batch(asynclm_ctx* c, int32_t nseq, const int32_t* seqs, const 
 
     // One weight pass per CHUNK_MAX rows: groups are packed in the order given; a group that does not fit is
     // continued in the next pass (its later rows see its earlier ones through the cache).
+    for (int i = 0; i < nseq; ++i)
+        if (forced_of(i) < 0) HIPCK(c, refresh_choice(c, seqs[i]));
     PassBuilder& pb = c->pass;
     std::vector<int> owner;                 // group of the current pass -> index i whose token it chooses, or -1
     auto flush = [&]() -> int {
@@ -661,6 +678,23 @@ int asynclm_step_batch(asynclm_ctx* c, int32_t nseq, const int32_t* seqs, const 
     return flush();
 }
 
+int asynclm_set_banned_tokens(asynclm_ctx* c, int32_t seq, const int32_t* ids, int32_t n) {
+    int r = check_seq(c, seq);
+    if (r) return r;
+    if (n < 0 || n > BAN_MAX || (n > 0 && !ids)) return ASYNCLM_E_INVAL;
+    int32_t row[1 + BAN_MAX] = {0};
+    row[0] = n;
+    for (int i = 0; i < n; ++i) {
+        if (ids[i] < 0 || ids[i] >= c->cfg.vocab) return ASYNCLM_E_INVAL;
+        row[1 + i] = ids[i];
+    }
+    // pageable source: the runtime stages the row before the call returns; stream order puts it before later steps
+    HIPCK(c, hipMemcpyAsync(c->b.banned + (size_t)seq * (1 + BAN_MAX), row, sizeof(row), hipMemcpyHostToDevice, c->stream));
+    c->nban[seq] = n;
+    if (c->len[seq] > 0) c->choice_stale[seq] = 1;      // the next greedy choice is recomputed under the new list
+    return ASYNCLM_OK;
+}
+
 int asynclm_logits(asynclm_ctx* c, int32_t seq, float* out_host, int32_t n) {
     int r = check_seq(c, seq);
     if (r) return r;
@@ -694,6 +728,7 @@ int asynclm_reset(asynclm_ctx* c, int32_t seq) {
     if (r) return r;
     HIPCK(c, hipMemsetAsync(c->b.seq_state + seq, 0, sizeof(SeqState), c->stream));
     c->len[seq] = 0;
+    c->choice_stale[seq] = 0;
     return ASYNCLM_OK;
 }
 

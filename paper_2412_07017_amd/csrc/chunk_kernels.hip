@@ -187,7 +187,8 @@ __global__ __launch_bounds__(256) void k_chunk_head_rows(const float* __restrict
 // Workgroup = group that wants logits: row `head` of the output-head product -> logits of its sequence,
 // greedy argmax (lowest index on ties) -> next_token.
 __global__ __launch_bounds__(1024) void k_chunk_logits(const float* __restrict__ P, int V, const ChunkTable* __restrict__ tab,
-                                                       float* __restrict__ logits_base, SeqState* st) {
+                                                       float* __restrict__ logits_base, SeqState* st,
+                                                       const int32_t* __restrict__ banned) {
     __shared__ float sv[16];
     __shared__ int si[16];
     const ChunkGroup G = tab->group[blockIdx.x];
@@ -196,10 +197,14 @@ __global__ __launch_bounds__(1024) void k_chunk_logits(const float* __restrict__
     float* dst = logits_base + (size_t)G.seq * V;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     float bv = -INFINITY; int bi = 0x7fffffff;
+    const int32_t* ban = banned + (size_t)G.seq * (1 + BAN_MAX);
+    const int nban = ban[0];
     for (int i = tid; i < V; i += 1024) {
         const float v = src[i];
         dst[i] = v;
-        if (v > bv) { bv = v; bi = i; }             // i ascends: the first maximum is kept
+        bool allowed = true;
+        for (int k = 0; k < nban; ++k) allowed = allowed && i != ban[1 + k];
+        if (allowed && v > bv) { bv = v; bi = i; }  // i ascends: the first maximum is kept
     }
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) {
@@ -735,7 +740,7 @@ hipError_t launch_chunk_head_rows(const ChunkBuffers& c, int S, int MT, const fl
 hipError_t launch_chunk_logits(const ChunkBuffers& c, int MT_head, float* logits_base, const DecodeBuffers& b, int ngroups,
                                const Geom& g, hipStream_t s) {
     (void)MT_head;
-    hipLaunchKernelGGL(k_chunk_logits, dim3(ngroups), dim3(1024), 0, s, c.part, g.V, c.tab, logits_base, b.seq_state);
+    hipLaunchKernelGGL(k_chunk_logits, dim3(ngroups), dim3(1024), 0, s, c.part, g.V, c.tab, logits_base, b.seq_state, b.banned);
     return hipGetLastError();
 }
 

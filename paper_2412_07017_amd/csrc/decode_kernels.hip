@@ -205,18 +205,25 @@ __global__ __launch_bounds__(256) void k_attn_decode(AttnArgs a, Geom g) {
 // ---------------------------------------------------------------------------------------------
 
 __global__ __launch_bounds__(256) void k_argmax(const float* __restrict__ logits_base, int V, const StepDesc* step,
-                                                SeqState* st, float* part_v, int32_t* part_i, int32_t* counter) {
+                                                SeqState* st, float* part_v, int32_t* part_i, int32_t* counter,
+                                                const int32_t* __restrict__ banned, int seq_arg) {
     __shared__ float sv[4];
     __shared__ int si[4];
     __shared__ int s_last;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int seq = step->seq;
+    const int seq = seq_arg >= 0 ? seq_arg : step->seq;
     const float* logits = logits_base + (size_t)seq * V;
     const int nb = gridDim.x;
     const int per = (V + nb - 1) / nb;
     const int i0 = blockIdx.x * per, i1 = min(V, i0 + per);
     float bv = -INFINITY; int bi = 0x7fffffff;
-    for (int i = i0 + tid; i < i1; i += 256) amax_merge(bv, bi, logits[i], i);
+    const int32_t* ban = banned + (size_t)seq * (1 + BAN_MAX);
+    const int nban = ban[0];
+    for (int i = i0 + tid; i < i1; i += 256) {
+        bool allowed = true;
+        for (int k = 0; k < nban; ++k) allowed = allowed && i != ban[1 + k];
+        if (allowed) amax_merge(bv, bi, logits[i], i);
+    }
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) {
         const float ov = __shfl_xor(bv, o, 64); const int oi = __shfl_xor(bi, o, 64);
@@ -403,10 +410,10 @@ hipError_t launch_attn_decode(int dtype, const void* kv_layer, int nsplit, bool 
     return g.dh == 64 ? launch_attn_t<bf16_t, 64, false>(a, g, s) : launch_attn_t<bf16_t, 128, false>(a, g, s);
 }
 
-hipError_t launch_argmax(const float* logits_base, const DecodeBuffers& b, const Geom& g, hipStream_t s) {
+hipError_t launch_argmax(const float* logits_base, const DecodeBuffers& b, const Geom& g, hipStream_t s, int seq) {
     int nb = (g.V + 2047) / 2048;
     if (nb > ARGMAX_MAX_BLOCKS) nb = ARGMAX_MAX_BLOCKS;
-    hipLaunchKernelGGL(k_argmax, dim3(nb), dim3(256), 0, s, logits_base, g.V, b.step, b.seq_state, b.amax_v, b.amax_i, b.amax_counter);
+    hipLaunchKernelGGL(k_argmax, dim3(nb), dim3(256), 0, s, logits_base, g.V, b.step, b.seq_state, b.amax_v, b.amax_i, b.amax_counter, b.banned, seq);
     return hipGetLastError();
 }
 

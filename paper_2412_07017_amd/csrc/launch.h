@@ -6,6 +6,7 @@
 namespace asynclm {
 
 constexpr int ARGMAX_MAX_BLOCKS = 256;
+constexpr int BAN_MAX = 31;            // token ids per sequence that the greedy choice may be told to skip
 constexpr int ATTN_MAX_SPLIT = 64;
 
 // Device buffers of the single-row (decode) path.  All fp32 unless noted.
@@ -23,6 +24,7 @@ struct DecodeBuffers {
     float* amax_v;            // [ARGMAX_MAX_BLOCKS]
     int32_t* amax_i;
     int32_t* amax_counter;
+    int32_t* banned;          // [max_seqs][1 + BAN_MAX]: count, then the ids the greedy choice of the sequence skips
     const float* rope_cos;    // [max_pos][dh/2]
     const float* rope_sin;
 };
@@ -132,6 +134,7 @@ hipError_t launch_gateup(int dtype, const void* wgu, const float* gain, const De
 hipError_t launch_down(int dtype, const void* wd, const DecodeBuffers& b, const Geom& g, hipStream_t s);
 hipError_t launch_lmhead(int dtype, const void* wout, const float* gain, float* logits, const DecodeBuffers& b,
                          const Geom& g, hipStream_t s);
-hipError_t launch_argmax(const float* logits_base, const DecodeBuffers& b, const Geom& g, hipStream_t s);
+// greedy choice (banned ids skipped) of sequence `seq`, or of the step descriptor's sequence when seq < 0
+hipError_t launch_argmax(const float* logits_base, const DecodeBuffers& b, const Geom& g, hipStream_t s, int seq = -1);
 
 }  // namespace asynclm

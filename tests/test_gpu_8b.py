@@ -258,6 +258,15 @@ def test_step_batch_ragged_sequences_match_independent_oracle_sequences(trunc4):
             worst = max(worst, float(np.abs(got_l - d.logits).max()))
             assert lm.seq_len(s) == d.length
     print("step_batch 8b/4-layer, 6 sequences: max |logit err| = %.3e, %d margin-gated ids identical" % (worst, gated))
+    # banned ids (token monitor): the batched greedy choice skips them, per sequence
+    ban = {1: [int(np.argmax(decs[1].logits))], 4: [int(v) for v in np.argsort(-decs[4].logits)[:2]]}
+    for s, ids in ban.items():
+        lm.set_banned_tokens(s, ids)
+    want = [d.decode_step(banned=ban.get(s, ())) for s, d in enumerate(decs)]
+    got = lm.step_batch(list(range(6)), None, None)
+    assert list(got) == want
+    for s in ban:
+        lm.set_banned_tokens(s, [])
     # the same sequences continue correctly through the single-sequence calls (they read the rows the batch wrote)
     for s, d in enumerate(decs):
         tok = d.decode_step()

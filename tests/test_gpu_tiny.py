@@ -253,3 +253,34 @@ def test_step_batch_rejects_bad_arguments_without_changing_state(tiny):
     assert lm.seq_len(0) == 30 and lm.seq_len(1) == 10
     assert np.array_equal(lm.logits(0), before)
     lm.close()
+
+
+def test_banned_tokens_change_the_greedy_choice_only(tiny):
+    """Device half of the token monitor (Sec. 5.1): banned ids are skipped by the greedy choice, starting with
+    the very next token, and the logits stay unmasked."""
+    pkg, wl, spec, w_cpu, w_dev, stream, ref = tiny
+    sh = orc.Shape.of(wl.model)
+    dec = orc.CachedDecoder(sh, w_cpu)
+    dec.prefill(spec["prompt"])
+    lm = _new(tiny)
+    lm.prefill(0, spec["prompt"])
+    order = list(np.argsort(-dec.logits, kind="stable"))
+    for banned in ([order[0]], [order[0], order[1], order[2]], [], [order[1]]):
+        lm.set_banned_tokens(0, banned)
+        want = dec.decode_step(banned=banned)
+        got = lm.decode_step(0)
+        assert got == want, banned
+        assert np.abs(lm.logits(0) - dec.logits).max() <= TOL
+        order = list(np.argsort(-dec.logits, kind="stable"))
+    # a list set before a forward pass applies to the token chosen after it, forced tokens ignore the list
+    lm.set_banned_tokens(0, [order[0]])
+    assert lm.decode_step(0, forced_token=int(order[0])) == order[0]
+    dec.decode_step(forced=int(order[0]))
+    top = int(np.argmax(dec.logits))
+    lm.set_banned_tokens(0, [top])
+    assert lm.decode_step(0) == dec.decode_step(banned=[top])
+    with pytest.raises(pkg.AsyncLMError):
+        lm.set_banned_tokens(0, [wl.model.vocab])
+    with pytest.raises(pkg.AsyncLMError):
+        lm.set_banned_tokens(0, list(range(32)))
+    lm.close()

@@ -293,3 +293,21 @@ def test_fp32_oracle_close_to_fp64():
     a = orc.full_logits(sh, w, toks)
     b = orc.full_logits(sh, w, toks, dtype=np.float32)
     assert b.dtype == np.float32 and np.abs(a - b).max() < 2e-4 * np.abs(a).max()
+
+
+def test_greedy_skips_banned_ids_and_keeps_the_lowest_index_on_ties():
+    """The masked choice (token monitor, Sec. 5.1) against its definition written as a loop."""
+    rng = np.random.default_rng(5)
+    for trial in range(50):
+        logits = rng.integers(-3, 4, size=40).astype(np.float64)        # many ties
+        banned = list(rng.choice(40, size=int(rng.integers(0, 6)), replace=False))
+        best, best_i = -np.inf, -1
+        for i, v in enumerate(logits):
+            if i in banned:
+                continue
+            if v > best:
+                best, best_i = v, i
+        assert orc.greedy(logits, banned) == best_i
+    assert orc.greedy(np.array([1.0, 5.0, 5.0, 2.0])) == 1
+    assert orc.greedy(np.array([1.0, 5.0, 5.0, 2.0]), [1]) == 2
+    assert orc.greedy(np.array([1.0, 5.0, 5.0, 2.0]), [1, 2]) == 3
