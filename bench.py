@@ -215,7 +215,7 @@ def main():
 
     stream = torch.cuda.Stream(device=dev)
     max_pos = wl.prompt_len + n_blocks * (block + k_intr) + 3 * (k_intr + 1) + 64
-    lm = pkg.AsyncLM(model, w_dev, max_positions=max_pos, stream=stream)
+    lm = pkg.AsyncLM(model, w_dev, max_positions=max_pos, max_seqs=2, stream=stream)
     if args.chunk:
         lm.set_option("chunk", args.chunk)
     if args.fused >= 0:
@@ -231,13 +231,16 @@ def main():
     intr = [ai.uniform_tokens(ai.MASTER_SEED, 102, k_intr, model.vocab, sub=j) for j in range(n_blocks)]
     ev = lambda: torch.cuda.Event(enable_timing=True)
 
+    history = [int(t) for t in spec["prompt"]]          # the whole context, as the stateless variant would resend it
+
     def run_block(j, rec):
         e0, e1, e2 = ev(), ev(), ev()
         e0.record(stream)
         for _ in range(block):
-            lm.decode_step(0)                       # greedy on the device, token returned to the host
+            history.append(lm.decode_step(0))       # greedy on the device, token returned to the host
         e1.record(stream)
         lm.inject_interrupt(0, intr[j])
+        history.extend(int(t) for t in intr[j])
         e2.record(stream)
         rec.append((e0, e1, e2))
 
@@ -255,6 +258,19 @@ def main():
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     len_end = lm.seq_len(0)
+
+    # Sec. 5.5 stateless alternative: the session is discarded and the whole context (ending with the interrupt)
+    # is prefilled again; same resulting context as the in-flight inject, timed on a second sequence slot.
+    r0, r1 = ev(), ev()
+    lm.prefill(1, history)
+    lm.reset(1)
+    lm.synchronize()
+    r0.record(stream)
+    lm.prefill(1, history)
+    r1.record(stream)
+    lm.synchronize()
+    reprefill_ms = r0.elapsed_time(r1)
+    lm.reset(1)
 
     # Sec. 5.3 merged form: the interrupt rides with the next chosen token in ONE forward pass
     # (asynclm_step_batch on one sequence); its cost beyond a plain decoding step is the price of the interrupt.
@@ -319,6 +335,7 @@ def main():
         "decode_tokens_per_s": decode_tok_s, "decode_ms_per_token": ms_dec_step,
         "decode_hbm_frac": decode_frac, "decode_bytes_per_token": bytes_step,
         "inject_us": ms_inject * 1e3, "inject_tokens": k_intr, "inject_in_decode_steps": ms_inject / ms_dec_step,
+        "reprefill_us": reprefill_ms * 1e3, "reprefill_tokens": len(history), "reprefill_over_inject": reprefill_ms / ms_inject,
         "merged_step_us": float(np.mean(merged_ms)) * 1e3,
         "merged_inject_extra_in_decode_steps": float(np.mean(merged_ms)) / ms_dec_step - 1.0,
         "prefill_s": t_prefill, "weights_s": t_weights,

@@ -478,16 +478,27 @@ __device__ __forceinline__ void attn_tile(AttnState& st, const uint4 (&vh)[8], c
                                           const uint4 (&ql)[8], const uint4* kt, int key0, int qpos, int lane) {
     const int i = lane & 31, gh = lane >> 5;
     const int krow = (i >> 3) * 4 + (i & 3) + 16 * ((i >> 2) & 1);   // key (within the tile) held in A row i
-    f32x16 s;
+    // three independent accumulators (hi.hi, lo.hi, hi.lo), K operands read from LDS two steps ahead
+    f32x16 s, s1, s2;
 #pragma unroll
-    for (int r = 0; r < 16; ++r) s[r] = 0.f;
+    for (int r = 0; r < 16; ++r) { s[r] = 0.f; s1[r] = 0.f; s2[r] = 0.f; }
+    uint4 kq[3][2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) { kq[j][0] = kt[attn_k_slot(krow, 2 * j + gh)]; kq[j][1] = kt[512 + attn_k_slot(krow, 2 * j + gh)]; }
 #pragma unroll
     for (int t = 0; t < 8; ++t) {
-        const uint4 ah = kt[attn_k_slot(krow, 2 * t + gh)], al = kt[512 + attn_k_slot(krow, 2 * t + gh)];
-        s = mfma_bf16(ah, qh[t], s);
-        s = mfma_bf16(al, qh[t], s);
-        s = mfma_bf16(ah, ql[t], s);
+        if (t + 2 < 8) {
+            kq[(t + 2) % 3][0] = kt[attn_k_slot(krow, 2 * (t + 2) + gh)];
+            kq[(t + 2) % 3][1] = kt[512 + attn_k_slot(krow, 2 * (t + 2) + gh)];
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        s = mfma_bf16(kq[t % 3][0], qh[t], s);
+        s1 = mfma_bf16(kq[t % 3][1], qh[t], s1);
+        s2 = mfma_bf16(kq[t % 3][0], ql[t], s2);
+        __builtin_amdgcn_sched_barrier(0);
     }
+#pragma unroll
+    for (int r = 0; r < 16; ++r) s[r] += s1[r] + s2[r];
     // register r of lane (j, g) is key key0 + 16 g + r for query column j
     float mx = -INFINITY;
 #pragma unroll
@@ -520,15 +531,18 @@ __device__ __forceinline__ void attn_tile(AttnState& st, const uint4 (&vh)[8], c
     st.lrun = st.lrun * corr + psum;
     st.mrun = mnew;
 #pragma unroll
-    for (int dt = 0; dt < 4; ++dt) {
+    for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
         for (int r = 0; r < 16; ++r) st.o[dt][r] *= corr;
+    // consecutive products go to different accumulators
 #pragma unroll
-        for (int t = 0; t < 2; ++t) {
-            st.o[dt] = mfma_bf16(vh[dt * 2 + t], ph[t], st.o[dt]);
-            st.o[dt] = mfma_bf16(vl[dt * 2 + t], ph[t], st.o[dt]);
-            st.o[dt] = mfma_bf16(vh[dt * 2 + t], pl[t], st.o[dt]);
-        }
+    for (int t = 0; t < 2; ++t) {
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt) st.o[dt] = mfma_bf16(vh[dt * 2 + t], ph[t], st.o[dt]);
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt) st.o[dt] = mfma_bf16(vl[dt * 2 + t], ph[t], st.o[dt]);
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt) st.o[dt] = mfma_bf16(vh[dt * 2 + t], pl[t], st.o[dt]);
     }
 }
 
