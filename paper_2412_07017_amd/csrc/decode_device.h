@@ -279,20 +279,20 @@ __device__ __forceinline__ float4 as_float4(const uint4& v) {
 // (valid after the trailing __syncthreads).  With `pad`, groups [Kg, 256 KT) and the last 64 groups of each
 // plane are zero-filled.
 // All loads of a batch are issued before the first is used.
-template <typename WT>
+template <typename WT, int NB = 4>
 __device__ __forceinline__ float stage_vector(float4* xs, int plane_stride, const VecSource& src, int K, int Kg, int KT,
                                               bool pad, float* red) {
     constexpr int NP = Elem<WT>::EPL / 4;
     const int tid = threadIdx.x, n4 = K >> 2;
     float ss = 0.f;
-    if (src.x) {
+    if (src.x && src.gain) {
         for (int base = 0; base < n4; base += 1024) {
             float4 v[4], gn[4];
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const int k4 = min(base + j * 256 + tid, n4 - 1);
                 v[j] = as_float4(load16(src.x + 4 * (size_t)k4));
-                gn[j] = src.gain ? as_float4(load16(src.gain + 4 * (size_t)k4)) : make_float4(1.f, 1.f, 1.f, 1.f);
+                gn[j] = as_float4(load16(src.gain + 4 * (size_t)k4));
             }
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
@@ -301,6 +301,22 @@ __device__ __forceinline__ float stage_vector(float4* xs, int plane_stride, cons
                     ss += v[j].x * v[j].x + v[j].y * v[j].y + v[j].z * v[j].z + v[j].w * v[j].w;
                     const int grp = k4 / NP, pl = k4 - grp * NP;
                     xs[pl * plane_stride + grp] = make_float4(v[j].x * gn[j].x, v[j].y * gn[j].y, v[j].z * gn[j].z, v[j].w * gn[j].w);
+                }
+            }
+        }
+    } else if (src.x) {
+        // no gain: NB loads per thread are in flight at once (a long vector costs few memory round trips)
+        for (int base = 0; base < n4; base += NB * 256) {
+            float4 v[NB];
+#pragma unroll
+            for (int j = 0; j < NB; ++j) v[j] = as_float4(load16(src.x + 4 * (size_t)min(base + j * 256 + tid, n4 - 1)));
+#pragma unroll
+            for (int j = 0; j < NB; ++j) {
+                const int k4 = base + j * 256 + tid;
+                if (k4 < n4) {
+                    ss += v[j].x * v[j].x + v[j].y * v[j].y + v[j].z * v[j].z + v[j].w * v[j].w;
+                    const int grp = k4 / NP, pl = k4 - grp * NP;
+                    xs[pl * plane_stride + grp] = v[j];
                 }
             }
         }

@@ -82,7 +82,7 @@ __global__ __launch_bounds__(256) void k_gemv(GemvArgs a, Geom g) {
     phase_prefetch_e<WT, EPI>(ring, ph, lc, g, eo);
 
     VecSource vs{a.x, a.gain, a.part_acc, a.part_ml, a.merge_nsplit, a.merge_dh, a.merge_hq};
-    const float ssq = stage_vector<WT>(lds4, plane_stride, vs, a.K, ph.Kg, ph.KT, true, red);
+    const float ssq = stage_vector<WT, (EPI == EPI_RESID ? 16 : 4)>(lds4, plane_stride, vs, a.K, ph.Kg, ph.KT, true, red);
     const float nscale = a.gain ? rsqrtf(ssq / (float)a.K + g.eps) : 1.f;
     float best_v = -INFINITY; int best_i = 0x7fffffff;
     phase_run<WT, EPI>(ring, ph, lc, lds4, plane_stride, nscale, eo, g, lane, done, best_v, best_i);
