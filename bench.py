@@ -272,6 +272,19 @@ def main():
     reprefill_ms = r0.elapsed_time(r1)
     lm.reset(1)
 
+    # Sec. 5.4 trap handling: swap the paused sequence's K/V to pinned host memory and back (second run timed)
+    nbytes = lm.kv_bytes(0)
+    pinned = torch.empty(nbytes, dtype=torch.uint8).pin_memory()
+    swap_out_ms = swap_in_ms = 0.0
+    for _ in range(2):
+        t_a = time.perf_counter()
+        lm.kv_swap_out(0, pinned.data_ptr(), nbytes)
+        t_b = time.perf_counter()
+        lm.kv_swap_in(1, pinned.data_ptr(), nbytes)
+        t_c = time.perf_counter()
+        lm.reset(1)
+        swap_out_ms, swap_in_ms = (t_b - t_a) * 1e3, (t_c - t_b) * 1e3
+
     # Sec. 5.3 merged form: the interrupt rides with the next chosen token in ONE forward pass
     # (asynclm_step_batch on one sequence); its cost beyond a plain decoding step is the price of the interrupt.
     merged_ms = []
@@ -336,6 +349,7 @@ def main():
         "decode_hbm_frac": decode_frac, "decode_bytes_per_token": bytes_step,
         "inject_us": ms_inject * 1e3, "inject_tokens": k_intr, "inject_in_decode_steps": ms_inject / ms_dec_step,
         "reprefill_us": reprefill_ms * 1e3, "reprefill_tokens": len(history), "reprefill_over_inject": reprefill_ms / ms_inject,
+        "kv_swap_bytes": int(nbytes), "kv_swap_out_us": swap_out_ms * 1e3, "kv_swap_in_us": swap_in_ms * 1e3,
         "merged_step_us": float(np.mean(merged_ms)) * 1e3,
         "merged_inject_extra_in_decode_steps": float(np.mean(merged_ms)) / ms_dec_step - 1.0,
         "prefill_s": t_prefill, "weights_s": t_weights,

@@ -133,6 +133,20 @@ int asynclm_step_batch(asynclm_ctx *ctx, int32_t nseq, const int32_t *seqs, cons
  * asynclm_reset. */
 int asynclm_set_banned_tokens(asynclm_ctx *ctx, int32_t seq, const int32_t *ids, int32_t n);
 
+/* Trap handling support (Sec. 5.4): while a sequence is paused its K/V state can be kept in place, dropped and
+ * recomputed later (asynclm_reset + asynclm_prefill of the whole stream: time grows faster than linearly with the
+ * context), or swapped to host memory and back (linear).  These calls are the swap; they synchronise the stream.
+ *   asynclm_kv_bytes     size of the host image of `seq` at its current length
+ *   asynclm_kv_swap_out  writes the image (cached rows of all layers, current logits, pending greedy token) to
+ *                        host_buf[0..capacity) (host pointer; pinned memory copies fastest); ASYNCLM_E_CAPACITY if it
+ *                        does not fit.  The sequence stays valid; asynclm_reset then frees its slot.
+ *   asynclm_kv_swap_in   restores an image into the EMPTY sequence `seq` (any slot of a context created with the
+ *                        same configuration; the image carries its own description and is checked).  Afterwards the
+ *                        sequence is exactly as it was at swap-out: same logits, same next greedy token. */
+int asynclm_kv_bytes(asynclm_ctx *ctx, int32_t seq, uint64_t *bytes);
+int asynclm_kv_swap_out(asynclm_ctx *ctx, int32_t seq, void *host_buf, uint64_t capacity);
+int asynclm_kv_swap_in(asynclm_ctx *ctx, int32_t seq, const void *host_buf, uint64_t bytes);
+
 /* Copy the current next-token logits of `seq` (fp32) to out_host[0..n); n must equal vocab.
  * Synchronises the stream. */
 int asynclm_logits(asynclm_ctx *ctx, int32_t seq, float *out_host, int32_t n);

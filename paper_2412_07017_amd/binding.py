@@ -12,7 +12,7 @@ KV_AUTO, KV_BF16 = 0, 1
 
 API_SYMBOLS = [
     "asynclm_create", "asynclm_destroy", "asynclm_prefill", "asynclm_decode_step",
-    "asynclm_inject_interrupt", "asynclm_step_batch", "asynclm_set_banned_tokens", "asynclm_logits", "asynclm_logits_device", "asynclm_seq_len",
+    "asynclm_inject_interrupt", "asynclm_step_batch", "asynclm_set_banned_tokens", "asynclm_kv_bytes", "asynclm_kv_swap_out", "asynclm_kv_swap_in", "asynclm_logits", "asynclm_logits_device", "asynclm_seq_len",
     "asynclm_reset", "asynclm_synchronize", "asynclm_set_option", "asynclm_profile_step", "asynclm_profile_trace",
     "asynclm_strerror", "asynclm_version",
 ]
@@ -178,6 +178,18 @@ class AsyncLM:
         t = _tok(ids)
         self._check(self._lib.asynclm_set_banned_tokens(self._h, seq, t.ctypes.data_as(C.POINTER(C.c_int32)) if len(t) else None,
                                                         len(t)), "asynclm_set_banned_tokens")
+
+    def kv_bytes(self, seq: int) -> int:
+        n = C.c_uint64()
+        self._check(self._lib.asynclm_kv_bytes(self._h, seq, C.byref(n)), "asynclm_kv_bytes")
+        return n.value
+
+    def kv_swap_out(self, seq: int, host_ptr: int, capacity: int) -> None:
+        """host_ptr: address of a host buffer of `capacity` bytes (e.g. tensor.data_ptr() of a pinned uint8 tensor)."""
+        self._check(self._lib.asynclm_kv_swap_out(self._h, seq, C.c_void_p(host_ptr), C.c_uint64(capacity)), "asynclm_kv_swap_out")
+
+    def kv_swap_in(self, seq: int, host_ptr: int, nbytes: int) -> None:
+        self._check(self._lib.asynclm_kv_swap_in(self._h, seq, C.c_void_p(host_ptr), C.c_uint64(nbytes)), "asynclm_kv_swap_in")
 
     def logits(self, seq: int) -> "np.ndarray":
         out = np.empty(self.vocab, dtype=np.float32)

@@ -695,6 +695,121 @@ int asynclm_set_banned_tokens(asynclm_ctx* c, int32_t seq, const int32_t* ids, i
     return ASYNCLM_OK;
 }
 
+// ---- K/V swap (trap handling) ---------------------------------------------------------------------------------
+
+namespace {
+
+struct SwapHeader {
+    uint32_t magic, version;
+    int32_t len, n_layers, n_planes, has_vt, elem_bytes, Hkv, dh, vocab, next_token, pad;
+    uint64_t total_bytes;
+};
+constexpr uint32_t SWAP_MAGIC = 0x4b56414cu;     // "LAVK"
+
+int swap_planes(const asynclm_ctx* c) {          // row-major planes per layer: K (+lo), V (+lo)
+    return c->g.kv_lo_offset ? 4 : 2;
+}
+
+size_t swap_bytes(const asynclm_ctx* c, int len) {
+    const Geom& g = c->g;
+    const size_t esz = elem_bytes(c);
+    const size_t rows = (size_t)len * g.dh * g.Hkv * esz;                                  // one row-major plane
+    const size_t vt = g.kv_vt_offset ? (size_t)((len + 31) / 32) * 32 * g.dh * g.Hkv * esz : 0;   // one tiled V^T plane
+    return sizeof(SwapHeader) + (size_t)c->cfg.n_layers * (swap_planes(c) * rows + 2 * vt) + (size_t)g.V * sizeof(float);
+}
+
+// Copies every cached row of `seq` between the cache and the packed host image (direction by `out`).
+hipError_t swap_copy(asynclm_ctx* c, int seq, int len, char* host, bool out) {
+    const Geom& g = c->g;
+    const size_t esz = elem_bytes(c);
+    const size_t width = (size_t)len * g.dh * esz, pitch = g.kv_head_stride * esz;
+    const size_t vt_width = (size_t)((len + 31) / 32) * 32 * g.dh * esz;
+    const hipMemcpyKind kind = out ? hipMemcpyDeviceToHost : hipMemcpyHostToDevice;
+    char* h = host;
+    hipError_t e;
+    for (int l = 0; l < c->cfg.n_layers; ++l) {
+        char* base = (char*)kv_layer_ptr(c, l) + (size_t)seq * g.kv_seq_stride * esz;
+        size_t offs[4]; int np = 0;
+        offs[np++] = 0;
+        if (g.kv_lo_offset) offs[np++] = g.kv_lo_offset;
+        offs[np++] = g.kv_v_offset;
+        if (g.kv_lo_offset) offs[np++] = g.kv_v_offset + g.kv_lo_offset;
+        for (int p = 0; p < np; ++p) {
+            char* dev = base + offs[p] * esz;
+            e = out ? hipMemcpy2DAsync(h, width, dev, pitch, width, g.Hkv, kind, c->stream)
+                    : hipMemcpy2DAsync(dev, pitch, h, width, width, g.Hkv, kind, c->stream);
+            if (e) return e;
+            h += width * g.Hkv;
+        }
+        if (g.kv_vt_offset) {
+            for (int p = 0; p < 2; ++p) {
+                char* dev = base + (g.kv_vt_offset + (p ? g.kv_lo_offset : 0)) * esz;
+                e = out ? hipMemcpy2DAsync(h, vt_width, dev, pitch, vt_width, g.Hkv, kind, c->stream)
+                        : hipMemcpy2DAsync(dev, pitch, h, vt_width, vt_width, g.Hkv, kind, c->stream);
+                if (e) return e;
+                h += vt_width * g.Hkv;
+            }
+        }
+    }
+    float* lg = c->logits + (size_t)seq * g.V;
+    e = out ? hipMemcpyAsync(h, lg, sizeof(float) * g.V, kind, c->stream) : hipMemcpyAsync(lg, h, sizeof(float) * g.V, kind, c->stream);
+    return e;
+}
+
+}  // namespace
+
+int asynclm_kv_bytes(asynclm_ctx* c, int32_t seq, uint64_t* bytes) {
+    int r = check_seq(c, seq);
+    if (r) return r;
+    if (!bytes) return ASYNCLM_E_INVAL;
+    if (c->len[seq] == 0) return ASYNCLM_E_STATE;
+    *bytes = swap_bytes(c, c->len[seq]);
+    return ASYNCLM_OK;
+}
+
+int asynclm_kv_swap_out(asynclm_ctx* c, int32_t seq, void* host_buf, uint64_t capacity) {
+    int r = check_seq(c, seq);
+    if (r) return r;
+    if (!host_buf) return ASYNCLM_E_INVAL;
+    if (c->len[seq] == 0) return ASYNCLM_E_STATE;
+    const int len = c->len[seq];
+    const size_t need = swap_bytes(c, len);
+    if (capacity < need) return ASYNCLM_E_CAPACITY;
+    HIPCK(c, refresh_choice(c, seq));           // the saved greedy token is the one under the current ban list
+    SwapHeader hd{};
+    hd.magic = SWAP_MAGIC; hd.version = 1; hd.len = len; hd.n_layers = c->cfg.n_layers; hd.n_planes = swap_planes(c);
+    hd.has_vt = c->g.kv_vt_offset ? 1 : 0; hd.elem_bytes = (int32_t)elem_bytes(c); hd.Hkv = c->g.Hkv; hd.dh = c->g.dh;
+    hd.vocab = c->g.V; hd.total_bytes = need;
+    HIPCK(c, swap_copy(c, seq, len, (char*)host_buf + sizeof(SwapHeader), true));
+    HIPCK(c, hipMemcpyAsync(c->token_host, &c->b.seq_state[seq].next_token, sizeof(int32_t), hipMemcpyDeviceToHost, c->stream));
+    HIPCK(c, hipStreamSynchronize(c->stream));
+    hd.next_token = c->token_host[0];
+    std::memcpy(host_buf, &hd, sizeof(hd));
+    return ASYNCLM_OK;
+}
+
+int asynclm_kv_swap_in(asynclm_ctx* c, int32_t seq, const void* host_buf, uint64_t bytes) {
+    int r = check_seq(c, seq);
+    if (r) return r;
+    if (!host_buf || bytes < sizeof(SwapHeader)) return ASYNCLM_E_INVAL;
+    if (c->len[seq] != 0) return ASYNCLM_E_STATE;
+    SwapHeader hd;
+    std::memcpy(&hd, host_buf, sizeof(hd));
+    if (hd.magic != SWAP_MAGIC || hd.version != 1 || hd.len < 1 || hd.n_layers != c->cfg.n_layers || hd.n_planes != swap_planes(c) ||
+        hd.has_vt != (c->g.kv_vt_offset ? 1 : 0) || hd.elem_bytes != (int32_t)elem_bytes(c) || hd.Hkv != c->g.Hkv || hd.dh != c->g.dh ||
+        hd.vocab != c->g.V || hd.next_token < 0 || hd.next_token >= c->g.V)
+        return ASYNCLM_E_INVAL;
+    if (hd.len > c->cfg.max_positions) return ASYNCLM_E_CAPACITY;
+    if (hd.total_bytes != swap_bytes(c, hd.len) || bytes < hd.total_bytes) return ASYNCLM_E_INVAL;
+    HIPCK(c, swap_copy(c, seq, hd.len, (char*)const_cast<void*>(host_buf) + sizeof(SwapHeader), false));
+    SeqState st{hd.len, hd.next_token};
+    HIPCK(c, hipMemcpyAsync(c->b.seq_state + seq, &st, sizeof(st), hipMemcpyHostToDevice, c->stream));
+    HIPCK(c, hipStreamSynchronize(c->stream));   // the host image may be released when the call returns
+    c->len[seq] = hd.len;
+    c->choice_stale[seq] = c->nban[seq] > 0;     // the restored token was chosen under the saver's list
+    return ASYNCLM_OK;
+}
+
 int asynclm_logits(asynclm_ctx* c, int32_t seq, float* out_host, int32_t n) {
     int r = check_seq(c, seq);
     if (r) return r;

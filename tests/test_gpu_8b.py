@@ -274,3 +274,33 @@ def test_step_batch_ragged_sequences_match_independent_oracle_sequences(trunc4):
         worst = max(worst, float(np.abs(lm.logits(s) - d.logits).max()))
     lm.close()
     assert worst <= TOL, worst
+
+
+@pytest.mark.timeout(600)
+def test_kv_swap_roundtrip_on_the_paired_cache_with_transposed_planes(trunc4):
+    """Swap-out / swap-in (Sec. 5.4) on the bf16 shape: all six cache planes per layer (K, V and the tiled V^T,
+    hi and lo) come back, so both the single-row kernels and the matrix-core append path continue exactly."""
+    import time
+    import paper_2412_07017_amd as pkg
+    wl, model, w_dev, w_cpu, spec = trunc4
+    toks = spec["prompt"]
+    lm = pkg.AsyncLM(model, w_dev, max_positions=1200, max_seqs=2, stream=torch.cuda.Stream())
+    lm.prefill(0, toks[:1000])
+    lm.decode_step(0)
+    nbytes = lm.kv_bytes(0)
+    buf = torch.empty(nbytes, dtype=torch.uint8).pin_memory()
+    t0 = time.perf_counter(); lm.kv_swap_out(0, buf.data_ptr(), nbytes); t_out = time.perf_counter() - t0
+    intr = toks[1000:1024]
+    lm.inject_interrupt(0, intr)                 # chunk attention over the original rows
+    want_inj = lm.logits(0).copy()
+    want_tok = [lm.decode_step(0) for _ in range(3)]
+    want = lm.logits(0).copy()
+    t0 = time.perf_counter(); lm.kv_swap_in(1, buf.data_ptr(), nbytes); t_in = time.perf_counter() - t0
+    lm.inject_interrupt(1, intr)
+    assert np.array_equal(lm.logits(1), want_inj)
+    assert [lm.decode_step(1) for _ in range(3)] == want_tok
+    assert np.array_equal(lm.logits(1), want)
+    t0 = time.perf_counter(); lm.reset(0); lm.prefill(0, toks[:1000]); lm.synchronize(); t_re = time.perf_counter() - t0
+    print("swap of %d positions x %d layers: %.1f MB, out %.2f ms, in %.2f ms; recompute (prefill) %.2f ms"
+          % (1001, model.n_layers, nbytes / 1e6, t_out * 1e3, t_in * 1e3, t_re * 1e3))
+    lm.close()

@@ -284,3 +284,42 @@ def test_banned_tokens_change_the_greedy_choice_only(tiny):
     with pytest.raises(pkg.AsyncLMError):
         lm.set_banned_tokens(0, list(range(32)))
     lm.close()
+
+
+def test_kv_swap_out_and_in_restores_the_sequence_exactly(tiny):
+    """Trap handling (Sec. 5.4): the K/V state swapped to host memory and back continues bit-identically, also
+    into another sequence slot and after the slot was used for something else."""
+    pkg, wl, spec, w_cpu, w_dev, stream, ref = tiny
+    lm = _new(tiny, max_seqs=2)
+    s = ref["stream"]
+    lm.prefill(0, s[:50])
+    for t in s[50:55]:
+        lm.decode_step(0, forced_token=t)
+    nbytes = lm.kv_bytes(0)
+    buf = torch.empty(nbytes, dtype=torch.uint8).pin_memory()
+    with pytest.raises(pkg.AsyncLMError) as ei:
+        lm.kv_swap_out(0, buf.data_ptr(), nbytes - 1)
+    assert ei.value.code == pkg.E_CAPACITY
+    lm.kv_swap_out(0, buf.data_ptr(), nbytes)
+    before = lm.logits(0).copy()
+    # uninterrupted continuation, for reference
+    want_tok = [lm.decode_step(0) for _ in range(4)]
+    want = lm.logits(0).copy()
+    lm.reset(0)
+    lm.prefill(0, s[3:20])                       # the slot is reused while the sequence is paused
+    lm.reset(0)
+    with pytest.raises(pkg.AsyncLMError) as ei:
+        lm.kv_swap_in(1, buf.data_ptr(), nbytes - 8)
+    assert ei.value.code == pkg.E_INVAL and lm.seq_len(1) == 0
+    for slot in (0, 1):
+        lm.kv_swap_in(slot, buf.data_ptr(), nbytes)
+        assert lm.seq_len(slot) == 55
+        assert np.array_equal(lm.logits(slot), before)
+        assert [lm.decode_step(slot) for _ in range(4)] == want_tok
+        assert np.array_equal(lm.logits(slot), want)
+    with pytest.raises(pkg.AsyncLMError) as ei:
+        lm.kv_swap_in(0, buf.data_ptr(), nbytes)  # not empty
+    assert ei.value.code == pkg.E_STATE
+    # and the result is the oracle's
+    assert np.abs(want - orc.full_logits(orc.Shape.of(wl.model), w_cpu, list(s[:55]) + want_tok)[-1]).max() <= TOL
+    lm.close()
