@@ -40,6 +40,9 @@ def parse():
     ap.add_argument("--opt", action="append", default=[], help="library option name=value (repeatable), for experiments")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run three plain device copies of 1 GiB (torch copy kernel) so that a counter run can be scaled by them")
+    ap.add_argument("--trap-map", action="store_true",
+                    help="instead of the benchmark: time K/V swap-out + swap-in against recomputation (re-prefill) over a range of "
+                         "context lengths (Sec. 5.4 trade-off) and print them as one JSON line")
     ap.add_argument("--fused", type=int, default=-1, help="1/0: force the single-kernel / per-operation decoding step (default: library's choice)")
     return ap.parse_args()
 
@@ -187,11 +190,50 @@ def bench_ragged(args):
     print(json.dumps(out))
 
 
+def trap_map(args):
+    """Sec. 5.4: cost of the two ways to free a paused sequence's cache and get it back, per context length."""
+    import numpy as np
+    import torch
+    import asynclm_inputs as ai
+    import paper_2412_07017_amd as pkg
+    wl = ai.preset(args.workload)
+    model = wl.model if not args.layers else ai.truncated(wl.model, args.layers)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    w_dev = ai.make_weights(model, device=dev)
+    stream = torch.cuda.Stream(device=dev)
+    lens = [256, 512, 1024, 2048, 4096, 8192, 16384]
+    lm = pkg.AsyncLM(model, w_dev, max_positions=lens[-1] + 8, stream=stream)
+    toks = ai.uniform_tokens(ai.MASTER_SEED, 103, lens[-1], model.vocab)
+    rows = []
+    for L in lens:
+        lm.reset(0)
+        lm.prefill(0, toks[:L])
+        lm.synchronize()
+        nbytes = lm.kv_bytes(0)
+        pinned = torch.empty(nbytes, dtype=torch.uint8).pin_memory()
+        best = {}
+        for rep in range(2):
+            t0 = time.perf_counter(); lm.kv_swap_out(0, pinned.data_ptr(), nbytes); t1 = time.perf_counter()
+            lm.reset(0)
+            t2 = time.perf_counter(); lm.kv_swap_in(0, pinned.data_ptr(), nbytes); t3 = time.perf_counter()
+            lm.reset(0)
+            t4 = time.perf_counter(); lm.prefill(0, toks[:L]); lm.synchronize(); t5 = time.perf_counter()
+            best = {"context": L, "image_MB": nbytes / 1e6, "swap_out_ms": (t1 - t0) * 1e3, "swap_in_ms": (t3 - t2) * 1e3,
+                    "recompute_ms": (t5 - t4) * 1e3}
+        rows.append(best)
+        del pinned
+    lm.close()
+    print(json.dumps({"trap_map": rows, "workload": wl.name, "layers": model.n_layers}))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (--gpus must be 1)", file=sys.stderr)
         sys.exit(2)
+    if args.trap_map:
+        return trap_map(args)
     if args.workload == "8b-ragged16":
         return bench_ragged(args)
     import numpy as np
