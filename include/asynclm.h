@@ -133,6 +133,12 @@ int asynclm_step_batch(asynclm_ctx *ctx, int32_t nseq, const int32_t *seqs, cons
  * asynclm_reset. */
 int asynclm_set_banned_tokens(asynclm_ctx *ctx, int32_t seq, const int32_t *ids, int32_t n);
 
+/* The token the next unforced asynclm_decode_step / asynclm_step_batch would choose for `seq` (greedy over the ids
+ * that are not banned), without changing anything.  The host-side interrupt manager needs it: whether queued
+ * interrupts may ride with the next token (Sec. 5.3) depends on that token (a token that opens a call block
+ * starts a critical section, Sec. 3.2).  Synchronises the stream. */
+int asynclm_peek_token(asynclm_ctx *ctx, int32_t seq, int32_t *token_out);
+
 /* Trap handling support (Sec. 5.4): while a sequence is paused its K/V state can be kept in place, dropped and
  * recomputed later (asynclm_reset + asynclm_prefill of the whole stream: time grows faster than linearly with the
  * context), or swapped to host memory and back (linear).  These calls are the swap; they synchronise the stream.

@@ -12,7 +12,7 @@ KV_AUTO, KV_BF16 = 0, 1
 
 API_SYMBOLS = [
     "asynclm_create", "asynclm_destroy", "asynclm_prefill", "asynclm_decode_step",
-    "asynclm_inject_interrupt", "asynclm_step_batch", "asynclm_set_banned_tokens", "asynclm_kv_bytes", "asynclm_kv_swap_out", "asynclm_kv_swap_in", "asynclm_logits", "asynclm_logits_device", "asynclm_seq_len",
+    "asynclm_inject_interrupt", "asynclm_step_batch", "asynclm_set_banned_tokens", "asynclm_peek_token", "asynclm_kv_bytes", "asynclm_kv_swap_out", "asynclm_kv_swap_in", "asynclm_logits", "asynclm_logits_device", "asynclm_seq_len",
     "asynclm_reset", "asynclm_synchronize", "asynclm_set_option", "asynclm_profile_step", "asynclm_profile_trace",
     "asynclm_strerror", "asynclm_version",
 ]
@@ -178,6 +178,11 @@ class AsyncLM:
         t = _tok(ids)
         self._check(self._lib.asynclm_set_banned_tokens(self._h, seq, t.ctypes.data_as(C.POINTER(C.c_int32)) if len(t) else None,
                                                         len(t)), "asynclm_set_banned_tokens")
+
+    def peek_choice(self, seq: int) -> int:
+        out = C.c_int32(-1)
+        self._check(self._lib.asynclm_peek_token(self._h, seq, C.byref(out)), "asynclm_peek_token")
+        return out.value
 
     def kv_bytes(self, seq: int) -> int:
         n = C.c_uint64()

@@ -810,6 +810,18 @@ int asynclm_kv_swap_in(asynclm_ctx* c, int32_t seq, const void* host_buf, uint64
     return ASYNCLM_OK;
 }
 
+int asynclm_peek_token(asynclm_ctx* c, int32_t seq, int32_t* token_out) {
+    int r = check_seq(c, seq);
+    if (r) return r;
+    if (!token_out) return ASYNCLM_E_INVAL;
+    if (c->len[seq] == 0) return ASYNCLM_E_STATE;
+    HIPCK(c, refresh_choice(c, seq));
+    HIPCK(c, hipMemcpyAsync(c->token_host, &c->b.seq_state[seq].next_token, sizeof(int32_t), hipMemcpyDeviceToHost, c->stream));
+    HIPCK(c, hipStreamSynchronize(c->stream));
+    *token_out = c->token_host[0];
+    return ASYNCLM_OK;
+}
+
 int asynclm_logits(asynclm_ctx* c, int32_t seq, float* out_host, int32_t n) {
     int r = check_seq(c, seq);
     if (r) return r;

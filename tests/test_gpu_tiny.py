@@ -323,3 +323,70 @@ def test_kv_swap_out_and_in_restores_the_sequence_exactly(tiny):
     # and the result is the oracle's
     assert np.abs(want - orc.full_logits(orc.Shape.of(wl.model), w_cpu, list(s[:55]) + want_tok)[-1]).max() <= TOL
     lm.close()
+
+
+def test_interruptible_session_end_to_end_matches_oracle_replay(tiny):
+    """The host control plane driving the library (token masks, peek, merged token + interrupt passes, forced
+    trap END, pause / resume) against a replay with the CPU oracle under the same rules: identical token stream,
+    logits within tolerance, the interrupt marker never generated, no interrupt inside a call block."""
+    pkg, wl, spec, w_cpu, w_dev, stream, ref = tiny
+    sh = orc.Shape.of(wl.model)
+    prompt = spec["prompt"]
+    # CML ids taken from tokens this random model likes to generate, so that a call block opens and closes, an
+    # interrupt is deferred and a trap pauses the session within the run (checked below)
+    cml = pkg.CML(call=65, intr=1001, trap=930, end=313, head=191)
+    arrivals = {1: ([7], [8, 9]), 4: ([10], [11]), 12: ([12, 13], [14] * 5), 30: ([15], [16])}
+    n_steps = 48
+
+    def blocks_of(q):
+        out = []
+        for cid, val in q:
+            out += [cml.intr] + cid + [cml.head] + val + [cml.end]
+        return out
+
+    # replay with the oracle
+    dec = orc.CachedDecoder(sh, w_cpu)
+    dec.prefill(prompt)
+    mon = pkg.TokenMonitor(cml)
+    queue, paused, want_stream, deferred, calls, traps = [], False, [], 0, 0, 0
+    for t in range(n_steps):
+        if t in arrivals:
+            queue.append(arrivals[t])
+        if paused:
+            if queue:
+                b = blocks_of(queue); queue = []
+                dec.inject(b); want_stream += b; paused = False
+            continue
+        forced = mon.forced()
+        tok = forced if forced is not None else orc.greedy(dec.logits, mon.banned())
+        merge = forced is None and not mon.critical and queue and tok not in (cml.call, cml.trap)
+        if queue and not merge:
+            deferred += 1
+        dec.decode_step(forced=tok)
+        want_stream.append(tok)
+        if merge:
+            b = blocks_of(queue); queue = []
+            dec.inject(b); want_stream += b
+        evn = mon.observe(tok)
+        if evn is not None and evn[0] == "call":
+            calls += 1
+        if evn is not None and evn[0] == "trap":
+            paused = True
+            traps += 1
+    assert calls >= 1 and deferred >= 1 and traps >= 1, (calls, deferred, traps)    # the run exercises all three
+
+    lm = _new(tiny, max_positions=400)
+    lm.prefill(0, prompt)
+    ses = pkg.InterruptibleSession(lm, 0, cml)
+    got_calls = 0
+    for t in range(n_steps):
+        if t in arrivals:
+            ses.submit_interrupt(*arrivals[t])
+        r = ses.step()
+        assert r.token != cml.intr
+        got_calls += r.call is not None
+    assert ses.stream == want_stream
+    assert got_calls == calls
+    assert lm.seq_len(0) == len(prompt) + len(want_stream) == dec.length
+    assert np.abs(lm.logits(0) - dec.logits).max() <= TOL
+    lm.close()
