@@ -286,17 +286,18 @@ __global__ void k_chunk_rope_kv(const float* __restrict__ P, int S, size_t s_str
 // Workgroup = 4 waves on 128 weight rows (32 per wave) and one contiguous run of 128-element k-blocks
 // (the S workgroups of a row tile split K and write separate partial planes that the consumer adds in
 // a fixed order: no atomics, results are bit-reproducible).
-//  * weights stream from HBM through a register ring of GEMM_RING tiles per wave (one tile = the wave's
+//  * weights stream from HBM through a register ring of GemmRing<MT>::N tiles per wave (one tile = the wave's
 //    32 rows x 128 columns, loaded 4 rows x 256 contiguous bytes per instruction), are transposed into
 //    operand order through a wave-private XOR-swizzled LDS tile and multiplied;
 //  * the activations of a k-block (all rows, hi and lo planes: MT x 16 KiB) are shared by the four waves
 //    through a double-buffered LDS tile that the workgroup fills one block ahead.
-// The loop body has no conditional code: past the end of its run a workgroup re-reads its last block
-// (cache hits) against activations replaced by zeros.  The compiler sinks loads into conditional users
+// The loop body has no conditional code around loads or their uses: the prefetches past the end of a run
+// re-read its last block (cache hits).  The compiler sinks loads into conditional users
 // and then waits for each load right before its product; the scheduling barriers keep the instruction
 // scheduler from doing the same within the straight-line body.
 
-constexpr int GEMM_RING = 4;
+// weight tiles per wave in the register ring: four for one row tile, three beyond (registers)
+template <int MT> struct GemmRing { static constexpr int N = MT == 1 ? 4 : 3; };
 
 template <int MT>
 struct BStage { uint4 v[MT][4]; };
@@ -348,13 +349,32 @@ __device__ __forceinline__ void gemm_tile_mma(const uint4 (&ta)[8], f32x16 (&acc
 #pragma unroll
         for (int k = 0; k < 8; ++k) a[k] = at[i * 16 + ((2 * k + gh) ^ (i & 15))];
     }
+    // The activation operands of k-step k + 1 are read from LDS while the products of step k run (a wave is alone on
+    // its SIMD: nothing else hides the LDS latency), and consecutive products go to different accumulators.
+    uint4 b0[MT][2], b1[MT][2];
 #pragma unroll
-    for (int k = 0; k < 8; ++k)
+    for (int mt = 0; mt < MT; ++mt) { b0[mt][0] = bt[(mt * 2 + 0) * 512 + lane]; b0[mt][1] = bt[(mt * 2 + 1) * 512 + lane]; }
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
-            acc[mt] = mfma_bf16(a[k], bt[(mt * 2 + 0) * 512 + k * 64 + lane], acc[mt]);
-            acc[mt] = mfma_bf16(a[k], bt[(mt * 2 + 1) * 512 + k * 64 + lane], acc[mt]);
+    for (int k = 0; k < 8; k += 2) {
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) { b1[mt][0] = bt[(mt * 2 + 0) * 512 + (k + 1) * 64 + lane]; b1[mt][1] = bt[(mt * 2 + 1) * 512 + (k + 1) * 64 + lane]; }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) acc[mt] = mfma_bf16(a[k], b0[mt][0], acc[mt]);
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) acc[mt] = mfma_bf16(a[k], b0[mt][1], acc[mt]);
+        __builtin_amdgcn_sched_barrier(0);
+        if (k + 2 < 8) {
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) { b0[mt][0] = bt[(mt * 2 + 0) * 512 + (k + 2) * 64 + lane]; b0[mt][1] = bt[(mt * 2 + 1) * 512 + (k + 2) * 64 + lane]; }
         }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) acc[mt] = mfma_bf16(a[k + 1], b1[mt][0], acc[mt]);
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) acc[mt] = mfma_bf16(a[k + 1], b1[mt][1], acc[mt]);
+        __builtin_amdgcn_sched_barrier(0);
+    }
 }
 
 template <int MT>
@@ -384,25 +404,30 @@ __global__ __launch_bounds__(256) void k_chunk_gemm(const bf16_t* __restrict__ W
 
     if (nb > 0) {
         // Waits are in issue order, so the activation loads of block t+2 are issued before the weight loads of
-        // block t+3: waiting for the activations of block t+1 (to store them) then leaves two weight tiles in flight.
-        uint4 ring[GEMM_RING][8];
+        // the newest block: waiting for the activations of block t+1 (to store them) then leaves the two newest
+        // weight tiles in flight.
+        constexpr int RING = GemmRing<MT>::N;
+        uint4 ring[RING][8];
         BStage<MT> st[2];
         gemm_b_load<MT>(st[0], xh, xl, nblk, b0);
         gemm_b_load<MT>(st[1], xh, xl, nblk, min(b0 + 1, last));
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int u = 0; u < GEMM_RING - 1; ++u) gemm_a_load(ring[u], wlane, wstep, min(b0 + u, last));
+        for (int u = 0; u < RING - 1; ++u) gemm_a_load(ring[u], wlane, wstep, min(b0 + u, last));
         gemm_b_store<MT>(st[0], bt, tid, true);
         __syncthreads();
-        for (int t = 0; t < nb; t += GEMM_RING) {
+        // unrolled over an even number of blocks, so that ring slot (u % RING) and activation buffer (u & 1) are static
+        constexpr int UNROLL = RING % 2 ? 2 * RING : RING;
+        for (int t = 0; t < nb; t += UNROLL) {
 #pragma unroll
-            for (int u = 0; u < GEMM_RING; ++u) {
-                const int tt = b0 + t + u;                  // this block (past the end: zeros)
+            for (int u = 0; u < UNROLL; ++u) {
+                const int tt = b0 + t + u;                  // this block
+                if (UNROLL > RING && tt > last) break;      // long unroll only: uniform exit, nothing below is conditional
                 gemm_b_load<MT>(st[u & 1], xh, xl, nblk, min(tt + 2, last));
                 __builtin_amdgcn_sched_barrier(0);
-                gemm_a_load(ring[(u + GEMM_RING - 1) % GEMM_RING], wlane, wstep, min(tt + GEMM_RING - 1, last));
+                gemm_a_load(ring[(u + RING - 1) % RING], wlane, wstep, min(tt + RING - 1, last));
                 __builtin_amdgcn_sched_barrier(0);
-                gemm_tile_mma<MT>(ring[u], acc, at, bt + (u & 1) * BT, lane);
+                gemm_tile_mma<MT>(ring[u % RING], acc, at, bt + (u & 1) * BT, lane);
                 __builtin_amdgcn_sched_barrier(0);
                 gemm_b_store<MT>(st[(u + 1) & 1], bt + ((u + 1) & 1) * BT, tid, tt + 1 <= last);
                 __syncthreads();
