@@ -120,7 +120,7 @@ int asynclm_inject_interrupt(asynclm_ctx *ctx, int32_t seq, const int32_t *token
  * row attends to its own sequence only); afterwards every sequence has valid logits for its next token.
  * seqs, forced, intr_tokens, intr_offsets (nseq + 1 ascending entries; NULL = no interrupts) are host pointers.
  * tokens_out (host, may be NULL): tokens_out[i] receives the token chosen for seqs[i]; NULL avoids the stream
- * synchronisation.  More rows than one pass holds (96) are processed in several passes.
+ * synchronisation.  More rows than one pass holds (512) are processed in several passes.
  * Everything is validated before any state changes (ASYNCLM_E_INVAL / _STATE / _CAPACITY as for the
  * single-sequence calls; a sequence may appear only once). */
 int asynclm_step_batch(asynclm_ctx *ctx, int32_t nseq, const int32_t *seqs, const int32_t *forced,
@@ -171,8 +171,8 @@ int asynclm_reset(asynclm_ctx *ctx, int32_t seq);
 int asynclm_synchronize(asynclm_ctx *ctx);
 
 /* Tuning knobs; all have working defaults.  Unknown names give ASYNCLM_E_INVAL.
- *   "chunk"        rows processed per forward pass by prefill / inject (1 .. 96); 1 = token by token
- *                  through the decode kernels.  Default 96 where the matrix-core append path applies
+ *   "chunk"        rows processed per forward pass by prefill / inject (1 .. 512); 1 = token by token
+ *                  through the decode kernels.  Default 512 where the matrix-core append path applies
  *                  (bf16 model, paired cache, head_dim 128, d_model and ffn multiples of 128), else 1.
  *   "chunk_split"  0 = split-K factors of the append path's products chosen from the shapes and the number
  *                  of compute units, 1..8 = force one

@@ -281,21 +281,24 @@ int check_tokens(const asynclm_ctx* c, const int32_t* t, int32_t n) {
 // Split-K factors of the four products of a layer (workgroups = N/32 * S, each of 4 waves).
 struct ChunkSplits { int qkv, o, gu, down; };
 
-// A product with N output rows and K columns runs N/128 * S workgroups, one per compute unit at a time:
-// S = the split that comes closest to one workgroup per unit, with at least two 128-column blocks per workgroup.
-int pick_gemm_split(const asynclm_ctx* c, int N, int K) {
-    const int tiles = N / 128, nblk = K / 128;
+// A product with N output rows and K columns over MT row tiles runs (N/128) * (row blocks) * S workgroups, one per
+// compute unit at a time: S = the split that comes closest to one workgroup per unit, with at least two
+// 128-column blocks per workgroup, within the capacity of the partial planes.
+int pick_gemm_split(const asynclm_ctx* c, int N, int K, int MT) {
+    const int row_blocks = MT <= 4 ? 1 : (MT + 7) / 8;          // as launch_chunk_gemm tiles the rows
+    const int tiles = N / 128 * row_blocks, nblk = K / 128;
     int s = (c->n_cu + tiles / 2) / tiles;
     s = std::min(s, std::min(CHUNK_GEMM_MAX_SPLIT, std::max(1, nblk / 2)));
     s = std::max(s, 1);
     if (c->opt_chunk_split > 0) s = std::min(c->opt_chunk_split, std::max(1, nblk));
+    while (s > 1 && (size_t)s * MT * 32 * N > c->cb.part_capacity) --s;
     return s;
 }
 
-ChunkSplits chunk_splits(const asynclm_ctx* c) {
+ChunkSplits chunk_splits(const asynclm_ctx* c, int MT) {
     const Geom& g = c->g;
-    return {pick_gemm_split(c, (g.Hq + 2 * g.Hkv) * g.dh, g.d), pick_gemm_split(c, g.d, g.Hq * g.dh),
-            pick_gemm_split(c, 2 * g.F, g.d), pick_gemm_split(c, g.d, g.F)};
+    return {pick_gemm_split(c, (g.Hq + 2 * g.Hkv) * g.dh, g.d, MT), pick_gemm_split(c, g.d, g.Hq * g.dh, MT),
+            pick_gemm_split(c, 2 * g.F, g.d, MT), pick_gemm_split(c, g.d, g.F, MT)};
 }
 
 // Key splits of the chunk attention: about two 32-key tiles per wave, a multiple of 4, within the capacity
@@ -316,13 +319,13 @@ hipError_t forward_chunk(asynclm_ctx* c, const PassBuilder& pb) {
     hipStream_t s = c->stream;
     const ChunkTable& t = pb.t;
     const int rows = t.rows, MT = (rows + 31) / 32;
-    const ChunkSplits sp = chunk_splits(c);
+    const ChunkSplits sp = chunk_splits(c, MT);
     const int nqkv = (g.Hq + 2 * g.Hkv) * g.dh, qd = g.Hq * g.dh;
     const int asplit = pick_chunk_attn_split(c, pb.max_keys, t.ntasks);
     const int dt = c->cfg.dtype;
     hipError_t e;
     // pageable source: the runtime stages the table before the call returns
-    if ((e = hipMemcpyAsync(cb.tab, &t, sizeof(ChunkTable), hipMemcpyHostToDevice, s))) return e;
+    if ((e = hipMemcpyAsync(cb.tab, &t, offsetof(ChunkTable, row) + sizeof(ChunkRow) * rows, hipMemcpyHostToDevice, s))) return e;
     if ((e = run(c, KC_BEGIN, [&] { return launch_begin_chunk(cb, c->b, t.ngroups, s); }))) return e;
     if ((e = run(c, KC_CHUNK_PREP, [&] { return launch_chunk_embed(c->embed, cb, rows, g, s); }))) return e;
     for (int l = 0; l < c->cfg.n_layers; ++l) {
@@ -456,9 +459,11 @@ int asynclm_create(asynclm_ctx** out, const asynclm_config* cfg, const asynclm_w
     if (c->chunk_ok) {
         ChunkBuffers& cb = c->cb;
         const size_t M = CHUNK_MAX, qd = (size_t)g.Hq * g.dh;
-        // split-K partial planes: up to CHUNK_GEMM_MAX_SPLIT planes of the widest product
-        const size_t nmax = std::max((size_t)g.V, CHUNK_GEMM_MAX_SPLIT * std::max(std::max((size_t)2 * g.F, (size_t)(g.Hq + 2 * g.Hkv) * g.dh), (size_t)g.d));
-        cb.part_capacity = M * nmax;
+        // split-K partial planes: every split of the widest product for passes of up to 96 rows (bound by the weight
+        // stream: many splits), two for the largest pass (bound by the matrix cores: few), the output head for one
+        // row per group
+        const size_t wmax = std::max(std::max((size_t)2 * g.F, (size_t)(g.Hq + 2 * g.Hkv) * g.dh), (size_t)g.d);
+        cb.part_capacity = std::max(std::max((size_t)96 * CHUNK_GEMM_MAX_SPLIT * wmax, 2 * M * wmax), (size_t)CHUNK_MAX_TASKS * g.V);
         if ((e = chunk_init()) != hipSuccess) { report_hip("chunk_init", e); return bail(ASYNCLM_E_DEVICE); }
         cb.q_cols = (g.Hq / g.Hkv) * CHUNK_MAX + 32;
         const size_t qn = (size_t)g.Hkv * cb.q_cols * g.dh;
@@ -470,7 +475,7 @@ int asynclm_create(asynclm_ctx** out, const asynclm_config* cfg, const asynclm_w
         ALLOC(cb.att_hi, M * qd); ALLOC(cb.att_lo, M * qd);
         ALLOC(cb.act_hi, M * g.F); ALLOC(cb.act_lo, M * g.F);
         ALLOC(cb.q_hi, qn); ALLOC(cb.q_lo, qn);
-        ALLOC(cb.part, M * nmax);
+        ALLOC(cb.part, cb.part_capacity);
         ALLOC(cb.attn_o, (size_t)CHUNK_ATTN_MAX_UNITS * g.dh * 32);
         ALLOC(cb.attn_ml, (size_t)CHUNK_ATTN_MAX_UNITS * 64);
         // rows beyond the current chunk are multiplied into discarded columns only, but must stay finite

@@ -446,6 +446,169 @@ __global__ __launch_bounds__(256) void k_chunk_gemm(const bf16_t* __restrict__ W
 }
 
 // ---------------------------------------------------------------------------------------------
+// wide GEMM on the matrix cores for passes of more than 96 rows (prefill, large batched steps)
+// ---------------------------------------------------------------------------------------------
+// Workgroup = 4 waves on a tile of 128 weight rows x (128 MW) token rows and one run of k-blocks.  Beyond 96
+// rows a pass is bound by the matrix cores, not by the weight stream, so the tile is shaped for operand reuse:
+//  * every wave multiplies ALL 128 weight rows of the tile with its own MW row tiles (32 token rows each):
+//    per 16-column k-step 4 weight operands and 2 MW activation operands (hi, lo) feed 8 MW products;
+//  * the weight block (128 rows x 128 columns) is loaded once per workgroup (4 rows x 256 contiguous bytes
+//    per instruction), transposed into operand order through a double-buffered, XOR-swizzled LDS tile that
+//    the four waves share: one barrier per k-block;
+//  * the activations are already in operand order in global memory (tiled planes: one contiguous KiB per
+//    wave-wide load) and go straight to registers through a ring of four 2-step units, three units ahead of
+//    the products; no wave reads another wave's rows, so they never pass through LDS.
+// Workgroups that share a weight tile (row blocks of one pass) get linear ids that land on the same XCD,
+// next to each other in dispatch order, so the second reads the weights from that XCD's L2.
+
+template <int MW> struct BUnit { uint4 v[MW][2][2]; };      // [row tile][k-step of the unit][hi | lo]
+
+template <int MW>
+__device__ __forceinline__ void wide_b_load(BUnit<MW>& b, const bf16_t* (&xh)[MW], const bf16_t* (&xl)[MW],
+                                            int blk, int unit) {
+#pragma unroll
+    for (int j = 0; j < MW; ++j)
+#pragma unroll
+        for (int st = 0; st < 2; ++st) {
+            const size_t o = ((size_t)blk * 8 + unit * 2 + st) * 512;
+            b.v[j][st][0] = load16(xh[j] + o);
+            b.v[j][st][1] = load16(xl[j] + o);
+        }
+}
+
+// weight operands of k-step k: all four 32-row tiles of the block in `at`
+__device__ __forceinline__ void wide_a_read(uint4 (&a)[4], const uint4* at, int k, int lane) {
+    const int i = lane & 31, gh = lane >> 5;
+#pragma unroll
+    for (int nt = 0; nt < 4; ++nt) a[nt] = at[nt * 512 + i * 16 + ((2 * k + gh) ^ (i & 15))];
+}
+
+template <int MW>
+__device__ __forceinline__ void wide_step(const uint4 (&a)[4], const BUnit<MW>& b, int st, f32x16 (&acc)[4][MW]) {
+#pragma unroll
+    for (int pl = 0; pl < 2; ++pl)
+#pragma unroll
+        for (int nt = 0; nt < 4; ++nt)
+#pragma unroll
+            for (int j = 0; j < MW; ++j) acc[nt][j] = mfma_bf16(a[nt], b.v[j][st][pl], acc[nt][j]);
+}
+
+template <int MW>
+__global__ __launch_bounds__(256) void k_chunk_gemm_wide(const bf16_t* __restrict__ W, int N, int K,
+                                                         const bf16_t* __restrict__ Xhi, const bf16_t* __restrict__ Xlo,
+                                                         float* __restrict__ P, size_t s_stride, int n_stride, int S, int MT) {
+    extern __shared__ uint4 gemm_lds[];             // [2 buffers][4 weight-row tiles][512]
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tiles = N >> 7, MY = (MT + 4 * MW - 1) / (4 * MW);
+    int ntile, my, sp;
+    {
+        int q = blockIdx.x;
+        if ((tiles & 7) == 0) {                     // XCDs take workgroups round robin by linear id
+            const int xcd = q & 7;
+            q >>= 3;
+            my = q % MY; q /= MY;
+            ntile = (q % (tiles >> 3)) * 8 + xcd; sp = q / (tiles >> 3);
+        } else {
+            my = q % MY; q /= MY;
+            ntile = q % tiles; sp = q / tiles;
+        }
+    }
+    const int nblk = K >> 7;
+    const int b0 = (int)((long long)nblk * sp / S), b1 = (int)((long long)nblk * (sp + 1) / S);
+    const int nb = b1 - b0, last = b1 - 1;
+    const int n0 = ntile * 128;
+
+    // weights: wave w stages rows 32 w .. 32 w + 31 of the tile
+    const bf16_t* wlane = W + (size_t)(n0 + wave * 32 + (lane >> 4)) * K + (lane & 15) * 8;
+    const size_t wstep = (size_t)4 * K;
+    // activations: row tiles (my MW + j) * 4 + wave of the pass; tiles past the end repeat the last one and are not stored
+    int mtile[MW];
+    const bf16_t* xh[MW];
+    const bf16_t* xl[MW];
+#pragma unroll
+    for (int j = 0; j < MW; ++j) {
+        mtile[j] = (my * MW + j) * 4 + wave;
+        const size_t o = (size_t)min(mtile[j], MT - 1) * nblk * 4096 + lane * 8;
+        xh[j] = Xhi + o; xl[j] = Xlo + o;
+    }
+
+    f32x16 acc[4][MW];
+#pragma unroll
+    for (int nt = 0; nt < 4; ++nt)
+#pragma unroll
+        for (int j = 0; j < MW; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[nt][j][r] = 0.f;
+
+    if (nb > 0) {
+        uint4 wreg[8];
+        BUnit<MW> ring[4];
+        const int wr0 = lane >> 4, wc = lane & 15;
+        auto w_store = [&](uint4* at) {
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                const int r = 4 * q + wr0;
+                at[wave * 512 + r * 16 + (wc ^ (r & 15))] = wreg[q];
+            }
+        };
+        // issue order = completion order: weights of the first block, three activation units, weights of the second block
+        gemm_a_load(wreg, wlane, wstep, b0);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int u = 0; u < 3; ++u) wide_b_load<MW>(ring[u], xh, xl, b0, u);
+        __builtin_amdgcn_sched_barrier(0);
+        w_store(gemm_lds);
+        gemm_a_load(wreg, wlane, wstep, min(b0 + 1, last));
+        __builtin_amdgcn_sched_barrier(0);
+        __syncthreads();
+        for (int t = 0; t < nb; t += 2) {
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int tt = b0 + t + h;                  // this block, in LDS buffer h
+                if (tt > last) break;                       // uniform
+                const uint4* at = gemm_lds + h * 2048;
+                uint4 a0[4], a1[4];
+                wide_a_read(a0, at, 0, lane);
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    // unit u + 3 of the stream: the last unit of this block, then the first three of the next
+                    wide_b_load<MW>(ring[(u + 3) & 3], xh, xl, u == 0 ? tt : min(tt + 1, last), (u + 3) & 3);
+                    __builtin_amdgcn_sched_barrier(0);
+                    if (u == 1) {
+                        // the next block's weights (requested one block ago) move to the other LDS buffer, whose
+                        // readers passed the barrier that ended the previous block; then the block after is requested
+                        w_store(gemm_lds + (h ^ 1) * 2048);
+                        gemm_a_load(wreg, wlane, wstep, min(tt + 2, last));
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                    wide_a_read(a1, at, 2 * u + 1, lane);
+                    __builtin_amdgcn_sched_barrier(0);
+                    wide_step<MW>(a0, ring[u], 0, acc);
+                    __builtin_amdgcn_sched_barrier(0);
+                    if (u < 3) wide_a_read(a0, at, 2 * u + 2, lane);
+                    __builtin_amdgcn_sched_barrier(0);
+                    wide_step<MW>(a1, ring[u], 1, acc);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                __syncthreads();
+            }
+        }
+    }
+
+    // lane (j, g) holds D[8b + 4g + r][j] in register 4b + r: four consecutive weight rows of token row j
+#pragma unroll
+    for (int j = 0; j < MW; ++j) {
+        if (mtile[j] >= MT) continue;
+        float* prow = P + sp * s_stride + (size_t)(mtile[j] * 32 + (lane & 31)) * n_stride + n0 + 4 * (lane >> 5);
+#pragma unroll
+        for (int nt = 0; nt < 4; ++nt)
+#pragma unroll
+            for (int b = 0; b < 4; ++b)
+                *(float4*)(prow + nt * 32 + 8 * b) = make_float4(acc[nt][j][4 * b], acc[nt][j][4 * b + 1], acc[nt][j][4 * b + 2], acc[nt][j][4 * b + 3]);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
 // causal chunk attention on the matrix cores (head_dim 128, paired bf16 cache)
 // ---------------------------------------------------------------------------------------------
 // One wave = one (task, kv head, key split); a task is a tile of 32 query columns of one group, the columns
@@ -800,6 +963,7 @@ hipError_t launch_chunk_rope_kv(const ChunkBuffers& c, int S, void* kv_layer, co
 constexpr int ATTN_LDS_BYTES = 4 * 1024 * 16;       // k_chunk_attn: per wave one K tile, two planes
 
 static size_t gemm_lds_bytes(int MT) { return (size_t)(2048 + 2 * MT * 2 * 512) * 16; }
+constexpr int GEMM_WIDE_LDS_BYTES = 2 * 2048 * 16;  // k_chunk_gemm_wide: two buffers of one 128 x 128 weight block
 
 hipError_t chunk_init() {
     hipError_t e;
@@ -807,6 +971,8 @@ hipError_t chunk_init() {
     if ((e = hipFuncSetAttribute((const void*)k_chunk_gemm<2>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)gemm_lds_bytes(2)))) return e;
     if ((e = hipFuncSetAttribute((const void*)k_chunk_attn, hipFuncAttributeMaxDynamicSharedMemorySize, ATTN_LDS_BYTES))) return e;
     if ((e = hipFuncSetAttribute((const void*)k_chunk_gemm<3>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)gemm_lds_bytes(3)))) return e;
+    if ((e = hipFuncSetAttribute((const void*)k_chunk_gemm_wide<1>, hipFuncAttributeMaxDynamicSharedMemorySize, GEMM_WIDE_LDS_BYTES))) return e;
+    if ((e = hipFuncSetAttribute((const void*)k_chunk_gemm_wide<2>, hipFuncAttributeMaxDynamicSharedMemorySize, GEMM_WIDE_LDS_BYTES))) return e;
     return hipSuccess;
 }
 
@@ -815,6 +981,15 @@ hipError_t launch_chunk_gemm(const void* W, int N, int K, const bf16_t* xhi, con
     const dim3 grid(N / 128, S), block(256);
     const size_t ps = (size_t)MT * 32 * N, lds = gemm_lds_bytes(MT);
     if (S < 1 || S > CHUNK_GEMM_MAX_SPLIT || S > K / 128 || N % 128 || K % 128 || ps * S > c.part_capacity) return hipErrorInvalidValue;
+    if (MT < 1 || MT > CHUNK_MAX / 32) return hipErrorInvalidValue;
+    if (MT > 3) {
+        // 128 rows per workgroup for exactly four row tiles, 256 beyond
+        const int MW = MT == 4 ? 1 : 2, MY = (MT + 4 * MW - 1) / (4 * MW);
+        const dim3 wgrid((unsigned)(N / 128) * MY * S);
+        if (MW == 1) hipLaunchKernelGGL(k_chunk_gemm_wide<1>, wgrid, block, GEMM_WIDE_LDS_BYTES, s, (const bf16_t*)W, N, K, xhi, xlo, c.part, ps, N, S, MT);
+        else hipLaunchKernelGGL(k_chunk_gemm_wide<2>, wgrid, block, GEMM_WIDE_LDS_BYTES, s, (const bf16_t*)W, N, K, xhi, xlo, c.part, ps, N, S, MT);
+        return hipGetLastError();
+    }
     if (MT == 1) hipLaunchKernelGGL(k_chunk_gemm<1>, grid, block, lds, s, (const bf16_t*)W, N, K, xhi, xlo, c.part, ps, N, S);
     else if (MT == 2) hipLaunchKernelGGL(k_chunk_gemm<2>, grid, block, lds, s, (const bf16_t*)W, N, K, xhi, xlo, c.part, ps, N, S);
     else if (MT == 3) hipLaunchKernelGGL(k_chunk_gemm<3>, grid, block, lds, s, (const bf16_t*)W, N, K, xhi, xlo, c.part, ps, N, S);

@@ -29,7 +29,7 @@ struct DecodeBuffers {
     const float* rope_sin;
 };
 
-constexpr int CHUNK_MAX = 96;          // rows per forward pass of the append-chunk path
+constexpr int CHUNK_MAX = 512;         // rows per forward pass of the append-chunk path
 constexpr int CHUNK_MAX_TASKS = 128;   // attention tiles (32 query columns of one group) per pass
 constexpr int CHUNK_ATTN_MAX_SPLIT = 64;
 constexpr int CHUNK_ATTN_MAX_UNITS = 4096;   // (task, kv head, key split) partial results per pass
@@ -46,11 +46,13 @@ struct ChunkGroup {
     int32_t pad0, pad1;
 };
 struct ChunkTask { int32_t seq, row0, n, pos0, tile, pad0, pad1, pad2; };         // query columns 32 tile .. 32 tile + 31 of a group
+// Every group has at least one task, so a pass holds at most CHUNK_MAX_TASKS groups.  The rows come last: a
+// pass uploads the table up to its last used row.
 struct ChunkTable {
     int32_t rows, ngroups, ntasks, nhead;
-    ChunkRow row[CHUNK_MAX];
-    ChunkGroup group[CHUNK_MAX];
+    ChunkGroup group[CHUNK_MAX_TASKS];
     ChunkTask task[CHUNK_MAX_TASKS];
+    ChunkRow row[CHUNK_MAX];
 };
 
 // Device buffers of the append-chunk path (bf16 models).  "hi/lo" are the two bf16 planes of a value.

@@ -102,32 +102,34 @@ def test_8b_workload_on_4_layers_matches_oracle(trunc4):
 
 @pytest.mark.timeout(600)
 def test_append_chunk_sizes_agree_with_oracle_and_each_other(trunc4):
-    """The matrix-core append path for every chunk shape (ragged tails, one to three column tiles, split-K
-    factors) against the from-scratch oracle, and against the token-by-token path of the decode kernels."""
+    """The matrix-core append path for every chunk shape (ragged tails, one to three row tiles through the
+    weight-streaming product, four to eleven through the wide one with one or two row blocks, split-K factors)
+    against the from-scratch oracle, and against the token-by-token path of the decode kernels."""
     import paper_2412_07017_amd as pkg
     wl, model, w_dev, w_cpu, spec = trunc4
-    toks = spec["prompt"][:203]
+    toks = spec["prompt"][:403]
     sh = orc.Shape.of(model)
     dec = orc.CachedDecoder(sh, w_cpu, dtype=np.float32)
-    want_a = dec.prefill(toks[:150]).copy()
-    want_b = dec.inject(toks[150:]).copy()
+    want_a = dec.prefill(toks[:340]).copy()
+    want_b = dec.inject(toks[340:]).copy()
     outs = {}
-    for chunk, split in ((1, 0), (2, 0), (7, 0), (24, 0), (32, 1), (33, 0), (48, 2), (64, 0), (64, 4), (64, 3), (65, 0), (96, 0), (96, 8), (24, 5)):
-        lm = pkg.AsyncLM(model, w_dev, max_positions=256, stream=torch.cuda.Stream())
+    for chunk, split in ((1, 0), (2, 0), (7, 0), (24, 0), (32, 1), (33, 0), (48, 2), (64, 0), (64, 4), (64, 3), (65, 0), (96, 0), (96, 8), (24, 5),
+                         (128, 0), (128, 3), (129, 0), (160, 0), (256, 1), (300, 2), (512, 0), (512, 4)):
+        lm = pkg.AsyncLM(model, w_dev, max_positions=448, stream=torch.cuda.Stream())
         lm.set_option("chunk", chunk)
         lm.set_option("chunk_split", split)
-        lm.prefill(0, toks[:150])
+        lm.prefill(0, toks[:340])
         la = lm.logits(0)
-        lm.inject_interrupt(0, toks[150:])
+        lm.inject_interrupt(0, toks[340:])
         lb = lm.logits(0)
-        assert lm.seq_len(0) == 203
+        assert lm.seq_len(0) == 403
         # a decoding step after chunked appends reads the cache rows the chunk kernels wrote
         tok = lm.decode_step(0)
         assert tok == int(np.argmax(lb))
         outs[(chunk, split)] = (la, lb, lm.logits(0))
         lm.close()
         ea, eb = float(np.abs(la - want_a).max()), float(np.abs(lb - want_b).max())
-        print("chunk %2d split %d: max |logit err| prefill %.3e inject %.3e" % (chunk, split, ea, eb))
+        print("chunk %3d split %d: max |logit err| prefill %.3e inject %.3e" % (chunk, split, ea, eb))
         assert ea <= TOL and eb <= TOL
     dec.decode_step()
     base = outs[(1, 0)]
