@@ -287,9 +287,22 @@ struct ChunkSplits { int qkv, o, gu, down; };
 int pick_gemm_split(const asynclm_ctx* c, int N, int K, int MT) {
     const int row_blocks = MT <= 4 ? 1 : (MT + 7) / 8;          // as launch_chunk_gemm tiles the rows
     const int tiles = N / 128 * row_blocks, nblk = K / 128;
-    int s = (c->n_cu + tiles / 2) / tiles;
-    s = std::min(s, std::min(CHUNK_GEMM_MAX_SPLIT, std::max(1, nblk / 2)));
-    s = std::max(s, 1);
+    const int smax = std::min(CHUNK_GEMM_MAX_SPLIT, std::max(1, nblk / 2));
+    int s;
+    if (MT <= 3) {
+        s = std::max(1, std::min((c->n_cu + tiles / 2) / tiles, smax));
+    } else {
+        // wide passes are bound by the matrix cores: the workgroups run in rounds of one per compute unit, each taking
+        // its k-blocks plus about one and a half blocks' time of prologue and epilogue; every split also costs a
+        // partial plane to write and read back
+        s = 1;
+        double best = 0;
+        for (int k = 1; k <= smax; ++k) {
+            const int rounds = (tiles * k + c->n_cu - 1) / c->n_cu;
+            const double cost = rounds * ((double)nblk / k + 1.5) + 0.8 * k;
+            if (k == 1 || cost < best) { best = cost; s = k; }
+        }
+    }
     if (c->opt_chunk_split > 0) s = std::min(c->opt_chunk_split, std::max(1, nblk));
     while (s > 1 && (size_t)s * MT * 32 * N > c->cb.part_capacity) --s;
     return s;
@@ -301,13 +314,17 @@ ChunkSplits chunk_splits(const asynclm_ctx* c, int MT) {
             pick_gemm_split(c, 2 * g.F, g.d, MT), pick_gemm_split(c, g.d, g.F, MT)};
 }
 
-// Key splits of the chunk attention: about two 32-key tiles per wave, a multiple of 4, within the capacity
-// of the partial-result buffers.
+// Key splits of the chunk attention: about two 32-key tiles per wave, a multiple of 4, no more than fill the
+// device eight waves deep (a large pass has enough tasks: more splits only add partial results to write and
+// merge), within the capacity of the partial-result buffers.
 int pick_chunk_attn_split(const asynclm_ctx* c, int max_keys, int ntasks) {
     const int tiles = (max_keys + 31) / 32;
     int n = ((tiles + 1) / 2 + 3) / 4 * 4;
     n = std::max(4, std::min(n, CHUNK_ATTN_MAX_SPLIT));
-    while (n > 4 && (long long)ntasks * c->g.Hkv * n > CHUNK_ATTN_MAX_UNITS) n -= 4;
+    const long long groups = (long long)ntasks * c->g.Hkv;
+    const int fill = (int)std::max(4LL, 8LL * c->n_cu / groups / 4 * 4);
+    n = std::min(n, fill);
+    while (n > 4 && groups * n > CHUNK_ATTN_MAX_UNITS) n -= 4;
     return n;
 }
 
@@ -336,8 +353,12 @@ hipError_t forward_chunk(asynclm_ctx* c, const PassBuilder& pb) {
         if ((e = run(c, KC_CHUNK_ATTN, [&] { return launch_chunk_attn(cb, kvl, asplit, t.ntasks, g, s); }))) return e;
         if ((e = run(c, KC_CHUNK_GEMM, [&] { return launch_chunk_gemm(c->wo[l], g.d, qd, cb.att_hi, cb.att_lo, cb, sp.o, MT, s); }))) return e;
         if ((e = run(c, KC_CHUNK_PREP, [&] { return launch_chunk_resid_norm(cb, true, sp.o, MT, c->ffn_norm[l], rows, g, s); }))) return e;
-        if ((e = run(c, KC_CHUNK_GEMM, [&] { return launch_chunk_gemm(c->wgate_up[l], 2 * g.F, g.d, cb.nrm_hi, cb.nrm_lo, cb, sp.gu, MT, s); }))) return e;
-        if ((e = run(c, KC_CHUNK_PREP, [&] { return launch_chunk_swiglu(cb, sp.gu, MT, rows, g, s); }))) return e;
+        if (MT > 3 && sp.gu == 1) {       // wide pass: the SwiGLU is the product's epilogue
+            if ((e = run(c, KC_CHUNK_GEMM, [&] { return launch_chunk_gemm_swiglu(c->wgate_up[l], g.F, g.d, cb.nrm_hi, cb.nrm_lo, cb, MT, s); }))) return e;
+        } else {
+            if ((e = run(c, KC_CHUNK_GEMM, [&] { return launch_chunk_gemm(c->wgate_up[l], 2 * g.F, g.d, cb.nrm_hi, cb.nrm_lo, cb, sp.gu, MT, s); }))) return e;
+            if ((e = run(c, KC_CHUNK_PREP, [&] { return launch_chunk_swiglu(cb, sp.gu, MT, rows, g, s); }))) return e;
+        }
         if ((e = run(c, KC_CHUNK_GEMM, [&] { return launch_chunk_gemm(c->wdown[l], g.d, g.F, cb.act_hi, cb.act_lo, cb, sp.down, MT, s); }))) return e;
     }
     const bool head_on_mfma = t.nhead > 1 && g.V % 128 == 0 && (size_t)((t.nhead + 31) / 32) * 32 * g.V <= cb.part_capacity;

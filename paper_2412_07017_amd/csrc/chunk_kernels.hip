@@ -448,13 +448,13 @@ __global__ __launch_bounds__(256) void k_chunk_gemm(const bf16_t* __restrict__ W
 // ---------------------------------------------------------------------------------------------
 // wide GEMM on the matrix cores for passes of more than 96 rows (prefill, large batched steps)
 // ---------------------------------------------------------------------------------------------
-// Workgroup = 4 waves on a tile of 128 weight rows x (128 MW) token rows and one run of k-blocks.  Beyond 96
+// Workgroup = NW waves on a tile of 128 weight rows x (32 NW MW) token rows and one run of k-blocks.  Beyond 96
 // rows a pass is bound by the matrix cores, not by the weight stream, so the tile is shaped for operand reuse:
 //  * every wave multiplies ALL 128 weight rows of the tile with its own MW row tiles (32 token rows each):
 //    per 16-column k-step 4 weight operands and 2 MW activation operands (hi, lo) feed 8 MW products;
 //  * the weight block (128 rows x 128 columns) is loaded once per workgroup (4 rows x 256 contiguous bytes
 //    per instruction), transposed into operand order through a double-buffered, XOR-swizzled LDS tile that
-//    the four waves share: one barrier per k-block;
+//    the waves share: one barrier per k-block;
 //  * the activations are already in operand order in global memory (tiled planes: one contiguous KiB per
 //    wave-wide load) and go straight to registers through a ring of four 2-step units, three units ahead of
 //    the products; no wave reads another wave's rows, so they never pass through LDS.
@@ -493,13 +493,20 @@ __device__ __forceinline__ void wide_step(const uint4 (&a)[4], const BUnit<MW>& 
             for (int j = 0; j < MW; ++j) acc[nt][j] = mfma_bf16(a[nt], b.v[j][st][pl], acc[nt][j]);
 }
 
-template <int MW>
-__global__ __launch_bounds__(256) void k_chunk_gemm_wide(const bf16_t* __restrict__ W, int N, int K,
-                                                         const bf16_t* __restrict__ Xhi, const bf16_t* __restrict__ Xlo,
-                                                         float* __restrict__ P, size_t s_stride, int n_stride, int S, int MT) {
+//
+// SWIGLU: W holds the gate rows [0, N/2) and the up rows [N/2, N) of a feed-forward block.  The workgroup
+// takes 64 gate rows and the 64 up rows of the same columns (weight-row tiles 0, 1 and 2, 3), and its
+// epilogue writes silu(gate) * up as hi/lo planes in operand order (act_hi, act_lo; N/2 columns) instead of
+// the fp32 products: S must be 1.
+template <int NW, int MW, bool SWIGLU>
+__global__ __launch_bounds__(NW * 64) void k_chunk_gemm_wide(const bf16_t* __restrict__ W, int N, int K,
+                                                             const bf16_t* __restrict__ Xhi, const bf16_t* __restrict__ Xlo,
+                                                             float* __restrict__ P, size_t s_stride, int n_stride, int S, int MT,
+                                                             bf16_t* __restrict__ act_hi, bf16_t* __restrict__ act_lo) {
     extern __shared__ uint4 gemm_lds[];             // [2 buffers][4 weight-row tiles][512]
+    constexpr int QN = 32 / NW;                     // weight loads per thread and block: wave w stages rows (128 / NW) w ...
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int tiles = N >> 7, MY = (MT + 4 * MW - 1) / (4 * MW);
+    const int tiles = N >> 7, MY = (MT + NW * MW - 1) / (NW * MW);
     int ntile, my, sp;
     {
         int q = blockIdx.x;
@@ -518,16 +525,23 @@ __global__ __launch_bounds__(256) void k_chunk_gemm_wide(const bf16_t* __restric
     const int nb = b1 - b0, last = b1 - 1;
     const int n0 = ntile * 128;
 
-    // weights: wave w stages rows 32 w .. 32 w + 31 of the tile
-    const bf16_t* wlane = W + (size_t)(n0 + wave * 32 + (lane >> 4)) * K + (lane & 15) * 8;
-    const size_t wstep = (size_t)4 * K;
-    // activations: row tiles (my MW + j) * 4 + wave of the pass; tiles past the end repeat the last one and are not stored
+    // weights: load q of a thread covers row (128 / NW) wave + 4 q + lane / 16 of the tile, 16-byte chunk lane % 16
+    const bf16_t* wq[QN];
+    int wslot[QN];
+#pragma unroll
+    for (int q = 0; q < QN; ++q) {
+        const int rg = wave * (128 / NW) + 4 * q + (lane >> 4), r = rg & 31, c = lane & 15;
+        const int row = SWIGLU ? (rg < 64 ? ntile * 64 + rg : (N >> 1) + ntile * 64 + rg - 64) : n0 + rg;
+        wq[q] = W + (size_t)row * K + c * 8;
+        wslot[q] = (rg >> 5) * 512 + r * 16 + (c ^ (r & 15));
+    }
+    // activations: row tiles (my MW + j) NW + wave of the pass; tiles past the end repeat the last one and are not stored
     int mtile[MW];
     const bf16_t* xh[MW];
     const bf16_t* xl[MW];
 #pragma unroll
     for (int j = 0; j < MW; ++j) {
-        mtile[j] = (my * MW + j) * 4 + wave;
+        mtile[j] = (my * MW + j) * NW + wave;
         const size_t o = (size_t)min(mtile[j], MT - 1) * nblk * 4096 + lane * 8;
         xh[j] = Xhi + o; xl[j] = Xlo + o;
     }
@@ -541,24 +555,24 @@ __global__ __launch_bounds__(256) void k_chunk_gemm_wide(const bf16_t* __restric
             for (int r = 0; r < 16; ++r) acc[nt][j][r] = 0.f;
 
     if (nb > 0) {
-        uint4 wreg[8];
+        uint4 wreg[QN];
         BUnit<MW> ring[4];
-        const int wr0 = lane >> 4, wc = lane & 15;
+        auto w_load = [&](int blk) {
+#pragma unroll
+            for (int q = 0; q < QN; ++q) wreg[q] = load16_stream(wq[q] + (size_t)blk * 128);
+        };
         auto w_store = [&](uint4* at) {
 #pragma unroll
-            for (int q = 0; q < 8; ++q) {
-                const int r = 4 * q + wr0;
-                at[wave * 512 + r * 16 + (wc ^ (r & 15))] = wreg[q];
-            }
+            for (int q = 0; q < QN; ++q) at[wslot[q]] = wreg[q];
         };
         // issue order = completion order: weights of the first block, three activation units, weights of the second block
-        gemm_a_load(wreg, wlane, wstep, b0);
+        w_load(b0);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int u = 0; u < 3; ++u) wide_b_load<MW>(ring[u], xh, xl, b0, u);
         __builtin_amdgcn_sched_barrier(0);
         w_store(gemm_lds);
-        gemm_a_load(wreg, wlane, wstep, min(b0 + 1, last));
+        w_load(min(b0 + 1, last));
         __builtin_amdgcn_sched_barrier(0);
         __syncthreads();
         for (int t = 0; t < nb; t += 2) {
@@ -578,7 +592,7 @@ __global__ __launch_bounds__(256) void k_chunk_gemm_wide(const bf16_t* __restric
                         // the next block's weights (requested one block ago) move to the other LDS buffer, whose
                         // readers passed the barrier that ended the previous block; then the block after is requested
                         w_store(gemm_lds + (h ^ 1) * 2048);
-                        gemm_a_load(wreg, wlane, wstep, min(tt + 2, last));
+                        w_load(min(tt + 2, last));
                         __builtin_amdgcn_sched_barrier(0);
                     }
                     wide_a_read(a1, at, 2 * u + 1, lane);
@@ -596,6 +610,29 @@ __global__ __launch_bounds__(256) void k_chunk_gemm_wide(const bf16_t* __restric
     }
 
     // lane (j, g) holds D[8b + 4g + r][j] in register 4b + r: four consecutive weight rows of token row j
+    if (SWIGLU) {
+        const int F = N >> 1, f0 = ntile * 64 + 4 * (lane >> 5);
+#pragma unroll
+        for (int j = 0; j < MW; ++j) {
+            if (mtile[j] >= MT) continue;
+            const int m = mtile[j] * 32 + (lane & 31);
+#pragma unroll
+            for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+                for (int b = 0; b < 4; ++b) {
+                    bf16_t hi[4], lo[4];
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        const float gt = acc[nt][j][4 * b + r], up = acc[nt + 2][j][4 * b + r];
+                        split_bf16(gt / (1.f + expf(-gt)) * up, hi[r], lo[r]);
+                    }
+                    const size_t o = tiled_off(m, f0 + nt * 32 + 8 * b, F);     // four columns inside one 8-element group
+                    *reinterpret_cast<uint2*>(act_hi + o) = make_uint2(hi[0] | ((uint32_t)hi[1] << 16), hi[2] | ((uint32_t)hi[3] << 16));
+                    *reinterpret_cast<uint2*>(act_lo + o) = make_uint2(lo[0] | ((uint32_t)lo[1] << 16), lo[2] | ((uint32_t)lo[3] << 16));
+                }
+        }
+        return;
+    }
 #pragma unroll
     for (int j = 0; j < MW; ++j) {
         if (mtile[j] >= MT) continue;
@@ -964,6 +1001,9 @@ constexpr int ATTN_LDS_BYTES = 4 * 1024 * 16;       // k_chunk_attn: per wave on
 
 static size_t gemm_lds_bytes(int MT) { return (size_t)(2048 + 2 * MT * 2 * 512) * 16; }
 constexpr int GEMM_WIDE_LDS_BYTES = 2 * 2048 * 16;  // k_chunk_gemm_wide: two buffers of one 128 x 128 weight block
+// 256-row workgroups of the wide product: four waves with two row tiles each (eight waves with one tile each, two
+// per SIMD, measure 2-4 % slower: the loop is bound by operand delivery and power, not by latency)
+constexpr int WIDE_NW = 4, WIDE_MW = 2;
 
 hipError_t chunk_init() {
     hipError_t e;
@@ -971,8 +1011,10 @@ hipError_t chunk_init() {
     if ((e = hipFuncSetAttribute((const void*)k_chunk_gemm<2>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)gemm_lds_bytes(2)))) return e;
     if ((e = hipFuncSetAttribute((const void*)k_chunk_attn, hipFuncAttributeMaxDynamicSharedMemorySize, ATTN_LDS_BYTES))) return e;
     if ((e = hipFuncSetAttribute((const void*)k_chunk_gemm<3>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)gemm_lds_bytes(3)))) return e;
-    if ((e = hipFuncSetAttribute((const void*)k_chunk_gemm_wide<1>, hipFuncAttributeMaxDynamicSharedMemorySize, GEMM_WIDE_LDS_BYTES))) return e;
-    if ((e = hipFuncSetAttribute((const void*)k_chunk_gemm_wide<2>, hipFuncAttributeMaxDynamicSharedMemorySize, GEMM_WIDE_LDS_BYTES))) return e;
+    if ((e = hipFuncSetAttribute((const void*)k_chunk_gemm_wide<4, 1, false>, hipFuncAttributeMaxDynamicSharedMemorySize, GEMM_WIDE_LDS_BYTES))) return e;
+    if ((e = hipFuncSetAttribute((const void*)k_chunk_gemm_wide<WIDE_NW, WIDE_MW, false>, hipFuncAttributeMaxDynamicSharedMemorySize, GEMM_WIDE_LDS_BYTES))) return e;
+    if ((e = hipFuncSetAttribute((const void*)k_chunk_gemm_wide<4, 1, true>, hipFuncAttributeMaxDynamicSharedMemorySize, GEMM_WIDE_LDS_BYTES))) return e;
+    if ((e = hipFuncSetAttribute((const void*)k_chunk_gemm_wide<WIDE_NW, WIDE_MW, true>, hipFuncAttributeMaxDynamicSharedMemorySize, GEMM_WIDE_LDS_BYTES))) return e;
     return hipSuccess;
 }
 
@@ -984,16 +1026,28 @@ hipError_t launch_chunk_gemm(const void* W, int N, int K, const bf16_t* xhi, con
     if (MT < 1 || MT > CHUNK_MAX / 32) return hipErrorInvalidValue;
     if (MT > 3) {
         // 128 rows per workgroup for exactly four row tiles, 256 beyond
-        const int MW = MT == 4 ? 1 : 2, MY = (MT + 4 * MW - 1) / (4 * MW);
+        const int MY = MT == 4 ? 1 : (MT + 7) / 8;
         const dim3 wgrid((unsigned)(N / 128) * MY * S);
-        if (MW == 1) hipLaunchKernelGGL(k_chunk_gemm_wide<1>, wgrid, block, GEMM_WIDE_LDS_BYTES, s, (const bf16_t*)W, N, K, xhi, xlo, c.part, ps, N, S, MT);
-        else hipLaunchKernelGGL(k_chunk_gemm_wide<2>, wgrid, block, GEMM_WIDE_LDS_BYTES, s, (const bf16_t*)W, N, K, xhi, xlo, c.part, ps, N, S, MT);
+        if (MT == 4) hipLaunchKernelGGL((k_chunk_gemm_wide<4, 1, false>), wgrid, block, GEMM_WIDE_LDS_BYTES, s, (const bf16_t*)W, N, K, xhi, xlo, c.part, ps, N, S, MT, nullptr, nullptr);
+        else hipLaunchKernelGGL((k_chunk_gemm_wide<WIDE_NW, WIDE_MW, false>), wgrid, dim3(WIDE_NW * 64), GEMM_WIDE_LDS_BYTES, s, (const bf16_t*)W, N, K, xhi, xlo, c.part, ps, N, S, MT, nullptr, nullptr);
         return hipGetLastError();
     }
     if (MT == 1) hipLaunchKernelGGL(k_chunk_gemm<1>, grid, block, lds, s, (const bf16_t*)W, N, K, xhi, xlo, c.part, ps, N, S);
     else if (MT == 2) hipLaunchKernelGGL(k_chunk_gemm<2>, grid, block, lds, s, (const bf16_t*)W, N, K, xhi, xlo, c.part, ps, N, S);
     else if (MT == 3) hipLaunchKernelGGL(k_chunk_gemm<3>, grid, block, lds, s, (const bf16_t*)W, N, K, xhi, xlo, c.part, ps, N, S);
     else return hipErrorInvalidValue;
+    return hipGetLastError();
+}
+
+// Gate/up product of a pass of more than 96 rows with the SwiGLU in its epilogue: W = [gate rows | up rows] (2F x K),
+// result in c.act_hi / c.act_lo.
+hipError_t launch_chunk_gemm_swiglu(const void* W, int F, int K, const bf16_t* xhi, const bf16_t* xlo, const ChunkBuffers& c,
+                                    int MT, hipStream_t s) {
+    if (MT < 4 || MT > CHUNK_MAX / 32 || F % 64 || K % 128) return hipErrorInvalidValue;
+    const int MY = MT == 4 ? 1 : (MT + 7) / 8;
+    const dim3 wgrid((unsigned)(F / 64) * MY);
+    if (MT == 4) hipLaunchKernelGGL((k_chunk_gemm_wide<4, 1, true>), wgrid, dim3(256), GEMM_WIDE_LDS_BYTES, s, (const bf16_t*)W, 2 * F, K, xhi, xlo, nullptr, (size_t)0, 0, 1, MT, c.act_hi, c.act_lo);
+    else hipLaunchKernelGGL((k_chunk_gemm_wide<WIDE_NW, WIDE_MW, true>), wgrid, dim3(WIDE_NW * 64), GEMM_WIDE_LDS_BYTES, s, (const bf16_t*)W, 2 * F, K, xhi, xlo, nullptr, (size_t)0, 0, 1, MT, c.act_hi, c.act_lo);
     return hipGetLastError();
 }
 

@@ -119,6 +119,8 @@ hipError_t launch_chunk_rope_kv(const ChunkBuffers& c, int S, void* kv_layer, co
                                 const Geom& g, hipStream_t s);
 hipError_t launch_chunk_gemm(const void* W, int N, int K, const bf16_t* xhi, const bf16_t* xlo, const ChunkBuffers& c,
                              int S, int MT, hipStream_t s);
+hipError_t launch_chunk_gemm_swiglu(const void* W, int F, int K, const bf16_t* xhi, const bf16_t* xlo, const ChunkBuffers& c,
+                                    int MT, hipStream_t s);
 hipError_t launch_chunk_attn(const ChunkBuffers& c, const void* kv_layer, int nsplit, int ntasks, const Geom& g, hipStream_t s);
 // single-row decoding attention on the matrix cores (long contexts): b.q -> b.o through the chunk attention
 hipError_t launch_decode_attn_mfma(const ChunkBuffers& c, const void* kv_layer, int nsplit, const DecodeBuffers& b, const Geom& g,
