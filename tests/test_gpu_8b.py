@@ -218,8 +218,9 @@ def test_full_depth_8b_short_stream_matches_oracle(trunc4):
 def test_step_batch_ragged_sequences_match_independent_oracle_sequences(trunc4):
     """asynclm_step_batch on the matrix-core path: six sequences of ragged length share every weight pass; rows
     are [chosen token] ++ [interrupt tokens] per sequence (Sec. 5.3).  Covers single-row groups, interrupts
-    of 16-32 tokens, one interrupt that is longer than a pass (continued in the next pass), greedy choice on
-    the device and the output head on the matrix cores, against one independent oracle decoder per sequence."""
+    of 16-32 tokens, a 126-row pass (wide product with several groups), one step whose 636 rows exceed a pass (a
+    group is cut and continued in the next pass), greedy choice on the device and the output head on the matrix
+    cores, against one independent oracle decoder per sequence."""
     import paper_2412_07017_amd as pkg
     wl, model, w_dev, w_cpu, spec = trunc4
     V = model.vocab
@@ -227,11 +228,12 @@ def test_step_batch_ragged_sequences_match_independent_oracle_sequences(trunc4):
     lens = (37, 64, 150, 200, 97, 256)
     prompts = [ai.uniform_tokens(ai.MASTER_SEED, 911, n, V, sub=i) for i, n in enumerate(lens)]
     tk = lambda n, sub: ai.uniform_tokens(ai.MASTER_SEED, 912, n, V, sub=sub)
-    plan = [{}, {2: tk(24, 0)}, {0: tk(16, 1), 5: tk(32, 2)}, {}, {1: tk(120, 3)}, {3: tk(31, 4), 4: tk(17, 5), 0: tk(20, 6)}, {}, {}]
+    plan = [{}, {2: tk(24, 0)}, {0: tk(16, 1), 5: tk(32, 2)}, {}, {1: tk(120, 3)}, {3: tk(31, 4), 4: tk(17, 5), 0: tk(20, 6)}, {},
+            {2: tk(250, 7), 5: tk(200, 8), 0: tk(180, 9)}, {}]
     decs = [orc.CachedDecoder(sh, w_cpu, dtype=np.float32) for _ in prompts]
     for d, p in zip(decs, prompts):
         d.prefill(p)
-    lm = pkg.AsyncLM(model, w_dev, max_positions=512, max_seqs=6, stream=torch.cuda.Stream())
+    lm = pkg.AsyncLM(model, w_dev, max_positions=1024, max_seqs=6, stream=torch.cuda.Stream())
     for s, p in enumerate(prompts):
         lm.prefill(s, p)
     worst, gated = 0.0, 0
