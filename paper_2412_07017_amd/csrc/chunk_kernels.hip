@@ -780,7 +780,10 @@ __global__ __launch_bounds__(256) void k_chunk_attn(ChunkAttnArgs a, Geom g) {
     const int G = g.Hq / g.Hkv;
     const int kvh = blockIdx.x % g.Hkv, split = blockIdx.y * 4 + wave;
     const ChunkTask T = a.tab->task[blockIdx.x / g.Hkv];
-    const int Lk = T.pos0 + T.n;                           // keys 0 .. Lk-1 exist
+    // Columns 32 tile .. 32 tile + 31 of the group are rows first .. first + 31 of one query head, or wrap into the
+    // next head (then the group's last row is among them): no column of the tile sees keys past its latest row.
+    const int first = (32 * T.tile) % T.n;
+    const int Lk = T.pos0 + min(first + 32, T.n);          // keys 0 .. Lk-1 matter to this tile
     const int ntile = (Lk + 31) >> 5;
     const int tps = (ntile + a.nsplit - 1) / a.nsplit;
     const int t0 = split * tps, t1 = min(ntile, t0 + tps);
