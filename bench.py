@@ -9,8 +9,12 @@ into the live K/V cache.  The default workload is the Llama-3-8B-shaped preset: 
 
 Prints ONE JSON line:
   value          generated tokens per second over the timed steps, injections included
-  decode_*       decode-only rate and its fraction of the HBM roofline (algorithmic bytes / time / 8 TB/s)
-  inject_*       microseconds per interrupt and its cost in decoding steps
+  decode_*       decode-only rate and its fraction of the HBM roofline (algorithmic bytes / time / 8 TB/s);
+                 10th / 50th / 90th percentile of the single steps (an event after every step)
+  inject_*       microseconds per interrupt (mean; min / median / max) and its cost in decoding steps
+  reprefill_*, kv_swap_*, merged_*   the stateless re-prefill of the same context (Sec. 5.5), the K/V swap of a
+                 trapped session (Sec. 5.4) and the interrupt riding with the next token (Sec. 5.3)
+  streaming_read_ceiling   what the longest plain stream of the step (the output head) reaches on this device
   roofline       dominant kernel (gate/up projection + SwiGLU): algorithmic bytes per launch over
                  its mean duration measured here with HIP events on the library's stream
   cpu_baseline   the CPU oracle timed on this host on a bounded sample (a baseline, not a target)
@@ -275,12 +279,18 @@ def main():
 
     history = [int(t) for t in spec["prompt"]]          # the whole context, as the stateless variant would resend it
 
+    step_marks = []                                     # one event after every decoding step of the timed blocks
+
     def run_block(j, rec):
         e0, e1, e2 = ev(), ev(), ev()
         e0.record(stream)
+        marks = [e0]
         for _ in range(block):
             history.append(lm.decode_step(0))       # greedy on the device, token returned to the host
-        e1.record(stream)
+            marks.append(ev())
+            marks[-1].record(stream)
+        e1 = marks[-1]
+        step_marks.append(marks)
         lm.inject_interrupt(0, intr[j])
         history.extend(int(t) for t in intr[j])
         e2.record(stream)
@@ -292,6 +302,7 @@ def main():
     lm.synchronize()
     torch.cuda.synchronize()
     rec = []
+    step_marks.clear()
     len_start = lm.seq_len(0)
     t0 = time.perf_counter()
     for j in range(args.warmup, n_blocks):
@@ -342,6 +353,7 @@ def main():
 
     dec_ms = [a.elapsed_time(b) for a, b, c in rec]
     inj_ms = [b.elapsed_time(c) for a, b, c in rec]
+    per_step_ms = np.array([m[i].elapsed_time(m[i + 1]) for m in step_marks for i in range(len(m) - 1)])
     ms_dec_step = float(np.mean(dec_ms)) / block
     ms_inject = float(np.mean(inj_ms))
     tokens = args.steps * block
@@ -376,6 +388,12 @@ def main():
     roofline["frac"] = roofline["achieved"] / roofline["peak"]
     per_class = {k: {"ms_per_step": v["ms"] / 5, "launches_per_step": v["launches"] // 5} for k, v in classes.items()}
     lm.synchronize()
+    # what a long plain stream reaches on this device: the output head reads its vocab x d matrix exactly once
+    ceiling = None
+    if "lm_head" in classes:
+        head_bytes = model.vocab * model.d_model * eb + 4 * model.vocab
+        ceiling = {"kernel": "output head (k_gemv), one pass over %.2f GB" % (head_bytes / 1e9),
+                   "GBps": head_bytes / (classes["lm_head"]["ms"] / classes["lm_head"]["launches"] * 1e-3) / 1e9}
 
     out = {
         "metric": "decode tokens/s @ batch 1 (% HBM roofline); us per k-token interrupt inject",
@@ -389,13 +407,15 @@ def main():
                    "context_len": [len_start, len_end], "seed": ai.MASTER_SEED},
         "decode_tokens_per_s": decode_tok_s, "decode_ms_per_token": ms_dec_step,
         "decode_hbm_frac": decode_frac, "decode_bytes_per_token": bytes_step,
+        "decode_ms_per_token_p10_p50_p90": [float(np.percentile(per_step_ms, q)) for q in (10, 50, 90)],
+        "inject_us_min_median_max": [float(np.min(inj_ms)) * 1e3, float(np.median(inj_ms)) * 1e3, float(np.max(inj_ms)) * 1e3],
         "inject_us": ms_inject * 1e3, "inject_tokens": k_intr, "inject_in_decode_steps": ms_inject / ms_dec_step,
         "reprefill_us": reprefill_ms * 1e3, "reprefill_tokens": len(history), "reprefill_over_inject": reprefill_ms / ms_inject,
         "kv_swap_bytes": int(nbytes), "kv_swap_out_us": swap_out_ms * 1e3, "kv_swap_in_us": swap_in_ms * 1e3,
         "merged_step_us": float(np.mean(merged_ms)) * 1e3,
         "merged_inject_extra_in_decode_steps": float(np.mean(merged_ms)) / ms_dec_step - 1.0,
         "prefill_s": t_prefill, "weights_s": t_weights,
-        "roofline": roofline, "kernel_classes": per_class,
+        "roofline": roofline, "streaming_read_ceiling": ceiling, "kernel_classes": per_class,
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, model, w_dev, spec)
