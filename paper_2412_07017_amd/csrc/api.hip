@@ -353,7 +353,7 @@ hipError_t forward_chunk(asynclm_ctx* c, const PassBuilder& pb) {
         if ((e = run(c, KC_CHUNK_ATTN, [&] { return launch_chunk_attn(cb, kvl, asplit, t.ntasks, g, s); }))) return e;
         if ((e = run(c, KC_CHUNK_GEMM, [&] { return launch_chunk_gemm(c->wo[l], g.d, qd, cb.att_hi, cb.att_lo, cb, sp.o, MT, s); }))) return e;
         if ((e = run(c, KC_CHUNK_PREP, [&] { return launch_chunk_resid_norm(cb, true, sp.o, MT, c->ffn_norm[l], rows, g, s); }))) return e;
-        if (MT > 3 && sp.gu == 1) {       // wide pass: the SwiGLU is the product's epilogue
+        if (sp.gu == 1) {                 // no split-K: the SwiGLU is the product's epilogue
             if ((e = run(c, KC_CHUNK_GEMM, [&] { return launch_chunk_gemm_swiglu(c->wgate_up[l], g.F, g.d, cb.nrm_hi, cb.nrm_lo, cb, MT, s); }))) return e;
         } else {
             if ((e = run(c, KC_CHUNK_GEMM, [&] { return launch_chunk_gemm(c->wgate_up[l], 2 * g.F, g.d, cb.nrm_hi, cb.nrm_lo, cb, sp.gu, MT, s); }))) return e;

@@ -377,16 +377,21 @@ __device__ __forceinline__ void gemm_tile_mma(const uint4 (&ta)[8], f32x16 (&acc
     }
 }
 
-template <int MT>
+// SWIGLU (S = 1 only): W holds the gate rows [0, N/2) and the up rows [N/2, N).  Waves 0, 1 of the workgroup take 64
+// gate rows, waves 2, 3 the 64 up rows of the same columns; the up products pass through LDS to the gate waves,
+// which write silu(gate) * up as hi/lo planes in operand order (act_hi, act_lo; N/2 columns).
+template <int MT, bool SWIGLU>
 __global__ __launch_bounds__(256) void k_chunk_gemm(const bf16_t* __restrict__ W, int N, int K,
                                                     const bf16_t* __restrict__ Xhi, const bf16_t* __restrict__ Xlo,
-                                                    float* __restrict__ P, size_t s_stride, int n_stride, int S) {
+                                                    float* __restrict__ P, size_t s_stride, int n_stride, int S,
+                                                    bf16_t* __restrict__ act_hi, bf16_t* __restrict__ act_lo) {
     extern __shared__ uint4 gemm_lds[];             // [4 waves][512] weight tiles, then [2][MT][2][512] activation tiles
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     uint4* at = gemm_lds + wave * 512;
     uint4* bt = gemm_lds + 2048;
     constexpr int BT = MT * 2 * 512;                // chunks in one activation buffer
-    const int n0 = blockIdx.x * 128 + wave * 32, sp = blockIdx.y;
+    const int n0 = SWIGLU ? (wave < 2 ? 0 : N >> 1) + blockIdx.x * 64 + (wave & 1) * 32 : blockIdx.x * 128 + wave * 32;
+    const int sp = blockIdx.y;
     const int nblk = K >> 7;
     const int b0 = (int)((long long)nblk * sp / S), b1 = (int)((long long)nblk * (sp + 1) / S);
     const int nb = b1 - b0, last = b1 - 1;
@@ -436,6 +441,38 @@ __global__ __launch_bounds__(256) void k_chunk_gemm(const bf16_t* __restrict__ W
     }
 
     // lane (j, g) holds D[8b + 4g + r][j] in register 4b + r: four consecutive weight rows of token row j
+    if (SWIGLU) {
+        // the loop's last barrier has released the activation tiles: [up wave][mt][register quad][lane] float4
+        float4* ex = reinterpret_cast<float4*>(bt);
+        if (wave >= 2) {
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                for (int b = 0; b < 4; ++b)
+                    ex[(((wave - 2) * MT + mt) * 4 + b) * 64 + lane] = make_float4(acc[mt][4 * b], acc[mt][4 * b + 1], acc[mt][4 * b + 2], acc[mt][4 * b + 3]);
+        }
+        __syncthreads();
+        if (wave < 2) {
+            const int F = N >> 1, f0 = n0 + 4 * (lane >> 5);
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                for (int b = 0; b < 4; ++b) {
+                    const float4 u4 = ex[((wave * MT + mt) * 4 + b) * 64 + lane];
+                    const float up[4] = {u4.x, u4.y, u4.z, u4.w};
+                    bf16_t hi[4], lo[4];
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        const float gt = acc[mt][4 * b + r];
+                        split_bf16(gt / (1.f + expf(-gt)) * up[r], hi[r], lo[r]);
+                    }
+                    const size_t o = tiled_off(mt * 32 + (lane & 31), f0 + 8 * b, F);   // four columns inside one 8-element group
+                    *reinterpret_cast<uint2*>(act_hi + o) = make_uint2(hi[0] | ((uint32_t)hi[1] << 16), hi[2] | ((uint32_t)hi[3] << 16));
+                    *reinterpret_cast<uint2*>(act_lo + o) = make_uint2(lo[0] | ((uint32_t)lo[1] << 16), lo[2] | ((uint32_t)lo[3] << 16));
+                }
+        }
+        return;
+    }
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
         float* prow = P + sp * s_stride + (size_t)(mt * 32 + (lane & 31)) * n_stride + n0 + 4 * (lane >> 5);
@@ -1010,10 +1047,13 @@ constexpr int WIDE_NW = 4, WIDE_MW = 2;
 
 hipError_t chunk_init() {
     hipError_t e;
-    if ((e = hipFuncSetAttribute((const void*)k_chunk_gemm<1>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)gemm_lds_bytes(1)))) return e;
-    if ((e = hipFuncSetAttribute((const void*)k_chunk_gemm<2>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)gemm_lds_bytes(2)))) return e;
+    if ((e = hipFuncSetAttribute((const void*)k_chunk_gemm<1, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)gemm_lds_bytes(1)))) return e;
+    if ((e = hipFuncSetAttribute((const void*)k_chunk_gemm<2, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)gemm_lds_bytes(2)))) return e;
+    if ((e = hipFuncSetAttribute((const void*)k_chunk_gemm<3, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)gemm_lds_bytes(3)))) return e;
+    if ((e = hipFuncSetAttribute((const void*)k_chunk_gemm<1, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)gemm_lds_bytes(1)))) return e;
+    if ((e = hipFuncSetAttribute((const void*)k_chunk_gemm<2, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)gemm_lds_bytes(2)))) return e;
+    if ((e = hipFuncSetAttribute((const void*)k_chunk_gemm<3, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)gemm_lds_bytes(3)))) return e;
     if ((e = hipFuncSetAttribute((const void*)k_chunk_attn, hipFuncAttributeMaxDynamicSharedMemorySize, ATTN_LDS_BYTES))) return e;
-    if ((e = hipFuncSetAttribute((const void*)k_chunk_gemm<3>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)gemm_lds_bytes(3)))) return e;
     if ((e = hipFuncSetAttribute((const void*)k_chunk_gemm_wide<4, 1, false>, hipFuncAttributeMaxDynamicSharedMemorySize, GEMM_WIDE_LDS_BYTES))) return e;
     if ((e = hipFuncSetAttribute((const void*)k_chunk_gemm_wide<WIDE_NW, WIDE_MW, false>, hipFuncAttributeMaxDynamicSharedMemorySize, GEMM_WIDE_LDS_BYTES))) return e;
     if ((e = hipFuncSetAttribute((const void*)k_chunk_gemm_wide<4, 1, true>, hipFuncAttributeMaxDynamicSharedMemorySize, GEMM_WIDE_LDS_BYTES))) return e;
@@ -1035,18 +1075,26 @@ hipError_t launch_chunk_gemm(const void* W, int N, int K, const bf16_t* xhi, con
         else hipLaunchKernelGGL((k_chunk_gemm_wide<WIDE_NW, WIDE_MW, false>), wgrid, dim3(WIDE_NW * 64), GEMM_WIDE_LDS_BYTES, s, (const bf16_t*)W, N, K, xhi, xlo, c.part, ps, N, S, MT, nullptr, nullptr);
         return hipGetLastError();
     }
-    if (MT == 1) hipLaunchKernelGGL(k_chunk_gemm<1>, grid, block, lds, s, (const bf16_t*)W, N, K, xhi, xlo, c.part, ps, N, S);
-    else if (MT == 2) hipLaunchKernelGGL(k_chunk_gemm<2>, grid, block, lds, s, (const bf16_t*)W, N, K, xhi, xlo, c.part, ps, N, S);
-    else if (MT == 3) hipLaunchKernelGGL(k_chunk_gemm<3>, grid, block, lds, s, (const bf16_t*)W, N, K, xhi, xlo, c.part, ps, N, S);
+    if (MT == 1) hipLaunchKernelGGL((k_chunk_gemm<1, false>), grid, block, lds, s, (const bf16_t*)W, N, K, xhi, xlo, c.part, ps, N, S, nullptr, nullptr);
+    else if (MT == 2) hipLaunchKernelGGL((k_chunk_gemm<2, false>), grid, block, lds, s, (const bf16_t*)W, N, K, xhi, xlo, c.part, ps, N, S, nullptr, nullptr);
+    else if (MT == 3) hipLaunchKernelGGL((k_chunk_gemm<3, false>), grid, block, lds, s, (const bf16_t*)W, N, K, xhi, xlo, c.part, ps, N, S, nullptr, nullptr);
     else return hipErrorInvalidValue;
     return hipGetLastError();
 }
 
-// Gate/up product of a pass of more than 96 rows with the SwiGLU in its epilogue: W = [gate rows | up rows] (2F x K),
-// result in c.act_hi / c.act_lo.
+// Gate/up product with the SwiGLU in its epilogue (no split-K): W = [gate rows | up rows] (2F x K), result in
+// c.act_hi / c.act_lo.
 hipError_t launch_chunk_gemm_swiglu(const void* W, int F, int K, const bf16_t* xhi, const bf16_t* xlo, const ChunkBuffers& c,
                                     int MT, hipStream_t s) {
-    if (MT < 4 || MT > CHUNK_MAX / 32 || F % 64 || K % 128) return hipErrorInvalidValue;
+    if (MT < 1 || MT > CHUNK_MAX / 32 || F % 64 || K % 128) return hipErrorInvalidValue;
+    if (MT <= 3) {
+        const dim3 grid(F / 64, 1), block(256);
+        const size_t lds = gemm_lds_bytes(MT);
+        if (MT == 1) hipLaunchKernelGGL((k_chunk_gemm<1, true>), grid, block, lds, s, (const bf16_t*)W, 2 * F, K, xhi, xlo, nullptr, (size_t)0, 0, 1, c.act_hi, c.act_lo);
+        else if (MT == 2) hipLaunchKernelGGL((k_chunk_gemm<2, true>), grid, block, lds, s, (const bf16_t*)W, 2 * F, K, xhi, xlo, nullptr, (size_t)0, 0, 1, c.act_hi, c.act_lo);
+        else hipLaunchKernelGGL((k_chunk_gemm<3, true>), grid, block, lds, s, (const bf16_t*)W, 2 * F, K, xhi, xlo, nullptr, (size_t)0, 0, 1, c.act_hi, c.act_lo);
+        return hipGetLastError();
+    }
     const int MY = MT == 4 ? 1 : (MT + 7) / 8;
     const dim3 wgrid((unsigned)(F / 64) * MY);
     if (MT == 4) hipLaunchKernelGGL((k_chunk_gemm_wide<4, 1, true>), wgrid, dim3(256), GEMM_WIDE_LDS_BYTES, s, (const bf16_t*)W, 2 * F, K, xhi, xlo, nullptr, (size_t)0, 0, 1, MT, c.act_hi, c.act_lo);
