@@ -181,7 +181,8 @@ int asynclm_synchronize(asynclm_ctx *ctx);
  *   "graph"        (per-operation kernels only) 1 = replay decoding steps as a captured HIP graph,
  *                  0 = launch kernels one by one
  *   "attn_split"   0 = choose the number of sequence splits of decode attention from the length,
- *                  n > 0 = always use n
+ *                  1..128 = always use n (at most 64 apply to the single-row attention kernel, at most 128,
+ *                  rounded up to a multiple of 4, to its matrix-core variant)
  *   "attn_mfma_min" context length from which a decoding step runs its attention on the matrix cores (the
  *                  append path's attention kernel with a one-row group; models with the append path only);
  *                  0 = never.  Default 4096. */

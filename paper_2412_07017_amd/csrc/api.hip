@@ -18,7 +18,7 @@ using namespace asynclm;
 struct PassBuilder {
     ChunkTable t{};
     int G = 1, max_keys = 0;
-    void clear() { t.rows = t.ngroups = t.ntasks = t.nhead = 0; max_keys = 0; }
+    void clear() { t.rows = t.ngroups = t.ntasks = t.nhead = t.nblocks = 0; max_keys = 0; }
     int tiles_of(int n) const { return (G * n + 31) / 32; }
     bool fits(int n) const { return t.rows + n <= CHUNK_MAX && t.ntasks + tiles_of(n) <= CHUNK_MAX_TASKS; }
     // Appends a group of n rows to sequence `seq` (length before: pos0).  forced: see ChunkGroup; `rest` holds the
@@ -35,6 +35,7 @@ struct PassBuilder {
         Gp = ChunkGroup{};
         Gp.seq = seq; Gp.row0 = row0; Gp.n = n; Gp.pos0 = pos0; Gp.forced = forced; Gp.head = want_head ? t.nhead++ : -1;
         for (int tile = 0; tile < tiles_of(n); ++tile) {
+            if (tile % 4 == 0) t.block[t.nblocks++] = ChunkTaskBlock{t.ntasks, std::min(4, tiles_of(n) - tile)};
             ChunkTask& T = t.task[t.ntasks++];
             T = ChunkTask{};
             T.seq = seq; T.row0 = row0; T.n = n; T.pos0 = pos0; T.tile = tile;
@@ -145,7 +146,7 @@ SplitPlan pick_nsplit(const asynclm_ctx* c, int len_after) {
         // long contexts: the chunk attention (matrix cores) with about two 32-key tiles per wave
         const int tiles = (len_after + 31) / 32;
         int n = ((tiles + 1) / 2 + 3) / 4 * 4;
-        n = std::max(4, std::min(n, CHUNK_ATTN_MAX_SPLIT));
+        n = std::max(4, std::min(n, 64));          // more splits measure slower: the merge grows, the waves get no shorter
         if (c->opt_attn_split > 0) n = std::max(4, std::min((c->opt_attn_split + 3) / 4 * 4, CHUNK_ATTN_MAX_SPLIT));
         return {n, false, true};
     }
@@ -185,7 +186,8 @@ hipError_t forward_single(asynclm_ctx* c, int seq, bool with_head, SplitPlan sp)
 
 // The same pass, replayed from a captured graph (one graph per split count / head flag / sequence).
 hipError_t forward_single_graph(asynclm_ctx* c, int seq, bool with_head, SplitPlan sp) {
-    const int key = (((((seq * (ATTN_MAX_SPLIT + 1) + sp.nsplit) << 1) | (sp.merge_in_oproj ? 1 : 0)) << 1 | (sp.mfma ? 1 : 0)) << 1) | (with_head ? 1 : 0);
+    constexpr int SPLIT_SLOTS = (ATTN_MAX_SPLIT > CHUNK_ATTN_MAX_SPLIT ? ATTN_MAX_SPLIT : CHUNK_ATTN_MAX_SPLIT) + 1;
+    const int key = (((((seq * SPLIT_SLOTS + sp.nsplit) << 1) | (sp.merge_in_oproj ? 1 : 0)) << 1 | (sp.mfma ? 1 : 0)) << 1) | (with_head ? 1 : 0);
     auto it = c->graphs.find(key);
     if (it == c->graphs.end()) {
         hipError_t e;
@@ -339,6 +341,16 @@ hipError_t forward_chunk(asynclm_ctx* c, const PassBuilder& pb) {
     const ChunkSplits sp = chunk_splits(c, MT);
     const int nqkv = (g.Hq + 2 * g.Hkv) * g.dh, qd = g.Hq * g.dh;
     const int asplit = pick_chunk_attn_split(c, pb.max_keys, t.ntasks);
+    // passes made of large groups (at least 16 tasks, three or more per block on average) share keys and values
+    // between the tasks of a block; their key splits: about two workgroups per compute unit, at least four tiles each
+    const bool wide_attn = t.ntasks >= 16 && t.ntasks >= 3 * t.nblocks;
+    int wsplit = 1;
+    if (wide_attn) {
+        const long long wgs = (long long)t.nblocks * g.Hkv;
+        wsplit = (int)std::max(1LL, std::min<long long>((2LL * c->n_cu + wgs - 1) / wgs, ((pb.max_keys + 31) / 32 + 3) / 4));
+        wsplit = std::min(wsplit, CHUNK_ATTN_MAX_SPLIT);
+        while (wsplit > 1 && (long long)t.ntasks * g.Hkv * wsplit > CHUNK_ATTN_MAX_UNITS) --wsplit;
+    }
     const int dt = c->cfg.dtype;
     hipError_t e;
     // pageable source: the runtime stages the table before the call returns
@@ -350,7 +362,8 @@ hipError_t forward_chunk(asynclm_ctx* c, const PassBuilder& pb) {
         if ((e = run(c, KC_CHUNK_PREP, [&] { return launch_chunk_resid_norm(cb, l > 0, sp.down, MT, c->attn_norm[l], rows, g, s); }))) return e;
         if ((e = run(c, KC_CHUNK_GEMM, [&] { return launch_chunk_gemm(c->wqkv[l], nqkv, g.d, cb.nrm_hi, cb.nrm_lo, cb, sp.qkv, MT, s); }))) return e;
         if ((e = run(c, KC_CHUNK_PREP, [&] { return launch_chunk_rope_kv(cb, sp.qkv, kvl, c->b, rows, MT, g, s); }))) return e;
-        if ((e = run(c, KC_CHUNK_ATTN, [&] { return launch_chunk_attn(cb, kvl, asplit, t.ntasks, g, s); }))) return e;
+        if (wide_attn) { if ((e = run(c, KC_CHUNK_ATTN, [&] { return launch_chunk_attn_wide(cb, kvl, wsplit, t.ntasks, t.nblocks, g, s); }))) return e; }
+        else if ((e = run(c, KC_CHUNK_ATTN, [&] { return launch_chunk_attn(cb, kvl, asplit, t.ntasks, g, s); }))) return e;
         if ((e = run(c, KC_CHUNK_GEMM, [&] { return launch_chunk_gemm(c->wo[l], g.d, qd, cb.att_hi, cb.att_lo, cb, sp.o, MT, s); }))) return e;
         if ((e = run(c, KC_CHUNK_PREP, [&] { return launch_chunk_resid_norm(cb, true, sp.o, MT, c->ffn_norm[l], rows, g, s); }))) return e;
         if (sp.gu == 1) {                 // no split-K: the SwiGLU is the product's epilogue
@@ -900,7 +913,7 @@ int asynclm_set_option(asynclm_ctx* c, const char* name, int32_t value) {
     if (!std::strcmp(name, "fused")) { c->opt_fused = (value && c->fused.supported) ? 1 : 0; return ASYNCLM_OK; }
     if (!std::strcmp(name, "graph")) { c->opt_graph = (value && c->stream) ? 1 : 0; return ASYNCLM_OK; }
     if (!std::strcmp(name, "attn_mfma_min")) { if (value < 0) return ASYNCLM_E_INVAL; c->opt_attn_mfma_min = value; return ASYNCLM_OK; }
-    if (!std::strcmp(name, "attn_split")) { if (value < 0 || value > ATTN_MAX_SPLIT) return ASYNCLM_E_INVAL; c->opt_attn_split = value; return ASYNCLM_OK; }
+    if (!std::strcmp(name, "attn_split")) { if (value < 0 || value > CHUNK_ATTN_MAX_SPLIT) return ASYNCLM_E_INVAL; c->opt_attn_split = value; return ASYNCLM_OK; }
     return ASYNCLM_E_INVAL;
 }
 

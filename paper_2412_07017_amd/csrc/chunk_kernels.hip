@@ -736,14 +736,34 @@ __device__ __forceinline__ void attn_stage_k(const uint4 (&kh)[8], const uint4 (
     }
 }
 
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+
+// two fp32 -> two bf16 (round to nearest even) in one 32-bit word, first value in the low half (v_cvt_pk_bf16_f32)
+__device__ __forceinline__ uint32_t pack_bf16x2(float x, float y) {
+    const f32x2 v = {x, y};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+}
+
+// hi = bf16(p), lo = bf16(p - hi) for a pair of values
+__device__ __forceinline__ void split_pair(float x, float y, uint32_t& hi, uint32_t& lo) {
+    hi = pack_bf16x2(x, y);
+    lo = pack_bf16x2(x - __uint_as_float(hi << 16), y - __uint_as_float(hi & 0xffff0000u));
+}
+
+// The per-tile arithmetic outside the matrix cores is what bounds this kernel (a wave is alone on its SIMD and every
+// vector instruction takes four cycles), so it is kept short: packed conversions, exp through the hardware exp2,
+// and the two steps that most tiles do not need (causal mask away from the diagonal, rescaling of the output when
+// no column's maximum moved) are skipped on a wave-uniform test.
 __device__ __forceinline__ void attn_tile(AttnState& st, const uint4 (&vh)[8], const uint4 (&vl)[8], const uint4 (&qh)[8],
                                           const uint4 (&ql)[8], const uint4* kt, int key0, int qpos, int lane) {
     const int i = lane & 31, gh = lane >> 5;
     const int krow = (i >> 3) * 4 + (i & 3) + 16 * ((i >> 2) & 1);   // key (within the tile) held in A row i
-    // three independent accumulators (hi.hi, lo.hi, hi.lo), K operands read from LDS two steps ahead
-    f32x16 s, s1, s2;
+    // hi.hi + lo.hi + hi.lo accumulate into one register set (back-to-back accumulation), K operands read from LDS
+    // two steps ahead
+    f32x16 s;
 #pragma unroll
-    for (int r = 0; r < 16; ++r) { s[r] = 0.f; s1[r] = 0.f; s2[r] = 0.f; }
+    for (int r = 0; r < 16; ++r) s[r] = 0.f;
     uint4 kq[3][2];
 #pragma unroll
     for (int j = 0; j < 2; ++j) { kq[j][0] = kt[attn_k_slot(krow, 2 * j + gh)]; kq[j][1] = kt[512 + attn_k_slot(krow, 2 * j + gh)]; }
@@ -755,56 +775,50 @@ __device__ __forceinline__ void attn_tile(AttnState& st, const uint4 (&vh)[8], c
         }
         __builtin_amdgcn_sched_barrier(0);
         s = mfma_bf16(kq[t % 3][0], qh[t], s);
-        s1 = mfma_bf16(kq[t % 3][1], qh[t], s1);
-        s2 = mfma_bf16(kq[t % 3][0], ql[t], s2);
+        s = mfma_bf16(kq[t % 3][1], qh[t], s);
+        s = mfma_bf16(kq[t % 3][0], ql[t], s);
         __builtin_amdgcn_sched_barrier(0);
     }
-#pragma unroll
-    for (int r = 0; r < 16; ++r) s[r] += s1[r] + s2[r];
     // register r of lane (j, g) is key key0 + 16 g + r for query column j
-    float mx = -INFINITY;
+    if (__builtin_amdgcn_ballot_w64(key0 + 31 > qpos) != 0) {        // the tile reaches past some column's position
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-        if (key0 + 16 * gh + r > qpos) s[r] = -INFINITY;
-        mx = fmaxf(mx, s[r]);
+        for (int r = 0; r < 16; ++r)
+            if (key0 + 16 * gh + r > qpos) s[r] = -INFINITY;
     }
+    float mx = s[0];
+#pragma unroll
+    for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s[r]);
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
     const float mnew = fmaxf(st.mrun, mx);
     const float msafe = mnew == -INFINITY ? 0.f : mnew;
-    const float corr = expf(st.mrun - msafe);
+    const float corr = __expf(st.mrun - msafe);
     float psum = 0.f;
-    uint4 ph[2], pl[2];
-    {
-        bf16_t hi[16], lw[16];
+    uint32_t ph[8], pl[8];
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const float p = expf(s[r] - msafe);
-            psum += p;
-            split_bf16(p, hi[r], lw[r]);
-        }
-#pragma unroll
-        for (int t = 0; t < 2; ++t) {
-            ph[t] = make_uint4(hi[8 * t] | ((uint32_t)hi[8 * t + 1] << 16), hi[8 * t + 2] | ((uint32_t)hi[8 * t + 3] << 16),
-                               hi[8 * t + 4] | ((uint32_t)hi[8 * t + 5] << 16), hi[8 * t + 6] | ((uint32_t)hi[8 * t + 7] << 16));
-            pl[t] = make_uint4(lw[8 * t] | ((uint32_t)lw[8 * t + 1] << 16), lw[8 * t + 2] | ((uint32_t)lw[8 * t + 3] << 16),
-                               lw[8 * t + 4] | ((uint32_t)lw[8 * t + 5] << 16), lw[8 * t + 6] | ((uint32_t)lw[8 * t + 7] << 16));
-        }
+    for (int r = 0; r < 16; r += 2) {
+        const float p0 = __expf(s[r] - msafe), p1 = __expf(s[r + 1] - msafe);
+        psum += p0 + p1;
+        split_pair(p0, p1, ph[r >> 1], pl[r >> 1]);
     }
     st.lrun = st.lrun * corr + psum;
+    if (__builtin_amdgcn_ballot_w64(mnew != st.mrun) != 0) {          // some column's running maximum moved
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) st.o[dt][r] *= corr;
+    }
     st.mrun = mnew;
-#pragma unroll
-    for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) st.o[dt][r] *= corr;
     // consecutive products go to different accumulators
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
+        const uint4 pht = make_uint4(ph[4 * t], ph[4 * t + 1], ph[4 * t + 2], ph[4 * t + 3]);
+        const uint4 plt = make_uint4(pl[4 * t], pl[4 * t + 1], pl[4 * t + 2], pl[4 * t + 3]);
 #pragma unroll
-        for (int dt = 0; dt < 4; ++dt) st.o[dt] = mfma_bf16(vh[dt * 2 + t], ph[t], st.o[dt]);
+        for (int dt = 0; dt < 4; ++dt) st.o[dt] = mfma_bf16(vh[dt * 2 + t], pht, st.o[dt]);
 #pragma unroll
-        for (int dt = 0; dt < 4; ++dt) st.o[dt] = mfma_bf16(vl[dt * 2 + t], ph[t], st.o[dt]);
+        for (int dt = 0; dt < 4; ++dt) st.o[dt] = mfma_bf16(vl[dt * 2 + t], pht, st.o[dt]);
 #pragma unroll
-        for (int dt = 0; dt < 4; ++dt) st.o[dt] = mfma_bf16(vh[dt * 2 + t], pl[t], st.o[dt]);
+        for (int dt = 0; dt < 4; ++dt) st.o[dt] = mfma_bf16(vh[dt * 2 + t], plt, st.o[dt]);
     }
 }
 
@@ -885,6 +899,118 @@ __global__ __launch_bounds__(256) void k_chunk_attn(ChunkAttnArgs a, Geom g) {
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// the same attention for large groups (prefill, long interrupts): keys and values shared by four tasks
+// ---------------------------------------------------------------------------------------------
+// Workgroup = (block of up to four consecutive tasks of one group, kv head, key split); wave w works on task w of
+// the block (128 query columns per workgroup).  The K and V^T tiles of 32 keys (both planes, 32 KiB) are loaded once
+// per workgroup, 8 x 16 bytes per thread, into a double-buffered LDS tile while the previous tile is multiplied:
+// K in the swizzled row layout of attn_stage_k, V^T verbatim (it is stored in operand order), and all four waves
+// read their operands from there.  Against one wave per task this divides the traffic from L2 by four, which is
+// what bounds a 512-row pass over a long context.  Partial results go to the same units as k_chunk_attn writes, so
+// k_chunk_attn_combine serves both.
+
+struct WideTileRegs { uint4 k[4], v[4]; };   // this thread's share of a tile: K hi, hi, lo, lo; V^T hi, hi, lo, lo
+
+__device__ __forceinline__ void attn_wide_load(WideTileRegs& r, const bf16_t* Kp, const bf16_t* Vt, size_t lo, int tile, int tid) {
+    // K: chunk c = tid + 256 h is row c / 16, 16-byte piece c % 16 of the tile; V^T: chunk c of the tile's contiguous 8 KiB
+    const bf16_t* kp = Kp + (size_t)tile * 32 * 128 + (size_t)tid * 8;
+    const bf16_t* vp = Vt + ((size_t)tile * 512 + tid) * 8;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        r.k[h] = load16(kp + h * 2048); r.k[2 + h] = load16(kp + lo + h * 2048);
+        r.v[h] = load16(vp + h * 2048); r.v[2 + h] = load16(vp + lo + h * 2048);
+    }
+}
+
+// buffer layout (16-byte chunks): K hi [0, 512), K lo [512, 1024), V^T hi [1024, 1536), V^T lo [1536, 2048)
+__device__ __forceinline__ void attn_wide_store(const WideTileRegs& r, uint4* buf, int tid) {
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const int row = (tid >> 4) + 16 * h, c = tid & 15;
+        buf[attn_k_slot(row, c)] = r.k[h];
+        buf[512 + attn_k_slot(row, c)] = r.k[2 + h];
+        buf[1024 + tid + 256 * h] = r.v[h];
+        buf[1536 + tid + 256 * h] = r.v[2 + h];
+    }
+}
+
+__global__ __launch_bounds__(256) void k_chunk_attn_wide(ChunkAttnArgs a, Geom g) {
+    constexpr int DH = 128;
+    extern __shared__ uint4 attn_lds[];                    // [2 buffers][2048 chunks]
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int i = lane & 31, gh = lane >> 5;
+    const int G = g.Hq / g.Hkv;
+    const int kvh = blockIdx.x % g.Hkv, split = blockIdx.y;
+    const ChunkTaskBlock B = a.tab->block[blockIdx.x / g.Hkv];
+    const bool live = wave < B.n;
+    const int task = B.task0 + min(wave, B.n - 1);
+    const ChunkTask T0 = a.tab->task[B.task0];
+    const ChunkTask T = a.tab->task[task];
+    // keys that matter to the block's columns (its tasks are consecutive tiles of one group), split evenly
+    const int Lk = T0.pos0 + min((32 * T0.tile) % T0.n + 32 * B.n, T0.n);
+    const int ntile = (Lk + 31) >> 5;
+    const int tps = (ntile + a.nsplit - 1) / a.nsplit;
+    const int t0 = split * tps, t1 = min(ntile, t0 + tps);
+    // and to this wave's own columns: later tiles are loaded for the other waves but not multiplied here
+    const int Lw = T.pos0 + min((32 * T.tile) % T.n + 32, T.n);
+
+    const size_t seq_off = (size_t)T.seq * g.kv_seq_stride + (size_t)kvh * g.kv_head_stride;
+    const bf16_t* Kp = a.kv_layer + seq_off;
+    const bf16_t* Vt = a.kv_layer + g.kv_vt_offset + seq_off;
+    const size_t lo = g.kv_lo_offset;
+    const int col = 32 * T.tile + i;
+    const int qpos = T.pos0 + col % T.n;
+
+    AttnState st;
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) st.o[dt][r] = 0.f;
+    st.mrun = -INFINITY; st.lrun = 0.f;
+
+    if (t0 < t1) {
+        uint4 qh[8], ql[8];
+        {
+            const size_t qo = ((size_t)kvh * a.q_cols + (size_t)G * T.row0 + col) * DH + gh * 8;
+#pragma unroll
+            for (int t = 0; t < 8; ++t) { qh[t] = load16(a.q_hi + qo + t * 16); ql[t] = load16(a.q_lo + qo + t * 16); }
+        }
+        WideTileRegs regs;
+        __builtin_amdgcn_sched_barrier(0);
+        attn_wide_load(regs, Kp, Vt, lo, t0, tid);
+        attn_wide_store(regs, attn_lds, tid);
+        __syncthreads();
+        for (int tile = t0; tile < t1; ++tile) {
+            uint4* buf = attn_lds + ((tile - t0) & 1) * 2048;
+            attn_wide_load(regs, Kp, Vt, lo, min(tile + 1, t1 - 1), tid);
+            __builtin_amdgcn_sched_barrier(0);
+            if (live && tile * 32 < Lw) {                   // uniform over the wave
+                uint4 vh[8], vl[8];
+#pragma unroll
+                for (int k = 0; k < 8; ++k) { vh[k] = buf[1024 + k * 64 + lane]; vl[k] = buf[1536 + k * 64 + lane]; }
+                attn_tile(st, vh, vl, qh, ql, buf, tile * 32, qpos, lane);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            attn_wide_store(regs, attn_lds + (((tile - t0) & 1) ^ 1) * 2048, tid);
+            __syncthreads();
+        }
+    }
+    st.lrun += __shfl_xor(st.lrun, 32, 64);
+    if (!live) return;
+
+    const size_t unit = ((size_t)task * g.Hkv + kvh) * a.nsplit + split;
+    float* po = a.part_o + unit * DH * 32;
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+        for (int r2 = 0; r2 < 16; ++r2) po[(size_t)(dt * 32 + 8 * (r2 >> 2) + 4 * gh + (r2 & 3)) * 32 + i] = st.o[dt][r2];
+    if (gh == 0) {
+        float* pm = a.part_ml + unit * 64;
+        pm[i] = st.mrun; pm[32 + i] = st.lrun;
+    }
+}
+
 // Merge the key splits of one (task, kv head) and emit the attention output as tiled hi/lo planes
 // (K = Hq*128), or as an fp32 vector for single-row decoding.  grid (tasks * Hkv, 4): workgroup y handles
 // channels 32 y .. 32 y + 31.
@@ -893,33 +1019,42 @@ __global__ __launch_bounds__(256) void k_chunk_attn_combine(const float* __restr
                                                             bf16_t* __restrict__ out_hi, bf16_t* __restrict__ out_lo,
                                                             float* __restrict__ out_f32) {
     constexpr int DH = 128;
-    __shared__ float f[CHUNK_ATTN_MAX_SPLIT][32];
+    __shared__ float f[CHUNK_ATTN_MAX_SPLIT][32];          // running maximum of every split, then its weight
+    __shared__ float red[8][32];
     const int tid = threadIdx.x;
     const int G = g.Hq / g.Hkv;
     const int kvh = blockIdx.x % g.Hkv;
     const ChunkTask T = tab->task[blockIdx.x / g.Hkv];
     const float* ml = part_ml + (size_t)blockIdx.x * nsplit * 64;
-    if (tid < 32) {
-        float ms[CHUNK_ATTN_MAX_SPLIT], ls[CHUNK_ATTN_MAX_SPLIT];
-#pragma unroll
-        for (int s = 0; s < CHUNK_ATTN_MAX_SPLIT; ++s) {
-            const int sc = min(s, nsplit - 1);
-            ms[s] = ml[sc * 64 + tid]; ls[s] = ml[sc * 64 + 32 + tid];
+    float inv;
+    {
+        // statistics per query column: thread (column c, slice q) covers splits q, q + 8, ...; partial results meet in LDS
+        const int c = tid & 31, q = tid >> 5;
+        float m = -INFINITY;
+        for (int sp = q; sp < nsplit; sp += 8) {
+            const float v = ml[sp * 64 + c];
+            f[sp][c] = v;
+            m = fmaxf(m, v);
         }
-        float M = -INFINITY, L = 0.f;
+        red[q][c] = m;
+        __syncthreads();
+        float M = red[0][c];
 #pragma unroll
-        for (int s = 0; s < CHUNK_ATTN_MAX_SPLIT; ++s) if (s < nsplit) M = fmaxf(M, ms[s]);
-#pragma unroll
-        for (int s = 0; s < CHUNK_ATTN_MAX_SPLIT; ++s) {
-            const float w = (s < nsplit && ms[s] > -INFINITY) ? expf(ms[s] - M) : 0.f;
-            L += ls[s] * w;
-            ms[s] = w;
+        for (int k = 1; k < 8; ++k) M = fmaxf(M, red[k][c]);
+        __syncthreads();
+        float lp = 0.f;
+        for (int sp = q; sp < nsplit; sp += 8) {
+            const float w = f[sp][c] > -INFINITY ? expf(f[sp][c] - M) : 0.f;
+            lp += ml[sp * 64 + 32 + c] * w;
+            f[sp][c] = w;
         }
-        const float inv = L > 0.f ? 1.f / L : 0.f;
+        red[q][c] = lp;
+        __syncthreads();
+        float L = 0.f;
 #pragma unroll
-        for (int s = 0; s < CHUNK_ATTN_MAX_SPLIT; ++s) f[s][tid] = ms[s] * inv;
+        for (int k = 0; k < 8; ++k) L += red[k][c];
+        inv = L > 0.f ? 1.f / L : 0.f;
     }
-    __syncthreads();
     const int j = tid & 31, dl = tid >> 5;                 // column, channel within a run of 8
     const float* po = part_o + (size_t)blockIdx.x * nsplit * DH * 32 + (size_t)(blockIdx.y * 32 + dl) * 32 + j;
     float v[4] = {0.f, 0.f, 0.f, 0.f};
@@ -945,6 +1080,7 @@ __global__ __launch_bounds__(256) void k_chunk_attn_combine(const float* __restr
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             const int ch = blockIdx.y * 32 + dl + 8 * u;
+            v[u] *= inv;
             if (out_f32) {                                  // single-row decoding: fp32 vector [Hq][dh] (m is 0)
                 out_f32[hq * DH + ch] = v[u];
             } else {
@@ -1054,6 +1190,7 @@ hipError_t chunk_init() {
     if ((e = hipFuncSetAttribute((const void*)k_chunk_gemm<2, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)gemm_lds_bytes(2)))) return e;
     if ((e = hipFuncSetAttribute((const void*)k_chunk_gemm<3, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)gemm_lds_bytes(3)))) return e;
     if ((e = hipFuncSetAttribute((const void*)k_chunk_attn, hipFuncAttributeMaxDynamicSharedMemorySize, ATTN_LDS_BYTES))) return e;
+    if ((e = hipFuncSetAttribute((const void*)k_chunk_attn_wide, hipFuncAttributeMaxDynamicSharedMemorySize, ATTN_LDS_BYTES))) return e;
     if ((e = hipFuncSetAttribute((const void*)k_chunk_gemm_wide<4, 1, false>, hipFuncAttributeMaxDynamicSharedMemorySize, GEMM_WIDE_LDS_BYTES))) return e;
     if ((e = hipFuncSetAttribute((const void*)k_chunk_gemm_wide<WIDE_NW, WIDE_MW, false>, hipFuncAttributeMaxDynamicSharedMemorySize, GEMM_WIDE_LDS_BYTES))) return e;
     if ((e = hipFuncSetAttribute((const void*)k_chunk_gemm_wide<4, 1, true>, hipFuncAttributeMaxDynamicSharedMemorySize, GEMM_WIDE_LDS_BYTES))) return e;
@@ -1120,6 +1257,23 @@ static hipError_t chunk_attn_launch(const ChunkBuffers& c, const void* kv_layer,
 
 hipError_t launch_chunk_attn(const ChunkBuffers& c, const void* kv_layer, int nsplit, int ntasks, const Geom& g, hipStream_t s) {
     return chunk_attn_launch(c, kv_layer, nsplit, ntasks, g, nullptr, s);
+}
+
+// The variant for passes made of large groups: one workgroup per block of up to four tasks, any number of key splits.
+hipError_t launch_chunk_attn_wide(const ChunkBuffers& c, const void* kv_layer, int nsplit, int ntasks, int nblocks, const Geom& g,
+                                  hipStream_t s) {
+    if (nsplit < 1 || nsplit > CHUNK_ATTN_MAX_SPLIT || ntasks < 1 || ntasks > CHUNK_MAX_TASKS || nblocks < 1 || nblocks > ntasks ||
+        (long long)ntasks * g.Hkv * nsplit > CHUNK_ATTN_MAX_UNITS)
+        return hipErrorInvalidValue;
+    ChunkAttnArgs a{};
+    a.q_hi = c.q_hi; a.q_lo = c.q_lo; a.kv_layer = (const bf16_t*)kv_layer; a.tab = c.tab;
+    a.part_o = c.attn_o; a.part_ml = c.attn_ml; a.nsplit = nsplit; a.q_cols = c.q_cols;
+    hipLaunchKernelGGL(k_chunk_attn_wide, dim3(nblocks * g.Hkv, nsplit), dim3(256), ATTN_LDS_BYTES, s, a, g);
+    hipError_t e = hipGetLastError();
+    if (e) return e;
+    hipLaunchKernelGGL(k_chunk_attn_combine, dim3(ntasks * g.Hkv, 4), dim3(256), 0, s, c.attn_o, c.attn_ml, nsplit, g, c.tab,
+                       c.att_hi, c.att_lo, (float*)nullptr);
+    return hipGetLastError();
 }
 
 hipError_t launch_decode_attn_mfma(const ChunkBuffers& c, const void* kv_layer, int nsplit, const DecodeBuffers& b, const Geom& g,

@@ -31,7 +31,7 @@ struct DecodeBuffers {
 
 constexpr int CHUNK_MAX = 512;         // rows per forward pass of the append-chunk path
 constexpr int CHUNK_MAX_TASKS = 128;   // attention tiles (32 query columns of one group) per pass
-constexpr int CHUNK_ATTN_MAX_SPLIT = 64;
+constexpr int CHUNK_ATTN_MAX_SPLIT = 128;
 constexpr int CHUNK_ATTN_MAX_UNITS = 4096;   // (task, kv head, key split) partial results per pass
 constexpr int CHUNK_GEMM_MAX_SPLIT = 8;
 
@@ -48,10 +48,13 @@ struct ChunkGroup {
 struct ChunkTask { int32_t seq, row0, n, pos0, tile, pad0, pad1, pad2; };         // query columns 32 tile .. 32 tile + 31 of a group
 // Every group has at least one task, so a pass holds at most CHUNK_MAX_TASKS groups.  The rows come last: a
 // pass uploads the table up to its last used row.
+struct ChunkTaskBlock { int32_t task0, n; };   // up to four consecutive tasks of one group (they share keys and values)
 struct ChunkTable {
     int32_t rows, ngroups, ntasks, nhead;
+    int32_t nblocks, pad0, pad1, pad2;
     ChunkGroup group[CHUNK_MAX_TASKS];
     ChunkTask task[CHUNK_MAX_TASKS];
+    ChunkTaskBlock block[CHUNK_MAX_TASKS];
     ChunkRow row[CHUNK_MAX];
 };
 
@@ -122,6 +125,8 @@ hipError_t launch_chunk_gemm(const void* W, int N, int K, const bf16_t* xhi, con
 hipError_t launch_chunk_gemm_swiglu(const void* W, int F, int K, const bf16_t* xhi, const bf16_t* xlo, const ChunkBuffers& c,
                                     int MT, hipStream_t s);
 hipError_t launch_chunk_attn(const ChunkBuffers& c, const void* kv_layer, int nsplit, int ntasks, const Geom& g, hipStream_t s);
+hipError_t launch_chunk_attn_wide(const ChunkBuffers& c, const void* kv_layer, int nsplit, int ntasks, int nblocks, const Geom& g,
+                                  hipStream_t s);
 // single-row decoding attention on the matrix cores (long contexts): b.q -> b.o through the chunk attention
 hipError_t launch_decode_attn_mfma(const ChunkBuffers& c, const void* kv_layer, int nsplit, const DecodeBuffers& b, const Geom& g,
                                    hipStream_t s);

@@ -151,7 +151,7 @@ def test_decode_attention_split_counts_agree_with_oracle(trunc4):
     want0 = dec.logits.copy()
     t1 = dec.decode_step()
     want1 = dec.logits.copy()
-    for nsplit in (1, 3, 8, 9, 24, 64, -4, -12, -64):
+    for nsplit in (1, 3, 8, 9, 24, 64, -4, -12, -64, -128):
         lm = pkg.AsyncLM(model, w_dev, max_positions=320, stream=torch.cuda.Stream())
         lm.set_option("chunk", 1)                 # the prompt goes through the decode kernels too
         if nsplit < 0:                            # the long-context variant: matrix-core attention for single rows
