@@ -216,15 +216,16 @@ def trap_map(args):
         lm.synchronize()
         nbytes = lm.kv_bytes(0)
         pinned = torch.empty(nbytes, dtype=torch.uint8).pin_memory()
-        best = {}
-        for rep in range(2):
+        best = {"context": L, "image_MB": nbytes / 1e6}
+        for rep in range(4):                    # the first round touches the pinned pages; the fastest of the rest is kept
             t0 = time.perf_counter(); lm.kv_swap_out(0, pinned.data_ptr(), nbytes); t1 = time.perf_counter()
             lm.reset(0)
             t2 = time.perf_counter(); lm.kv_swap_in(0, pinned.data_ptr(), nbytes); t3 = time.perf_counter()
             lm.reset(0)
             t4 = time.perf_counter(); lm.prefill(0, toks[:L]); lm.synchronize(); t5 = time.perf_counter()
-            best = {"context": L, "image_MB": nbytes / 1e6, "swap_out_ms": (t1 - t0) * 1e3, "swap_in_ms": (t3 - t2) * 1e3,
-                    "recompute_ms": (t5 - t4) * 1e3}
+            if rep:
+                for key, ms in (("swap_out_ms", (t1 - t0) * 1e3), ("swap_in_ms", (t3 - t2) * 1e3), ("recompute_ms", (t5 - t4) * 1e3)):
+                    best[key] = min(best.get(key, ms), ms)
         rows.append(best)
         del pinned
     lm.close()
