@@ -283,6 +283,9 @@ __global__ void k_chunk_rope_kv(const float* __restrict__ P, int S, size_t s_str
 // ---------------------------------------------------------------------------------------------
 // skinny GEMM on the matrix cores:  P[s][m][n] = sum_{k in slice s} X[m][k] W[n][k]
 // ---------------------------------------------------------------------------------------------
+// Which kernel takes a pass (launch_chunk_gemm): up to 32 rows this one (bound by the weight stream, a wave per 32
+// weight rows); 33-64 rows k_chunk_gemm_ks (the waves split the k-steps); 65-128 rows k_chunk_gemm_wide with a wave
+// per row tile; more rows k_chunk_gemm_wide with 256-row workgroups.  The template serves any MT <= 3; MT = 1 is used.
 // Workgroup = 4 waves on 128 weight rows (32 per wave) and one contiguous run of 128-element k-blocks
 // (the S workgroups of a row tile split K and write separate partial planes that the consumer adds in
 // a fixed order: no atomics, results are bit-reproducible).
@@ -679,6 +682,151 @@ __global__ __launch_bounds__(NW * 64) void k_chunk_gemm_wide(const bf16_t* __res
 #pragma unroll
             for (int b = 0; b < 4; ++b)
                 *(float4*)(prow + nt * 32 + 8 * b) = make_float4(acc[nt][j][4 * b], acc[nt][j][4 * b + 1], acc[nt][j][4 * b + 2], acc[nt][j][4 * b + 3]);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// GEMM for passes of 33-64 rows: the four waves of a workgroup split the k-steps
+// ---------------------------------------------------------------------------------------------
+// With two row tiles k_chunk_gemm is bound by LDS: a wave that owns 32 weight rows uses every activation
+// operand it reads for one product only.  Here every wave multiplies the whole tile of the workgroup, 128 weight
+// rows x all MT row tiles, but only for two of the eight 16-column steps of each k-block (wave w: steps 2w, 2w+1):
+// per step 4 weight operands (from the shared LDS tile, staged as in k_chunk_gemm_wide) and 2 MT activation
+// operands (straight from the operand-order planes, two blocks ahead) feed 8 MT products, and no operand
+// is read by two waves.  The four partial tiles are added through LDS at the end, in wave order.
+
+template <int MT, bool SWIGLU>
+__global__ __launch_bounds__(256) void k_chunk_gemm_ks(const bf16_t* __restrict__ W, int N, int K,
+                                                       const bf16_t* __restrict__ Xhi, const bf16_t* __restrict__ Xlo,
+                                                       float* __restrict__ P, size_t s_stride, int n_stride, int S,
+                                                       bf16_t* __restrict__ act_hi, bf16_t* __restrict__ act_lo) {
+    extern __shared__ uint4 gemm_lds[];             // [2 buffers][4 weight-row tiles][512]; reused by the final sum
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int ntile = blockIdx.x, sp = blockIdx.y;
+    const int nblk = K >> 7;
+    const int b0 = (int)((long long)nblk * sp / S), b1 = (int)((long long)nblk * (sp + 1) / S);
+    const int nb = b1 - b0, last = b1 - 1;
+    const int n0 = ntile * 128;
+
+    // weights: load q of a thread covers row 32 wave + 4 q + lane / 16 of the tile, 16-byte chunk lane % 16
+    const int wrow = SWIGLU ? (wave < 2 ? ntile * 64 + wave * 32 : (N >> 1) + ntile * 64 + (wave - 2) * 32) : n0 + wave * 32;
+    const bf16_t* wlane = W + (size_t)(wrow + (lane >> 4)) * K + (lane & 15) * 8;
+    const size_t wstep = (size_t)4 * K;
+    const int wr0 = lane >> 4, wc = lane & 15;
+    const bf16_t* xh[MT];
+    const bf16_t* xl[MT];
+#pragma unroll
+    for (int j = 0; j < MT; ++j) {
+        const size_t o = (size_t)j * nblk * 4096 + lane * 8;
+        xh[j] = Xhi + o; xl[j] = Xlo + o;
+    }
+
+    f32x16 acc[4][MT];
+#pragma unroll
+    for (int nt = 0; nt < 4; ++nt)
+#pragma unroll
+        for (int j = 0; j < MT; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[nt][j][r] = 0.f;
+
+    if (nb > 0) {
+        // A block is short (32 products per wave with two row tiles), so the weights of block b0 + i travel in register
+        // set i % 2, requested two blocks ahead of their use, and the activations (from L2) in a ring of three blocks.
+        // (Three row tiles do not fit the register file this way; they take k_chunk_gemm_wide with an idle wave.)
+        static_assert(MT == 2, "register budget");
+        constexpr int NSET = 2, RING = 3, UNROLL = 6;   // LDS buffer u % 2 and ring slot u % RING are static
+        uint4 wreg[NSET][8];
+        BUnit<MT> ring[RING];
+        auto w_load = [&](uint4 (&set)[8], int blk) { gemm_a_load(set, wlane, wstep, blk); };
+        auto w_store = [&](const uint4 (&set)[8], uint4* at) {
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                const int r = 4 * q + wr0;
+                at[wave * 512 + r * 16 + (wc ^ (r & 15))] = set[q];
+            }
+        };
+        // issue order = completion order: weights of the first block, activations of the first two, weights of the second
+        w_load(wreg[0], b0);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < RING - 1; ++i) wide_b_load<MT>(ring[i], xh, xl, min(b0 + i, last), wave);
+        __builtin_amdgcn_sched_barrier(0);
+        w_store(wreg[0], gemm_lds);
+        w_load(wreg[NSET - 1], min(b0 + 1, last));
+        __builtin_amdgcn_sched_barrier(0);
+        __syncthreads();
+        for (int t = 0; t < nb; t += UNROLL) {
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u) {
+                const int tt = b0 + t + u;                  // this block: LDS buffer u % 2, ring slot u % RING
+                if (tt > last) break;                       // uniform
+                const uint4* at = gemm_lds + (u & 1) * 2048;
+                uint4* other = gemm_lds + ((u & 1) ^ 1) * 2048;   // its readers passed the barrier that ended the previous block
+                wide_b_load<MT>(ring[(u + RING - 1) % RING], xh, xl, min(tt + RING - 1, last), wave);
+                __builtin_amdgcn_sched_barrier(0);
+                w_load(wreg[u & 1], min(tt + 2, last));     // this set's previous block was stored one block ago
+                __builtin_amdgcn_sched_barrier(0);
+                uint4 a0[4], a1[4];
+                wide_a_read(a0, at, 2 * wave, lane);
+                wide_a_read(a1, at, 2 * wave + 1, lane);
+                __builtin_amdgcn_sched_barrier(0);
+                wide_step<MT>(a0, ring[u % RING], 0, acc);
+                __builtin_amdgcn_sched_barrier(0);
+                wide_step<MT>(a1, ring[u % RING], 1, acc);
+                __builtin_amdgcn_sched_barrier(0);
+                w_store(wreg[(u + 1) & 1], other);          // the next block's weights, requested two blocks ago
+                __syncthreads();
+            }
+        }
+    }
+
+    // sum of the four waves' partial tiles, one row tile at a time: [wave][weight-row tile][register quad][lane] float4
+    float4* ex = reinterpret_cast<float4*>(gemm_lds);
+#pragma unroll
+    for (int j = 0; j < MT; ++j) {
+#pragma unroll
+        for (int nt = 0; nt < 4; ++nt)
+#pragma unroll
+            for (int b = 0; b < 4; ++b)
+                ex[((wave * 4 + nt) * 4 + b) * 64 + lane] = make_float4(acc[nt][j][4 * b], acc[nt][j][4 * b + 1], acc[nt][j][4 * b + 2], acc[nt][j][4 * b + 3]);
+        __syncthreads();
+        // lane (j, g) holds D[8b + 4g + r][j] in register 4b + r: four consecutive weight rows of token row j
+        const int m = j * 32 + (lane & 31);
+        if (SWIGLU) {
+            if (wave < 2) {                                 // wave w: gate tile w and up tile w + 2
+                const int F = N >> 1, f0 = ntile * 64 + wave * 32 + 4 * (lane >> 5);
+#pragma unroll
+                for (int b = 0; b < 4; ++b) {
+                    float4 gt = ex[((0 * 4 + wave) * 4 + b) * 64 + lane], up = ex[((0 * 4 + wave + 2) * 4 + b) * 64 + lane];
+#pragma unroll
+                    for (int w = 1; w < 4; ++w) {
+                        const float4 g2 = ex[((w * 4 + wave) * 4 + b) * 64 + lane], u2 = ex[((w * 4 + wave + 2) * 4 + b) * 64 + lane];
+                        gt.x += g2.x; gt.y += g2.y; gt.z += g2.z; gt.w += g2.w;
+                        up.x += u2.x; up.y += u2.y; up.z += u2.z; up.w += u2.w;
+                    }
+                    const float gv[4] = {gt.x, gt.y, gt.z, gt.w}, uv[4] = {up.x, up.y, up.z, up.w};
+                    bf16_t hi[4], lo[4];
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) split_bf16(gv[r] / (1.f + expf(-gv[r])) * uv[r], hi[r], lo[r]);
+                    const size_t o = tiled_off(m, f0 + 8 * b, F);       // four columns inside one 8-element group
+                    *reinterpret_cast<uint2*>(act_hi + o) = make_uint2(hi[0] | ((uint32_t)hi[1] << 16), hi[2] | ((uint32_t)hi[3] << 16));
+                    *reinterpret_cast<uint2*>(act_lo + o) = make_uint2(lo[0] | ((uint32_t)lo[1] << 16), lo[2] | ((uint32_t)lo[3] << 16));
+                }
+            }
+        } else {                                            // wave w: weight-row tile w
+            float* prow = P + sp * s_stride + (size_t)m * n_stride + n0 + wave * 32 + 4 * (lane >> 5);
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                float4 v = ex[((0 * 4 + wave) * 4 + b) * 64 + lane];
+#pragma unroll
+                for (int w = 1; w < 4; ++w) {
+                    const float4 v2 = ex[((w * 4 + wave) * 4 + b) * 64 + lane];
+                    v.x += v2.x; v.y += v2.y; v.z += v2.z; v.w += v2.w;
+                }
+                *(float4*)(prow + 8 * b) = v;
+            }
+        }
+        __syncthreads();
     }
 }
 
@@ -1184,13 +1332,11 @@ constexpr int WIDE_NW = 4, WIDE_MW = 2;
 hipError_t chunk_init() {
     hipError_t e;
     if ((e = hipFuncSetAttribute((const void*)k_chunk_gemm<1, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)gemm_lds_bytes(1)))) return e;
-    if ((e = hipFuncSetAttribute((const void*)k_chunk_gemm<2, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)gemm_lds_bytes(2)))) return e;
-    if ((e = hipFuncSetAttribute((const void*)k_chunk_gemm<3, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)gemm_lds_bytes(3)))) return e;
     if ((e = hipFuncSetAttribute((const void*)k_chunk_gemm<1, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)gemm_lds_bytes(1)))) return e;
-    if ((e = hipFuncSetAttribute((const void*)k_chunk_gemm<2, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)gemm_lds_bytes(2)))) return e;
-    if ((e = hipFuncSetAttribute((const void*)k_chunk_gemm<3, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)gemm_lds_bytes(3)))) return e;
     if ((e = hipFuncSetAttribute((const void*)k_chunk_attn, hipFuncAttributeMaxDynamicSharedMemorySize, ATTN_LDS_BYTES))) return e;
     if ((e = hipFuncSetAttribute((const void*)k_chunk_attn_wide, hipFuncAttributeMaxDynamicSharedMemorySize, ATTN_LDS_BYTES))) return e;
+    if ((e = hipFuncSetAttribute((const void*)k_chunk_gemm_ks<2, false>, hipFuncAttributeMaxDynamicSharedMemorySize, GEMM_WIDE_LDS_BYTES))) return e;
+    if ((e = hipFuncSetAttribute((const void*)k_chunk_gemm_ks<2, true>, hipFuncAttributeMaxDynamicSharedMemorySize, GEMM_WIDE_LDS_BYTES))) return e;
     if ((e = hipFuncSetAttribute((const void*)k_chunk_gemm_wide<4, 1, false>, hipFuncAttributeMaxDynamicSharedMemorySize, GEMM_WIDE_LDS_BYTES))) return e;
     if ((e = hipFuncSetAttribute((const void*)k_chunk_gemm_wide<WIDE_NW, WIDE_MW, false>, hipFuncAttributeMaxDynamicSharedMemorySize, GEMM_WIDE_LDS_BYTES))) return e;
     if ((e = hipFuncSetAttribute((const void*)k_chunk_gemm_wide<4, 1, true>, hipFuncAttributeMaxDynamicSharedMemorySize, GEMM_WIDE_LDS_BYTES))) return e;
@@ -1204,18 +1350,18 @@ hipError_t launch_chunk_gemm(const void* W, int N, int K, const bf16_t* xhi, con
     const size_t ps = (size_t)MT * 32 * N, lds = gemm_lds_bytes(MT);
     if (S < 1 || S > CHUNK_GEMM_MAX_SPLIT || S > K / 128 || N % 128 || K % 128 || ps * S > c.part_capacity) return hipErrorInvalidValue;
     if (MT < 1 || MT > CHUNK_MAX / 32) return hipErrorInvalidValue;
-    if (MT > 3) {
-        // 128 rows per workgroup for exactly four row tiles, 256 beyond
-        const int MY = MT == 4 ? 1 : (MT + 7) / 8;
+    // one row tile: weight-streaming kernel, a wave per 32 weight rows; two: the waves split the k-steps; three or four:
+    // a wave per row tile (128-row workgroups); more: 256-row workgroups
+    if (MT == 1) {
+        hipLaunchKernelGGL((k_chunk_gemm<1, false>), grid, block, lds, s, (const bf16_t*)W, N, K, xhi, xlo, c.part, ps, N, S, nullptr, nullptr);
+    } else if (MT == 2) {
+        hipLaunchKernelGGL((k_chunk_gemm_ks<2, false>), grid, block, GEMM_WIDE_LDS_BYTES, s, (const bf16_t*)W, N, K, xhi, xlo, c.part, ps, N, S, nullptr, nullptr);
+    } else {
+        const int MY = MT <= 4 ? 1 : (MT + 7) / 8;
         const dim3 wgrid((unsigned)(N / 128) * MY * S);
-        if (MT == 4) hipLaunchKernelGGL((k_chunk_gemm_wide<4, 1, false>), wgrid, block, GEMM_WIDE_LDS_BYTES, s, (const bf16_t*)W, N, K, xhi, xlo, c.part, ps, N, S, MT, nullptr, nullptr);
+        if (MT <= 4) hipLaunchKernelGGL((k_chunk_gemm_wide<4, 1, false>), wgrid, block, GEMM_WIDE_LDS_BYTES, s, (const bf16_t*)W, N, K, xhi, xlo, c.part, ps, N, S, MT, nullptr, nullptr);
         else hipLaunchKernelGGL((k_chunk_gemm_wide<WIDE_NW, WIDE_MW, false>), wgrid, dim3(WIDE_NW * 64), GEMM_WIDE_LDS_BYTES, s, (const bf16_t*)W, N, K, xhi, xlo, c.part, ps, N, S, MT, nullptr, nullptr);
-        return hipGetLastError();
     }
-    if (MT == 1) hipLaunchKernelGGL((k_chunk_gemm<1, false>), grid, block, lds, s, (const bf16_t*)W, N, K, xhi, xlo, c.part, ps, N, S, nullptr, nullptr);
-    else if (MT == 2) hipLaunchKernelGGL((k_chunk_gemm<2, false>), grid, block, lds, s, (const bf16_t*)W, N, K, xhi, xlo, c.part, ps, N, S, nullptr, nullptr);
-    else if (MT == 3) hipLaunchKernelGGL((k_chunk_gemm<3, false>), grid, block, lds, s, (const bf16_t*)W, N, K, xhi, xlo, c.part, ps, N, S, nullptr, nullptr);
-    else return hipErrorInvalidValue;
     return hipGetLastError();
 }
 
@@ -1224,18 +1370,17 @@ hipError_t launch_chunk_gemm(const void* W, int N, int K, const bf16_t* xhi, con
 hipError_t launch_chunk_gemm_swiglu(const void* W, int F, int K, const bf16_t* xhi, const bf16_t* xlo, const ChunkBuffers& c,
                                     int MT, hipStream_t s) {
     if (MT < 1 || MT > CHUNK_MAX / 32 || F % 64 || K % 128) return hipErrorInvalidValue;
-    if (MT <= 3) {
-        const dim3 grid(F / 64, 1), block(256);
-        const size_t lds = gemm_lds_bytes(MT);
-        if (MT == 1) hipLaunchKernelGGL((k_chunk_gemm<1, true>), grid, block, lds, s, (const bf16_t*)W, 2 * F, K, xhi, xlo, nullptr, (size_t)0, 0, 1, c.act_hi, c.act_lo);
-        else if (MT == 2) hipLaunchKernelGGL((k_chunk_gemm<2, true>), grid, block, lds, s, (const bf16_t*)W, 2 * F, K, xhi, xlo, nullptr, (size_t)0, 0, 1, c.act_hi, c.act_lo);
-        else hipLaunchKernelGGL((k_chunk_gemm<3, true>), grid, block, lds, s, (const bf16_t*)W, 2 * F, K, xhi, xlo, nullptr, (size_t)0, 0, 1, c.act_hi, c.act_lo);
-        return hipGetLastError();
+    const bf16_t* Wb = (const bf16_t*)W;
+    if (MT == 1) {
+        hipLaunchKernelGGL((k_chunk_gemm<1, true>), dim3(F / 64, 1), dim3(256), gemm_lds_bytes(1), s, Wb, 2 * F, K, xhi, xlo, nullptr, (size_t)0, 0, 1, c.act_hi, c.act_lo);
+    } else if (MT == 2) {
+        hipLaunchKernelGGL((k_chunk_gemm_ks<2, true>), dim3(F / 64, 1), dim3(256), GEMM_WIDE_LDS_BYTES, s, Wb, 2 * F, K, xhi, xlo, nullptr, (size_t)0, 0, 1, c.act_hi, c.act_lo);
+    } else {
+        const int MY = MT <= 4 ? 1 : (MT + 7) / 8;
+        const dim3 wgrid((unsigned)(F / 64) * MY);
+        if (MT <= 4) hipLaunchKernelGGL((k_chunk_gemm_wide<4, 1, true>), wgrid, dim3(256), GEMM_WIDE_LDS_BYTES, s, Wb, 2 * F, K, xhi, xlo, nullptr, (size_t)0, 0, 1, MT, c.act_hi, c.act_lo);
+        else hipLaunchKernelGGL((k_chunk_gemm_wide<WIDE_NW, WIDE_MW, true>), wgrid, dim3(WIDE_NW * 64), GEMM_WIDE_LDS_BYTES, s, Wb, 2 * F, K, xhi, xlo, nullptr, (size_t)0, 0, 1, MT, c.act_hi, c.act_lo);
     }
-    const int MY = MT == 4 ? 1 : (MT + 7) / 8;
-    const dim3 wgrid((unsigned)(F / 64) * MY);
-    if (MT == 4) hipLaunchKernelGGL((k_chunk_gemm_wide<4, 1, true>), wgrid, dim3(256), GEMM_WIDE_LDS_BYTES, s, (const bf16_t*)W, 2 * F, K, xhi, xlo, nullptr, (size_t)0, 0, 1, MT, c.act_hi, c.act_lo);
-    else hipLaunchKernelGGL((k_chunk_gemm_wide<WIDE_NW, WIDE_MW, true>), wgrid, dim3(WIDE_NW * 64), GEMM_WIDE_LDS_BYTES, s, (const bf16_t*)W, 2 * F, K, xhi, xlo, nullptr, (size_t)0, 0, 1, MT, c.act_hi, c.act_lo);
     return hipGetLastError();
 }
 
