@@ -9,6 +9,9 @@ top-2 ids and values.  Checked here, through the C ABI, in the configuration ben
     the oracle's stream);
   * sampled logits within the bf16 tolerance 2e-2, and the sampled top-2 values;
   * sequence lengths.
+The last test runs the 8B preset at full depth and full size (the configuration bench.py times) and checks the
+method's invariants, which hold at any size: in-flight inject == stateless re-prefill == token-by-token append,
+merged pass == token then inject, K/V swap round trip bit-exact.
 """
 import os
 
@@ -138,3 +141,72 @@ def test_8b_ragged16_batched_steps_match_frozen_oracle():
     lm.close()
     print("%s / %d layers: max sampled |logit err| = %.3e over %d batched steps (%.1f rows per step), %d greedy ids identical"
           % (name, model.n_layers, worst, n_steps, rows / n_steps, gated))
+
+
+@pytest.mark.timeout(900)
+def test_8b_full_depth_full_size_invariants_of_the_method():
+    """The 8B preset as bench.py runs it (32 layers, 1024-token prompt, greedy decoding steps, a 24-token interrupt
+    injected in flight), checked through properties that hold at any size, because no oracle run fits a test here:
+      * Sec. 3.2 / 5.5: the live context after the in-flight inject and a stateless re-prefill of the same token
+        stream give the same next-token logits (two different kernel paths: single-row decode kernels + 24-row
+        pass against 512-row prefill passes);
+      * the same stream appended token by token through the decode kernels alone agrees as well;
+      * Sec. 5.4: swapping the K/V cache out and in again reproduces the logits bit for bit, and decoding goes on
+        identically from the restored sequence;
+      * the merged form of Sec. 5.3 (chosen token + interrupt in one pass) equals token-then-inject.
+    """
+    import paper_2412_07017_amd as pkg
+    wl = ai.preset("8b")
+    model = wl.model
+    w_dev = ai.make_weights(model, device=torch.device("cuda:0"))
+    torch.cuda.synchronize()
+    spec = ai.build_workload("8b")
+    prompt = [int(t) for t in spec["prompt"]]
+    intr = [int(t) for t in spec["events"][0][1]]
+    assert len(prompt) == 1024 and len(intr) == 24
+    lm = pkg.AsyncLM(model, w_dev, max_positions=1280, max_seqs=3, stream=torch.cuda.Stream())
+    lm.prefill(0, prompt)
+    history = list(prompt)
+    for _ in range(64):
+        history.append(lm.decode_step(0))
+    # merged form on a copy of the sequence (slot 2): chosen token + interrupt in one pass
+    lm.prefill(2, history)
+    tok_merged = lm.step_batch([2], None, [intr])[0]
+    tok = lm.decode_step(0)
+    assert tok == tok_merged
+    history.append(tok)
+    lm.inject_interrupt(0, intr)
+    history += intr
+    live = lm.logits(0)
+    assert np.isfinite(live).all() and lm.seq_len(0) == len(history) == 1024 + 65 + 24
+    merged = lm.logits(2)
+    top2 = np.sort(live)[-2:]
+    margin = float(top2[1] - top2[0])
+
+    def agree(other, what):
+        err = float(np.abs(other - live).max())
+        print("%s vs live context: max |logit diff| = %.3e (top-2 margin %.3e)" % (what, err, margin))
+        assert err <= TOL, (what, err)
+        if margin > MARGIN:
+            assert int(np.argmax(other)) == int(np.argmax(live)), what
+
+    agree(merged, "merged token + interrupt pass")
+    lm.reset(2)
+    lm.prefill(1, history)                                  # stateless variant: the whole stream again
+    agree(lm.logits(1), "re-prefill in 512-row passes")
+    lm.reset(1)
+    lm.set_option("chunk", 1)                               # the whole stream through the single-row kernels
+    lm.prefill(1, history)
+    agree(lm.logits(1), "token-by-token append")
+    lm.set_option("chunk", 512)
+    lm.reset(1)
+    # trap: swap out, drop, swap in on another slot
+    nbytes = lm.kv_bytes(0)
+    image = torch.empty(nbytes, dtype=torch.uint8).pin_memory()
+    lm.kv_swap_out(0, image.data_ptr(), nbytes)
+    lm.kv_swap_in(1, image.data_ptr(), nbytes)
+    assert np.array_equal(lm.logits(1), live) and lm.seq_len(1) == lm.seq_len(0)
+    a = [lm.decode_step(0) for _ in range(4)]
+    b = [lm.decode_step(1) for _ in range(4)]
+    assert a == b and np.array_equal(lm.logits(0), lm.logits(1))
+    lm.close()
