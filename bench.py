@@ -11,7 +11,10 @@ Prints ONE JSON line:
   value          generated tokens per second over the timed steps, injections included
   decode_*       decode-only rate and its fraction of the HBM roofline (algorithmic bytes / time / 8 TB/s);
                  10th / 50th / 90th percentile of the single steps (an event after every step)
-  inject_*       microseconds per interrupt (mean; min / median / max) and its cost in decoding steps
+  inject_*       microseconds per interrupt (mean; min / median / max), its cost in decoding steps and its fraction
+                 of the HBM roofline (one pass over the same weights and cache)
+  prefill_*      seconds for the prompt and the fraction of the bf16 matrix-core peak that 2 flop per weight and
+                 token amount to
   reprefill_*, kv_swap_*, merged_*   the stateless re-prefill of the same context (Sec. 5.5), the K/V swap of a
                  trapped session (Sec. 5.4) and the interrupt riding with the next token (Sec. 5.3)
   streaming_read_ceiling   what the longest plain stream of the step (the output head) reaches on this device
@@ -411,11 +414,16 @@ def main():
         "decode_ms_per_token_p10_p50_p90": [float(np.percentile(per_step_ms, q)) for q in (10, 50, 90)],
         "inject_us_min_median_max": [float(np.min(inj_ms)) * 1e3, float(np.median(inj_ms)) * 1e3, float(np.max(inj_ms)) * 1e3],
         "inject_us": ms_inject * 1e3, "inject_tokens": k_intr, "inject_in_decode_steps": ms_inject / ms_dec_step,
+        # one pass over the same weights and cache: the inject's fraction of the HBM roofline
+        "inject_hbm_frac": (bytes_step + (k_intr - 1) * model.kv_bytes_per_position()) / (ms_inject * 1e-3) / HBM_PEAK,
         "reprefill_us": reprefill_ms * 1e3, "reprefill_tokens": len(history), "reprefill_over_inject": reprefill_ms / ms_inject,
         "kv_swap_bytes": int(nbytes), "kv_swap_out_us": swap_out_ms * 1e3, "kv_swap_in_us": swap_in_ms * 1e3,
         "merged_step_us": float(np.mean(merged_ms)) * 1e3,
         "merged_inject_extra_in_decode_steps": float(np.mean(merged_ms)) / ms_dec_step - 1.0,
         "prefill_s": t_prefill, "weights_s": t_weights,
+        # prompt through the matrix cores: 2 flop per layer weight and prompt token (the second activation plane and
+        # the attention are not counted), over the bf16 matrix-core peak
+        "prefill_mfma_frac": 2.0 * model.n_layers * model.layer_weight_elems() * wl.prompt_len / t_prefill / 2.5e15,
         "roofline": roofline, "streaming_read_ceiling": ceiling, "kernel_classes": per_class,
     }
     if not args.no_cpu_baseline:
