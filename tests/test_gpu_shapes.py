@@ -1,0 +1,75 @@
+"""GPU parity of the matrix-core append path on small bf16 models with other head layouts than the presets:
+one, two and four query heads per kv head (the presets have four and eight), d_model 512, so that every kernel
+variant runs against the full-vocabulary oracle in seconds: 230-row prefill (wide product, both attention
+kernels depending on the number of query tiles), interrupts of 40 rows (k-split product), 70 rows (wide product,
+a wave per row tile), 5 rows (weight-streaming product), single-row steps, and a batched step over three
+sequences.  The N(0, 0.02) weights make small logits at this width, so the error is also checked relative to the
+largest logit."""
+import numpy as np
+import pytest
+import torch
+
+import asynclm_inputs as ai
+from asynclm_inputs.configs import ModelConfig
+from oracle import asynclm_oracle as orc
+
+pytestmark = pytest.mark.gpu
+
+TOL = 2e-2
+REL = 2e-4       # measured 9e-6: the hi/lo activation planes and the paired cache keep about 16 mantissa bits
+
+
+def _host_weights(w_dev):
+    conv = lambda t: t.detach().to("cpu").to(torch.float32).numpy()
+    return {k: ([conv(t) for t in v] if isinstance(v, list) else conv(v)) for k, v in w_dev.items()}
+
+
+@pytest.mark.parametrize("n_kv", [4, 2, 1])
+def test_append_path_on_other_head_layouts(n_kv):
+    import paper_2412_07017_amd as pkg
+    model = ModelConfig(n_layers=2, d_model=512, n_q_heads=4, n_kv_heads=n_kv, head_dim=128, ffn=1024, vocab=2048,
+                        rms_eps=1e-5, rope_theta=10000.0, dtype="bf16")
+    w_dev = ai.make_weights(model, device=torch.device("cuda:0"))
+    torch.cuda.synchronize()
+    w_cpu = _host_weights(w_dev)
+    sh = orc.Shape.of(model)
+    tk = lambda n, sub: [int(t) for t in ai.uniform_tokens(ai.MASTER_SEED, 921, n, model.vocab, sub=sub)]
+    worst_abs, worst_rel = 0.0, 0.0
+
+    def check(got, want, what):
+        nonlocal worst_abs, worst_rel
+        assert np.isfinite(got).all(), what
+        err = float(np.abs(got - want).max())
+        rel = err / float(np.abs(want).max())
+        worst_abs, worst_rel = max(worst_abs, err), max(worst_rel, rel)
+        assert err <= TOL and rel <= REL, (what, err, rel)
+
+    lm = pkg.AsyncLM(model, w_dev, max_positions=512, max_seqs=3, stream=torch.cuda.Stream())
+    dec = orc.CachedDecoder(sh, w_cpu, dtype=np.float32)
+    check_steps = [("prefill 230", lambda: lm.prefill(0, tk(230, 0)), lambda: dec.prefill(tk(230, 0))),
+                   ("inject 40", lambda: lm.inject_interrupt(0, tk(40, 1)), lambda: dec.inject(tk(40, 1))),
+                   ("inject 70", lambda: lm.inject_interrupt(0, tk(70, 2)), lambda: dec.inject(tk(70, 2))),
+                   ("inject 5", lambda: lm.inject_interrupt(0, tk(5, 3)), lambda: dec.inject(tk(5, 3)))]
+    for what, gpu, cpu in check_steps:
+        gpu(); cpu()
+        check(lm.logits(0), dec.logits, what)
+    for j in range(3):
+        tok = dec.decode_step()
+        assert lm.decode_step(0, forced_token=tok) == tok
+        check(lm.logits(0), dec.logits, "decode %d" % j)
+    # a batched step: sequence 0 with a 33-row interrupt, two fresh sequences, one of them with a single-token interrupt
+    decs = [dec, orc.CachedDecoder(sh, w_cpu, dtype=np.float32), orc.CachedDecoder(sh, w_cpu, dtype=np.float32)]
+    for s in (1, 2):
+        lm.prefill(s, tk(17 + 30 * s, 10 + s))
+        decs[s].prefill(tk(17 + 30 * s, 10 + s))
+    intr = [tk(33, 20), [], tk(1, 21)]
+    forced = [d.decode_step() for d in decs]
+    for d, t in zip(decs, intr):
+        if t:
+            d.inject(t)
+    assert list(lm.step_batch([0, 1, 2], forced, intr)) == forced
+    for s, d in enumerate(decs):
+        check(lm.logits(s), d.logits, "batched step, sequence %d" % s)
+        assert lm.seq_len(s) == d.length
+    lm.close()
+    print("%d q heads per kv head: max |logit err| = %.3e (%.2e of the largest logit)" % (4 // n_kv, worst_abs, worst_rel))
