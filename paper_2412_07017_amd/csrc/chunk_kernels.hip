@@ -847,6 +847,10 @@ struct ChunkAttnArgs {
     float* part_o;      // [unit][128][32]
     float* part_ml;     // [unit][2][32]
     int32_t nsplit, q_cols;
+    // single-row decoding (long contexts): the step's rotated fp32 query [Hq][128] and its descriptor stand in for
+    // the query planes and the row table (one task: the q heads of a kv group are its columns); else null
+    const float* q_f32;
+    const StepDesc* step;
 };
 
 // K tile (32 keys x 128 channels, one plane) as loaded: instruction q covers rows 4q .. 4q+3, lane l holds
@@ -978,7 +982,9 @@ __global__ __launch_bounds__(256) void k_chunk_attn(ChunkAttnArgs a, Geom g) {
     uint4* kt = attn_lds + wave * 1024;
     const int G = g.Hq / g.Hkv;
     const int kvh = blockIdx.x % g.Hkv, split = blockIdx.y * 4 + wave;
-    const ChunkTask T = a.tab->task[blockIdx.x / g.Hkv];
+    ChunkTask T;
+    if (a.step) { T.seq = a.step->seq; T.row0 = 0; T.n = 1; T.pos0 = a.step->pos; T.tile = 0; }
+    else T = a.tab->task[blockIdx.x / g.Hkv];
     // Columns 32 tile .. 32 tile + 31 of the group are rows first .. first + 31 of one query head, or wrap into the
     // next head (then the group's last row is among them): no column of the tile sees keys past its latest row.
     const int first = (32 * T.tile) % T.n;
@@ -1006,7 +1012,16 @@ __global__ __launch_bounds__(256) void k_chunk_attn(ChunkAttnArgs a, Geom g) {
     if (t0 < t1) {
         // B operand of S^T = K Q^T: lane (j, g) holds q[j][16 t + 8 g + e]
         uint4 qh[8], ql[8];
-        {
+        if (a.q_f32) {                              // column i is q head i of the kv group; the other columns are zero
+            const float* qp = a.q_f32 + (size_t)(kvh * G + min(i, G - 1)) * DH + gh * 8;
+            const float sc = i < G ? g.scale : 0.f;
+#pragma unroll
+            for (int t = 0; t < 8; ++t) {
+                const float4 v0 = *reinterpret_cast<const float4*>(qp + t * 16), v1 = *reinterpret_cast<const float4*>(qp + t * 16 + 4);
+                split_pair(v0.x * sc, v0.y * sc, qh[t].x, ql[t].x); split_pair(v0.z * sc, v0.w * sc, qh[t].y, ql[t].y);
+                split_pair(v1.x * sc, v1.y * sc, qh[t].z, ql[t].z); split_pair(v1.z * sc, v1.w * sc, qh[t].w, ql[t].w);
+            }
+        } else {
             const size_t qo = ((size_t)kvh * a.q_cols + (size_t)G * T.row0 + col) * DH + gh * 8;
 #pragma unroll
             for (int t = 0; t < 8; ++t) { qh[t] = load16(a.q_hi + qo + t * 16); ql[t] = load16(a.q_lo + qo + t * 16); }
@@ -1172,7 +1187,9 @@ __global__ __launch_bounds__(256) void k_chunk_attn_combine(const float* __restr
     const int tid = threadIdx.x;
     const int G = g.Hq / g.Hkv;
     const int kvh = blockIdx.x % g.Hkv;
-    const ChunkTask T = tab->task[blockIdx.x / g.Hkv];
+    ChunkTask T;
+    if (out_f32) { T.row0 = 0; T.n = 1; T.tile = 0; }     // single-row decoding: one task, no row table
+    else T = tab->task[blockIdx.x / g.Hkv];
     const float* ml = part_ml + (size_t)blockIdx.x * nsplit * 64;
     float inv;
     {
@@ -1238,25 +1255,6 @@ __global__ __launch_bounds__(256) void k_chunk_attn_combine(const float* __restr
                 out_hi[o] = hi; out_lo[o] = lw;
             }
         }
-    }
-}
-
-// Single-row decoding through the chunk attention (long contexts): the rotated fp32 query of the step becomes
-// the hi/lo query planes of a one-row group (columns = the q heads of each kv head), and the row table gets the
-// group's only task.  grid = Hq, block = dh.
-__global__ void k_decode_attn_prep(const float* __restrict__ q, const StepDesc* __restrict__ step, Geom g,
-                                   ChunkTable* tab, bf16_t* __restrict__ q_hi, bf16_t* __restrict__ q_lo, int q_cols) {
-    const int hq = blockIdx.x, i = threadIdx.x;
-    const int G = g.Hq / g.Hkv, kvh = hq / G, gq = hq - kvh * G;
-    bf16_t hi, lo;
-    split_bf16(q[hq * g.dh + i] * g.scale, hi, lo);
-    const size_t o = ((size_t)kvh * q_cols + gq) * g.dh + i;
-    q_hi[o] = hi; q_lo[o] = lo;
-    if (hq == 0 && i == 0) {
-        ChunkTask T{};
-        T.seq = step->seq; T.row0 = 0; T.n = 1; T.pos0 = step->pos; T.tile = 0;
-        tab->task[0] = T;
-        tab->ntasks = 1;
     }
 }
 
@@ -1385,13 +1383,15 @@ hipError_t launch_chunk_gemm_swiglu(const void* W, int F, int K, const bf16_t* x
 }
 
 static hipError_t chunk_attn_launch(const ChunkBuffers& c, const void* kv_layer, int nsplit, int ntasks, const Geom& g,
-                                    float* out_f32, hipStream_t s) {
+                                    const DecodeBuffers* decode, hipStream_t s) {
+    float* out_f32 = decode ? decode->o : nullptr;
     if (nsplit < 4 || nsplit % 4 || nsplit > CHUNK_ATTN_MAX_SPLIT || ntasks < 1 || ntasks > CHUNK_MAX_TASKS ||
         (long long)ntasks * g.Hkv * nsplit > CHUNK_ATTN_MAX_UNITS)
         return hipErrorInvalidValue;
     ChunkAttnArgs a{};
     a.q_hi = c.q_hi; a.q_lo = c.q_lo; a.kv_layer = (const bf16_t*)kv_layer; a.tab = c.tab;
     a.part_o = c.attn_o; a.part_ml = c.attn_ml; a.nsplit = nsplit; a.q_cols = c.q_cols;
+    if (decode) { a.q_f32 = decode->q; a.step = decode->step; }
     hipLaunchKernelGGL(k_chunk_attn, dim3(ntasks * g.Hkv, nsplit / 4), dim3(256), ATTN_LDS_BYTES, s, a, g);
     hipError_t e = hipGetLastError();
     if (e) return e;
@@ -1423,11 +1423,8 @@ hipError_t launch_chunk_attn_wide(const ChunkBuffers& c, const void* kv_layer, i
 
 hipError_t launch_decode_attn_mfma(const ChunkBuffers& c, const void* kv_layer, int nsplit, const DecodeBuffers& b, const Geom& g,
                                    hipStream_t s) {
-    if (g.dh != 128) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(k_decode_attn_prep, dim3(g.Hq), dim3(g.dh), 0, s, b.q, b.step, g, c.tab, c.q_hi, c.q_lo, c.q_cols);
-    hipError_t e = hipGetLastError();
-    if (e) return e;
-    return chunk_attn_launch(c, kv_layer, nsplit, 1, g, b.o, s);
+    if (g.dh != 128 || g.Hq / g.Hkv > 32) return hipErrorInvalidValue;
+    return chunk_attn_launch(c, kv_layer, nsplit, 1, g, &b, s);
 }
 
 }  // namespace asynclm
