@@ -297,11 +297,13 @@ int pick_gemm_split(const asynclm_ctx* c, int N, int K, int MT) {
         // wide passes are bound by the matrix cores: the workgroups run in rounds of one per compute unit, each taking
         // its k-blocks plus about one and a half blocks' time of prologue and epilogue; every split also costs a
         // partial plane to write and read back
+        // (a plane of 512 x 4096 floats, written and read back, costs about as much as one k-block of a workgroup)
         s = 1;
         double best = 0;
+        const double plane = 0.9 * ((double)MT * 32 * N) / (512.0 * 4096.0);
         for (int k = 1; k <= smax; ++k) {
             const int rounds = (tiles * k + c->n_cu - 1) / c->n_cu;
-            const double cost = rounds * ((double)nblk / k + 1.5) + 0.8 * k;
+            const double cost = rounds * ((double)nblk / k + 1.5) + plane * (k - 1);
             if (k == 1 || cost < best) { best = cost; s = k; }
         }
     }
@@ -312,8 +314,10 @@ int pick_gemm_split(const asynclm_ctx* c, int N, int K, int MT) {
 
 ChunkSplits chunk_splits(const asynclm_ctx* c, int MT) {
     const Geom& g = c->g;
-    return {pick_gemm_split(c, (g.Hq + 2 * g.Hkv) * g.dh, g.d, MT), pick_gemm_split(c, g.d, g.Hq * g.dh, MT),
-            pick_gemm_split(c, 2 * g.F, g.d, MT), pick_gemm_split(c, g.d, g.F, MT)};
+    // the gate/up product of a wide pass is never split (unless forced): split-K would lose its SwiGLU epilogue
+    const int gu = MT > 3 && c->opt_chunk_split == 0 ? 1 : pick_gemm_split(c, 2 * g.F, g.d, MT);
+    return {pick_gemm_split(c, (g.Hq + 2 * g.Hkv) * g.dh, g.d, MT), pick_gemm_split(c, g.d, g.Hq * g.dh, MT), gu,
+            pick_gemm_split(c, g.d, g.F, MT)};
 }
 
 // Key splits of the chunk attention: about two 32-key tiles per wave, a multiple of 4, no more than fill the
