@@ -80,7 +80,7 @@ struct asynclm_ctx {
     int32_t* chosen_host = nullptr;     // pinned, CHUNK_MAX ints
 
     // options
-    int opt_chunk = 1, opt_graph = 1, opt_attn_split = 0, opt_chunk_split = 0, opt_fused = 0, opt_attn_mfma_min = 4096;
+    int opt_chunk = 1, opt_graph = 1, opt_attn_split = 0, opt_chunk_split = 0, opt_fused = 0, opt_attn_mfma_min = 1024;
 
     std::map<int, hipGraphExec_t> graphs;   // key: nsplit * 2 + with_head
 
@@ -154,10 +154,13 @@ SplitPlan pick_nsplit(const asynclm_ctx* c, int len_after) {
         const int n = c->opt_attn_split < ATTN_MAX_SPLIT ? c->opt_attn_split : ATTN_MAX_SPLIT;
         return {n, n <= 8, false};
     }
-    const int want = (len_after + 63) / 64, cap = len_after <= 2048 ? 8 : ATTN_MAX_SPLIT;
+    // up to 2048 tokens: a split per 64 positions, at most the 8 that the O projection merges; beyond: a split per
+    // 256 positions (one pass of the kernel's inner loop), merged by the last workgroup of each kv head
+    const bool merged = len_after <= 2048;
+    const int want = merged ? (len_after + 63) / 64 : (len_after + 255) / 256, cap = merged ? 8 : ATTN_MAX_SPLIT;
     int n = 1;
     while (n < want && n < cap) n *= 2;
-    return {n, cap == 8, false};
+    return {n, merged, false};
 }
 
 // One forward pass of a single row whose token/position are already in the step descriptor.
