@@ -123,6 +123,34 @@ def test_attention_split_count_does_not_change_logits(tiny, nsplit):
     lm.close()
 
 
+@pytest.mark.timeout(300)
+def test_long_context_single_row_attention_with_automatic_splits(tiny):
+    """Contexts beyond 2048 tokens on the single-row attention kernel (fp32 models never take the matrix-core
+    variant): one split per 256 positions, merged by the last workgroup of each kv head; below, up to 8 splits
+    merged by the O projection.  Checked across both regimes against the incremental oracle."""
+    pkg, wl, spec, w_cpu, w_dev, stream, ref = tiny
+    toks = [int(t) for t in ai.uniform_tokens(ai.MASTER_SEED, 931, 2600, wl.model.vocab)]
+    dec = orc.CachedDecoder(orc.Shape.of(wl.model), w_cpu)
+    lm = _new(tiny, max_positions=2700)
+    worst = 0.0
+    done = 0
+    for upto in (1000, 2040, 2049, 2300, 2600):      # prefill, then appends that cross the 2048 boundary
+        part = toks[done:upto]
+        if done == 0:
+            lm.prefill(0, part); dec.prefill(part)
+        else:
+            lm.inject_interrupt(0, part); dec.inject(part)
+        done = upto
+        worst = max(worst, float(np.abs(lm.logits(0) - dec.logits).max()))
+        tok = dec.decode_step()                       # one decoding step at each length (the stream grows by it)
+        assert lm.decode_step(0, forced_token=tok) == tok
+        worst = max(worst, float(np.abs(lm.logits(0) - dec.logits).max()))
+        assert lm.seq_len(0) == dec.length
+    lm.close()
+    print("tiny fp32, contexts 1000..2600: max |logit err| = %.3e" % worst)
+    assert worst <= TOL, worst
+
+
 def test_two_sequences_are_independent(tiny):
     pkg, wl, spec, w_cpu, w_dev, stream, ref = tiny
     s = ref["stream"]
