@@ -6,8 +6,8 @@ by callers for device memory and streams and is not needed to import this packag
 """
 from .binding import (AsyncLM, AsyncLMError, library_path, load_library, E_INVAL, E_STATE, E_CAPACITY,
                       E_NOMEM, E_DEVICE, API_SYMBOLS, KV_AUTO, KV_BF16)
-from .session import CML, InterruptibleSession, StepResult, TokenMonitor, TrapPolicy
+from .session import CML, InterruptibleSession, SessionGroup, StepResult, TokenMonitor, TrapPolicy
 
 __all__ = ["AsyncLM", "AsyncLMError", "library_path", "load_library", "E_INVAL", "E_STATE", "E_CAPACITY",
            "E_NOMEM", "E_DEVICE", "API_SYMBOLS", "KV_AUTO", "KV_BF16", "CML", "InterruptibleSession", "StepResult",
-           "TokenMonitor", "TrapPolicy"]
+           "SessionGroup", "TokenMonitor", "TrapPolicy"]

@@ -12,7 +12,9 @@ What the paper's inference process does around the model (Fig. 4, Sec. 3, Sec. 5
   interruptible, ALL queued interrupts are formatted as interrupt blocks, concatenated, and appended to the
   token that was just chosen, so the model processes them in the same forward pass (asynclm_step_batch on one
   sequence);
-* trap (Sec. 3.3 / 5.4): after a trap block the session pauses; it resumes when an interrupt arrives.
+* trap (Sec. 3.3 / 5.4): after a trap block the session pauses; it resumes when an interrupt arrives;
+* several sessions (SessionGroup): one batched pass per iteration carries every running session's chosen token
+  and queued interrupts.
 
 The CML text grammar, tokenisation and the executor itself are outside: this class sees integer ids.  A call
 block is  CALL id.. HEAD body.. END,  an interrupt block  INTR id.. HEAD value.. END,  a trap  TRAP END.
@@ -187,6 +189,57 @@ class InterruptibleSession:
             res.trapped = True
             self.paused = True
         return res
+
+
+class SessionGroup:
+    """Several sessions of one AsyncLM context generating together: every iteration is ONE batched forward pass
+    (asynclm_step_batch) whose rows are, per running session, [token just chosen] ++ [its queued interrupts], as in
+    the interrupt manager of Sec. 5.3 applied to a batch of requests.  Each session keeps its own token monitor,
+    mask, critical section, queue and trap state; paused sessions take no rows (a paused session with queued
+    interrupts is resumed by an append pass of its own before the batched pass)."""
+
+    def __init__(self, lm, sessions: Sequence[InterruptibleSession]):
+        seqs = [s.seq for s in sessions]
+        if len(set(seqs)) != len(seqs) or any(s.lm is not lm for s in sessions):
+            raise ValueError("sessions must use distinct sequences of the same context")
+        self.lm, self.sessions = lm, list(sessions)
+
+    def step(self) -> List[StepResult]:
+        results: List[Optional[StepResult]] = [None] * len(self.sessions)
+        rows = []                                   # (index, session, token, blocks, event)
+        for i, s in enumerate(self.sessions):
+            if s.paused:
+                if s.pending() == 0:
+                    results[i] = StepResult(token=None)
+                    continue
+                blocks = s._drain()                 # resume: the interrupts become the next rows on their own
+                self.lm.inject_interrupt(s.seq, blocks)
+                s.stream += blocks
+                s.paused = False
+                results[i] = StepResult(token=None, injected=blocks)
+                continue
+            s._set_mask()
+            forced = s.monitor.forced()
+            # the token is chosen on the device under the session's mask; the host reads it before the pass because
+            # whether interrupts may follow it depends on the token (a token that opens a block starts a critical section)
+            token = int(self.lm.peek_choice(s.seq)) if forced is None else int(forced)
+            event = s.monitor.observe(token)
+            trapped = event is not None and event[0] == "trap"
+            blocks = s._drain() if (not s.monitor.critical and not trapped and s.pending()) else []
+            rows.append((i, s, token, blocks, event))
+        if rows:
+            got = self.lm.step_batch([r[1].seq for r in rows], [r[2] for r in rows], [r[3] for r in rows])
+            for (i, s, token, blocks, event), g in zip(rows, got):
+                assert int(g) == token
+                s.stream += [token] + blocks
+                res = StepResult(token=token, injected=blocks)
+                if event is not None and event[0] == "call":
+                    res.call = (event[1], event[2])
+                elif event is not None:
+                    res.trapped = True
+                    s.paused = True
+                results[i] = res
+        return results
 
 
 class TrapPolicy:

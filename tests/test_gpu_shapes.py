@@ -73,3 +73,71 @@ def test_append_path_on_other_head_layouts(n_kv):
         assert lm.seq_len(s) == d.length
     lm.close()
     print("%d q heads per kv head: max |logit err| = %.3e (%.2e of the largest logit)" % (4 // n_kv, worst_abs, worst_rel))
+
+
+def test_session_group_on_the_batched_matrix_core_path():
+    """SessionGroup (host control plane over several sessions) on a bf16 model, where every iteration really is one
+    batched pass of the matrix-core append path: token streams identical to per-session oracle replays under the
+    same rules, logits within tolerance."""
+    import paper_2412_07017_amd as pkg
+    model = ModelConfig(n_layers=2, d_model=512, n_q_heads=4, n_kv_heads=2, head_dim=128, ffn=1024, vocab=2048,
+                        rms_eps=1e-5, rope_theta=10000.0, dtype="bf16")
+    w_dev = ai.make_weights(model, device=torch.device("cuda:0"))
+    torch.cuda.synchronize()
+    w_cpu = _host_weights(w_dev)
+    sh = orc.Shape.of(model)
+    cml = pkg.CML(call=2000, intr=2001, trap=2002, end=2003, head=2004)
+    tk = lambda n, sub: [int(t) % 1990 for t in ai.uniform_tokens(ai.MASTER_SEED, 951, n, model.vocab, sub=sub)]
+    prompts = [tk(70, 0), tk(131, 1), tk(40, 2), tk(200, 3)]
+    arrivals = [{0: ([1], tk(20, 10)), 7: ([2], tk(3, 11))}, {3: ([3], tk(45, 12))}, {}, {5: ([4], tk(9, 13)), 6: ([5], tk(70, 14)), 20: ([6], tk(2, 15))}]
+    n_steps = 28
+
+    def blocks_of(q):
+        out = []
+        for cid, val in q:
+            out += [cml.intr] + cid + [cml.head] + val + [cml.end]
+        return out
+
+    want, decs = [], []
+    for prompt, arr in zip(prompts, arrivals):
+        dec = orc.CachedDecoder(sh, w_cpu, dtype=np.float32)
+        dec.prefill(prompt)
+        mon = pkg.TokenMonitor(cml)
+        queue, paused, out = [], False, []
+        for t in range(n_steps):
+            if t in arr:
+                queue.append(arr[t])
+            if paused:
+                if queue:
+                    b = blocks_of(queue); queue = []
+                    dec.inject(b); out += b; paused = False
+                continue
+            forced = mon.forced()
+            tok = forced if forced is not None else orc.greedy(dec.logits, mon.banned())
+            dec.decode_step(forced=tok)
+            out.append(tok)
+            evn = mon.observe(tok)
+            trapped = evn is not None and evn[0] == "trap"
+            if queue and not mon.critical and not trapped:
+                b = blocks_of(queue); queue = []
+                dec.inject(b); out += b
+            if trapped:
+                paused = True
+        want.append(out); decs.append(dec)
+
+    lm = pkg.AsyncLM(model, w_dev, max_positions=512, max_seqs=4, stream=torch.cuda.Stream())
+    for q, prompt in enumerate(prompts):
+        lm.prefill(q, prompt)
+    sessions = [pkg.InterruptibleSession(lm, q, cml) for q in range(4)]
+    grp = pkg.SessionGroup(lm, sessions)
+    for t in range(n_steps):
+        for q, arr in enumerate(arrivals):
+            if t in arr:
+                sessions[q].submit_interrupt(*arr[t])
+        grp.step()
+    for q in range(4):
+        assert sessions[q].stream == want[q], q
+        err = float(np.abs(lm.logits(q) - decs[q].logits).max())
+        assert err <= TOL and err / float(np.abs(decs[q].logits).max()) <= REL, (q, err)
+        assert lm.seq_len(q) == decs[q].length
+    lm.close()

@@ -418,3 +418,68 @@ def test_interruptible_session_end_to_end_matches_oracle_replay(tiny):
     assert lm.seq_len(0) == len(prompt) + len(want_stream) == dec.length
     assert np.abs(lm.logits(0) - dec.logits).max() <= TOL
     lm.close()
+
+
+def test_session_group_end_to_end_matches_oracle_replays(tiny):
+    """Three sessions of one context driven by SessionGroup: every iteration is one batched pass carrying each running
+    session's chosen token and queued interrupts.  Each session is replayed alone with the CPU oracle under the same
+    rules (mask per monitor state, interrupts only outside blocks, trap END forced, pause / resume): identical token
+    streams and logits within tolerance for every session."""
+    pkg, wl, spec, w_cpu, w_dev, stream, ref = tiny
+    sh = orc.Shape.of(wl.model)
+    cml = pkg.CML(call=65, intr=1001, trap=930, end=313, head=191)
+    prompts = [spec["prompt"], spec["prompt"][5:50], [int(t) for t in ai.uniform_tokens(ai.MASTER_SEED, 941, 33, wl.model.vocab)]]
+    arrivals = [{1: ([7], [8, 9]), 4: ([10], [11]), 12: ([12, 13], [14] * 5), 30: ([15], [16])},
+                {0: ([20], [21]), 9: ([22], [23, 24, 25])},
+                {3: ([30], [31] * 7), 17: ([32], [33]), 18: ([34], [35])}]
+    n_steps = 40
+
+    def blocks_of(q):
+        out = []
+        for cid, val in q:
+            out += [cml.intr] + cid + [cml.head] + val + [cml.end]
+        return out
+
+    want, decs = [], []
+    for prompt, arr in zip(prompts, arrivals):
+        dec = orc.CachedDecoder(sh, w_cpu)
+        dec.prefill(prompt)
+        mon = pkg.TokenMonitor(cml)
+        queue, paused, out = [], False, []
+        for t in range(n_steps):
+            if t in arr:
+                queue.append(arr[t])
+            if paused:
+                if queue:
+                    b = blocks_of(queue); queue = []
+                    dec.inject(b); out += b; paused = False
+                continue
+            forced = mon.forced()
+            tok = forced if forced is not None else orc.greedy(dec.logits, mon.banned())
+            dec.decode_step(forced=tok)
+            out.append(tok)
+            evn = mon.observe(tok)
+            trapped = evn is not None and evn[0] == "trap"
+            if queue and not mon.critical and not trapped:
+                b = blocks_of(queue); queue = []
+                dec.inject(b); out += b
+            if trapped:
+                paused = True
+        want.append(out); decs.append(dec)
+
+    lm = _new(tiny, max_positions=400, max_seqs=3)
+    for q, prompt in enumerate(prompts):
+        lm.prefill(q, prompt)
+    sessions = [pkg.InterruptibleSession(lm, q, cml) for q in range(3)]
+    grp = pkg.SessionGroup(lm, sessions)
+    for t in range(n_steps):
+        for q, arr in enumerate(arrivals):
+            if t in arr:
+                sessions[q].submit_interrupt(*arr[t])
+        for r in grp.step():
+            assert r.token != cml.intr
+    for q in range(3):
+        assert sessions[q].stream == want[q], q
+        assert lm.seq_len(q) == decs[q].length
+        assert np.abs(lm.logits(q) - decs[q].logits).max() <= TOL
+    lm.close()

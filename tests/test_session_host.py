@@ -158,3 +158,83 @@ def test_trap_policy_follows_the_rule_of_the_paper():
     pts = [(n, p.swap_ms(n), p.recompute_ms(n)) for n in (256, 1024, 4096, 16384)]
     f = TrapPolicy.fit(pts)
     assert f.swap_ms(2000) == pytest.approx(p.swap_ms(2000)) and f.recompute_ms(2000) == pytest.approx(p.recompute_ms(2000))
+
+
+class ScriptedBatchLM:
+    """Stand-in with one token script per sequence; records the rows of every batched pass."""
+
+    def __init__(self, scripts):
+        self.scripts = {q: list(s) for q, s in scripts.items()}
+        self.banned = {q: [] for q in scripts}
+        self.context = {q: [] for q in scripts}
+        self.passes = []
+
+    def set_banned_tokens(self, seq, ids):
+        self.banned[seq] = list(ids)
+
+    def peek_choice(self, seq):
+        tok = self.scripts[seq][0]
+        assert tok not in self.banned[seq], ("scripted token is masked", seq, tok)
+        return tok
+
+    def step_batch(self, seqs, forced, interrupts):
+        assert len(set(seqs)) == len(seqs)
+        for q, t, it in zip(seqs, forced, interrupts):
+            assert self.scripts[q].pop(0) == t
+            self.context[q] += [t] + list(it)
+        self.passes.append([(q, t, tuple(it)) for q, t, it in zip(seqs, forced, interrupts)])
+        return list(forced)
+
+    def inject_interrupt(self, seq, tokens):
+        self.context[seq] += list(tokens)
+        self.passes.append([(seq, None, tuple(tokens))])
+
+
+def test_session_group_shares_one_pass_per_iteration_and_keeps_every_session_rule():
+    from paper_2412_07017_amd.session import SessionGroup
+    scripts = {0: [5, C.call, 11, C.head, 21, C.end, 6, 7],             # a call block in the middle
+               1: [8, 9, C.trap, C.end, 30, 31],                          # traps, resumes on an interrupt
+               2: [40, 41, 42, 43, 44, 45, 46, 47]}                       # plain text
+    lm = ScriptedBatchLM(scripts)
+    sess = [InterruptibleSession(lm, q, C) for q in (0, 1, 2)]
+    grp = SessionGroup(lm, sess)
+    # iteration 1: everybody generates; sequence 2 has an interrupt queued and takes it with its token
+    sess[2].submit_interrupt([90], [91, 92])
+    r = grp.step()
+    assert [x.token for x in r] == [5, 8, 40] and r[2].injected == [C.intr, 90, C.head, 91, 92, C.end]
+    assert len(lm.passes) == 1 and len(lm.passes[0]) == 3            # ONE pass with three row groups
+    # iteration 2: sequence 0 opens a call block: an interrupt queued for it must wait (Sec. 3.2)
+    sess[0].submit_interrupt([70], [71])
+    r = grp.step()
+    assert r[0].token == C.call and r[0].injected == [] and sess[0].pending() == 1
+    # iterations 3-5: inside the block nothing is injected for sequence 0; sequence 1 traps in iteration 4
+    r = grp.step(); assert r[0].injected == [] and r[1].token == C.trap
+    r = grp.step(); assert r[0].injected == [] and r[1].token == C.end and r[1].trapped and sess[1].paused
+    r = grp.step(); assert r[0].token == 21 and r[0].injected == [] and r[1].token is None     # paused: no rows
+    assert [q for q, _, _ in lm.passes[-1]] == [0, 2]
+    # iteration 6: END closes the call: it is reported and the queued interrupt rides with this very token
+    r = grp.step()
+    assert r[0].token == C.end and r[0].call == ([11], [21]) and r[0].injected == [C.intr, 70, C.head, 71, C.end]
+    # the paused sequence resumes when an interrupt arrives: an append pass of its own, then it rejoins the batch
+    sess[1].submit_interrupt([60], [61])
+    n_before = len(lm.passes)
+    r = grp.step()
+    assert r[1].token is None and r[1].injected == [C.intr, 60, C.head, 61, C.end] and not sess[1].paused
+    assert lm.passes[n_before] == [(1, None, (C.intr, 60, C.head, 61, C.end))] and [q for q, _, _ in lm.passes[-1]] == [0, 2]
+    r = grp.step()
+    assert [x.token for x in r] == [7, 30, 47] and [q for q, _, _ in lm.passes[-1]] == [0, 1, 2]
+    # every context is the session's own record of its stream, well-formed CML
+    for q in (0, 1, 2):
+        assert lm.context[q] == sess[q].stream
+        m = TokenMonitor(C)
+        i = 0
+        toks = lm.context[q]
+        while i < len(toks):                       # interrupt blocks are skipped as units, the rest must parse
+            if toks[i] == C.intr:
+                j = toks.index(C.end, i)
+                assert C.head in toks[i:j]
+                i = j + 1
+                continue
+            m.observe(toks[i]); i += 1
+    with pytest.raises(ValueError):
+        SessionGroup(lm, [sess[0], InterruptibleSession(lm, 0, C)])
