@@ -21,6 +21,8 @@ Prints ONE JSON line:
   roofline       dominant kernel (gate/up projection + SwiGLU): algorithmic bytes per launch over
                  its mean duration measured here with HIP events on the library's stream
   cpu_baseline   the CPU oracle timed on this host on a bounded sample (a baseline, not a target)
+Other modes: --trap-map (Sec. 5.4 swap against recomputation), --e2e-calls N (Sec. 6.3 synchronous against
+asynchronous calling, measured end to end next to the latency model).
 """
 import argparse
 import json
@@ -50,6 +52,9 @@ def parse():
     ap.add_argument("--trap-map", action="store_true",
                     help="instead of the benchmark: time K/V swap-out + swap-in against recomputation (re-prefill) over a range of "
                          "context lengths (Sec. 5.4 trade-off) and print them as one JSON line")
+    ap.add_argument("--e2e-calls", type=int, default=0,
+                    help="instead of the benchmark: N scripted function calls with timer-backed executions, run synchronously "
+                         "and asynchronously through the library, against the latency model of Sec. 6.3 (one JSON line)")
     ap.add_argument("--fused", type=int, default=-1, help="1/0: force the single-kernel / per-operation decoding step (default: library's choice)")
     return ap.parse_args()
 
@@ -235,6 +240,113 @@ def trap_map(args):
     print(json.dumps({"trap_map": rows, "workload": wl.name, "layers": model.n_layers}))
 
 
+def e2e_calls(args):
+    """Sec. 6.3 on the device: N independent calls, each a 20-token call block that the model has to generate and
+    an execution of a seeded random duration (30-500 ms, a timer thread stands in for the executor).  Synchronous
+    calling generates a block, waits for its result, appends it and goes on; asynchronous calling keeps generating
+    while calls execute, appends every returned result as an interrupt block with the next token (never inside a
+    call block), and waits (trap) only when nothing is left to generate.  Token values are scripted (forced): the
+    timing does not depend on them."""
+    import threading
+    import numpy as np
+    import torch
+    import asynclm_inputs as ai
+    import paper_2412_07017_amd as pkg
+    from paper_2412_07017_amd.latency_model import Call, latency_sync, simulate_async
+    wl = ai.preset(args.workload)
+    model = wl.model if not args.layers else ai.truncated(wl.model, args.layers)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    w_dev = ai.make_weights(model, device=dev)
+    stream = torch.cuda.Stream(device=dev)
+    n, block, result_len = args.e2e_calls, 20, 20
+    rng = np.random.default_rng([ai.MASTER_SEED, 77, n])
+    exe = rng.uniform(0.030, 0.500, n)
+    prompt = ai.uniform_tokens(ai.MASTER_SEED, 105, wl.prompt_len, model.vocab)
+    tok = lambda purpose, k: [int(t) for t in ai.uniform_tokens(ai.MASTER_SEED, 106, k, model.vocab, sub=purpose)]
+    lm = pkg.AsyncLM(model, w_dev, max_positions=wl.prompt_len + n * (block + result_len + 8) + 64, stream=stream)
+
+    def run(asynchronous, order):
+        lm.reset(0)
+        lm.prefill(0, prompt)
+        lm.synchronize()
+        lock, returned, timers = threading.Lock(), [], []
+
+        def launch(i):
+            def done():
+                with lock:
+                    returned.append(i)
+            t = threading.Timer(float(exe[i]), done)
+            timers.append(t)
+            t.start()
+
+        def take():
+            with lock:
+                out = list(returned)
+                returned.clear()
+            return out
+
+        injected = 0
+        t0 = time.perf_counter()
+        for i in order:
+            body = tok(i, block)
+            for j, t in enumerate(body):
+                last = j == block - 1
+                if asynchronous and last:
+                    launch(i)                                   # the block is complete with this token: the call starts
+                ready = take() if (asynchronous and last) else []
+                if ready:                                       # outside the block again: results ride with the token
+                    lm.step_batch([0], [t], [sum((tok(1000 + r, result_len) for r in ready), [])], want_tokens=False)
+                    injected += len(ready)
+                else:
+                    lm.decode_step(0, forced_token=t)
+            if not asynchronous:
+                lm.synchronize()
+                launch(i)
+                timers[-1].join()                               # the model waits for the result
+                take()
+                lm.inject_interrupt(0, tok(1000 + i, result_len))
+                injected += 1
+        while injected < n:                                     # trap: nothing left to generate, wait for results
+            ready = take()
+            if ready:
+                lm.inject_interrupt(0, sum((tok(1000 + r, result_len) for r in ready), []))
+                injected += len(ready)
+            else:
+                time.sleep(0.0005)
+        lm.synchronize()
+        wall = time.perf_counter() - t0
+        for t in timers:
+            t.join()
+        return wall
+
+    fifo = list(range(n))
+    lpt = [int(i) for i in np.argsort(-exe)]
+    run(True, fifo)                                             # warm-up (graphs, kernels)
+    t_sync = run(False, fifo)
+    t_async_fifo = run(True, fifo)
+    t_async_lpt = run(True, lpt)
+    # the model's prediction from this device's step costs
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(stream)
+    for t in tok(5000, 32):
+        lm.decode_step(0, forced_token=t)
+    e1.record(stream)
+    lm.synchronize()
+    step_s = e0.elapsed_time(e1) / 32 * 1e-3
+    calls = [Call("f%d" % i, block * step_s, float(exe[i])) for i in range(n)]
+    inject_s = 1.25 * step_s
+    out = {"e2e_calls": n, "workload": wl.name, "layers": model.n_layers, "call_block_tokens": block, "result_tokens": result_len,
+           "execution_s": [round(float(x), 4) for x in exe], "decode_step_ms": step_s * 1e3,
+           "measured_s": {"sync": t_sync, "async_fifo": t_async_fifo, "async_lpt": t_async_lpt},
+           "model_s": {"sync": latency_sync(calls) + n * inject_s,
+                       "async_fifo": simulate_async(calls, order=[c.name for c in calls], interrupt_cost=0.3 * step_s)[0],
+                       "async_lpt": simulate_async(calls, policy="lpt", interrupt_cost=0.3 * step_s)[0]},
+           "speedup_async_lpt_over_sync": t_sync / t_async_lpt}
+    lm.close()
+    print(json.dumps(out))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -242,6 +354,8 @@ def main():
         sys.exit(2)
     if args.trap_map:
         return trap_map(args)
+    if args.e2e_calls:
+        return e2e_calls(args)
     if args.workload == "8b-ragged16":
         return bench_ragged(args)
     import numpy as np
