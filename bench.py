@@ -266,7 +266,9 @@ def e2e_calls(args):
     tok = lambda purpose, k: [int(t) for t in ai.uniform_tokens(ai.MASTER_SEED, 106, k, model.vocab, sub=purpose)]
     lm = pkg.AsyncLM(model, w_dev, max_positions=wl.prompt_len + n * (block + result_len + 8) + 64, stream=stream)
 
-    def run(asynchronous, order):
+    def run(asynchronous, order, naive=False):
+        # naive = the stateless variant of Sec. 5.5: every batch of returned results costs a re-prefill of the whole stream
+        history = [int(t) for t in prompt]
         lm.reset(0)
         lm.prefill(0, prompt)
         lm.synchronize()
@@ -286,7 +288,7 @@ def e2e_calls(args):
                 returned.clear()
             return out
 
-        injected = 0
+        injected = events = 0                                   # results appended; passes that appended them
         t0 = time.perf_counter()
         for i in order:
             body = tok(i, block)
@@ -295,9 +297,19 @@ def e2e_calls(args):
                 if asynchronous and last:
                     launch(i)                                   # the block is complete with this token: the call starts
                 ready = take() if (asynchronous and last) else []
-                if ready:                                       # outside the block again: results ride with the token
-                    lm.step_batch([0], [t], [sum((tok(1000 + r, result_len) for r in ready), [])], want_tokens=False)
+                history.append(t)
+                if ready and naive:
+                    history.extend(sum((tok(1000 + r, result_len) for r in ready), []))
+                    lm.reset(0)
+                    lm.prefill(0, history)
                     injected += len(ready)
+                    events += 1
+                elif ready:                                     # outside the block again: results ride with the token
+                    res = sum((tok(1000 + r, result_len) for r in ready), [])
+                    history.extend(res)
+                    lm.step_batch([0], [t], [res], want_tokens=False)
+                    injected += len(ready)
+                    events += 1
                 else:
                     lm.decode_step(0, forced_token=t)
             if not asynchronous:
@@ -309,23 +321,37 @@ def e2e_calls(args):
                 injected += 1
         while injected < n:                                     # trap: nothing left to generate, wait for results
             ready = take()
-            if ready:
+            if ready and naive:
+                history.extend(sum((tok(1000 + r, result_len) for r in ready), []))
+                lm.reset(0)
+                lm.prefill(0, history)
+                injected += len(ready)
+                events += 1
+            elif ready:
                 lm.inject_interrupt(0, sum((tok(1000 + r, result_len) for r in ready), []))
                 injected += len(ready)
+                events += 1
             else:
                 time.sleep(0.0005)
         lm.synchronize()
         wall = time.perf_counter() - t0
         for t in timers:
             t.join()
-        return wall
+        return wall, events
 
     fifo = list(range(n))
     lpt = [int(i) for i in np.argsort(-exe)]
     run(True, fifo)                                             # warm-up (graphs, kernels)
-    t_sync = run(False, fifo)
-    t_async_fifo = run(True, fifo)
-    t_async_lpt = run(True, lpt)
+    t_sync = run(False, fifo)[0]
+    t_async_fifo = run(True, fifo)[0]
+    t_async_lpt = run(True, lpt)[0]
+    run(True, lpt, naive=True)
+    t_naive_lpt, naive_events = run(True, lpt, naive=True)
+    r0 = time.perf_counter()
+    lm.reset(0)
+    lm.prefill(0, ai.uniform_tokens(ai.MASTER_SEED, 105, wl.prompt_len + n * (block + result_len) // 2, model.vocab))
+    lm.synchronize()
+    reprefill_s = time.perf_counter() - r0                      # a re-prefill at the middle length of the run
     # the model's prediction from this device's step costs
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     e0.record(stream)
@@ -338,10 +364,12 @@ def e2e_calls(args):
     inject_s = 1.25 * step_s
     out = {"e2e_calls": n, "workload": wl.name, "layers": model.n_layers, "call_block_tokens": block, "result_tokens": result_len,
            "execution_s": [round(float(x), 4) for x in exe], "decode_step_ms": step_s * 1e3,
-           "measured_s": {"sync": t_sync, "async_fifo": t_async_fifo, "async_lpt": t_async_lpt},
+           "measured_s": {"sync": t_sync, "async_fifo": t_async_fifo, "async_lpt": t_async_lpt, "async_naive_lpt": t_naive_lpt},
            "model_s": {"sync": latency_sync(calls) + n * inject_s,
                        "async_fifo": simulate_async(calls, order=[c.name for c in calls], interrupt_cost=0.3 * step_s)[0],
-                       "async_lpt": simulate_async(calls, policy="lpt", interrupt_cost=0.3 * step_s)[0]},
+                       "async_lpt": simulate_async(calls, policy="lpt", interrupt_cost=0.3 * step_s)[0],
+                       "async_naive_lpt": simulate_async(calls, policy="lpt", interrupt_cost=reprefill_s)[0]},
+           "reprefill_ms": reprefill_s * 1e3, "naive_reprefills": naive_events,   # results that return together share one
            "speedup_async_lpt_over_sync": t_sync / t_async_lpt}
     lm.close()
     print(json.dumps(out))
