@@ -376,6 +376,54 @@ __device__ __forceinline__ float stage_vector(float4* xs, int plane_stride, cons
     return red[0] + red[1] + red[2] + red[3];
 }
 
+// The same staging for a normalised vector of at most 1024 NBG elements, in two steps with the loads held in
+// registers between them.  A caller that requests the vector before its first weight tiles gets it back first
+// (loads return in issue order) and stages it while the tiles are still on their way.  Straight-line code on
+// purpose: a loop with loads between the tile requests and their uses would make the compiler wait for all of them.
+template <int NBG>
+struct GainBatch { float4 v[NBG], gn[NBG]; };
+
+template <int NBG>
+__device__ __forceinline__ void gain_request(GainBatch<NBG>& b, const float* x, const float* gain, int K) {
+    const int tid = threadIdx.x, n4 = K >> 2;
+#pragma unroll
+    for (int j = 0; j < NBG; ++j) {
+        const int k4 = min(j * 256 + tid, n4 - 1);
+        b.v[j] = as_float4(load16(x + 4 * (size_t)k4));
+        b.gn[j] = as_float4(load16(gain + 4 * (size_t)k4));
+    }
+}
+
+// Needs K <= 1024 NBG and 256 KT - Kg <= 256 (one padding group per thread at most).
+template <typename WT, int NBG>
+__device__ __forceinline__ float gain_stage(const GainBatch<NBG>& b, float4* xs, int plane_stride, int K, int Kg, int KT,
+                                            float* red) {
+    constexpr int NP = Elem<WT>::EPL / 4;
+    const int tid = threadIdx.x, n4 = K >> 2;
+    const float4 zero = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (Kg + tid < KT * 256)
+#pragma unroll
+        for (int pl = 0; pl < NP; ++pl) xs[pl * plane_stride + Kg + tid] = zero;
+    if (tid < 64)
+#pragma unroll
+        for (int pl = 0; pl < NP; ++pl) xs[pl * plane_stride + plane_stride - 64 + tid] = zero;
+    float ss = 0.f;
+#pragma unroll
+    for (int j = 0; j < NBG; ++j) {
+        const int k4 = j * 256 + tid;
+        if (k4 < n4) {
+            const float4 v = b.v[j], gn = b.gn[j];
+            ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+            const int grp = k4 / NP, pl = k4 - grp * NP;
+            xs[pl * plane_stride + grp] = make_float4(v.x * gn.x, v.y * gn.y, v.z * gn.z, v.w * gn.w);
+        }
+    }
+    ss = wave_sum(ss);
+    if ((tid & 63) == 0) red[tid >> 6] = ss;
+    __syncthreads();
+    return red[0] + red[1] + red[2] + red[3];
+}
+
 // ---------------------------------------------------------------------------------------------
 // matrix-vector product of one wave over its share of the rows, through a ring of register tiles
 // ---------------------------------------------------------------------------------------------
@@ -535,8 +583,8 @@ __device__ __forceinline__ void phase_prefetch_w(Slot (&ring)[RING], const Phase
     for (int j = 0; j < RING; ++j) {
         tile_load_w<WT, EPI>(ring[j], p, c, lane, g);
         advance(c, p.KT);
+        __builtin_amdgcn_sched_barrier(0);      // tile by tile: the first tile's loads are the first to return
     }
-    __builtin_amdgcn_sched_barrier(0);
 }
 template <typename WT, int EPI>
 __device__ __forceinline__ void phase_prefetch_e(Slot (&ring)[RING], const Phase<WT>& p, Cursor& lc, const Geom& g, const EpiOut& eo) {

@@ -61,7 +61,7 @@ struct GemvArgs {
 
 // Every wave owns a contiguous share of the row pairs and streams them through a ring of four register
 // tiles (decode_device.h); the first tiles are requested before the input vector is staged.
-template <typename WT, int EPI>
+template <typename WT, int EPI, int NBG>
 __global__ __launch_bounds__(256) void k_gemv(GemvArgs a, Geom g) {
     constexpr int EPL = Elem<WT>::EPL;
     extern __shared__ float4 lds4[];
@@ -72,6 +72,15 @@ __global__ __launch_bounds__(256) void k_gemv(GemvArgs a, Geom g) {
     const int plane_stride = ph.KT * 256 + 64;
     float4* done = lds4 + (size_t)plane_stride * (EPL / 4) + (size_t)wave * a.done_cap;
 
+    // NBG > 0 (normalising products whose vector fits one batch): the input vector is requested before the first
+    // weight tiles, so it is back and staged long before them, and the first tile is multiplied as soon as it
+    // arrives.  NBG = 0: the vector is staged after the requests.
+    constexpr int NBG1 = NBG > 0 ? NBG : 1;
+    GainBatch<NBG1> vb;
+    if (NBG > 0) {
+        gain_request(vb, a.x, a.gain, a.K);
+        __builtin_amdgcn_sched_barrier(0);
+    }
     Slot ring[RING];
     Cursor lc;
     phase_prefetch_w<WT, EPI>(ring, ph, lane, g);
@@ -81,8 +90,12 @@ __global__ __launch_bounds__(256) void k_gemv(GemvArgs a, Geom g) {
     if (EPI == EPI_QKV) { eo.pos = a.step->pos; eo.seq = a.step->seq; }
     phase_prefetch_e<WT, EPI>(ring, ph, lc, g, eo);
 
-    VecSource vs{a.x, a.gain, a.part_acc, a.part_ml, a.merge_nsplit, a.merge_dh, a.merge_hq};
-    const float ssq = stage_vector<WT, (EPI == EPI_RESID ? 16 : 4)>(lds4, plane_stride, vs, a.K, ph.Kg, ph.KT, true, red);
+    float ssq;
+    if (NBG > 0) ssq = gain_stage<WT, NBG1>(vb, lds4, plane_stride, a.K, ph.Kg, ph.KT, red);
+    else {
+        VecSource vs{a.x, a.gain, a.part_acc, a.part_ml, a.merge_nsplit, a.merge_dh, a.merge_hq};
+        ssq = stage_vector<WT, (EPI == EPI_RESID ? 16 : 4)>(lds4, plane_stride, vs, a.K, ph.Kg, ph.KT, true, red);
+    }
     const float nscale = a.gain ? rsqrtf(ssq / (float)a.K + g.eps) : 1.f;
     float best_v = -INFINITY; int best_i = 0x7fffffff;
     phase_run<WT, EPI>(ring, ph, lc, lds4, plane_stride, nscale, eo, g, lane, done, best_v, best_i);
@@ -264,6 +277,12 @@ __global__ __launch_bounds__(256) void k_argmax(const float* __restrict__ logits
 static int g_gemv_grid = 256;       // workgroups per matrix-vector kernel; decode_init sets it to the number of compute units
 static size_t g_gemv_lds_limit = 48 * 1024;   // dynamic LDS a matrix-vector kernel may ask for (raised by decode_init)
 
+template <typename WT, int EPI, int NBG>
+static hipError_t launch_gemv_n(const GemvArgs& a, size_t lds, const Geom& g, hipStream_t s) {
+    hipLaunchKernelGGL((k_gemv<WT, EPI, NBG>), dim3(g_gemv_grid), dim3(256), lds, s, a, g);
+    return hipGetLastError();
+}
+
 template <typename WT, int EPI>
 static hipError_t launch_gemv_t(const GemvArgs& a0, const Geom& g, hipStream_t s) {
     GemvArgs a = a0;
@@ -272,8 +291,12 @@ static hipError_t launch_gemv_t(const GemvArgs& a0, const Geom& g, hipStream_t s
     const int kg = a.K / Elem<WT>::EPL, kt = (kg + 255) / 256;
     const size_t lds = (size_t)(kt * 256 + 64) * Elem<WT>::EPL * sizeof(float) + (size_t)4 * a.done_cap * sizeof(float4);
     if (lds > g_gemv_lds_limit) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((k_gemv<WT, EPI>), dim3(grid), dim3(256), lds, s, a, g);
-    return hipGetLastError();
+    if (EPI == EPI_RESID) return launch_gemv_n<WT, EPI, 0>(a, lds, g, s);
+    if (!(a.x && a.gain)) return hipErrorInvalidValue;       // the normalising products take a vector and a gain
+    // early request of the vector when it fits one batch of 4 or 8 x 16 bytes per thread
+    if (a.K <= 4096) return launch_gemv_n<WT, EPI, 4>(a, lds, g, s);
+    if (a.K <= 8192) return launch_gemv_n<WT, EPI, 8>(a, lds, g, s);
+    return launch_gemv_n<WT, EPI, 0>(a, lds, g, s);
 }
 
 template <typename WT>
@@ -288,7 +311,10 @@ static hipError_t launch_gemv_w(int epi, const GemvArgs& a, const Geom& g, hipSt
 
 template <typename WT, int EPI>
 static hipError_t set_lds_t(int bytes) {
-    return hipFuncSetAttribute((const void*)(k_gemv<WT, EPI>), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    hipError_t e = hipFuncSetAttribute((const void*)(k_gemv<WT, EPI, 0>), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e || EPI == EPI_RESID) return e;
+    if ((e = hipFuncSetAttribute((const void*)(k_gemv<WT, EPI, 4>), hipFuncAttributeMaxDynamicSharedMemorySize, bytes))) return e;
+    return hipFuncSetAttribute((const void*)(k_gemv<WT, EPI, 8>), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
 }
 
 void decode_set_gemv_grid(int grid) { g_gemv_grid = grid; }
