@@ -376,28 +376,29 @@ __device__ __forceinline__ float stage_vector(float4* xs, int plane_stride, cons
     return red[0] + red[1] + red[2] + red[3];
 }
 
-// The same staging for a normalised vector of at most 1024 NBG elements, in two steps with the loads held in
-// registers between them.  A caller that requests the vector before its first weight tiles gets it back first
-// (loads return in issue order) and stages it while the tiles are still on their way.  Straight-line code on
-// purpose: a loop with loads between the tile requests and their uses would make the compiler wait for all of them.
-template <int NBG>
-struct GainBatch { float4 v[NBG], gn[NBG]; };
+// The same staging for a plain vector x (times a gain if GAIN) of at most 1024 NB elements, in two steps with the
+// loads held in registers between them.  A caller that requests the vector before its first weight tiles gets it
+// back first (loads return in issue order) and stages it while the tiles are still on their way.  Straight-line
+// code on purpose: a loop with loads between the tile requests and their uses would make the compiler wait for
+// all of them.
+template <int NB, bool GAIN>
+struct EarlyBatch { float4 v[NB], gn[GAIN ? NB : 1]; };
 
-template <int NBG>
-__device__ __forceinline__ void gain_request(GainBatch<NBG>& b, const float* x, const float* gain, int K) {
+template <int NB, bool GAIN>
+__device__ __forceinline__ void early_request(EarlyBatch<NB, GAIN>& b, const float* x, const float* gain, int K) {
     const int tid = threadIdx.x, n4 = K >> 2;
 #pragma unroll
-    for (int j = 0; j < NBG; ++j) {
+    for (int j = 0; j < NB; ++j) {
         const int k4 = min(j * 256 + tid, n4 - 1);
         b.v[j] = as_float4(load16(x + 4 * (size_t)k4));
-        b.gn[j] = as_float4(load16(gain + 4 * (size_t)k4));
+        if (GAIN) b.gn[j] = as_float4(load16(gain + 4 * (size_t)k4));
     }
 }
 
-// Needs K <= 1024 NBG and 256 KT - Kg <= 256 (one padding group per thread at most).
-template <typename WT, int NBG>
-__device__ __forceinline__ float gain_stage(const GainBatch<NBG>& b, float4* xs, int plane_stride, int K, int Kg, int KT,
-                                            float* red) {
+// Needs K <= 1024 NB (256 KT - Kg < 256 always holds: one padding group per thread at most).
+template <typename WT, int NB, bool GAIN>
+__device__ __forceinline__ float early_stage(const EarlyBatch<NB, GAIN>& b, float4* xs, int plane_stride, int K, int Kg, int KT,
+                                             float* red) {
     constexpr int NP = Elem<WT>::EPL / 4;
     const int tid = threadIdx.x, n4 = K >> 2;
     const float4 zero = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -409,13 +410,14 @@ __device__ __forceinline__ float gain_stage(const GainBatch<NBG>& b, float4* xs,
         for (int pl = 0; pl < NP; ++pl) xs[pl * plane_stride + plane_stride - 64 + tid] = zero;
     float ss = 0.f;
 #pragma unroll
-    for (int j = 0; j < NBG; ++j) {
+    for (int j = 0; j < NB; ++j) {
         const int k4 = j * 256 + tid;
         if (k4 < n4) {
-            const float4 v = b.v[j], gn = b.gn[j];
+            float4 v = b.v[j];
             ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+            if (GAIN) { const float4 gn = b.gn[j]; v = make_float4(v.x * gn.x, v.y * gn.y, v.z * gn.z, v.w * gn.w); }
             const int grp = k4 / NP, pl = k4 - grp * NP;
-            xs[pl * plane_stride + grp] = make_float4(v.x * gn.x, v.y * gn.y, v.z * gn.z, v.w * gn.w);
+            xs[pl * plane_stride + grp] = v;
         }
     }
     ss = wave_sum(ss);
@@ -492,10 +494,9 @@ __device__ __forceinline__ void tile_load_e(Slot& sl, const Phase<WT>& p, const 
         sl.e0 = load_f32(eo.res + rA); sl.e1 = load_f32(eo.res + rB);
     } else if (EPI == EPI_QKV) {
         const int hs = g.dh == 128 ? 6 : 5, h = u >> hs, i = u & ((1 << hs) - 1);
-        const bool rot = h < g.Hq + g.Hkv;                         // value rows are not rotated
         const size_t ri = ((size_t)eo.pos << hs) + i;
-        const float c = load_f32(eo.rope_cos + ri), sn = load_f32(eo.rope_sin + ri);
-        sl.e0 = rot ? c : 1.f; sl.e1 = rot ? sn : 0.f;
+        // as loaded: a select here would have to wait for the loads (finish_unit drops them for value rows)
+        sl.e0 = load_f32(eo.rope_cos + ri); sl.e1 = load_f32(eo.rope_sin + ri);
     } else { sl.e0 = 0.f; sl.e1 = 0.f; }
 }
 
@@ -519,6 +520,7 @@ __device__ __forceinline__ void finish_unit(int u, float sa, float sb, float e0,
     } else {
         const int hs = g.dh == 128 ? 6 : 5, half = 1 << hs;
         const int h = u >> hs, i = u & (half - 1);
+        if (h >= g.Hq + g.Hkv) { e0 = 1.f; e1 = 0.f; }                 // value rows are not rotated
         const float ra = sa * e0 - sb * e1, rb = sb * e0 + sa * e1;
         const size_t seq_off = (size_t)o.seq * g.kv_seq_stride;
         if (h < g.Hq) { o.q_out[h * g.dh + i] = ra; o.q_out[h * g.dh + i + half] = rb; }
@@ -616,16 +618,17 @@ __device__ __forceinline__ void phase_run(Slot (&ring)[RING], const Phase<WT>& p
         for (int j = 0; j < RING; ++j) {
             const bool past = cc.u >= p.u1;
             tile_fma<WT>(ring[j].v, xs, plane_stride, zero_group, past, cc.kt, lane, accA, accB);
-            const float e0 = ring[j].e0, e1 = ring[j].e1;
+            // The slot's epilogue operands are parked before the slot is requested again: read after the request
+            // they would have to be copied aside when the loop rotates, and the copy waits for every load in flight.
+            if (!past && cc.kt == p.KT - 1) {
+                const float sa = wave_sum(accA) * nscale, sb = wave_sum(accB) * nscale;
+                if (lane == 0) done[cc.u - p.u0] = make_float4(sa, sb, ring[j].e0, ring[j].e1);
+                accA = 0.f; accB = 0.f;
+            }
             __builtin_amdgcn_sched_barrier(0);
             tile_load<WT, EPI>(ring[j], p, lc, lane, g, eo);
             advance(lc, p.KT);
             __builtin_amdgcn_sched_barrier(0);
-            if (!past && cc.kt == p.KT - 1) {
-                const float sa = wave_sum(accA) * nscale, sb = wave_sum(accB) * nscale;
-                if (lane == 0) done[cc.u - p.u0] = make_float4(sa, sb, e0, e1);
-                accA = 0.f; accB = 0.f;
-            }
             advance(cc, p.KT);
         }
     }

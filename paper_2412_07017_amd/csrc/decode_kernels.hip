@@ -61,7 +61,7 @@ struct GemvArgs {
 
 // Every wave owns a contiguous share of the row pairs and streams them through a ring of four register
 // tiles (decode_device.h); the first tiles are requested before the input vector is staged.
-template <typename WT, int EPI, int NBG>
+template <typename WT, int EPI, int NB>
 __global__ __launch_bounds__(256) void k_gemv(GemvArgs a, Geom g) {
     constexpr int EPL = Elem<WT>::EPL;
     extern __shared__ float4 lds4[];
@@ -72,13 +72,15 @@ __global__ __launch_bounds__(256) void k_gemv(GemvArgs a, Geom g) {
     const int plane_stride = ph.KT * 256 + 64;
     float4* done = lds4 + (size_t)plane_stride * (EPL / 4) + (size_t)wave * a.done_cap;
 
-    // NBG > 0 (normalising products whose vector fits one batch): the input vector is requested before the first
-    // weight tiles, so it is back and staged long before them, and the first tile is multiplied as soon as it
-    // arrives.  NBG = 0: the vector is staged after the requests.
-    constexpr int NBG1 = NBG > 0 ? NBG : 1;
-    GainBatch<NBG1> vb;
-    if (NBG > 0) {
-        gain_request(vb, a.x, a.gain, a.K);
+    // NB > 0 (the vector is a plain one that fits one batch of NB x 16 bytes per thread; with a gain in the
+    // normalising products, without in the residual ones): it is requested before the first weight tiles, so it is
+    // back and staged long before them, and the first tile is multiplied as soon as it arrives.  NB = 0: the vector
+    // (any source) is staged after the requests.
+    constexpr int NB1 = NB > 0 ? NB : 1;
+    constexpr bool GAIN = EPI != EPI_RESID;
+    EarlyBatch<NB1, GAIN> vb;
+    if (NB > 0) {
+        early_request(vb, a.x, a.gain, a.K);
         __builtin_amdgcn_sched_barrier(0);
     }
     Slot ring[RING];
@@ -91,7 +93,7 @@ __global__ __launch_bounds__(256) void k_gemv(GemvArgs a, Geom g) {
     phase_prefetch_e<WT, EPI>(ring, ph, lc, g, eo);
 
     float ssq;
-    if (NBG > 0) ssq = gain_stage<WT, NBG1>(vb, lds4, plane_stride, a.K, ph.Kg, ph.KT, red);
+    if (NB > 0) ssq = early_stage<WT, NB1, GAIN>(vb, lds4, plane_stride, a.K, ph.Kg, ph.KT, red);
     else {
         VecSource vs{a.x, a.gain, a.part_acc, a.part_ml, a.merge_nsplit, a.merge_dh, a.merge_hq};
         ssq = stage_vector<WT, (EPI == EPI_RESID ? 16 : 4)>(lds4, plane_stride, vs, a.K, ph.Kg, ph.KT, true, red);
@@ -277,11 +279,15 @@ __global__ __launch_bounds__(256) void k_argmax(const float* __restrict__ logits
 static int g_gemv_grid = 256;       // workgroups per matrix-vector kernel; decode_init sets it to the number of compute units
 static size_t g_gemv_lds_limit = 48 * 1024;   // dynamic LDS a matrix-vector kernel may ask for (raised by decode_init)
 
-template <typename WT, int EPI, int NBG>
+template <typename WT, int EPI, int NB>
 static hipError_t launch_gemv_n(const GemvArgs& a, size_t lds, const Geom& g, hipStream_t s) {
-    hipLaunchKernelGGL((k_gemv<WT, EPI, NBG>), dim3(g_gemv_grid), dim3(256), lds, s, a, g);
+    hipLaunchKernelGGL((k_gemv<WT, EPI, NB>), dim3(g_gemv_grid), dim3(256), lds, s, a, g);
     return hipGetLastError();
 }
+
+// Early request of the vector when it is a plain one that fits one batch: 4 or 8 x 16 bytes per thread (with as
+// many of the gain) in the normalising products, 4 or 16 in the residual ones.
+template <int EPI> struct EarlyNB { static constexpr int SMALL = 4, LARGE = EPI == EPI_RESID ? 16 : 8; };
 
 template <typename WT, int EPI>
 static hipError_t launch_gemv_t(const GemvArgs& a0, const Geom& g, hipStream_t s) {
@@ -291,11 +297,10 @@ static hipError_t launch_gemv_t(const GemvArgs& a0, const Geom& g, hipStream_t s
     const int kg = a.K / Elem<WT>::EPL, kt = (kg + 255) / 256;
     const size_t lds = (size_t)(kt * 256 + 64) * Elem<WT>::EPL * sizeof(float) + (size_t)4 * a.done_cap * sizeof(float4);
     if (lds > g_gemv_lds_limit) return hipErrorInvalidValue;
-    if (EPI == EPI_RESID) return launch_gemv_n<WT, EPI, 0>(a, lds, g, s);
-    if (!(a.x && a.gain)) return hipErrorInvalidValue;       // the normalising products take a vector and a gain
-    // early request of the vector when it fits one batch of 4 or 8 x 16 bytes per thread
-    if (a.K <= 4096) return launch_gemv_n<WT, EPI, 4>(a, lds, g, s);
-    if (a.K <= 8192) return launch_gemv_n<WT, EPI, 8>(a, lds, g, s);
+    if (EPI != EPI_RESID && !(a.x && a.gain)) return hipErrorInvalidValue;   // the normalising products take a vector and a gain
+    if (EPI == EPI_RESID && a.gain) return hipErrorInvalidValue;
+    if (a.x && a.K <= 1024 * EarlyNB<EPI>::SMALL) return launch_gemv_n<WT, EPI, EarlyNB<EPI>::SMALL>(a, lds, g, s);
+    if (a.x && a.K <= 1024 * EarlyNB<EPI>::LARGE) return launch_gemv_n<WT, EPI, EarlyNB<EPI>::LARGE>(a, lds, g, s);
     return launch_gemv_n<WT, EPI, 0>(a, lds, g, s);
 }
 
@@ -311,10 +316,10 @@ static hipError_t launch_gemv_w(int epi, const GemvArgs& a, const Geom& g, hipSt
 
 template <typename WT, int EPI>
 static hipError_t set_lds_t(int bytes) {
-    hipError_t e = hipFuncSetAttribute((const void*)(k_gemv<WT, EPI, 0>), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
-    if (e || EPI == EPI_RESID) return e;
-    if ((e = hipFuncSetAttribute((const void*)(k_gemv<WT, EPI, 4>), hipFuncAttributeMaxDynamicSharedMemorySize, bytes))) return e;
-    return hipFuncSetAttribute((const void*)(k_gemv<WT, EPI, 8>), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    hipError_t e;
+    if ((e = hipFuncSetAttribute((const void*)(k_gemv<WT, EPI, 0>), hipFuncAttributeMaxDynamicSharedMemorySize, bytes))) return e;
+    if ((e = hipFuncSetAttribute((const void*)(k_gemv<WT, EPI, EarlyNB<EPI>::SMALL>), hipFuncAttributeMaxDynamicSharedMemorySize, bytes))) return e;
+    return hipFuncSetAttribute((const void*)(k_gemv<WT, EPI, EarlyNB<EPI>::LARGE>), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
 }
 
 void decode_set_gemv_grid(int grid) { g_gemv_grid = grid; }
