@@ -183,9 +183,9 @@ int asynclm_synchronize(asynclm_ctx *ctx);
  *   "attn_split"   0 = choose the number of sequence splits of decode attention from the length,
  *                  1..128 = always use n (at most 64 apply to the single-row attention kernel, at most 128,
  *                  rounded up to a multiple of 4, to its matrix-core variant)
- *   "attn_mfma_min" context length from which a decoding step runs its attention on the matrix cores (the
- *                  append path's attention kernel with a one-row group; models with the append path only);
- *                  0 = never.  Default 1024 (measured crossover on the 8B shape). */
+ *   "attn_mfma_min" context length from which a decoding step runs its attention on the matrix cores (models
+ *                  with the append path only); 0 = never.  Default 1: measured faster than the single-row
+ *                  attention kernel at every context length on the 8B shape. */
 int asynclm_set_option(asynclm_ctx *ctx, const char *name, int32_t value);
 
 /* Per-kernel-class GPU time of ONE decoding step (forced token), measured with HIP events around

@@ -80,7 +80,7 @@ struct asynclm_ctx {
     int32_t* chosen_host = nullptr;     // pinned, CHUNK_MAX ints
 
     // options
-    int opt_chunk = 1, opt_graph = 1, opt_attn_split = 0, opt_chunk_split = 0, opt_fused = 0, opt_attn_mfma_min = 1024;
+    int opt_chunk = 1, opt_graph = 1, opt_attn_split = 0, opt_chunk_split = 0, opt_fused = 0, opt_attn_mfma_min = 1;
 
     std::map<int, hipGraphExec_t> graphs;   // key: nsplit * 2 + with_head
 
@@ -143,12 +143,10 @@ struct SplitPlan { int nsplit; bool merge_in_oproj; bool mfma; };
 
 SplitPlan pick_nsplit(const asynclm_ctx* c, int len_after) {
     if (c->chunk_ok && c->opt_attn_mfma_min > 0 && len_after >= c->opt_attn_mfma_min) {
-        // the chunk attention (matrix cores) with a one-row group.  Measured optima: 20-24 splits for 35-46 tiles of 32
-        // keys, 32-48 for 132 tiles, 64 for 514 tiles (more splits make the merge longer, fewer the waves): two tiles
-        // per wave while that is below 4 sqrt(tiles) splits, at most 64
+        // attention on the matrix cores.  Measured optima: one tile of 32 keys per wave up to about 96 tiles (36 splits
+        // for 35 tiles, 68 for 66), 68-96 splits for 132 tiles, 96 for 260 and 513 (more only lengthen the merge)
         const int tiles = (len_after + 31) / 32;
-        int n = std::min(((tiles + 1) / 2 + 3) / 4 * 4, ((int)(4.0 * std::sqrt((double)tiles)) + 3) / 4 * 4);
-        n = std::max(4, std::min(n, 64));
+        int n = std::max(4, std::min((tiles + 3) / 4 * 4, 96));
         if (c->opt_attn_split > 0) n = std::max(4, std::min((c->opt_attn_split + 3) / 4 * 4, CHUNK_ATTN_MAX_SPLIT));
         return {n, false, true};
     }

@@ -847,10 +847,6 @@ struct ChunkAttnArgs {
     float* part_o;      // [unit][128][32]
     float* part_ml;     // [unit][2][32]
     int32_t nsplit, q_cols;
-    // single-row decoding (long contexts): the step's rotated fp32 query [Hq][128] and its descriptor stand in for
-    // the query planes and the row table (one task: the q heads of a kv group are its columns); else null
-    const float* q_f32;
-    const StepDesc* step;
 };
 
 // K tile (32 keys x 128 channels, one plane) as loaded: instruction q covers rows 4q .. 4q+3, lane l holds
@@ -982,9 +978,7 @@ __global__ __launch_bounds__(256) void k_chunk_attn(ChunkAttnArgs a, Geom g) {
     uint4* kt = attn_lds + wave * 1024;
     const int G = g.Hq / g.Hkv;
     const int kvh = blockIdx.x % g.Hkv, split = blockIdx.y * 4 + wave;
-    ChunkTask T;
-    if (a.step) { T.seq = a.step->seq; T.row0 = 0; T.n = 1; T.pos0 = a.step->pos; T.tile = 0; }
-    else T = a.tab->task[blockIdx.x / g.Hkv];
+    const ChunkTask T = a.tab->task[blockIdx.x / g.Hkv];
     // Columns 32 tile .. 32 tile + 31 of the group are rows first .. first + 31 of one query head, or wrap into the
     // next head (then the group's last row is among them): no column of the tile sees keys past its latest row.
     const int first = (32 * T.tile) % T.n;
@@ -1012,16 +1006,7 @@ __global__ __launch_bounds__(256) void k_chunk_attn(ChunkAttnArgs a, Geom g) {
     if (t0 < t1) {
         // B operand of S^T = K Q^T: lane (j, g) holds q[j][16 t + 8 g + e]
         uint4 qh[8], ql[8];
-        if (a.q_f32) {                              // column i is q head i of the kv group; the other columns are zero
-            const float* qp = a.q_f32 + (size_t)(kvh * G + min(i, G - 1)) * DH + gh * 8;
-            const float sc = i < G ? g.scale : 0.f;
-#pragma unroll
-            for (int t = 0; t < 8; ++t) {
-                const float4 v0 = *reinterpret_cast<const float4*>(qp + t * 16), v1 = *reinterpret_cast<const float4*>(qp + t * 16 + 4);
-                split_pair(v0.x * sc, v0.y * sc, qh[t].x, ql[t].x); split_pair(v0.z * sc, v0.w * sc, qh[t].y, ql[t].y);
-                split_pair(v1.x * sc, v1.y * sc, qh[t].z, ql[t].z); split_pair(v1.z * sc, v1.w * sc, qh[t].w, ql[t].w);
-            }
-        } else {
+        {
             const size_t qo = ((size_t)kvh * a.q_cols + (size_t)G * T.row0 + col) * DH + gh * 8;
 #pragma unroll
             for (int t = 0; t < 8; ++t) { qh[t] = load16(a.q_hi + qo + t * 16); ql[t] = load16(a.q_lo + qo + t * 16); }
@@ -1059,6 +1044,140 @@ __global__ __launch_bounds__(256) void k_chunk_attn(ChunkAttnArgs a, Geom g) {
     if (gh == 0) {
         float* pm = a.part_ml + unit * 64;
         pm[i] = st.mrun; pm[32 + i] = st.lrun;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// single-row decoding attention on the matrix cores, one kernel
+// ---------------------------------------------------------------------------------------------
+// grid (Hkv, nsplit / 4); wave = (kv head, key split), the q heads of the kv group are the first G query columns
+// of the tile (the other columns are zero and dropped).  Keys and values of the wave's first tile are requested
+// first, then the step's fp32 query, which is split into bf16 pairs while they arrive.  Each wave leaves the G
+// useful columns of its partial result ([G][128] + running maximum and sum); k_decode_attn_merge, a kernel of its
+// own, merges the splits that had keys.  (Merging in the same kernel by the workgroup that finishes last needs two
+// device-wide fences and a ticket before the partial results can be read, a longer chain than a kernel boundary.)
+struct DecodeAttnArgs {
+    const float* q;             // [Hq][128] rotated, unscaled
+    const StepDesc* step;
+    const bf16_t* kv_layer;
+    float* part_o;              // [Hkv][nsplit][G][128]
+    float* part_ml;             // [Hkv][nsplit][2][G]
+    float* out;                 // [Hq][128]
+    int32_t nsplit;
+};
+
+__global__ __launch_bounds__(256) void k_decode_attn_mfma(DecodeAttnArgs a, Geom g) {
+    constexpr int DH = 128;
+    extern __shared__ uint4 attn_lds[];                    // [4 waves][hi | lo][512 chunks] K tiles
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int i = lane & 31, gh = lane >> 5;
+    uint4* kt = attn_lds + wave * 1024;
+    const int G = g.Hq / g.Hkv;
+    const int kvh = blockIdx.x, split = blockIdx.y * 4 + wave, nsplit = a.nsplit;
+    const int seq = a.step->seq, pos = a.step->pos;
+    const int ntile = (pos + 32) >> 5;                     // keys 0 .. pos
+    const int tps = (ntile + nsplit - 1) / nsplit;
+    const int t0 = split * tps, t1 = min(ntile, t0 + tps);
+
+    const size_t seq_off = (size_t)seq * g.kv_seq_stride + (size_t)kvh * g.kv_head_stride;
+    const bf16_t* Kp = a.kv_layer + seq_off;
+    const bf16_t* Vt = a.kv_layer + g.kv_vt_offset + seq_off;
+    const size_t lo = g.kv_lo_offset;
+
+    if (t0 < t1) {
+        AttnState st;
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) st.o[dt][r] = 0.f;
+        st.mrun = -INFINITY; st.lrun = 0.f;
+        uint4 kh[8], kl[8], vh[8], vl[8];
+        __builtin_amdgcn_sched_barrier(0);          // issue order K, V, q: the waits in the loop count on it
+        attn_k_load(kh, kl, Kp, lo, t0 * 32, lane);
+        __builtin_amdgcn_sched_barrier(0);
+        attn_v_load(vh, vl, Vt, lo, t0, lane);
+        __builtin_amdgcn_sched_barrier(0);
+        // B operand of S^T = K Q^T: lane (j, g) holds q[j][16 t + 8 g + e]; column j is q head j of the kv group
+        uint4 qh[8], ql[8];
+        {
+            const float* qp = a.q + (size_t)(kvh * G + min(i, G - 1)) * DH + gh * 8;
+            const float sc = i < G ? g.scale : 0.f;
+#pragma unroll
+            for (int t = 0; t < 8; ++t) {
+                const float4 v0 = *reinterpret_cast<const float4*>(qp + t * 16), v1 = *reinterpret_cast<const float4*>(qp + t * 16 + 4);
+                split_pair(v0.x * sc, v0.y * sc, qh[t].x, ql[t].x); split_pair(v0.z * sc, v0.w * sc, qh[t].y, ql[t].y);
+                split_pair(v1.x * sc, v1.y * sc, qh[t].z, ql[t].z); split_pair(v1.z * sc, v1.w * sc, qh[t].w, ql[t].w);
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        for (int tile = t0; tile < t1; ++tile) {
+            const int n1 = min(tile + 1, t1 - 1);
+            attn_stage_k(kh, kl, kt, lane);
+            __builtin_amdgcn_sched_barrier(0);
+            attn_k_load(kh, kl, Kp, lo, n1 * 32, lane);
+            __builtin_amdgcn_sched_barrier(0);
+            attn_tile(st, vh, vl, qh, ql, kt, tile * 32, pos, lane);
+            __builtin_amdgcn_sched_barrier(0);
+            attn_v_load(vh, vl, Vt, lo, n1, lane);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        st.lrun += __shfl_xor(st.lrun, 32, 64);
+        if (i < G) {
+            // register r2 of accumulator dt is channel 32 dt + 8 (r2 / 4) + 4 gh + r2 % 4 of column i
+            const size_t unit = (size_t)kvh * nsplit + split;
+            float* po = a.part_o + (unit * G + i) * DH + 4 * gh;
+#pragma unroll
+            for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+                for (int q4 = 0; q4 < 4; ++q4)
+                    *reinterpret_cast<float4*>(po + dt * 32 + 8 * q4) =
+                        make_float4(st.o[dt][4 * q4], st.o[dt][4 * q4 + 1], st.o[dt][4 * q4 + 2], st.o[dt][4 * q4 + 3]);
+            if (gh == 0) {
+                float* pm = a.part_ml + unit * 2 * G;
+                pm[i] = st.mrun; pm[G + i] = st.lrun;
+            }
+        }
+    }
+
+}
+
+// Merge of the key splits: grid (Hkv, 2), workgroup y writes half of the kv group's G x 128 outputs.
+__global__ __launch_bounds__(256) void k_decode_attn_merge(DecodeAttnArgs a, Geom g) {
+    constexpr int DH = 128;
+    __shared__ float f[8 * CHUNK_ATTN_MAX_SPLIT];          // [G][nused] weights exp(m_s - M) / L
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int G = g.Hq / g.Hkv;
+    const int kvh = blockIdx.x, nsplit = a.nsplit;
+    const int ntile = (a.step->pos + 32) >> 5;
+    const int tps = (ntile + nsplit - 1) / nsplit;
+    const int nused = (ntile + tps - 1) / tps;             // splits that had keys
+    const float* ml = a.part_ml + (size_t)kvh * nsplit * 2 * G;
+    for (int gq = wave; gq < G; gq += 4) {                 // lanes over splits
+        float M = -INFINITY;
+        for (int sp = lane; sp < nused; sp += 64) M = fmaxf(M, ml[sp * 2 * G + gq]);
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) M = fmaxf(M, __shfl_xor(M, o, 64));
+        float L = 0.f;
+        for (int sp = lane; sp < nused; sp += 64) {
+            const float m = ml[sp * 2 * G + gq];
+            const float w = m > -INFINITY ? expf(m - M) : 0.f;
+            L += ml[sp * 2 * G + G + gq] * w;
+            f[gq * nused + sp] = w;
+        }
+        L = wave_sum(L);
+        const float inv = L > 0.f ? 1.f / L : 0.f;
+        for (int sp = lane; sp < nused; sp += 64) f[gq * nused + sp] *= inv;
+    }
+    __syncthreads();
+    const int half = (G * DH + 1) / 2;
+    for (int idx = blockIdx.y * half + tid; idx < min((int)(blockIdx.y + 1) * half, G * DH); idx += 256) {
+        const int gq = idx >> 7, ch = idx & (DH - 1);
+        const float* po = a.part_o + ((size_t)kvh * nsplit * G + gq) * DH + ch;
+        const float* fw = f + gq * nused;
+        float acc = 0.f;
+#pragma unroll 16
+        for (int sp = 0; sp < nused; ++sp) acc = fmaf(po[(size_t)sp * G * DH], fw[sp], acc);
+        a.out[(size_t)(kvh * G + gq) * DH + ch] = acc;
     }
 }
 
@@ -1175,21 +1294,17 @@ __global__ __launch_bounds__(256) void k_chunk_attn_wide(ChunkAttnArgs a, Geom g
 }
 
 // Merge the key splits of one (task, kv head) and emit the attention output as tiled hi/lo planes
-// (K = Hq*128), or as an fp32 vector for single-row decoding.  grid (tasks * Hkv, 4): workgroup y handles
-// channels 32 y .. 32 y + 31.
+// (K = Hq*128).  grid (tasks * Hkv, 4): workgroup y handles channels 32 y .. 32 y + 31.
 __global__ __launch_bounds__(256) void k_chunk_attn_combine(const float* __restrict__ part_o, const float* __restrict__ part_ml,
                                                             int nsplit, Geom g, const ChunkTable* __restrict__ tab,
-                                                            bf16_t* __restrict__ out_hi, bf16_t* __restrict__ out_lo,
-                                                            float* __restrict__ out_f32) {
+                                                            bf16_t* __restrict__ out_hi, bf16_t* __restrict__ out_lo) {
     constexpr int DH = 128;
     __shared__ float f[CHUNK_ATTN_MAX_SPLIT][32];          // running maximum of every split, then its weight
     __shared__ float red[8][32];
     const int tid = threadIdx.x;
     const int G = g.Hq / g.Hkv;
     const int kvh = blockIdx.x % g.Hkv;
-    ChunkTask T;
-    if (out_f32) { T.row0 = 0; T.n = 1; T.tile = 0; }     // single-row decoding: one task, no row table
-    else T = tab->task[blockIdx.x / g.Hkv];
+    const ChunkTask T = tab->task[blockIdx.x / g.Hkv];
     const float* ml = part_ml + (size_t)blockIdx.x * nsplit * 64;
     float inv;
     {
@@ -1246,14 +1361,10 @@ __global__ __launch_bounds__(256) void k_chunk_attn_combine(const float* __restr
         for (int u = 0; u < 4; ++u) {
             const int ch = blockIdx.y * 32 + dl + 8 * u;
             v[u] *= inv;
-            if (out_f32) {                                  // single-row decoding: fp32 vector [Hq][dh] (m is 0)
-                out_f32[hq * DH + ch] = v[u];
-            } else {
-                bf16_t hi, lw;
-                split_bf16(v[u], hi, lw);
-                const size_t o = tiled_off(m, hq * DH + ch, g.Hq * DH);
-                out_hi[o] = hi; out_lo[o] = lw;
-            }
+            bf16_t hi, lw;
+            split_bf16(v[u], hi, lw);
+            const size_t o = tiled_off(m, hq * DH + ch, g.Hq * DH);
+            out_hi[o] = hi; out_lo[o] = lw;
         }
     }
 }
@@ -1333,6 +1444,7 @@ hipError_t chunk_init() {
     if ((e = hipFuncSetAttribute((const void*)k_chunk_gemm<1, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)gemm_lds_bytes(1)))) return e;
     if ((e = hipFuncSetAttribute((const void*)k_chunk_attn, hipFuncAttributeMaxDynamicSharedMemorySize, ATTN_LDS_BYTES))) return e;
     if ((e = hipFuncSetAttribute((const void*)k_chunk_attn_wide, hipFuncAttributeMaxDynamicSharedMemorySize, ATTN_LDS_BYTES))) return e;
+    if ((e = hipFuncSetAttribute((const void*)k_decode_attn_mfma, hipFuncAttributeMaxDynamicSharedMemorySize, ATTN_LDS_BYTES))) return e;
     if ((e = hipFuncSetAttribute((const void*)k_chunk_gemm_ks<2, false>, hipFuncAttributeMaxDynamicSharedMemorySize, GEMM_WIDE_LDS_BYTES))) return e;
     if ((e = hipFuncSetAttribute((const void*)k_chunk_gemm_ks<2, true>, hipFuncAttributeMaxDynamicSharedMemorySize, GEMM_WIDE_LDS_BYTES))) return e;
     if ((e = hipFuncSetAttribute((const void*)k_chunk_gemm_wide<4, 1, false>, hipFuncAttributeMaxDynamicSharedMemorySize, GEMM_WIDE_LDS_BYTES))) return e;
@@ -1382,26 +1494,19 @@ hipError_t launch_chunk_gemm_swiglu(const void* W, int F, int K, const bf16_t* x
     return hipGetLastError();
 }
 
-static hipError_t chunk_attn_launch(const ChunkBuffers& c, const void* kv_layer, int nsplit, int ntasks, const Geom& g,
-                                    const DecodeBuffers* decode, hipStream_t s) {
-    float* out_f32 = decode ? decode->o : nullptr;
+hipError_t launch_chunk_attn(const ChunkBuffers& c, const void* kv_layer, int nsplit, int ntasks, const Geom& g, hipStream_t s) {
     if (nsplit < 4 || nsplit % 4 || nsplit > CHUNK_ATTN_MAX_SPLIT || ntasks < 1 || ntasks > CHUNK_MAX_TASKS ||
         (long long)ntasks * g.Hkv * nsplit > CHUNK_ATTN_MAX_UNITS)
         return hipErrorInvalidValue;
     ChunkAttnArgs a{};
     a.q_hi = c.q_hi; a.q_lo = c.q_lo; a.kv_layer = (const bf16_t*)kv_layer; a.tab = c.tab;
     a.part_o = c.attn_o; a.part_ml = c.attn_ml; a.nsplit = nsplit; a.q_cols = c.q_cols;
-    if (decode) { a.q_f32 = decode->q; a.step = decode->step; }
     hipLaunchKernelGGL(k_chunk_attn, dim3(ntasks * g.Hkv, nsplit / 4), dim3(256), ATTN_LDS_BYTES, s, a, g);
     hipError_t e = hipGetLastError();
     if (e) return e;
     hipLaunchKernelGGL(k_chunk_attn_combine, dim3(ntasks * g.Hkv, 4), dim3(256), 0, s, c.attn_o, c.attn_ml, nsplit, g, c.tab,
-                       c.att_hi, c.att_lo, out_f32);
+                       c.att_hi, c.att_lo);
     return hipGetLastError();
-}
-
-hipError_t launch_chunk_attn(const ChunkBuffers& c, const void* kv_layer, int nsplit, int ntasks, const Geom& g, hipStream_t s) {
-    return chunk_attn_launch(c, kv_layer, nsplit, ntasks, g, nullptr, s);
 }
 
 // The variant for passes made of large groups: one workgroup per block of up to four tasks, any number of key splits.
@@ -1417,14 +1522,24 @@ hipError_t launch_chunk_attn_wide(const ChunkBuffers& c, const void* kv_layer, i
     hipError_t e = hipGetLastError();
     if (e) return e;
     hipLaunchKernelGGL(k_chunk_attn_combine, dim3(ntasks * g.Hkv, 4), dim3(256), 0, s, c.attn_o, c.attn_ml, nsplit, g, c.tab,
-                       c.att_hi, c.att_lo, (float*)nullptr);
+                       c.att_hi, c.att_lo);
     return hipGetLastError();
 }
 
 hipError_t launch_decode_attn_mfma(const ChunkBuffers& c, const void* kv_layer, int nsplit, const DecodeBuffers& b, const Geom& g,
                                    hipStream_t s) {
-    if (g.dh != 128 || g.Hq / g.Hkv > 32) return hipErrorInvalidValue;
-    return chunk_attn_launch(c, kv_layer, nsplit, 1, g, &b, s);
+    const int G = g.Hq / g.Hkv;
+    if (g.dh != 128 || G > 8 || nsplit < 4 || nsplit % 4 || nsplit > CHUNK_ATTN_MAX_SPLIT ||
+        (long long)g.Hkv * nsplit > CHUNK_ATTN_MAX_UNITS)
+        return hipErrorInvalidValue;
+    DecodeAttnArgs a{};
+    a.q = b.q; a.step = b.step; a.kv_layer = (const bf16_t*)kv_layer;
+    a.part_o = c.attn_o; a.part_ml = c.attn_ml; a.out = b.o; a.nsplit = nsplit;
+    hipLaunchKernelGGL(k_decode_attn_mfma, dim3(g.Hkv, nsplit / 4), dim3(256), ATTN_LDS_BYTES, s, a, g);
+    hipError_t e = hipGetLastError();
+    if (e) return e;
+    hipLaunchKernelGGL(k_decode_attn_merge, dim3(g.Hkv, 2), dim3(256), 0, s, a, g);
+    return hipGetLastError();
 }
 
 }  // namespace asynclm

@@ -141,8 +141,8 @@ def test_append_chunk_sizes_agree_with_oracle_and_each_other(trunc4):
 @pytest.mark.timeout(600)
 def test_decode_attention_split_counts_agree_with_oracle(trunc4):
     """Decode attention with forced split counts: up to 8 splits are merged by the O projection, more by the
-    last workgroup of each kv head, and the matrix-core variant used for long contexts (negative entries), on
-    the grouped-query bf16 shape."""
+    last workgroup of each kv head (the single-row kernel, switched on for this model by attn_mfma_min = 0), and the
+    matrix-core variant that such models use by default (negative entries), on the grouped-query bf16 shape."""
     import paper_2412_07017_amd as pkg
     wl, model, w_dev, w_cpu, spec = trunc4
     toks = spec["prompt"][:300]
@@ -154,9 +154,8 @@ def test_decode_attention_split_counts_agree_with_oracle(trunc4):
     for nsplit in (1, 3, 8, 9, 24, 64, -4, -12, -64, -128):
         lm = pkg.AsyncLM(model, w_dev, max_positions=320, stream=torch.cuda.Stream())
         lm.set_option("chunk", 1)                 # the prompt goes through the decode kernels too
-        if nsplit < 0:                            # the long-context variant: matrix-core attention for single rows
-            lm.set_option("attn_mfma_min", 1)
-            nsplit = -nsplit
+        lm.set_option("attn_mfma_min", 1 if nsplit < 0 else 0)    # negative: matrix-core attention for single rows
+        nsplit = abs(nsplit)
         lm.set_option("attn_split", nsplit)
         lm.prefill(0, toks[:280])
         lm.inject_interrupt(0, toks[280:])
