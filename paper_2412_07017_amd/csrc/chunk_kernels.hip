@@ -75,10 +75,11 @@ __global__ __launch_bounds__(256) void k_chunk_embed(const bf16_t* __restrict__ 
 constexpr int ROW_VEC_MAX = 8;      // float4 groups per thread of a row kernel: d <= 8192
 
 // One row by one workgroup: v = x[m] + sum_s P[s][row pm] (S <= CHUNK_GEMM_MAX_SPLIT planes; all loads of the
-// row are issued before the first use), returns the sum of squares over the workgroup.  Thread tid owns the
-// float4 groups tid + 256 u.
+// row are issued before the first use, the gain's of the following norm among them), returns the sum of squares
+// over the workgroup.  Thread tid owns the float4 groups tid + 256 u.
 __device__ __forceinline__ float row_gather(const float* __restrict__ xr, const float* __restrict__ Pr, int S,
-                                            size_t s_stride, int d4, int tid, float4 (&v)[ROW_VEC_MAX], float* red) {
+                                            size_t s_stride, int d4, int tid, const float* __restrict__ gain,
+                                            float4 (&v)[ROW_VEC_MAX], float4 (&gn)[ROW_VEC_MAX], float* red) {
     const float4* x4 = reinterpret_cast<const float4*>(xr);
     float ss = 0.f;
 #pragma unroll
@@ -90,6 +91,7 @@ __device__ __forceinline__ float row_gather(const float* __restrict__ xr, const 
             for (int u = 0; u < HU; ++u) {
                 const int i4 = min(tid + 256 * (hf * HU + u), d4 - 1);      // past the end: a repeated load, dropped below
                 v[hf * HU + u] = x4[i4];
+                gn[hf * HU + u] = reinterpret_cast<const float4*>(gain)[i4];
 #pragma unroll
                 for (int s = 0; s < CHUNK_GEMM_MAX_SPLIT; ++s)
                     p[u][s] = Pr ? reinterpret_cast<const float4*>(Pr + (size_t)min(s, S - 1) * s_stride)[i4] : make_float4(0.f, 0.f, 0.f, 0.f);
@@ -106,7 +108,7 @@ __device__ __forceinline__ float row_gather(const float* __restrict__ xr, const 
             }
         } else {
 #pragma unroll
-            for (int u = 0; u < HU; ++u) v[hf * HU + u] = make_float4(0.f, 0.f, 0.f, 0.f);
+            for (int u = 0; u < HU; ++u) { v[hf * HU + u] = make_float4(0.f, 0.f, 0.f, 0.f); gn[hf * HU + u] = v[hf * HU + u]; }
         }
     }
     ss = wave_sum(ss);
@@ -117,14 +119,14 @@ __device__ __forceinline__ float row_gather(const float* __restrict__ xr, const 
 }
 
 // v * sc * gain -> tiled bf16 hi/lo planes at row `mo`
-__device__ __forceinline__ void row_emit(const float4 (&v)[ROW_VEC_MAX], float sc, const float* __restrict__ gain, int d,
+__device__ __forceinline__ void row_emit(const float4 (&v)[ROW_VEC_MAX], float sc, const float4 (&gain)[ROW_VEC_MAX], int d,
                                          int tid, int mo, bf16_t* __restrict__ out_hi, bf16_t* __restrict__ out_lo) {
     const int d4 = d >> 2;
 #pragma unroll
     for (int u = 0; u < ROW_VEC_MAX; ++u) {
         const int i4 = tid + 256 * u;
         if (i4 < d4) {
-            const float4 gn = reinterpret_cast<const float4*>(gain)[i4];
+            const float4 gn = gain[u];
             bf16_t h0, l0, h1, l1, h2, l2, h3, l3;
             split_bf16(v[u].x * sc * gn.x, h0, l0); split_bf16(v[u].y * sc * gn.y, h1, l1);
             split_bf16(v[u].z * sc * gn.z, h2, l2); split_bf16(v[u].w * sc * gn.w, h3, l3);
@@ -144,14 +146,14 @@ __global__ __launch_bounds__(256) void k_chunk_resid_norm(float* __restrict__ x,
     __shared__ float red[4];
     const int m = blockIdx.x, tid = threadIdx.x, d4 = d >> 2;
     float* xr = x + (size_t)m * d;
-    float4 v[ROW_VEC_MAX];
-    const float ss = row_gather(xr, P ? P + (size_t)m * n_stride : nullptr, S, s_stride, d4, tid, v, red);
+    float4 v[ROW_VEC_MAX], gn[ROW_VEC_MAX];
+    const float ss = row_gather(xr, P ? P + (size_t)m * n_stride : nullptr, S, s_stride, d4, tid, gain, v, gn, red);
     if (P) {
 #pragma unroll
         for (int u = 0; u < ROW_VEC_MAX; ++u)
             if (tid + 256 * u < d4) reinterpret_cast<float4*>(xr)[tid + 256 * u] = v[u];
     }
-    row_emit(v, rsqrtf(ss / (float)d + eps), gain, d, tid, m, out_hi, out_lo);
+    row_emit(v, rsqrtf(ss / (float)d + eps), gn, d, tid, m, out_hi, out_lo);
 }
 
 // Last row of group `group` only: out[:] = x[row] + sum_s P[s][row]  (residual stream handed to the
@@ -179,9 +181,9 @@ __global__ __launch_bounds__(256) void k_chunk_head_rows(const float* __restrict
     const ChunkGroup G = tab->group[blockIdx.x];
     if (G.head < 0) return;
     const int row = G.row0 + G.n - 1, tid = threadIdx.x, d4 = d >> 2;
-    float4 v[ROW_VEC_MAX];
-    const float ss = row_gather(x + (size_t)row * d, P + (size_t)row * n_stride, S, s_stride, d4, tid, v, red);
-    row_emit(v, rsqrtf(ss / (float)d + eps), gain, d, tid, G.head, out_hi, out_lo);
+    float4 v[ROW_VEC_MAX], gn[ROW_VEC_MAX];
+    const float ss = row_gather(x + (size_t)row * d, P + (size_t)row * n_stride, S, s_stride, d4, tid, gain, v, gn, red);
+    row_emit(v, rsqrtf(ss / (float)d + eps), gn, d, tid, G.head, out_hi, out_lo);
 }
 
 // Workgroup = group that wants logits: row `head` of the output-head product -> logits of its sequence,
