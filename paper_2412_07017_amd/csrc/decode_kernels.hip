@@ -287,7 +287,7 @@ static hipError_t launch_gemv_n(const GemvArgs& a, size_t lds, const Geom& g, hi
 
 // Early request of the vector when it is a plain one that fits one batch: 4 or 8 x 16 bytes per thread (with as
 // many of the gain) in the normalising products, 4 or 16 in the residual ones.
-template <int EPI> struct EarlyNB { static constexpr int SMALL = 4, LARGE = EPI == EPI_RESID ? 16 : 8; };
+template <int EPI> struct EarlyNB { static constexpr int SMALL = 4, LARGE = EPI == EPI_RESID ? 16 : 8, HUGE = 32; };
 
 template <typename WT, int EPI>
 static hipError_t launch_gemv_t(const GemvArgs& a0, const Geom& g, hipStream_t s) {
@@ -301,6 +301,7 @@ static hipError_t launch_gemv_t(const GemvArgs& a0, const Geom& g, hipStream_t s
     if (EPI == EPI_RESID && a.gain) return hipErrorInvalidValue;
     if (a.x && a.K <= 1024 * EarlyNB<EPI>::SMALL) return launch_gemv_n<WT, EPI, EarlyNB<EPI>::SMALL>(a, lds, g, s);
     if (a.x && a.K <= 1024 * EarlyNB<EPI>::LARGE) return launch_gemv_n<WT, EPI, EarlyNB<EPI>::LARGE>(a, lds, g, s);
+    if (EPI == EPI_RESID && a.x && a.K <= 1024 * EarlyNB<EPI>::HUGE) return launch_gemv_n<WT, EPI_RESID, EarlyNB<EPI_RESID>::HUGE>(a, lds, g, s);
     return launch_gemv_n<WT, EPI, 0>(a, lds, g, s);
 }
 
@@ -319,7 +320,9 @@ static hipError_t set_lds_t(int bytes) {
     hipError_t e;
     if ((e = hipFuncSetAttribute((const void*)(k_gemv<WT, EPI, 0>), hipFuncAttributeMaxDynamicSharedMemorySize, bytes))) return e;
     if ((e = hipFuncSetAttribute((const void*)(k_gemv<WT, EPI, EarlyNB<EPI>::SMALL>), hipFuncAttributeMaxDynamicSharedMemorySize, bytes))) return e;
-    return hipFuncSetAttribute((const void*)(k_gemv<WT, EPI, EarlyNB<EPI>::LARGE>), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if ((e = hipFuncSetAttribute((const void*)(k_gemv<WT, EPI, EarlyNB<EPI>::LARGE>), hipFuncAttributeMaxDynamicSharedMemorySize, bytes))) return e;
+    if (EPI != EPI_RESID) return hipSuccess;
+    return hipFuncSetAttribute((const void*)(k_gemv<WT, EPI_RESID, EarlyNB<EPI_RESID>::HUGE>), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
 }
 
 void decode_set_gemv_grid(int grid) { g_gemv_grid = grid; }
