@@ -1143,7 +1143,8 @@ __global__ __launch_bounds__(256) void k_decode_attn_mfma(DecodeAttnArgs a, Geom
 
 }
 
-// Merge of the key splits: grid (Hkv, 2), workgroup y writes half of the kv group's G x 128 outputs.
+// Merge of the key splits: grid (Hkv, Y), workgroup y writes its share of the kv group's G x 128 outputs (Y = G / 2:
+// one output per thread).
 __global__ __launch_bounds__(256) void k_decode_attn_merge(DecodeAttnArgs a, Geom g) {
     constexpr int DH = 128;
     __shared__ float f[8 * CHUNK_ATTN_MAX_SPLIT];          // [G][nused] weights exp(m_s - M) / L
@@ -1171,8 +1172,8 @@ __global__ __launch_bounds__(256) void k_decode_attn_merge(DecodeAttnArgs a, Geo
         for (int sp = lane; sp < nused; sp += 64) f[gq * nused + sp] *= inv;
     }
     __syncthreads();
-    const int half = (G * DH + 1) / 2;
-    for (int idx = blockIdx.y * half + tid; idx < min((int)(blockIdx.y + 1) * half, G * DH); idx += 256) {
+    const int per = (G * DH + (int)gridDim.y - 1) / (int)gridDim.y;
+    for (int idx = blockIdx.y * per + tid; idx < min((int)(blockIdx.y + 1) * per, G * DH); idx += 256) {
         const int gq = idx >> 7, ch = idx & (DH - 1);
         const float* po = a.part_o + ((size_t)kvh * nsplit * G + gq) * DH + ch;
         const float* fw = f + gq * nused;
@@ -1540,7 +1541,7 @@ hipError_t launch_decode_attn_mfma(const ChunkBuffers& c, const void* kv_layer, 
     hipLaunchKernelGGL(k_decode_attn_mfma, dim3(g.Hkv, nsplit / 4), dim3(256), ATTN_LDS_BYTES, s, a, g);
     hipError_t e = hipGetLastError();
     if (e) return e;
-    hipLaunchKernelGGL(k_decode_attn_merge, dim3(g.Hkv, 2), dim3(256), 0, s, a, g);
+    hipLaunchKernelGGL(k_decode_attn_merge, dim3(g.Hkv, std::max(1, G / 2)), dim3(256), 0, s, a, g);
     return hipGetLastError();
 }
 
