@@ -167,6 +167,29 @@ def test_decode_attention_split_counts_agree_with_oracle(trunc4):
         assert e0 <= TOL and e1 <= TOL, nsplit
 
 
+@pytest.mark.timeout(600)
+def test_decode_from_a_one_token_context_across_the_first_key_tiles(trunc4):
+    """Single-row decoding from a one-token prompt: the matrix-core attention starts with one 32-key tile in one of
+    its four splits (three waves without keys), crosses into the second and third tile, and the merge has to ignore
+    the splits that had no keys; every step's logits against the oracle."""
+    import paper_2412_07017_amd as pkg
+    wl, model, w_dev, w_cpu, spec = trunc4
+    toks = spec["prompt"]
+    dec = orc.CachedDecoder(orc.Shape.of(model), w_cpu, dtype=np.float32)
+    dec.prefill(toks[:1])
+    lm = pkg.AsyncLM(model, w_dev, max_positions=128, stream=torch.cuda.Stream())
+    lm.prefill(0, toks[:1])
+    worst = float(np.abs(lm.logits(0) - dec.logits).max())
+    for j in range(70):
+        t = int(toks[1 + j])
+        dec.decode_step(forced=t)
+        assert lm.decode_step(0, forced_token=t) == t
+        worst = max(worst, float(np.abs(lm.logits(0) - dec.logits).max()))
+    lm.close()
+    print("one-token context, 70 steps: max |logit err| = %.3e" % worst)
+    assert worst <= TOL
+
+
 @pytest.mark.timeout(900)
 def test_single_plane_bf16_cache_matches_oracle_with_rounded_cache(trunc4):
     """The 2-byte cache format (hi plane only) rounds K and V to bf16 when they are written.  That
