@@ -193,6 +193,9 @@ def bench_ragged(args):
                                   model.ffn, model.vocab, model.dtype, ns, min(map(len, spec["prompts"])), max(map(len, spec["prompts"]))),
                    "context_tokens_total": [len_start, len_end], "rows_per_step": rows / timed, "seed": ai.MASTER_SEED},
         "batch_ms_per_step": ms_step, "batch_hbm_frac": ach / HBM_PEAK, "batch_bytes_per_step": bytes_step,
+        # the same with the K/V bytes that the attention actually reads (the cache keeps every value as two bf16 planes)
+        "batch_hbm_frac_as_stored": (bytes_step + (len_start + len_end) / 2.0 * model.kv_bytes_per_position())
+                                    / (ms_step * 1e-3) / HBM_PEAK if model.dtype == "bf16" else ach / HBM_PEAK,
         "prefill_s": t_prefill, "weights_s": t_weights,
         "roofline": {"bound": "hbm", "kernel": "whole batched step (all kernels of one pass)", "achieved": ach / 1e9,
                      "peak": HBM_PEAK / 1e9, "unit": "GB/s", "frac": ach / HBM_PEAK, "traffic": None,
