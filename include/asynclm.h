@@ -102,8 +102,11 @@ int asynclm_prefill(asynclm_ctx *ctx, int32_t seq, const int32_t *tokens, int32_
 /* One decoding step (Fig. 4): choose the next token - `forced_token` if >= 0, else the greedy
  * argmax of the current logits, lowest index on ties, computed on the device - append it to the
  * sequence and run one forward pass, leaving the logits for the token after it.
- * token_out (host pointer, may be NULL): receives the chosen token; passing NULL avoids the
- * stream synchronisation that reading it back needs. */
+ * token_out (host pointer, may be NULL): receives the chosen token.  The call waits only until the
+ * token has been chosen (the first kernel of the step), not for the forward pass, which is still
+ * running when it returns: the caller (the token monitor of Sec. 5.3) works on the token while
+ * the device computes, and the next call queues behind the running step.  (With the "fused"
+ * option the call waits for the whole step.)  NULL: nothing is waited for. */
 int asynclm_decode_step(asynclm_ctx *ctx, int32_t seq, int32_t forced_token, int32_t *token_out);
 
 /* In-flight interrupt injection (Sec. 3.2, 5.3): append the k >= 1 tokens (host pointer) to the end

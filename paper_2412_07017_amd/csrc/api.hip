@@ -71,7 +71,9 @@ struct asynclm_ctx {
     bool want_trace = false;
     std::vector<unsigned long long> last_trace;  // raw stamps [stamp][workgroup] of the last profiled fused step
     int last_trace_stamps = 0;
-    int32_t* token_host = nullptr;      // pinned, 1 int
+    int32_t* token_host = nullptr;      // pinned, 16 ints: [0..1] staging of read-backs, [4] the token of the running step (early copy)
+    hipEvent_t tok_event = nullptr;     // recorded right after the step's token has been chosen
+    bool tok_early = false;             // the last decoding step left its token in token_host[4] behind tok_event
 
     std::vector<int32_t> len;           // host mirror of the sequence lengths
     std::vector<int32_t> nban;          // host mirror of the number of banned token ids per sequence
@@ -219,6 +221,7 @@ hipError_t refresh_choice(asynclm_ctx* c, int seq) {
 
 hipError_t step_one_token(asynclm_ctx* c, int seq, int forced, bool with_head) {
     hipError_t e;
+    c->tok_early = false;
     if (forced < 0 && (e = refresh_choice(c, seq))) return e;
     if (c->opt_fused && c->nban[seq] == 0) {      // the single-kernel step has no token mask
         FusedLaunch L{};
@@ -237,7 +240,13 @@ hipError_t step_one_token(asynclm_ctx* c, int seq, int forced, bool with_head) {
         return hipSuccess;
     }
     const SplitPlan sp = pick_nsplit(c, c->len[seq] + 1);
-    if ((e = run(c, KC_BEGIN, [&] { return launch_begin_step(c->b, seq, forced, c->stream); }))) return e;
+    // the chosen token also goes to pinned host memory, and an event marks the point: asynclm_decode_step waits for that
+    // event only, so the host has the token while the forward pass is still running
+    if ((e = run(c, KC_BEGIN, [&] { return launch_begin_step(c->b, seq, forced, c->tok_event ? c->token_host + 4 : nullptr, c->stream); }))) return e;
+    if (c->tok_event && !c->prof) {
+        if ((e = hipEventRecord(c->tok_event, c->stream))) return e;
+        c->tok_early = true;
+    }
     if (c->opt_graph && !c->prof) e = forward_single_graph(c, seq, with_head, sp);
     else e = forward_single(c, seq, with_head, sp);
     if (e) return e;
@@ -557,6 +566,8 @@ int asynclm_create(asynclm_ctx** out, const asynclm_config* cfg, const asynclm_w
         hipMemset(c->b.step, 0, sizeof(StepDesc)) != hipSuccess || hipMemset(c->b.token_log, 0, 2 * sizeof(int32_t)) != hipSuccess)
         return bail(ASYNCLM_E_DEVICE);
     if (hipHostMalloc((void**)&c->token_host, 64, hipHostMallocDefault) != hipSuccess) return bail(ASYNCLM_E_NOMEM);
+    std::memset(c->token_host, 0, 64);
+    if (hipEventCreateWithFlags(&c->tok_event, hipEventDisableTiming) != hipSuccess) return bail(ASYNCLM_E_DEVICE);
     if (hipHostMalloc((void**)&c->chosen_host, sizeof(int32_t) * CHUNK_MAX, hipHostMallocDefault) != hipSuccess) return bail(ASYNCLM_E_NOMEM);
     // fused decoding step: pointer table, barrier counters, launch plan
     {
@@ -592,6 +603,7 @@ int asynclm_destroy(asynclm_ctx* c) {
     for (hipEvent_t ev : c->prof_events) hipEventDestroy(ev);
     for (void* p : c->allocs) hipFree(p);
     if (c->token_host) hipHostFree(c->token_host);
+    if (c->tok_event) hipEventDestroy(c->tok_event);
     if (c->chosen_host) hipHostFree(c->chosen_host);
     delete c;
     return ASYNCLM_OK;
@@ -614,6 +626,11 @@ int asynclm_decode_step(asynclm_ctx* c, int32_t seq, int32_t forced_token, int32
     if (c->len[seq] + 1 > c->cfg.max_positions) return ASYNCLM_E_CAPACITY;
     HIPCK(c, step_one_token(c, seq, forced_token < 0 ? -1 : forced_token, true));
     if (token_out) {
+        if (c->tok_early) {                         // per-operation step: wait for the choice only
+            HIPCK(c, hipEventSynchronize(c->tok_event));
+            *token_out = c->token_host[4];
+            return ASYNCLM_OK;
+        }
         HIPCK(c, hipMemcpyAsync(c->token_host, c->b.token_log, 2 * sizeof(int32_t), hipMemcpyDeviceToHost, c->stream));
         HIPCK(c, hipStreamSynchronize(c->stream));
         if (c->token_host[1]) return fail_device(c, hipErrorLaunchFailure);

@@ -16,7 +16,9 @@ namespace asynclm {
 
 // Chooses the token of this step (forced, or the greedy one left by the previous forward pass),
 // publishes it and its position to the step descriptor, and grows the sequence by one.
-__global__ void k_begin_step(StepDesc* step, SeqState* st, int32_t seq, int32_t forced, int32_t* token_log) {
+// token_early: optional host-visible word that also receives the token, so that the host can read it as soon as this
+// kernel has run instead of after the whole step.
+__global__ void k_begin_step(StepDesc* step, SeqState* st, int32_t seq, int32_t forced, int32_t* token_log, int32_t* token_early) {
     if (threadIdx.x == 0 && blockIdx.x == 0) {
         SeqState s = st[seq];
         int32_t tok = forced >= 0 ? forced : s.next_token;
@@ -26,6 +28,7 @@ __global__ void k_begin_step(StepDesc* step, SeqState* st, int32_t seq, int32_t 
         step->rows = 1;
         st[seq].len = s.len + 1;
         *token_log = tok;
+        if (token_early) *token_early = tok;
     }
 }
 
@@ -356,8 +359,8 @@ static hipError_t launch_gemv(int dtype, int epi, const GemvArgs& a, const Geom&
     return dtype == 0 ? launch_gemv_w<float>(epi, a, g, s) : launch_gemv_w<bf16_t>(epi, a, g, s);
 }
 
-hipError_t launch_begin_step(const DecodeBuffers& b, int seq, int forced, hipStream_t s) {
-    hipLaunchKernelGGL(k_begin_step, dim3(1), dim3(64), 0, s, b.step, b.seq_state, seq, forced, b.token_log);
+hipError_t launch_begin_step(const DecodeBuffers& b, int seq, int forced, int32_t* token_early, hipStream_t s) {
+    hipLaunchKernelGGL(k_begin_step, dim3(1), dim3(64), 0, s, b.step, b.seq_state, seq, forced, b.token_log, token_early);
     return hipGetLastError();
 }
 

@@ -130,7 +130,8 @@ hipError_t launch_chunk_attn_wide(const ChunkBuffers& c, const void* kv_layer, i
 // single-row decoding attention on the matrix cores (long contexts): b.q -> b.o through the chunk attention
 hipError_t launch_decode_attn_mfma(const ChunkBuffers& c, const void* kv_layer, int nsplit, const DecodeBuffers& b, const Geom& g,
                                    hipStream_t s);
-hipError_t launch_begin_step(const DecodeBuffers& b, int seq, int forced, hipStream_t s);
+// token_early: pinned host word that also gets the chosen token (or nullptr)
+hipError_t launch_begin_step(const DecodeBuffers& b, int seq, int forced, int32_t* token_early, hipStream_t s);
 hipError_t launch_embed(int dtype, const void* E, const DecodeBuffers& b, const Geom& g, hipStream_t s);
 hipError_t launch_qkv(int dtype, const void* wqkv, const float* gain, void* kv_layer, const DecodeBuffers& b,
                       const Geom& g, hipStream_t s);
