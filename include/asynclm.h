@@ -183,6 +183,12 @@ int asynclm_synchronize(asynclm_ctx *ctx);
  *                  model shape allow it; ignored otherwise), 0 = one kernel per operation (default)
  *   "graph"        (per-operation kernels only) 1 = replay decoding steps as a captured HIP graph,
  *                  0 = launch kernels one by one
+ *   "pipeline"     (per-operation kernels only) 1 = run a decoding step with its kernels alternating between the
+ *                  caller's stream and a second stream of the library's, neighbouring kernels overlapping and handing
+ *                  over through counters in device memory instead of kernel boundaries (contexts up to 2048 tokens,
+ *                  models of which two workgroups per kernel fit a compute unit; ignored otherwise); 0 (default) = one
+ *                  stream.  Same arithmetic per kernel (bf16 models take the single-row attention kernel here, so their
+ *                  logits agree with the default within rounding).  Measured slower than the default on the 8B shape.
  *   "attn_split"   0 = choose the number of sequence splits of decode attention from the length,
  *                  1..128 = always use n (at most 64 apply to the single-row attention kernel, at most 128,
  *                  rounded up to a multiple of 4, to its matrix-core variant)
@@ -199,7 +205,11 @@ int asynclm_set_option(asynclm_ctx *ctx, const char *name, int32_t value);
 int asynclm_profile_step(asynclm_ctx *ctx, int32_t seq, int32_t forced_token, const char *const **names_out,
                          float *ms_out, int32_t *launches_out, int32_t cap);
 
-/* Raw time stamps of the last asynclm_profile_step that ran as the fused kernel: out_host[i * n_workgroups + w]
+/* Raw time stamps.  After a decoding step that ran on two streams ("pipeline"): n_workgroups = 2 and, for kernel k
+ * of the step (per layer: QKV, attention, O, gate/up, down; then the output head), out_host[(3 k + j) * 2 + w] is the
+ * 100 MHz device clock at j = 0 kernel start, 1 hand-over from the previous kernel seen, 2 done, of w = 0 the first
+ * workgroup (done: the workgroup that finished first), w = 1 the last one (done: the one that finished last).
+ * Otherwise, of the last asynclm_profile_step that ran as the fused kernel: out_host[i * n_workgroups + w]
  * is the 100 MHz device clock of workgroup w at phase boundary i (per layer: end of QKV, barrier passed, end of
  * attention, barrier, end of merge, barrier, end of O, barrier, end of gate/up, barrier, end of down, barrier;
  * stamp 0 is the first barrier, the last two are the output head and its barrier).  Call with out_host = NULL

@@ -50,6 +50,14 @@ struct asynclm_ctx {
     asynclm_config cfg{};
     Geom g{};
     hipStream_t stream = nullptr;
+    hipStream_t stream2 = nullptr;      // library-owned: every other kernel of a two-stream decoding step
+    hipEvent_t ev_fork = nullptr, ev_join = nullptr;
+    bool pipe_ok = false;               // two workgroups of every single-row kernel fit one compute unit
+    unsigned long long* pipe_stamps = nullptr;   // per kernel of the step: see pipe_stamp
+    int pipe_kernels = 0;               // kernels of the last two-stream step (0: the last step was not one)
+    int pipe_kernels_max = 0;
+    unsigned* pipe_go = nullptr;        // [PIPE_REGIONS][PIPE_MAX_WORKGROUPS] hand-over words, one per cache line
+    unsigned* pipe_counters = nullptr;  // [pipe_kernels_max] arrival counters, one per cache line
     int device = 0, n_cu = 0;
     bool poisoned = false;
     hipError_t last_hip = hipSuccess;
@@ -83,6 +91,7 @@ struct asynclm_ctx {
 
     // options
     int opt_chunk = 1, opt_graph = 1, opt_attn_split = 0, opt_chunk_split = 0, opt_fused = 0, opt_attn_mfma_min = 1;
+    int opt_pipeline = 0;
 
     std::map<int, hipGraphExec_t> graphs;   // key: nsplit * 2 + with_head
 
@@ -143,8 +152,8 @@ void* kv_layer_ptr(const asynclm_ctx* c, int layer) {
 // splits with a merge step of their own.
 struct SplitPlan { int nsplit; bool merge_in_oproj; bool mfma; };
 
-SplitPlan pick_nsplit(const asynclm_ctx* c, int len_after) {
-    if (c->chunk_ok && c->opt_attn_mfma_min > 0 && len_after >= c->opt_attn_mfma_min) {
+SplitPlan pick_nsplit(const asynclm_ctx* c, int len_after, bool single_row_kernel = false) {
+    if (!single_row_kernel && c->chunk_ok && c->opt_attn_mfma_min > 0 && len_after >= c->opt_attn_mfma_min) {
         // attention on the matrix cores.  Measured optima: one tile of 32 keys per wave up to about 96 tiles (36 splits
         // for 35 tiles, 68 for 66), 68-96 splits for 132 tiles, 96 for 260 and 513 (more only lengthen the merge)
         const int tiles = (len_after + 31) / 32;
@@ -189,16 +198,84 @@ hipError_t forward_single(asynclm_ctx* c, int seq, bool with_head, SplitPlan sp)
     return hipSuccess;
 }
 
+// The same pass with its kernels alternating between two streams, so that two neighbouring kernels run at the same
+// time: while kernel n streams its weights and finishes, kernel n + 1 is already resident, has its first weight tiles
+// in flight, and waits for kernel n's hand-over counter (PipeSync) before it reads kernel n's output.  Kernel n + 2
+// follows kernel n on the same stream, so at most two kernels are in flight; two workgroups of any of them fit one
+// compute unit (pipe_ok) and none launches more workgroups than there are compute units, so all workgroups of both
+// are resident whatever the order of dispatch and no wait can starve the kernel it waits for.  The attention is the
+// single-row kernel with at most 8 key splits, merged by the O projection while it stages its input.
+// Visibility without fences (a device-scope release / acquire pair per workgroup writes back and invalidates a whole
+// L2 and costs about 10 us once 256 workgroups do it): producers store their results write-through and signal after
+// the stores have completed; a consumer reads them with ordinary loads, which cannot hit a stale line, because its
+// die's L2 was invalidated when the consumer was dispatched, after every earlier reader of those buffers had ended,
+// and nothing reads them again before the producer writes: no vector is updated in place (the residual stream
+// alternates between b.x and b.x2), and before its hand-over a kernel reads nothing but weights.
+// Measured on the 8B shape (time stamps of asynclm_profile_trace): a hand-over takes about 1 us, but the step is
+// slower than the one-stream step (3.7 against 3.4 ms per token): what follows a hand-over - the input vector's round
+// trip to memory, the last tiles, the write-through of the results, the counter, the hand-over words - is a chain of
+// five to six memory round trips per kernel during which little is streamed, where a kernel of the one-stream step
+// overlaps the same chain with its own first 32 MB of weights.  Kept as an option ("pipeline"), off by default.
+hipError_t forward_single_pipelined(asynclm_ctx* c, int seq, bool with_head, SplitPlan sp) {
+    const int dt = c->cfg.dtype;
+    const Geom& g = c->g;
+    hipStream_t sa = c->stream, sb = c->stream2;
+    hipError_t e;
+    if ((e = launch_embed(dt, c->embed, c->b, g, sa))) return e;
+    if ((e = hipEventRecord(c->ev_fork, sa))) return e;
+    if ((e = hipStreamWaitEvent(sb, c->ev_fork, 0))) return e;
+    int idx = 0;
+    hipStream_t s = sa;
+    PipeSync ps{};
+    // kernel k: arrival counter k, signals region k % PIPE_REGIONS, waits on region (k - 1) % PIPE_REGIONS
+    auto next = [&]() {
+        const size_t region = (size_t)PIPE_MAX_WORKGROUPS * PIPE_LINE_WORDS;
+        ps.go_wait = idx > 0 ? c->pipe_go + (size_t)((idx - 1) % PIPE_REGIONS) * region : nullptr;
+        ps.go_signal = c->pipe_go + (size_t)(idx % PIPE_REGIONS) * region;
+        ps.counter = c->pipe_counters + (size_t)idx * PIPE_LINE_WORDS;
+        ps.abort = c->b.pipe_abort;
+        ps.error_word = c->b.token_log + 1;
+        ps.step = c->b.step;
+        ps.wait_kernel = (unsigned)(idx > 0 ? idx - 1 : 0); ps.my_kernel = (unsigned)idx;
+        ps.stamps = c->pipe_stamps ? c->pipe_stamps + (size_t)idx * 6 : nullptr;
+        s = (idx & 1) ? sb : sa;
+        ++idx;
+    };
+    for (int l = 0; l < c->cfg.n_layers; ++l) {
+        void* kvl = kv_layer_ptr(c, l);
+        next(); if ((e = launch_qkv(dt, c->wqkv[l], c->attn_norm[l], kvl, c->b, g, s, &ps))) return e;
+        next(); if ((e = launch_attn_decode(dt, kvl, sp.nsplit, true, c->b, g, s, &ps))) return e;
+        next(); if ((e = launch_oproj(dt, c->wo[l], sp.nsplit, c->b, g, s, &ps, c->b.x2))) return e;
+        next(); if ((e = launch_gateup(dt, c->wgate_up[l], c->ffn_norm[l], c->b, g, s, &ps, c->b.x2))) return e;
+        next(); if ((e = launch_down(dt, c->wdown[l], c->b, g, s, &ps, c->b.x2))) return e;
+    }
+    if (with_head) {
+        next(); if ((e = launch_lmhead(dt, c->lm_head, c->final_norm, c->logits + (size_t)seq * g.V, c->b, g, s, &ps))) return e;
+    }
+    if ((e = hipEventRecord(c->ev_join, sb))) return e;
+    if ((e = hipStreamWaitEvent(sa, c->ev_join, 0))) return e;
+    if (with_head && (e = launch_argmax(c->logits, c->b, g, sa))) return e;
+    return hipSuccess;
+}
+
+bool use_pipeline(const asynclm_ctx* c, int len_after) {
+    // (contexts beyond what 8 key splits of the single-row attention cover take the one-stream step)
+    return c->opt_pipeline && c->pipe_ok && !c->prof && c->opt_attn_split == 0 && len_after <= 2048 &&
+           5 * c->cfg.n_layers + 1 <= c->pipe_kernels_max && decode_gemv_grid() <= c->n_cu && decode_gemv_grid() <= PIPE_MAX_WORKGROUPS &&
+           c->g.Hkv * 8 <= PIPE_MAX_WORKGROUPS;      // at most 8 key splits reach this step
+}
+
 // The same pass, replayed from a captured graph (one graph per split count / head flag / sequence).
-hipError_t forward_single_graph(asynclm_ctx* c, int seq, bool with_head, SplitPlan sp) {
+hipError_t forward_single_graph(asynclm_ctx* c, int seq, bool with_head, SplitPlan sp, bool pipelined) {
     constexpr int SPLIT_SLOTS = (ATTN_MAX_SPLIT > CHUNK_ATTN_MAX_SPLIT ? ATTN_MAX_SPLIT : CHUNK_ATTN_MAX_SPLIT) + 1;
-    const int key = (((((seq * SPLIT_SLOTS + sp.nsplit) << 1) | (sp.merge_in_oproj ? 1 : 0)) << 1 | (sp.mfma ? 1 : 0)) << 1) | (with_head ? 1 : 0);
+    const int key = ((((((seq * SPLIT_SLOTS + sp.nsplit) << 1) | (sp.merge_in_oproj ? 1 : 0)) << 1 | (sp.mfma ? 1 : 0)) << 1) | (with_head ? 1 : 0)) << 1 |
+                    (pipelined ? 1 : 0);
     auto it = c->graphs.find(key);
     if (it == c->graphs.end()) {
         hipError_t e;
         hipGraph_t graph = nullptr;
         if ((e = hipStreamBeginCapture(c->stream, hipStreamCaptureModeRelaxed))) return e;
-        e = forward_single(c, seq, with_head, sp);
+        e = pipelined ? forward_single_pipelined(c, seq, with_head, sp) : forward_single(c, seq, with_head, sp);
         hipError_t e2 = hipStreamEndCapture(c->stream, &graph);
         if (e) { if (graph) hipGraphDestroy(graph); return e; }
         if (e2) return e2;
@@ -239,7 +316,8 @@ hipError_t step_one_token(asynclm_ctx* c, int seq, int forced, bool with_head) {
         c->len[seq] += 1;
         return hipSuccess;
     }
-    const SplitPlan sp = pick_nsplit(c, c->len[seq] + 1);
+    const bool pipelined = use_pipeline(c, c->len[seq] + 1);
+    const SplitPlan sp = pick_nsplit(c, c->len[seq] + 1, pipelined);
     // the chosen token also goes to pinned host memory, and an event marks the point: asynclm_decode_step waits for that
     // event only, so the host has the token while the forward pass is still running
     if ((e = run(c, KC_BEGIN, [&] { return launch_begin_step(c->b, seq, forced, c->tok_event ? c->token_host + 4 : nullptr, c->stream); }))) return e;
@@ -247,7 +325,9 @@ hipError_t step_one_token(asynclm_ctx* c, int seq, int forced, bool with_head) {
         if ((e = hipEventRecord(c->tok_event, c->stream))) return e;
         c->tok_early = true;
     }
-    if (c->opt_graph && !c->prof) e = forward_single_graph(c, seq, with_head, sp);
+    c->pipe_kernels = pipelined ? 5 * c->cfg.n_layers + (with_head ? 1 : 0) : 0;
+    if (c->opt_graph && !c->prof) e = forward_single_graph(c, seq, with_head, sp, pipelined);
+    else if (pipelined) e = forward_single_pipelined(c, seq, with_head, sp);
     else e = forward_single(c, seq, with_head, sp);
     if (e) return e;
     c->len[seq] += 1;
@@ -496,6 +576,7 @@ int asynclm_create(asynclm_ctx** out, const asynclm_config* cfg, const asynclm_w
     ALLOC(c->b.seq_state, (size_t)cfg->max_seqs);
     ALLOC(c->b.token_log, 2);        // [0] chosen token, [1] set when a fused step gave up at a grid barrier
     ALLOC(c->b.x, (size_t)g.d);
+    ALLOC(c->b.x2, (size_t)g.d);
     ALLOC(c->b.q, (size_t)g.Hq * g.dh);
     ALLOC(c->b.o, (size_t)g.Hq * g.dh);
     ALLOC(c->b.a, (size_t)g.F);
@@ -506,6 +587,11 @@ int asynclm_create(asynclm_ctx** out, const asynclm_config* cfg, const asynclm_w
     ALLOC(c->b.amax_i, (size_t)ARGMAX_MAX_BLOCKS);
     ALLOC(c->b.amax_counter, 1);
     ALLOC(c->b.banned, (size_t)cfg->max_seqs * (1 + BAN_MAX));
+    c->pipe_kernels_max = 5 * cfg->n_layers + 2;
+    ALLOC(c->b.pipe_abort, (size_t)PIPE_LINE_WORDS);
+    ALLOC(c->pipe_go, (size_t)PIPE_REGIONS * PIPE_MAX_WORKGROUPS * PIPE_LINE_WORDS);
+    ALLOC(c->pipe_counters, (size_t)c->pipe_kernels_max * PIPE_LINE_WORDS);
+    ALLOC(c->pipe_stamps, (size_t)c->pipe_kernels_max * 6);
     if (c->chunk_ok) {
         ChunkBuffers& cb = c->cb;
         const size_t M = CHUNK_MAX, qd = (size_t)g.Hq * g.dh;
@@ -568,6 +654,16 @@ int asynclm_create(asynclm_ctx** out, const asynclm_config* cfg, const asynclm_w
     if (hipHostMalloc((void**)&c->token_host, 64, hipHostMallocDefault) != hipSuccess) return bail(ASYNCLM_E_NOMEM);
     std::memset(c->token_host, 0, 64);
     if (hipEventCreateWithFlags(&c->tok_event, hipEventDisableTiming) != hipSuccess) return bail(ASYNCLM_E_DEVICE);
+    if (hipMemset(c->b.pipe_abort, 0, sizeof(unsigned) * PIPE_LINE_WORDS) != hipSuccess ||
+        hipMemset(c->pipe_go, 0xff, sizeof(unsigned) * PIPE_REGIONS * PIPE_MAX_WORKGROUPS * PIPE_LINE_WORDS) != hipSuccess ||
+        hipMemset(c->pipe_counters, 0, sizeof(unsigned) * c->pipe_kernels_max * PIPE_LINE_WORDS) != hipSuccess)
+        return bail(ASYNCLM_E_DEVICE);
+    if (c->stream) {     // second stream of the two-stream decoding step (default priority, as every stream here)
+        if (hipStreamCreateWithFlags(&c->stream2, hipStreamNonBlocking) != hipSuccess ||
+            hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming) != hipSuccess ||
+            hipEventCreateWithFlags(&c->ev_join, hipEventDisableTiming) != hipSuccess)
+            return bail(ASYNCLM_E_DEVICE);
+    }
     if (hipHostMalloc((void**)&c->chosen_host, sizeof(int32_t) * CHUNK_MAX, hipHostMallocDefault) != hipSuccess) return bail(ASYNCLM_E_NOMEM);
     // fused decoding step: pointer table, barrier counters, launch plan
     {
@@ -591,6 +687,9 @@ int asynclm_create(asynclm_ctx** out, const asynclm_config* cfg, const asynclm_w
     }
     const int max_k = g.F > g.d ? (g.F > g.Hq * g.dh ? g.F : g.Hq * g.dh) : (g.d > g.Hq * g.dh ? g.d : g.Hq * g.dh);
     if ((e = decode_init(cfg->dtype, max_k)) != hipSuccess) { report_hip("decode_init", e); return bail(ASYNCLM_E_DEVICE); }
+    c->pipe_ok = c->stream2 && decode_pipeline_fits(cfg->dtype, g, g.kv_lo_offset != 0);
+    if (const char* pv = std::getenv("ASYNCLM_PIPELINE")) c->opt_pipeline = (std::atoi(pv) != 0 && c->pipe_ok) ? 1 : 0;
+    if (std::getenv("ASYNCLM_VERBOSE")) std::fprintf(stderr, "[asynclm] two-stream step: fits %d, on %d\n", (int)c->pipe_ok, c->opt_pipeline);
     if ((e = hipDeviceSynchronize()) != hipSuccess) { report_hip("hipDeviceSynchronize", e); return bail(ASYNCLM_E_DEVICE); }
     *out = c;
     return ASYNCLM_OK;
@@ -604,6 +703,9 @@ int asynclm_destroy(asynclm_ctx* c) {
     for (void* p : c->allocs) hipFree(p);
     if (c->token_host) hipHostFree(c->token_host);
     if (c->tok_event) hipEventDestroy(c->tok_event);
+    if (c->stream2) { hipStreamSynchronize(c->stream2); hipStreamDestroy(c->stream2); }
+    if (c->ev_fork) hipEventDestroy(c->ev_fork);
+    if (c->ev_join) hipEventDestroy(c->ev_join);
     if (c->chosen_host) hipHostFree(c->chosen_host);
     delete c;
     return ASYNCLM_OK;
@@ -935,6 +1037,7 @@ int asynclm_set_option(asynclm_ctx* c, const char* name, int32_t value) {
     if (!std::strcmp(name, "chunk_split")) { if (value < 0 || value > CHUNK_GEMM_MAX_SPLIT) return ASYNCLM_E_INVAL; c->opt_chunk_split = value; return ASYNCLM_OK; }
     if (!std::strcmp(name, "gemv_grid")) { if (value < 1 || value > 4096) return ASYNCLM_E_INVAL; decode_set_gemv_grid(value); return ASYNCLM_OK; }
     if (!std::strcmp(name, "fused")) { c->opt_fused = (value && c->fused.supported) ? 1 : 0; return ASYNCLM_OK; }
+    if (!std::strcmp(name, "pipeline")) { c->opt_pipeline = (value && c->pipe_ok) ? 1 : 0; return ASYNCLM_OK; }
     if (!std::strcmp(name, "graph")) { c->opt_graph = (value && c->stream) ? 1 : 0; return ASYNCLM_OK; }
     if (!std::strcmp(name, "attn_mfma_min")) { if (value < 0) return ASYNCLM_E_INVAL; c->opt_attn_mfma_min = value; return ASYNCLM_OK; }
     if (!std::strcmp(name, "attn_split")) { if (value < 0 || value > CHUNK_ATTN_MAX_SPLIT) return ASYNCLM_E_INVAL; c->opt_attn_split = value; return ASYNCLM_OK; }
@@ -1001,6 +1104,20 @@ int asynclm_profile_step(asynclm_ctx* c, int32_t seq, int32_t forced_token, cons
 
 int asynclm_profile_trace(asynclm_ctx* c, uint64_t* out_host, int32_t cap, int32_t* n_stamps, int32_t* n_workgroups) {
     if (!c || !n_stamps || !n_workgroups) return ASYNCLM_E_INVAL;
+    if (c->pipe_kernels > 0 && !c->opt_fused) {
+        // the last two-stream step: per kernel, start / hand-over seen / done of its first and of its last workgroup
+        *n_stamps = 3 * c->pipe_kernels; *n_workgroups = 2;
+        if (out_host) {
+            if (cap < 6 * c->pipe_kernels) return ASYNCLM_E_INVAL;
+            std::vector<unsigned long long> raw((size_t)6 * c->pipe_kernels);
+            HIPCK(c, hipStreamSynchronize(c->stream));
+            HIPCK(c, hipMemcpy(raw.data(), c->pipe_stamps, raw.size() * sizeof(unsigned long long), hipMemcpyDeviceToHost));
+            for (int k = 0; k < c->pipe_kernels; ++k)
+                for (int w = 0; w < 2; ++w)
+                    for (int j = 0; j < 3; ++j) out_host[(size_t)(3 * k + j) * 2 + w] = raw[(size_t)k * 6 + w * 3 + j];
+        }
+        return ASYNCLM_OK;
+    }
     *n_stamps = c->last_trace_stamps;
     *n_workgroups = c->last_trace_stamps ? (int32_t)(c->last_trace.size() / c->last_trace_stamps) : 0;
     if (out_host) {

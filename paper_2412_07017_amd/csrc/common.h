@@ -17,6 +17,7 @@ struct StepDesc {
     int32_t pos;     // absolute position of the first row of this pass = sequence length before it
     int32_t seq;     // sequence index
     int32_t rows;    // rows in this pass (1 for decode)
+    int32_t epoch;   // number of the decoding step (k_begin_step counts it up): part of the hand-over words of PipeSync
 };
 
 struct SeqState {
@@ -105,6 +106,100 @@ __device__ __forceinline__ uint4 load16(const void* p) {
     return make_uint4(v.x, v.y, v.z, v.w);
 }
 __device__ __forceinline__ float load_f32(const float* p) { return *(global_f32_ptr)(uintptr_t)p; }
+
+// Write-through stores.  The dies of the device have an L2 cache each; data that one running kernel hands to another
+// (no kernel boundary in between) is stored with relaxed atomic stores at device scope, which go through to memory,
+// and the reader only touches it after the hand-over (PipeSync), on lines that no cache of its die can hold.
+__device__ __forceinline__ void store_coherent(float* p, float v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ void store_coherent(bf16_t* p, bf16_t v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+
+// Hand-over between two kernels that run at the same time on two streams.  The producer's workgroups count
+// themselves into `counter` once their write-through stores have completed; the workgroup that arrives last resets the
+// counter and writes the hand-over word (step number and producer kernel number) into one cache line PER CONSUMER
+// WORKGROUP, and consumer workgroup w polls only line w: a word that every waiting workgroup polls would keep one
+// memory channel busy with polls and slow the weight stream of the kernel that is still running, which visits every
+// channel.  Every wait is bounded: after PIPE_SPIN_LIMIT polls, or once another workgroup has given up, the workgroup
+// sets `abort` (and the host-visible error word) and leaves, so a launch always drains.
+constexpr int PIPE_LINE_WORDS = 32;         // one hand-over word per 128 bytes
+constexpr int PIPE_MAX_WORKGROUPS = 256;    // workgroups of a kernel that takes part (lines per region)
+constexpr int PIPE_REGIONS = 4;             // kernel k signals region k % 4 (at most two kernels are in flight)
+struct PipeSync {
+    const unsigned* go_wait;    // region written by the previous kernel; nullptr: the inputs are complete at kernel start
+    unsigned* go_signal;        // region this kernel writes when all its workgroups are done; nullptr: nobody waits
+    unsigned* counter;          // arrivals of this kernel's workgroups (zero between kernels)
+    unsigned* abort;            // shared by all kernels of a step
+    int32_t* error_word;        // set to 1 when a wait gave up
+    const StepDesc* step;       // step number
+    unsigned wait_kernel, my_kernel;   // kernel numbers within the step
+    unsigned long long* stamps; // optional, see pipe_stamp
+};
+constexpr unsigned PIPE_SPIN_LIMIT = 1u << 17;
+#ifndef PIPE_POLL_SLEEP
+#define PIPE_POLL_SLEEP 2      // x 64 clocks between two polls of a waiting workgroup
+#endif
+
+__device__ __forceinline__ unsigned pipe_word(const StepDesc* step, unsigned kernel) { return ((unsigned)step->epoch << 10) | kernel; }
+
+// stamps[0..2]: start and hand-over seen of the first workgroup, done of the workgroup that finished first;
+// stamps[3..5]: the same of the last workgroup / the workgroup that finished last.
+__device__ __forceinline__ void pipe_stamp(const PipeSync& ps, int which) {
+    if (!ps.stamps || threadIdx.x != 0) return;
+    const bool first = blockIdx.x == 0 && blockIdx.y == 0, last = blockIdx.x == gridDim.x - 1 && blockIdx.y == gridDim.y - 1;
+#ifdef PIPE_STAMP_ALL       // diagnosis builds: the latest start / hand-over seen over all workgroups
+    if (first) ps.stamps[which] = wall_clock64();
+    atomicMax(ps.stamps + 3 + which, (unsigned long long)wall_clock64());
+#else
+    if (first) ps.stamps[which] = wall_clock64();
+    if (last) ps.stamps[3 + which] = wall_clock64();
+#endif
+}
+
+// All threads of the workgroup call this; false: give up (uniform).
+__device__ __forceinline__ bool pipe_wait(const PipeSync& ps, int* s_flag) {
+    if (!ps.go_wait) { pipe_stamp(ps, 1); return true; }
+    if (threadIdx.x == 0) {
+        const unsigned want = pipe_word(ps.step, ps.wait_kernel);
+        const unsigned* mine = ps.go_wait + (size_t)(blockIdx.y * gridDim.x + blockIdx.x) * PIPE_LINE_WORDS;
+        int ok = 1;
+        unsigned spins = 0;
+        while (__hip_atomic_load(mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != want) {
+            __builtin_amdgcn_s_sleep(PIPE_POLL_SLEEP);
+            ++spins;
+            if (spins > PIPE_SPIN_LIMIT || ((spins & 255u) == 0 && __hip_atomic_load(ps.abort, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0)) { ok = 0; break; }
+        }
+        if (!ok) {
+            __hip_atomic_store(ps.abort, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            *ps.error_word = 1;
+        }
+        *s_flag = ok;
+    }
+    pipe_stamp(ps, 1);
+    __syncthreads();
+    return *s_flag != 0;
+}
+
+// All threads call this after their last write-through store (256 threads per workgroup).
+__device__ __forceinline__ void pipe_signal(const PipeSync& ps, int* s_flag) {
+    if (!ps.go_signal) return;
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // this thread's write-through stores have completed
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const unsigned n = gridDim.x * gridDim.y;
+        const unsigned ticket = __hip_atomic_fetch_add(ps.counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (ps.stamps) {
+            if (ticket == 0) ps.stamps[2] = wall_clock64();
+            if (ticket == n - 1) ps.stamps[5] = wall_clock64();
+        }
+        if (ticket == n - 1) __hip_atomic_store(ps.counter, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        *s_flag = ticket == n - 1;
+    }
+    __syncthreads();
+    if (*s_flag) {
+        const unsigned word = pipe_word(ps.step, ps.my_kernel);
+        for (int w = threadIdx.x; w < PIPE_MAX_WORKGROUPS; w += blockDim.x)
+            __hip_atomic_store(ps.go_signal + (size_t)w * PIPE_LINE_WORDS, word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+}
 
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll

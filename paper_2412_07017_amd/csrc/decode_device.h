@@ -12,11 +12,13 @@ enum { EPI_STORE = 0, EPI_RESID = 1, EPI_SWIGLU = 2, EPI_QKV = 3 };
 
 // Cache write: fp32 as is; bf16 as the rounded value, plus the rounded remainder in the lo plane
 // when the cache has one.
-__device__ __forceinline__ void kv_store(float* p, float v, size_t) { *p = v; }
+// Written through (device-coherent stores): the attention of the same step may already be running on
+// another stream when the row is written.
+__device__ __forceinline__ void kv_store(float* p, float v, size_t) { store_coherent(p, v); }
 __device__ __forceinline__ void kv_store(bf16_t* p, float v, size_t lo_offset) {
     const bf16_t hi = f32_to_bf16(v);
-    *p = hi;
-    if (lo_offset) p[lo_offset] = f32_to_bf16(v - __uint_as_float((uint32_t)hi << 16));
+    store_coherent(p, hi);
+    if (lo_offset) store_coherent(p + lo_offset, f32_to_bf16(v - __uint_as_float((uint32_t)hi << 16)));
 }
 
 // A "unit" is the pair of matrix rows one wave reduces together:
@@ -513,17 +515,18 @@ __device__ __forceinline__ void finish_unit(int u, float sa, float sb, float e0,
         o.y[2 * u] = sa;
         if (2 * u + 1 < o.rows) o.y[2 * u + 1] = sb;
     } else if (EPI == EPI_RESID) {
-        o.y[2 * u] = e0 + sa;
-        if (2 * u + 1 < o.rows) o.y[2 * u + 1] = e1 + sb;
+        // vectors that the next kernel of the step reads are written through (it may already be running)
+        store_coherent(o.y + 2 * u, e0 + sa);
+        if (2 * u + 1 < o.rows) store_coherent(o.y + 2 * u + 1, e1 + sb);
     } else if (EPI == EPI_SWIGLU) {
-        o.y[u] = sa / (1.f + expf(-sa)) * sb;
+        store_coherent(o.y + u, sa / (1.f + expf(-sa)) * sb);
     } else {
         const int hs = g.dh == 128 ? 6 : 5, half = 1 << hs;
         const int h = u >> hs, i = u & (half - 1);
         if (h >= g.Hq + g.Hkv) { e0 = 1.f; e1 = 0.f; }                 // value rows are not rotated
         const float ra = sa * e0 - sb * e1, rb = sb * e0 + sa * e1;
         const size_t seq_off = (size_t)o.seq * g.kv_seq_stride;
-        if (h < g.Hq) { o.q_out[h * g.dh + i] = ra; o.q_out[h * g.dh + i + half] = rb; }
+        if (h < g.Hq) { store_coherent(o.q_out + h * g.dh + i, ra); store_coherent(o.q_out + h * g.dh + i + half, rb); }
         else if (h < g.Hq + g.Hkv) {
             WT* kp = (WT*)o.kv_layer + seq_off + (size_t)(h - g.Hq) * g.kv_head_stride + (size_t)o.pos * g.dh;
             kv_store(kp + i, ra, g.kv_lo_offset); kv_store(kp + i + half, rb, g.kv_lo_offset);

@@ -18,8 +18,13 @@ namespace asynclm {
 // publishes it and its position to the step descriptor, and grows the sequence by one.
 // token_early: optional host-visible word that also receives the token, so that the host can read it as soon as this
 // kernel has run instead of after the whole step.
-__global__ void k_begin_step(StepDesc* step, SeqState* st, int32_t seq, int32_t forced, int32_t* token_log, int32_t* token_early) {
+// pipe_abort: the give-up word of a step that runs on two streams, cleared here (this kernel runs alone, after the
+// previous step has ended and before any kernel of this one starts); the step number goes up by one.
+__global__ void k_begin_step(StepDesc* step, SeqState* st, int32_t seq, int32_t forced, int32_t* token_log, int32_t* token_early,
+                             unsigned* pipe_abort) {
     if (threadIdx.x == 0 && blockIdx.x == 0) {
+        if (pipe_abort) *pipe_abort = 0u;
+        step->epoch = (step->epoch + 1) & 0x3fffff;
         SeqState s = st[seq];
         int32_t tok = forced >= 0 ? forced : s.next_token;
         step->token = tok;
@@ -60,16 +65,23 @@ struct GemvArgs {
     int32_t layer;
     // merged attention output as input vector (x == nullptr): see VecSource
     const float* part_acc; const float* part_ml; int32_t merge_nsplit, merge_dh, merge_hq;
+    PipeSync sync;          // hand-over from / to the neighbouring kernels of a step that runs on two streams
 };
 
 // Every wave owns a contiguous share of the row pairs and streams them through a ring of four register
 // tiles (decode_device.h); the first tiles are requested before the input vector is staged.
-template <typename WT, int EPI, int NB>
-__global__ __launch_bounds__(256) void k_gemv(GemvArgs a, Geom g) {
+// PIPE: the kernel may start while the kernel that produces its input vector is still running (two streams).  It then
+// requests its first weight tiles, waits for the producer's workgroups (PipeSync), and only then reads the vector;
+// its own results are written through, and when they have arrived it counts itself into its own flag.  Two workgroups of such kernels
+// fit one compute unit (launch bounds), so the workgroups of two neighbouring kernels are always all resident.
+template <typename WT, int EPI, int NB, bool PIPE>
+__global__ __launch_bounds__(256, PIPE ? 2 : 1) void k_gemv(GemvArgs a, Geom g) {
     constexpr int EPL = Elem<WT>::EPL;
     extern __shared__ float4 lds4[];
     __shared__ float red[4];
+    __shared__ int s_go;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if (PIPE) pipe_stamp(a.sync, 0);
 
     Phase<WT> ph = make_phase<WT, EPI>(a.W, a.rows, a.K, a.units);
     const int plane_stride = ph.KT * 256 + 64;
@@ -82,7 +94,7 @@ __global__ __launch_bounds__(256) void k_gemv(GemvArgs a, Geom g) {
     constexpr int NB1 = NB > 0 ? NB : 1;
     constexpr bool GAIN = EPI != EPI_RESID;
     EarlyBatch<NB1, GAIN> vb;
-    if (NB > 0) {
+    if (NB > 0 && !PIPE) {
         early_request(vb, a.x, a.gain, a.K);
         __builtin_amdgcn_sched_barrier(0);
     }
@@ -93,6 +105,14 @@ __global__ __launch_bounds__(256) void k_gemv(GemvArgs a, Geom g) {
     eo.y = a.y; eo.res = a.res; eo.q_out = a.q_out; eo.kv_layer = a.kv_layer;
     eo.rope_cos = a.rope_cos; eo.rope_sin = a.rope_sin; eo.rows = a.rows; eo.pos = 0; eo.seq = 0;
     if (EPI == EPI_QKV) { eo.pos = a.step->pos; eo.seq = a.step->seq; }
+    if (PIPE) {
+        // nothing but weights before the hand-over: the residual may come from the kernel before the previous one,
+        // which is only known to be complete once the previous one is
+        __builtin_amdgcn_sched_barrier(0);
+        if (!pipe_wait(a.sync, &s_go)) return;
+        if (NB > 0) early_request(vb, a.x, a.gain, a.K);
+        __builtin_amdgcn_sched_barrier(0);
+    }
     phase_prefetch_e<WT, EPI>(ring, ph, lc, g, eo);
 
     float ssq;
@@ -104,6 +124,7 @@ __global__ __launch_bounds__(256) void k_gemv(GemvArgs a, Geom g) {
     const float nscale = a.gain ? rsqrtf(ssq / (float)a.K + g.eps) : 1.f;
     float best_v = -INFINITY; int best_i = 0x7fffffff;
     phase_run<WT, EPI>(ring, ph, lc, lds4, plane_stride, nscale, eo, g, lane, done, best_v, best_i);
+    if (PIPE) pipe_signal(a.sync, &s_go);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -120,18 +141,24 @@ struct AttnArgs {
     int32_t* counters;      // [Hkv], zero between launches
     int32_t nsplit;
     int32_t defer_merge;    // 1: leave the partials to the O projection (no merge here, even for one split)
+    PipeSync sync;
 };
 
-template <typename KVT, int DH, int G, bool PAIR>
-__global__ __launch_bounds__(256) void k_attn_decode(AttnArgs a, Geom g) {
+// PIPE: see k_gemv.  The query and the newest cache row come from the QKV kernel of the same step, which may still be
+// running when this kernel starts: neither the query nor any cache row is read before its hand-over.
+template <typename KVT, int DH, int G, bool PAIR, bool PIPE>
+__global__ __launch_bounds__(256, PIPE ? 2 : 1) void k_attn_decode(AttnArgs a, Geom g) {
     constexpr int EPL = Elem<KVT>::EPL;
     constexpr int PPW = 64 / (DH / EPL);        // positions per wave-wide load
     extern __shared__ float lds[];
     __shared__ int s_last;
+    __shared__ int s_go;
 
     const int tid = threadIdx.x;
     const int kvh = blockIdx.x, split = blockIdx.y, nsplit = a.nsplit;
     const int len = a.step->pos + 1;
+    if (PIPE) pipe_stamp(a.sync, 0);
+    if (PIPE && !pipe_wait(a.sync, &s_go)) return;
     // split boundaries: equal shares rounded up to whole workgroup rounds
     const int quantum = 4 * PPW;
     int per = (len + nsplit - 1) / nsplit;
@@ -151,13 +178,19 @@ __global__ __launch_bounds__(256) void k_attn_decode(AttnArgs a, Geom g) {
         for (int hh = 1; hh < G; ++hh) if (hh == h) { M = mh[hh]; L = lh[hh]; }
         const int hq = kvh * G + h;
         if (nsplit == 1 && !a.defer_merge) {
-            a.o[hq * DH + dim] = A / L;
+            store_coherent(a.o + hq * DH + dim, A / L);
         } else {
-            a.part_acc[((size_t)hq * nsplit + split) * DH + dim] = A;
-            if (dim == 0) { a.part_ml[((size_t)hq * nsplit + split) * 2] = M; a.part_ml[((size_t)hq * nsplit + split) * 2 + 1] = L; }
+            store_coherent(a.part_acc + ((size_t)hq * nsplit + split) * DH + dim, A);
+            if (dim == 0) {
+                store_coherent(a.part_ml + ((size_t)hq * nsplit + split) * 2, M);
+                store_coherent(a.part_ml + ((size_t)hq * nsplit + split) * 2 + 1, L);
+            }
         }
     }
-    if (nsplit == 1 || a.defer_merge) return;
+    if (nsplit == 1 || a.defer_merge) {
+        if (PIPE) pipe_signal(a.sync, &s_go);
+        return;
+    }
 
     // the workgroup that finishes last for this kv head merges the splits, in split order
     __threadfence();
@@ -167,7 +200,10 @@ __global__ __launch_bounds__(256) void k_attn_decode(AttnArgs a, Geom g) {
         s_last = (ticket == nsplit - 1);
     }
     __syncthreads();
-    if (!s_last) return;
+    if (!s_last) {
+        if (PIPE) pipe_signal(a.sync, &s_go);
+        return;
+    }
     __threadfence();
     // weights of the splits: f_s = exp(m_s - M) / L, one wave per head at a time, lane = split
     __syncthreads();                              // the partial accumulators in LDS have been read
@@ -210,12 +246,15 @@ __global__ __launch_bounds__(256) void k_attn_decode(AttnArgs a, Geom g) {
             __syncthreads();
             if (half == 0 && t < NO) {
                 const float4 o2 = s_half[tid];
-                ((float4*)(a.o + (size_t)hq * DH))[d4] = make_float4(r.x + o2.x, r.y + o2.y, r.z + o2.z, r.w + o2.w);
+                float* op = a.o + (size_t)hq * DH + 4 * d4;
+                store_coherent(op, r.x + o2.x); store_coherent(op + 1, r.y + o2.y);
+                store_coherent(op + 2, r.z + o2.z); store_coherent(op + 3, r.w + o2.w);
             }
             __syncthreads();
         }
     }
     if (tid == 0) a.counters[kvh] = 0;
+    if (PIPE) pipe_signal(a.sync, &s_go);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -282,30 +321,42 @@ __global__ __launch_bounds__(256) void k_argmax(const float* __restrict__ logits
 static int g_gemv_grid = 256;       // workgroups per matrix-vector kernel; decode_init sets it to the number of compute units
 static size_t g_gemv_lds_limit = 48 * 1024;   // dynamic LDS a matrix-vector kernel may ask for (raised by decode_init)
 
-template <typename WT, int EPI, int NB>
-static hipError_t launch_gemv_n(const GemvArgs& a, size_t lds, const Geom& g, hipStream_t s) {
-    hipLaunchKernelGGL((k_gemv<WT, EPI, NB>), dim3(g_gemv_grid), dim3(256), lds, s, a, g);
-    return hipGetLastError();
-}
-
 // Early request of the vector when it is a plain one that fits one batch: 4 or 8 x 16 bytes per thread (with as
 // many of the gain) in the normalising products, 4 or 16 in the residual ones.
 template <int EPI> struct EarlyNB { static constexpr int SMALL = 4, LARGE = EPI == EPI_RESID ? 16 : 8, HUGE = 32; };
 
+template <typename WT, int EPI, int NB>
+static const void* gemv_func_n(bool pipe) {
+    return pipe ? (const void*)(k_gemv<WT, EPI, NB, true>) : (const void*)(k_gemv<WT, EPI, NB, false>);
+}
+
+// The instantiation that serves a product with K columns (plain_x: the input is a plain vector, not split partials).
+template <typename WT, int EPI>
+static const void* gemv_func(int K, bool plain_x, bool pipe) {
+    if (plain_x && K <= 1024 * EarlyNB<EPI>::SMALL) return gemv_func_n<WT, EPI, EarlyNB<EPI>::SMALL>(pipe);
+    if (plain_x && K <= 1024 * EarlyNB<EPI>::LARGE) return gemv_func_n<WT, EPI, EarlyNB<EPI>::LARGE>(pipe);
+    if (EPI == EPI_RESID && plain_x && K <= 1024 * EarlyNB<EPI>::HUGE) return gemv_func_n<WT, EPI_RESID, EarlyNB<EPI_RESID>::HUGE>(pipe);
+    return gemv_func_n<WT, EPI, 0>(pipe);
+}
+
+template <typename WT>
+static size_t gemv_lds_bytes(int K, int units, int grid, int* done_cap) {
+    *done_cap = (units + grid * 4 - 1) / (grid * 4) + 1;
+    const int kg = K / Elem<WT>::EPL, kt = (kg + 255) / 256;
+    return (size_t)(kt * 256 + 64) * Elem<WT>::EPL * sizeof(float) + (size_t)4 * (*done_cap) * sizeof(float4);
+}
+
 template <typename WT, int EPI>
 static hipError_t launch_gemv_t(const GemvArgs& a0, const Geom& g, hipStream_t s) {
     GemvArgs a = a0;
-    const int grid = g_gemv_grid;
-    a.done_cap = (a.units + grid * 4 - 1) / (grid * 4) + 1;
-    const int kg = a.K / Elem<WT>::EPL, kt = (kg + 255) / 256;
-    const size_t lds = (size_t)(kt * 256 + 64) * Elem<WT>::EPL * sizeof(float) + (size_t)4 * a.done_cap * sizeof(float4);
+    const size_t lds = gemv_lds_bytes<WT>(a.K, a.units, g_gemv_grid, &a.done_cap);
     if (lds > g_gemv_lds_limit) return hipErrorInvalidValue;
     if (EPI != EPI_RESID && !(a.x && a.gain)) return hipErrorInvalidValue;   // the normalising products take a vector and a gain
     if (EPI == EPI_RESID && a.gain) return hipErrorInvalidValue;
-    if (a.x && a.K <= 1024 * EarlyNB<EPI>::SMALL) return launch_gemv_n<WT, EPI, EarlyNB<EPI>::SMALL>(a, lds, g, s);
-    if (a.x && a.K <= 1024 * EarlyNB<EPI>::LARGE) return launch_gemv_n<WT, EPI, EarlyNB<EPI>::LARGE>(a, lds, g, s);
-    if (EPI == EPI_RESID && a.x && a.K <= 1024 * EarlyNB<EPI>::HUGE) return launch_gemv_n<WT, EPI_RESID, EarlyNB<EPI_RESID>::HUGE>(a, lds, g, s);
-    return launch_gemv_n<WT, EPI, 0>(a, lds, g, s);
+    const bool pipe = a.sync.go_wait || a.sync.go_signal;
+    Geom gg = g;
+    void* params[] = {&a, &gg};
+    return hipLaunchKernel(gemv_func<WT, EPI>(a.K, a.x != nullptr, pipe), dim3(g_gemv_grid), dim3(256), params, lds, s);
 }
 
 template <typename WT>
@@ -318,14 +369,19 @@ static hipError_t launch_gemv_w(int epi, const GemvArgs& a, const Geom& g, hipSt
     }
 }
 
+template <typename WT, int EPI, bool PIPE>
+static hipError_t set_lds_p(int bytes) {
+    hipError_t e;
+    if ((e = hipFuncSetAttribute((const void*)(k_gemv<WT, EPI, 0, PIPE>), hipFuncAttributeMaxDynamicSharedMemorySize, bytes))) return e;
+    if ((e = hipFuncSetAttribute((const void*)(k_gemv<WT, EPI, EarlyNB<EPI>::SMALL, PIPE>), hipFuncAttributeMaxDynamicSharedMemorySize, bytes))) return e;
+    if ((e = hipFuncSetAttribute((const void*)(k_gemv<WT, EPI, EarlyNB<EPI>::LARGE, PIPE>), hipFuncAttributeMaxDynamicSharedMemorySize, bytes))) return e;
+    if (EPI != EPI_RESID) return hipSuccess;
+    return hipFuncSetAttribute((const void*)(k_gemv<WT, EPI_RESID, EarlyNB<EPI_RESID>::HUGE, PIPE>), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+}
 template <typename WT, int EPI>
 static hipError_t set_lds_t(int bytes) {
-    hipError_t e;
-    if ((e = hipFuncSetAttribute((const void*)(k_gemv<WT, EPI, 0>), hipFuncAttributeMaxDynamicSharedMemorySize, bytes))) return e;
-    if ((e = hipFuncSetAttribute((const void*)(k_gemv<WT, EPI, EarlyNB<EPI>::SMALL>), hipFuncAttributeMaxDynamicSharedMemorySize, bytes))) return e;
-    if ((e = hipFuncSetAttribute((const void*)(k_gemv<WT, EPI, EarlyNB<EPI>::LARGE>), hipFuncAttributeMaxDynamicSharedMemorySize, bytes))) return e;
-    if (EPI != EPI_RESID) return hipSuccess;
-    return hipFuncSetAttribute((const void*)(k_gemv<WT, EPI_RESID, EarlyNB<EPI_RESID>::HUGE>), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    hipError_t e = set_lds_p<WT, EPI, false>(bytes);
+    return e ? e : set_lds_p<WT, EPI, true>(bytes);
 }
 
 void decode_set_gemv_grid(int grid) { g_gemv_grid = grid; }
@@ -338,8 +394,8 @@ hipError_t decode_init(int dtype, int max_k) {
     }
     // staged vector with its padding + parked units (16 KiB cover 256 units per wave), within the 160 KiB of a compute unit
     const int bytes = std::min((max_k + 8 * 256 + 64 * 8) * (int)sizeof(float) + 16 * 1024, 160 * 1024);
-    if (bytes <= 48 * 1024) return hipSuccess;
-    g_gemv_lds_limit = (size_t)bytes;
+    // process-wide, shared by every context: only ever raised
+    if ((size_t)bytes <= g_gemv_lds_limit) return hipSuccess;
     hipError_t e;
     if (dtype == 0) {
         if ((e = set_lds_t<float, EPI_STORE>(bytes))) return e;
@@ -352,6 +408,7 @@ hipError_t decode_init(int dtype, int max_k) {
         if ((e = set_lds_t<bf16_t, EPI_SWIGLU>(bytes))) return e;
         if ((e = set_lds_t<bf16_t, EPI_QKV>(bytes))) return e;
     }
+    g_gemv_lds_limit = (size_t)bytes;
     return hipSuccess;
 }
 
@@ -360,9 +417,11 @@ static hipError_t launch_gemv(int dtype, int epi, const GemvArgs& a, const Geom&
 }
 
 hipError_t launch_begin_step(const DecodeBuffers& b, int seq, int forced, int32_t* token_early, hipStream_t s) {
-    hipLaunchKernelGGL(k_begin_step, dim3(1), dim3(64), 0, s, b.step, b.seq_state, seq, forced, b.token_log, token_early);
+    hipLaunchKernelGGL(k_begin_step, dim3(1), dim3(64), 0, s, b.step, b.seq_state, seq, forced, b.token_log, token_early, b.pipe_abort);
     return hipGetLastError();
 }
+
+int decode_gemv_grid() { return g_gemv_grid; }
 
 hipError_t launch_embed(int dtype, const void* E, const DecodeBuffers& b, const Geom& g, hipStream_t s) {
     const int grid = (g.d + 255) / 256;
@@ -372,18 +431,21 @@ hipError_t launch_embed(int dtype, const void* E, const DecodeBuffers& b, const 
 }
 
 hipError_t launch_qkv(int dtype, const void* wqkv, const float* gain, void* kv_layer, const DecodeBuffers& b,
-                      const Geom& g, hipStream_t s) {
+                      const Geom& g, hipStream_t s, const PipeSync* sync) {
     GemvArgs a{};
+    if (sync) a.sync = *sync;
     a.W = wqkv; a.rows = (g.Hq + 2 * g.Hkv) * g.dh; a.K = g.d; a.units = a.rows / 2;
     a.x = b.x; a.gain = gain; a.q_out = b.q; a.kv_layer = kv_layer;
     a.rope_cos = b.rope_cos; a.rope_sin = b.rope_sin; a.step = b.step;
     return launch_gemv(dtype, EPI_QKV, a, g, s);
 }
 
-hipError_t launch_oproj(int dtype, const void* wo, int merge_nsplit, const DecodeBuffers& b, const Geom& g, hipStream_t s) {
+hipError_t launch_oproj(int dtype, const void* wo, int merge_nsplit, const DecodeBuffers& b, const Geom& g, hipStream_t s,
+                        const PipeSync* sync, float* x_out) {
     GemvArgs a{};
+    if (sync) a.sync = *sync;
     a.W = wo; a.rows = g.d; a.K = g.Hq * g.dh; a.units = (a.rows + 1) / 2;
-    a.x = b.o; a.gain = nullptr; a.y = b.x; a.res = b.x; a.step = b.step;
+    a.x = b.o; a.gain = nullptr; a.y = x_out ? x_out : b.x; a.res = b.x; a.step = b.step;
     if (merge_nsplit > 0) {
         if (merge_nsplit > MERGE_MAX_SPLIT) return hipErrorInvalidValue;
         a.x = nullptr; a.part_acc = b.part_acc; a.part_ml = b.part_ml;
@@ -392,23 +454,28 @@ hipError_t launch_oproj(int dtype, const void* wo, int merge_nsplit, const Decod
     return launch_gemv(dtype, EPI_RESID, a, g, s);
 }
 
-hipError_t launch_gateup(int dtype, const void* wgu, const float* gain, const DecodeBuffers& b, const Geom& g, hipStream_t s) {
+hipError_t launch_gateup(int dtype, const void* wgu, const float* gain, const DecodeBuffers& b, const Geom& g, hipStream_t s,
+                         const PipeSync* sync, const float* x_in) {
     GemvArgs a{};
+    if (sync) a.sync = *sync;
     a.W = wgu; a.rows = 2 * g.F; a.K = g.d; a.units = g.F;
-    a.x = b.x; a.gain = gain; a.y = b.a; a.step = b.step;
+    a.x = x_in ? x_in : b.x; a.gain = gain; a.y = b.a; a.step = b.step;
     return launch_gemv(dtype, EPI_SWIGLU, a, g, s);
 }
 
-hipError_t launch_down(int dtype, const void* wd, const DecodeBuffers& b, const Geom& g, hipStream_t s) {
+hipError_t launch_down(int dtype, const void* wd, const DecodeBuffers& b, const Geom& g, hipStream_t s, const PipeSync* sync,
+                       const float* res_in) {
     GemvArgs a{};
+    if (sync) a.sync = *sync;
     a.W = wd; a.rows = g.d; a.K = g.F; a.units = (a.rows + 1) / 2;
-    a.x = b.a; a.gain = nullptr; a.y = b.x; a.res = b.x; a.step = b.step;
+    a.x = b.a; a.gain = nullptr; a.y = b.x; a.res = res_in ? res_in : b.x; a.step = b.step;
     return launch_gemv(dtype, EPI_RESID, a, g, s);
 }
 
 hipError_t launch_lmhead(int dtype, const void* wout, const float* gain, float* logits, const DecodeBuffers& b,
-                         const Geom& g, hipStream_t s) {
+                         const Geom& g, hipStream_t s, const PipeSync* sync) {
     GemvArgs a{};
+    if (sync) a.sync = *sync;
     a.W = wout; a.rows = g.V; a.K = g.d; a.units = (a.rows + 1) / 2;
     a.x = b.x; a.gain = gain; a.y = logits; a.step = b.step;
     return launch_gemv(dtype, EPI_STORE, a, g, s);
@@ -417,15 +484,18 @@ hipError_t launch_lmhead(int dtype, const void* wout, const float* gain, float* 
 template <typename KVT, int DH, bool PAIR>
 static hipError_t launch_attn_t(const AttnArgs& a, const Geom& g, hipStream_t s) {
     const dim3 grid(g.Hkv, a.nsplit), block(256);
+    const bool pipe = a.sync.go_wait || a.sync.go_signal;
 #define ATTN_CASE(GG)                                                                                                   \
     case GG: {                                                                                                          \
         const size_t lds = sizeof(float) * attn_lds_floats<KVT, DH, GG>();                                              \
         if (lds > 48 * 1024) {                                                                                          \
-            hipError_t e = hipFuncSetAttribute((const void*)(k_attn_decode<KVT, DH, GG, PAIR>),                         \
+            hipError_t e = hipFuncSetAttribute(pipe ? (const void*)(k_attn_decode<KVT, DH, GG, PAIR, true>)             \
+                                                    : (const void*)(k_attn_decode<KVT, DH, GG, PAIR, false>),           \
                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);                   \
             if (e) return e;                                                                                            \
         }                                                                                                               \
-        hipLaunchKernelGGL((k_attn_decode<KVT, DH, GG, PAIR>), grid, block, lds, s, a, g);                              \
+        if (pipe) hipLaunchKernelGGL((k_attn_decode<KVT, DH, GG, PAIR, true>), grid, block, lds, s, a, g);              \
+        else hipLaunchKernelGGL((k_attn_decode<KVT, DH, GG, PAIR, false>), grid, block, lds, s, a, g);                  \
         break;                                                                                                          \
     }
     switch (g.Hq / g.Hkv) {
@@ -437,8 +507,9 @@ static hipError_t launch_attn_t(const AttnArgs& a, const Geom& g, hipStream_t s)
 }
 
 hipError_t launch_attn_decode(int dtype, const void* kv_layer, int nsplit, bool merge_in_oproj, const DecodeBuffers& b,
-                              const Geom& g, hipStream_t s) {
+                              const Geom& g, hipStream_t s, const PipeSync* sync) {
     AttnArgs a{};
+    if (sync) a.sync = *sync;
     a.defer_merge = merge_in_oproj ? 1 : 0;
     a.q = b.q; a.kv_layer = kv_layer; a.step = b.step; a.o = b.o;
     a.part_acc = b.part_acc; a.part_ml = b.part_ml; a.counters = b.attn_counters; a.nsplit = nsplit;
@@ -452,6 +523,53 @@ hipError_t launch_argmax(const float* logits_base, const DecodeBuffers& b, const
     if (nb > ARGMAX_MAX_BLOCKS) nb = ARGMAX_MAX_BLOCKS;
     hipLaunchKernelGGL(k_argmax, dim3(nb), dim3(256), 0, s, logits_base, g.V, b.step, b.seq_state, b.amax_v, b.amax_i, b.amax_counter, b.banned, seq);
     return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
+// two-stream step: can the workgroups of two neighbouring kernels always all be resident?
+// ---------------------------------------------------------------------------------------------
+
+template <typename KVT, int DH, bool PAIR>
+static const void* attn_func_pipe(int G, size_t* lds) {
+    switch (G) {
+        case 1: *lds = sizeof(float) * attn_lds_floats<KVT, DH, 1>(); return (const void*)(k_attn_decode<KVT, DH, 1, PAIR, true>);
+        case 2: *lds = sizeof(float) * attn_lds_floats<KVT, DH, 2>(); return (const void*)(k_attn_decode<KVT, DH, 2, PAIR, true>);
+        case 4: *lds = sizeof(float) * attn_lds_floats<KVT, DH, 4>(); return (const void*)(k_attn_decode<KVT, DH, 4, PAIR, true>);
+        case 8: *lds = sizeof(float) * attn_lds_floats<KVT, DH, 8>(); return (const void*)(k_attn_decode<KVT, DH, 8, PAIR, true>);
+        default: return nullptr;
+    }
+}
+
+template <typename WT>
+static bool pipeline_fits_t(const Geom& g, bool kv_pair) {
+    struct Item { const void* f; size_t lds; };
+    Item items[6];
+    int dc = 0, n = 0;
+    const int nqkv = (g.Hq + 2 * g.Hkv) * g.dh, qd = g.Hq * g.dh, grid = g_gemv_grid;
+    items[n++] = {gemv_func<WT, EPI_QKV>(g.d, true, true), gemv_lds_bytes<WT>(g.d, nqkv / 2, grid, &dc)};
+    items[n++] = {gemv_func<WT, EPI_RESID>(qd, false, true), gemv_lds_bytes<WT>(qd, (g.d + 1) / 2, grid, &dc)};   // merges the key splits
+    items[n++] = {gemv_func<WT, EPI_RESID>(qd, true, true), gemv_lds_bytes<WT>(qd, (g.d + 1) / 2, grid, &dc)};
+    items[n++] = {gemv_func<WT, EPI_SWIGLU>(g.d, true, true), gemv_lds_bytes<WT>(g.d, g.F, grid, &dc)};
+    items[n++] = {gemv_func<WT, EPI_RESID>(g.F, true, true), gemv_lds_bytes<WT>(g.F, (g.d + 1) / 2, grid, &dc)};
+    items[n++] = {gemv_func<WT, EPI_STORE>(g.d, true, true), gemv_lds_bytes<WT>(g.d, (g.V + 1) / 2, grid, &dc)};
+    for (int i = 0; i < n; ++i) {
+        int per_cu = 0;
+        if (items[i].lds > g_gemv_lds_limit) return false;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, items[i].f, 256, items[i].lds) != hipSuccess || per_cu < 2) return false;
+    }
+    size_t lds = 0;
+    const void* af = g.dh == 64 ? (kv_pair ? attn_func_pipe<WT, 64, true>(g.Hq / g.Hkv, &lds) : attn_func_pipe<WT, 64, false>(g.Hq / g.Hkv, &lds))
+                                : (kv_pair ? attn_func_pipe<WT, 128, true>(g.Hq / g.Hkv, &lds) : attn_func_pipe<WT, 128, false>(g.Hq / g.Hkv, &lds));
+    if (!af) return false;
+    if (lds > 48 * 1024 && hipFuncSetAttribute(af, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) return false;
+    int per_cu = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, af, 256, lds) != hipSuccess || per_cu < 2) return false;
+    return true;
+}
+
+bool decode_pipeline_fits(int dtype, const Geom& g, bool kv_pair) {
+    if (dtype == 0) return pipeline_fits_t<float>(g, false);
+    return pipeline_fits_t<bf16_t>(g, kv_pair);
 }
 
 }  // namespace asynclm

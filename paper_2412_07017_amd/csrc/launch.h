@@ -15,6 +15,7 @@ struct DecodeBuffers {
     SeqState* seq_state;      // [max_seqs]
     int32_t* token_log;       // last token chosen by k_begin_step
     float* x;                 // [d] residual stream
+    float* x2;                // [d] residual stream after the attention block (two-stream step only)
     float* q;                 // [Hq*dh]
     float* o;                 // [Hq*dh]
     float* a;                 // [F]
@@ -27,6 +28,7 @@ struct DecodeBuffers {
     int32_t* banned;          // [max_seqs][1 + BAN_MAX]: count, then the ids the greedy choice of the sequence skips
     const float* rope_cos;    // [max_pos][dh/2]
     const float* rope_sin;
+    unsigned* pipe_abort;     // give-up word of the two-stream step (see PipeSync)
 };
 
 constexpr int CHUNK_MAX = 512;         // rows per forward pass of the append-chunk path
@@ -103,6 +105,7 @@ hipError_t launch_decode_fused(int dtype, const FusedPlan& plan, const FusedLaun
 
 hipError_t decode_init(int dtype, int max_k);
 void decode_set_gemv_grid(int grid);
+int decode_gemv_grid();
 hipError_t chunk_init();
 hipError_t launch_begin_chunk(const ChunkBuffers& c, const DecodeBuffers& b, int ngroups, hipStream_t s);
 hipError_t launch_chunk_embed(const void* E, const ChunkBuffers& c, int rows, const Geom& g, hipStream_t s);
@@ -133,17 +136,26 @@ hipError_t launch_decode_attn_mfma(const ChunkBuffers& c, const void* kv_layer, 
 // token_early: pinned host word that also gets the chosen token (or nullptr)
 hipError_t launch_begin_step(const DecodeBuffers& b, int seq, int forced, int32_t* token_early, hipStream_t s);
 hipError_t launch_embed(int dtype, const void* E, const DecodeBuffers& b, const Geom& g, hipStream_t s);
+// sync (all single-row launchers): hand-over flags when the step's kernels alternate between two streams (see PipeSync)
 hipError_t launch_qkv(int dtype, const void* wqkv, const float* gain, void* kv_layer, const DecodeBuffers& b,
-                      const Geom& g, hipStream_t s);
+                      const Geom& g, hipStream_t s, const PipeSync* sync = nullptr);
 // merge_in_oproj: the attention only leaves per-split partials and the O projection merges them (nsplit <= 8)
 hipError_t launch_attn_decode(int dtype, const void* kv_layer, int nsplit, bool merge_in_oproj, const DecodeBuffers& b,
-                              const Geom& g, hipStream_t s);
-hipError_t launch_oproj(int dtype, const void* wo, int merge_nsplit, const DecodeBuffers& b, const Geom& g, hipStream_t s);
+                              const Geom& g, hipStream_t s, const PipeSync* sync = nullptr);
+// x_out / x_in / res_in: the residual stream between the O projection and the down projection lives in a second
+// vector when given (the two-stream step never updates a vector in place); default: b.x throughout
+hipError_t launch_oproj(int dtype, const void* wo, int merge_nsplit, const DecodeBuffers& b, const Geom& g, hipStream_t s,
+                        const PipeSync* sync = nullptr, float* x_out = nullptr);
 hipError_t launch_gateup(int dtype, const void* wgu, const float* gain, const DecodeBuffers& b, const Geom& g,
-                         hipStream_t s);
-hipError_t launch_down(int dtype, const void* wd, const DecodeBuffers& b, const Geom& g, hipStream_t s);
+                         hipStream_t s, const PipeSync* sync = nullptr, const float* x_in = nullptr);
+hipError_t launch_down(int dtype, const void* wd, const DecodeBuffers& b, const Geom& g, hipStream_t s, const PipeSync* sync = nullptr,
+                       const float* res_in = nullptr);
 hipError_t launch_lmhead(int dtype, const void* wout, const float* gain, float* logits, const DecodeBuffers& b,
-                         const Geom& g, hipStream_t s);
+                         const Geom& g, hipStream_t s, const PipeSync* sync = nullptr);
+// True when two workgroups of every single-row kernel of this model fit one compute unit (registers, LDS), i.e. when
+// the workgroups of two neighbouring kernels of a step can always all be resident: the condition for running the
+// step on two streams.
+bool decode_pipeline_fits(int dtype, const Geom& g, bool kv_pair);
 // greedy choice (banned ids skipped) of sequence `seq`, or of the step descriptor's sequence when seq < 0
 hipError_t launch_argmax(const float* logits_base, const DecodeBuffers& b, const Geom& g, hipStream_t s, int seq = -1);
 

@@ -101,6 +101,28 @@ def test_8b_workload_on_4_layers_matches_oracle(trunc4):
 
 
 @pytest.mark.timeout(600)
+def test_two_stream_decoding_step_matches_oracle(trunc4):
+    """The decoding step with its kernels alternating between two streams ("pipeline": neighbouring kernels overlap
+    and hand over through counters in device memory, results written through, no vector updated in place), as a
+    captured graph and launched directly, across a change of the attention's split count, with an interrupt between."""
+    import paper_2412_07017_amd as pkg
+    wl, model, w_dev, w_cpu, spec = trunc4
+    prompt, n_decode, events = spec["prompt"][:230], 48, [(20, spec["events"][0][1])]
+    ref = orc.run_stream(orc.Shape.of(model), w_cpu, prompt, n_decode, events, dtype=np.float32)
+    for graph in (1, 0):
+        lm = pkg.AsyncLM(model, w_dev, max_positions=640, stream=torch.cuda.Stream())
+        lm.set_option("pipeline", 1)
+        lm.set_option("graph", graph)
+        lm.prefill(0, prompt)
+        worst, n, n_gated = _compare_stream(lm, ref, spec, n_decode, events)
+        stamps = lm.profile_trace()
+        assert stamps.shape == (3 * (5 * model.n_layers + 1), 2), stamps.shape     # the last step ran on two streams
+        print("two-stream step (graph %d): max |logit err| = %.3e over %d vectors, %d margin-gated ids identical" % (graph, worst, n + 2, n_gated))
+        lm.close()
+        assert worst <= TOL, worst
+
+
+@pytest.mark.timeout(600)
 def test_append_chunk_sizes_agree_with_oracle_and_each_other(trunc4):
     """The matrix-core append path for every chunk shape (ragged tails, one to three row tiles through the
     weight-streaming product, four to eleven through the wide one with one or two row blocks, split-K factors)
