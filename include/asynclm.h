@@ -142,6 +142,20 @@ int asynclm_set_banned_tokens(asynclm_ctx *ctx, int32_t seq, const int32_t *ids,
  * starts a critical section, Sec. 3.2).  Synchronises the stream. */
 int asynclm_peek_token(asynclm_ctx *ctx, int32_t seq, int32_t *token_out);
 
+/* asynclm_peek_token's choice for callers that cannot allocate and have no context: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Picks the greedy token (maximum, lowest index on ties, the
+ * n_banned ids in banned_dev skipped) of logits_dev[0..n) and stores it to *token_out_dev, with the same kernel as
+ * asynclm_peek_token; the kernel's scratch (per-block maxima, a counter: about 2.3 KB) is a static array in device
+ * memory, one copy per GPU, held until the process ends, instead of a workspace of a context.  All three pointers are
+ * DEVICE pointers owned by the caller; the work is enqueued on hip_stream (a stream of the current device) and the
+ * call does not wait for it.  No hipMalloc, hipFree or other allocating call is made.
+ * Limits: 1 <= n <= ASYNCLM_STATIC_MAX_VOCAB, 0 <= n_banned <= 31, else ASYNCLM_E_INVAL and nothing is enqueued.
+ * Every call on a GPU uses that GPU's one scratch array: calls that overlap on one GPU (two streams, two threads)
+ * race; calls on one stream are ordered.  The array keeps the last call's contents; the call clears what it needs. */
+#define ASYNCLM_STATIC_MAX_VOCAB (1 << 24)
+int asynclm_greedy_token_static(const float *logits_dev, int32_t n, const int32_t *banned_dev, int32_t n_banned,
+                                int32_t *token_out_dev, void *hip_stream);
+
 /* Trap handling support (Sec. 5.4): while a sequence is paused its K/V state can be kept in place, dropped and
  * recomputed later (asynclm_reset + asynclm_prefill of the whole stream: time grows faster than linearly with the
  * context), or swapped to host memory and back (linear).  These calls are the swap; they synchronise the stream.

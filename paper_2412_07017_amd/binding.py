@@ -14,7 +14,7 @@ API_SYMBOLS = [
     "asynclm_create", "asynclm_destroy", "asynclm_prefill", "asynclm_decode_step",
     "asynclm_inject_interrupt", "asynclm_step_batch", "asynclm_set_banned_tokens", "asynclm_peek_token", "asynclm_kv_bytes", "asynclm_kv_swap_out", "asynclm_kv_swap_in", "asynclm_logits", "asynclm_logits_device", "asynclm_seq_len",
     "asynclm_reset", "asynclm_synchronize", "asynclm_set_option", "asynclm_profile_step", "asynclm_profile_trace",
-    "asynclm_strerror", "asynclm_version",
+    "asynclm_strerror", "asynclm_version", "asynclm_greedy_token_static",
 ]
 
 
@@ -79,6 +79,17 @@ def load_library():
     lib.asynclm_set_option.argtypes = [p, C.c_char_p, i32]
     lib.asynclm_profile_step.argtypes = [p, i32, i32, C.POINTER(C.POINTER(C.c_char_p)), C.POINTER(C.c_float), C.POINTER(i32), i32]
     lib.asynclm_profile_trace.argtypes = [p, C.POINTER(C.c_uint64), i32, C.POINTER(i32), C.POINTER(i32)]
+    lib.asynclm_step_batch.argtypes = [p, i32, C.POINTER(i32), C.POINTER(i32), C.POINTER(i32), C.POINTER(i32), C.POINTER(i32)]
+    lib.asynclm_set_banned_tokens.argtypes = [p, i32, C.POINTER(i32), i32]
+    lib.asynclm_peek_token.argtypes = [p, i32, C.POINTER(i32)]
+    lib.asynclm_kv_bytes.argtypes = [p, i32, C.POINTER(C.c_uint64)]
+    lib.asynclm_kv_swap_out.argtypes = [p, i32, p, C.c_uint64]
+    lib.asynclm_kv_swap_in.argtypes = [p, i32, p, C.c_uint64]
+    lib.asynclm_seq_len.argtypes = [p, i32, C.POINTER(i32)]
+    lib.asynclm_reset.argtypes = [p, i32]
+    lib.asynclm_synchronize.argtypes = [p]
+    lib.asynclm_set_option.argtypes = [p, C.c_char_p, i32]
+    lib.asynclm_greedy_token_static.argtypes = [p, i32, p, i32, p, p]
     lib.asynclm_strerror.argtypes = [C.c_int]
     lib.asynclm_strerror.restype = C.c_char_p
     lib.asynclm_version.restype = C.c_char_p
@@ -87,6 +98,11 @@ def load_library():
             getattr(lib, name).restype = C.c_int
     _lib = lib
     return lib
+
+
+def greedy_token_static(logits_dev: int, n: int, banned_dev: int, n_banned: int, token_out_dev: int, stream: int) -> int:
+    """asynclm_greedy_token_static: all pointers are device addresses (ints); returns the C return code."""
+    return int(load_library().asynclm_greedy_token_static(logits_dev, int(n), banned_dev or None, int(n_banned), token_out_dev, stream or None))
 
 
 def _strerror(code: int) -> str:

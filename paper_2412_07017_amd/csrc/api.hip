@@ -1127,6 +1127,40 @@ int asynclm_profile_trace(asynclm_ctx* c, uint64_t* out_host, int32_t cap, int32
     return ASYNCLM_OK;
 }
 
+// ---- greedy choice without any allocation -----------------------------------------------------------------------
+
+namespace {
+
+// Scratch of asynclm_greedy_token_static: per-block maxima, their indices, the arrival counter.  One copy per device
+// that loads the library, held until the process ends.  In host code the array's name is not a device address: the
+// address comes from hipGetSymbolAddress, once per device, and only that pointer is handed to kernels.
+struct ArgmaxScratch { float part_v[ARGMAX_MAX_BLOCKS]; int32_t part_i[ARGMAX_MAX_BLOCKS]; int32_t counter; int32_t pad[63]; };
+static __device__ __align__(256) unsigned char scratch[sizeof(ArgmaxScratch)];
+
+constexpr int STATIC_MAX_DEVICES = 64;
+void* g_scratch_ptr[STATIC_MAX_DEVICES] = {};      // per device: device address of `scratch`
+
+}  // namespace
+
+int asynclm_greedy_token_static(const float* logits_dev, int32_t n, const int32_t* banned_dev, int32_t n_banned,
+                                int32_t* token_out_dev, void* hip_stream) {
+    if (!logits_dev || !token_out_dev || n < 1 || n > ASYNCLM_STATIC_MAX_VOCAB) return ASYNCLM_E_INVAL;
+    if (n_banned < 0 || n_banned > BAN_MAX || (n_banned > 0 && !banned_dev)) return ASYNCLM_E_INVAL;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= STATIC_MAX_DEVICES) return ASYNCLM_E_DEVICE;
+    if (!g_scratch_ptr[dev]) {          // first call on this device (it is the current one)
+        void* p = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) { report_hip("hipGetSymbolAddress", e); return ASYNCLM_E_DEVICE; }
+        g_scratch_ptr[dev] = p;
+    }
+    ArgmaxScratch* sc = (ArgmaxScratch*)g_scratch_ptr[dev];
+    const hipError_t e = launch_argmax_flat(logits_dev, n, banned_dev, n_banned, sc->part_v, sc->part_i, &sc->counter, token_out_dev,
+                                            (hipStream_t)hip_stream);
+    if (e != hipSuccess) { report_hip("asynclm_greedy_token_static", e); return ASYNCLM_E_DEVICE; }
+    return ASYNCLM_OK;
+}
+
 const char* asynclm_strerror(int code) {
     switch (code) {
         case ASYNCLM_OK: return "ok";

@@ -261,24 +261,21 @@ __global__ __launch_bounds__(256, PIPE ? 2 : 1) void k_attn_decode(AttnArgs a, G
 // greedy argmax over the vocabulary: per-block (max, lowest index), last block merges
 // ---------------------------------------------------------------------------------------------
 
-__global__ __launch_bounds__(256) void k_argmax(const float* __restrict__ logits_base, int V, const StepDesc* step,
-                                                SeqState* st, float* part_v, int32_t* part_i, int32_t* counter,
-                                                const int32_t* __restrict__ banned, int seq_arg) {
+// (max, lowest index) over logits[0..V) without the `nban` ids in `ban`: per-block results in part_v / part_i, the block
+// that arrives last (counter, zero between launches) merges them and stores the index to *out.
+__device__ __forceinline__ void argmax_blocks(const float* __restrict__ logits, int V, const int32_t* __restrict__ ban, int nban,
+                                              float* part_v, int32_t* part_i, int32_t* counter, int32_t* out) {
     __shared__ float sv[4];
     __shared__ int si[4];
     __shared__ int s_last;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int seq = seq_arg >= 0 ? seq_arg : step->seq;
-    const float* logits = logits_base + (size_t)seq * V;
     const int nb = gridDim.x;
     const int per = (V + nb - 1) / nb;
     const int i0 = blockIdx.x * per, i1 = min(V, i0 + per);
     float bv = -INFINITY; int bi = 0x7fffffff;
-    const int32_t* ban = banned + (size_t)seq * (1 + BAN_MAX);
-    const int nban = ban[0];
     for (int i = i0 + tid; i < i1; i += 256) {
         bool allowed = true;
-        for (int k = 0; k < nban; ++k) allowed = allowed && i != ban[1 + k];
+        for (int k = 0; k < nban; ++k) allowed = allowed && i != ban[k];
         if (allowed) amax_merge(bv, bi, logits[i], i);
     }
 #pragma unroll
@@ -309,10 +306,26 @@ __global__ __launch_bounds__(256) void k_argmax(const float* __restrict__ logits
     __syncthreads();
     if (tid == 0) {
         for (int w = 1; w < 4; ++w) amax_merge(bv, bi, sv[w], si[w]);
-        st[seq].next_token = bi;
+        *out = bi;
         *counter = 0;
     }
 }
+
+__global__ __launch_bounds__(256) void k_argmax(const float* __restrict__ logits_base, int V, const StepDesc* step,
+                                                SeqState* st, float* part_v, int32_t* part_i, int32_t* counter,
+                                                const int32_t* __restrict__ banned, int seq_arg) {
+    const int seq = seq_arg >= 0 ? seq_arg : step->seq;
+    const int32_t* ban = banned + (size_t)seq * (1 + BAN_MAX);
+    argmax_blocks(logits_base + (size_t)seq * V, V, ban + 1, ban[0], part_v, part_i, counter, &st[seq].next_token);
+}
+
+// The same choice for a caller that brings the logits, the ids to skip and the place for the result itself.
+__global__ __launch_bounds__(256) void k_argmax_flat(const float* __restrict__ logits, int V, const int32_t* __restrict__ ban, int nban,
+                                                     float* part_v, int32_t* part_i, int32_t* counter, int32_t* out) {
+    argmax_blocks(logits, V, ban, nban, part_v, part_i, counter, out);
+}
+
+__global__ void k_clear_word(int32_t* p) { *p = 0; }
 
 // ---------------------------------------------------------------------------------------------
 // launchers
@@ -516,6 +529,15 @@ hipError_t launch_attn_decode(int dtype, const void* kv_layer, int nsplit, bool 
     if (dtype == 0) return g.dh == 64 ? launch_attn_t<float, 64, false>(a, g, s) : launch_attn_t<float, 128, false>(a, g, s);
     if (g.kv_lo_offset) return g.dh == 64 ? launch_attn_t<bf16_t, 64, true>(a, g, s) : launch_attn_t<bf16_t, 128, true>(a, g, s);
     return g.dh == 64 ? launch_attn_t<bf16_t, 64, false>(a, g, s) : launch_attn_t<bf16_t, 128, false>(a, g, s);
+}
+
+hipError_t launch_argmax_flat(const float* logits, int n, const int32_t* ban, int nban, float* part_v, int32_t* part_i,
+                              int32_t* counter, int32_t* out, hipStream_t s) {
+    int nb = (n + 2047) / 2048;
+    if (nb > ARGMAX_MAX_BLOCKS) nb = ARGMAX_MAX_BLOCKS;
+    hipLaunchKernelGGL(k_clear_word, dim3(1), dim3(1), 0, s, counter);      // whatever an earlier launch left there
+    hipLaunchKernelGGL(k_argmax_flat, dim3(nb), dim3(256), 0, s, logits, n, ban, nban, part_v, part_i, counter, out);
+    return hipGetLastError();
 }
 
 hipError_t launch_argmax(const float* logits_base, const DecodeBuffers& b, const Geom& g, hipStream_t s, int seq) {

@@ -158,5 +158,9 @@ hipError_t launch_lmhead(int dtype, const void* wout, const float* gain, float* 
 bool decode_pipeline_fits(int dtype, const Geom& g, bool kv_pair);
 // greedy choice (banned ids skipped) of sequence `seq`, or of the step descriptor's sequence when seq < 0
 hipError_t launch_argmax(const float* logits_base, const DecodeBuffers& b, const Geom& g, hipStream_t s, int seq = -1);
+// the same choice over caller-provided logits[n], skipping the nban ids in ban; part_v / part_i: ARGMAX_MAX_BLOCKS entries
+// of scratch, counter: one word of scratch (cleared by the launch); the result goes to *out (device)
+hipError_t launch_argmax_flat(const float* logits, int n, const int32_t* ban, int nban, float* part_v, int32_t* part_i,
+                              int32_t* counter, int32_t* out, hipStream_t s);
 
 }  // namespace asynclm
