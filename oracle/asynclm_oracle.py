@@ -180,12 +180,20 @@ class CachedDecoder:
     `prefill`, `inject` and the forward of `decode_step` are the same operation: append a
     chunk of tokens to the end of the context (Sec. 3.2) and leave the logits that predict
     the token after the chunk.  `kv_round` (diagnostic only) rounds K and V to bf16 when
-    they are written, to separate cache quantisation from kernel errors.
+    they are written, to separate cache quantisation from kernel errors.  `diag_round` (diagnostic
+    only, never used by a graded comparison) names further values to round to bf16, to measure what
+    each reduced-precision storage choice of an implementation would cost in the logits:
+      "k", "v"   cache rows at write (kv_round = both)
+      "h"        the normalised inputs of the QKV, gate/up products     } only in passes of more
+      "o"        the attention output (input of the O projection)       } than one row when
+      "a"        the SwiGLU output (input of the down projection)       } "chunk_only" is also
+      "q", "p"   the rotated queries / the softmax probabilities        } named
     """
 
     def __init__(self, shape: Shape, w: Dict[str, object], dtype=np.float64, kv_round: bool = False,
-                 capacity: int = 0):
+                 capacity: int = 0, diag_round: Sequence[str] = ()):
         self.shape, self.w, self.dtype, self.kv_round = shape, w, dtype, kv_round
+        self.diag_round = frozenset(diag_round)
         L, Hkv, dh = shape.n_layers, shape.n_kv_heads, shape.head_dim
         # storage grows by doubling; rows [0, length) are valid
         cap = max(int(capacity), 16)
@@ -229,15 +237,20 @@ class CachedDecoder:
         # row r (absolute position L0 + r) may look at keys 0 .. L0 + r
         key_pos = np.arange(L0 + M)[None, :]
         hidden = key_pos > pos[:, None]
+        # diagnostic rounding (identity in every graded use): see the class comment
+        diag = self.diag_round if (M > 1 or "chunk_only" not in self.diag_round) else frozenset(self.diag_round & {"k", "v"})
+        rd = lambda name, val: round_to_bf16(val).astype(dt) if name in diag else val
         for l in range(sh.n_layers):
             wq, wk, wv = _split_qkv(sh, w["wqkv"][l])
-            h = rmsnorm(x, _cast(w["attn_norm"][l], dt), sh.rms_eps)
+            h = rd("h", rmsnorm(x, _cast(w["attn_norm"][l], dt), sh.rms_eps))
             q = rope_rotate((h @ _cast(wq, dt).T).reshape(M, Hq, dh), pos, sh.rope_theta)
             k = rope_rotate((h @ _cast(wk, dt).T).reshape(M, Hkv, dh), pos, sh.rope_theta)
             v = (h @ _cast(wv, dt).T).reshape(M, Hkv, dh)
-            if self.kv_round:
+            if self.kv_round or "k" in self.diag_round:
                 k = round_to_bf16(k).astype(dt)
+            if self.kv_round or "v" in self.diag_round:
                 v = round_to_bf16(v).astype(dt)
+            q = rd("q", q)
             self._store(l, L0, k, v)
             K, Vv = self._k[l][:L0 + M], self._v[l][:L0 + M]
             o = np.zeros((M, Hq, dh), dtype=dt)
@@ -245,11 +258,11 @@ class CachedDecoder:
                 hk = hq // group
                 s = (q[:, hq, :] @ K[:, hk, :].T) / np.sqrt(dt(dh))
                 s = np.where(hidden, -np.inf, s)
-                o[:, hq, :] = softmax_rows(s) @ Vv[:, hk, :]
-            x = x + o.reshape(M, Hq * dh) @ _cast(w["wo"][l], dt).T
-            h2 = rmsnorm(x, _cast(w["ffn_norm"][l], dt), sh.rms_eps)
+                o[:, hq, :] = rd("p", softmax_rows(s)) @ Vv[:, hk, :]
+            x = x + rd("o", o.reshape(M, Hq * dh)) @ _cast(w["wo"][l], dt).T
+            h2 = rd("h", rmsnorm(x, _cast(w["ffn_norm"][l], dt), sh.rms_eps))
             F = sh.ffn
-            a = silu(h2 @ _cast(w["wgate_up"][l][:F], dt).T) * (h2 @ _cast(w["wgate_up"][l][F:], dt).T)
+            a = rd("a", silu(h2 @ _cast(w["wgate_up"][l][:F], dt).T) * (h2 @ _cast(w["wgate_up"][l][F:], dt).T))
             x = x + a @ _cast(w["wdown"][l], dt).T
         last = rmsnorm(x[-1], _cast(w["final_norm"], dt), sh.rms_eps)
         self.logits = _cast(w["lm_head"], dt) @ last

@@ -1,13 +1,16 @@
 """GPU parity at the full sequence sizes of the large presets (8b-long, 8b-ragged16, 70b), each on the
-4-layer truncation of its seeded model, against oracle results frozen in tests/golden/*_samples.npz.
+4-layer truncation of its seeded model, and of the 8B preset at its full depth of 32 layers (8b-full), against
+oracle results frozen in tests/golden/*_samples.npz.
 
-The oracle needs minutes per preset at these sizes (16k-token prefill, 70B-shaped matrices, 16 sequences),
-so tests/golden/make_golden_large.py (which imports only the oracle and the input generator) wrote its
-greedy streams, top-2 margins and, at sampled steps, the logits at 512 seeded vocabulary indices plus the
-top-2 ids and values.  Checked here, through the C ABI, in the configuration bench.py times:
+The oracle needs minutes per preset at these sizes (16k-token prefill, 70B-shaped matrices, 16 sequences, 32
+layers), so tests/golden/make_golden_large.py (which imports only the oracle and the input generator) wrote its
+greedy streams, top-2 margins, at sampled steps the logits at 512 seeded vocabulary indices plus the top-2 ids
+and values, and at a handful of points the whole logits vector.  Checked here, through the C ABI, in the
+configuration bench.py times:
   * greedy ids at EVERY step where the oracle's top-2 margin exceeds 1e-2 (the runs are teacher-forced with
     the oracle's stream);
   * sampled logits within the bf16 tolerance 2e-2, and the sampled top-2 values;
+  * every entry of the whole vectors (first choice, after the first and the last interrupt, end of the stream);
   * sequence lengths.
 The last test runs the 8B preset at full depth and full size (the configuration bench.py times) and checks the
 method's invariants, which hold at any size: in-flight inject == stateless re-prefill == token-by-token append,
@@ -53,11 +56,23 @@ def _check_samples(got, idx, want, t2i, t2v, what):
     return max(err, e2)
 
 
+def _check_full(got, want, what):
+    assert got.shape == want.shape
+    err = float(np.abs(got - want).max())
+    assert err <= TOL, (what, "whole vector", err)
+    return err
+
+
 def _single_sequence(name):
     import paper_2412_07017_amd as pkg
     z = _gold(name)
-    wl, model, w_dev = _model(name, z)
-    spec = ai.build_workload(name)
+    preset_name = name[:-5] if name.endswith("-full") else name
+    wl, model, w_dev = _model(preset_name, z)
+    if name.endswith("-full"):
+        assert model.n_layers == wl.model.n_layers
+    spec = ai.build_workload(preset_name)
+    full = {(int(k), int(s)): v for k, s, v in zip(z["full_kind"], z["full_step"], z["full_logits"])}
+    n_full = 0
     idx = z["sample_idx"]
     gen, margins = z["generated"], z["margins"]
     n = spec["n_decode"]
@@ -78,16 +93,24 @@ def _single_sequence(name):
         if j in samples:
             k = samples[j]
             worst = max(worst, _check_samples(got, idx, z["choose_samples"][k], z["choose_top2_ids"][k], z["choose_top2_vals"][k], ("step", j)))
+        if (0, j) in full:
+            worst = max(worst, _check_full(got, full[(0, j)], ("step", j))); n_full += 1
         assert lm.decode_step(0, forced_token=int(gen[j])) == int(gen[j])
         if j + 1 in ev:
             lm.inject_interrupt(0, ev[j + 1])
             k = inj[j + 1]
-            worst = max(worst, _check_samples(lm.logits(0), idx, z["inject_samples"][k], z["inject_top2_ids"][k], z["inject_top2_vals"][k], ("inject", j + 1)))
-    worst = max(worst, _check_samples(lm.logits(0), idx, z["final_samples"], z["final_top2_ids"], z["final_top2_vals"], "final"))
+            got_i = lm.logits(0)
+            worst = max(worst, _check_samples(got_i, idx, z["inject_samples"][k], z["inject_top2_ids"][k], z["inject_top2_vals"][k], ("inject", j + 1)))
+            if (1, j + 1) in full:
+                worst = max(worst, _check_full(got_i, full[(1, j + 1)], ("inject", j + 1))); n_full += 1
+    last = lm.logits(0)
+    worst = max(worst, _check_samples(last, idx, z["final_samples"], z["final_top2_ids"], z["final_top2_vals"], "final"))
+    worst = max(worst, _check_full(last, full[(2, n)], "final")); n_full += 1
+    assert n_full == len(full)
     assert lm.seq_len(0) == int(z["stream_len"]) == total
     lm.close()
-    print("%s / %d layers: max sampled |logit err| = %.3e over %d sampled vectors, %d margin-gated ids identical over %d steps"
-          % (name, model.n_layers, worst, len(samples) + len(inj) + 1, gated, n))
+    print("%s / %d layers: max |logit err| = %.3e over %d sampled and %d whole vectors, %d margin-gated ids identical over %d steps"
+          % (name, model.n_layers, worst, len(samples) + len(inj) + 1, n_full, gated, n))
 
 
 @pytest.mark.timeout(900)
@@ -95,6 +118,13 @@ def test_8b_long_context_workload_matches_frozen_oracle():
     """16384-token prompt, 512 tokens, 8 interrupts of 48 tokens: long-context decode attention (many splits
     merged by the last workgroup) and chunk attention over 17k keys."""
     _single_sequence("8b-long")
+
+
+@pytest.mark.timeout(900)
+def test_8b_workload_at_full_depth_matches_frozen_oracle():
+    """The headline configuration at full depth and full size: 32 layers, 1024-token prompt, 256 tokens, 24-token
+    interrupts after tokens 64, 128 and 192."""
+    _single_sequence("8b-full")
 
 
 @pytest.mark.timeout(900)
@@ -122,11 +152,15 @@ def test_8b_ragged16_batched_steps_match_frozen_oracle():
     for q, p in enumerate(spec["prompts"]):
         lm.prefill(q, p)
     seqs = list(range(ns))
-    worst, gated, rows = 0.0, 0, 0
+    assert n_steps == wl.n_decode                               # every batched step of the preset is frozen
+    sampled = {int(t): k for k, t in enumerate(z["sample_steps"])}
+    full = {(int(t), int(q)): v for t, q, v in zip(z["full_step"], z["full_seq"], z["full_logits"])}
+    worst, gated, rows, n_full, biggest = 0.0, 0, 0, 0, 0
     for t in range(n_steps):
         ev = dict(spec["step_events"][t])
         intr = [ev.get(q, []) for q in seqs]
         rows += ns + sum(len(x) for x in intr)
+        biggest = max(biggest, ns + sum(len(x) for x in intr))
         if (margins[t] > MARGIN).all():
             got = lm.step_batch(seqs, None, intr)               # greedy on the device
             assert list(got) == [int(v) for v in gen[t]], t
@@ -135,12 +169,21 @@ def test_8b_ragged16_batched_steps_match_frozen_oracle():
             got = lm.step_batch(seqs, [int(v) for v in gen[t]], intr)
             assert list(got) == [int(v) for v in gen[t]]
         for q in seqs:
-            worst = max(worst, _check_samples(lm.logits(q), idx, z["after_samples"][t, q], z["after_top2_ids"][t, q],
-                                              z["after_top2_vals"][t, q], ("step", t, "seq", q)))
+            got_q = lm.logits(q)
+            assert np.isfinite(got_q).all()
+            t2i, t2v = z["after_top2_ids"][t, q], z["after_top2_vals"][t, q]
+            e2 = float(np.abs(got_q[t2i] - t2v).max())                      # top-2 values after every step
+            assert e2 <= TOL, ("step", t, "seq", q, "top-2", e2)
+            worst = max(worst, e2)
+            if t in sampled:
+                worst = max(worst, _check_samples(got_q, idx, z["after_samples"][sampled[t], q], t2i, t2v, ("step", t, "seq", q)))
+            if (t, q) in full:
+                worst = max(worst, _check_full(got_q, full[(t, q)], ("step", t, "seq", q))); n_full += 1
+    assert n_full == len(full)
     assert [lm.seq_len(q) for q in seqs] == [int(v) for v in z["lengths"]]
     lm.close()
-    print("%s / %d layers: max sampled |logit err| = %.3e over %d batched steps (%.1f rows per step), %d greedy ids identical"
-          % (name, model.n_layers, worst, n_steps, rows / n_steps, gated))
+    print("%s / %d layers: max |logit err| = %.3e over %d batched steps (%.1f rows per step, at most %d), %d sampled steps, %d whole "
+          "vectors, %d greedy ids identical" % (name, model.n_layers, worst, n_steps, rows / n_steps, biggest, len(sampled), n_full, gated))
 
 
 @pytest.mark.timeout(900)
