@@ -54,11 +54,17 @@ extern "C" {
 /* Storage of cached keys and values.
  * AUTO: fp32 for fp32 models; for bf16 models a PAIR of bf16 planes, hi = bf16(x) and
  *       lo = bf16(x - hi) (about 16 mantissa bits, 4 bytes per element), which keeps the logits within
- *       the bf16 parity tolerance of an fp32 reference at any depth.
+ *       the bf16 parity tolerance of an fp32 reference at any depth.  Models that the matrix-core append path
+ *       serves (bf16, head_dim 128, d_model and ffn multiples of 128) keep the values only transposed and tiled
+ *       (the operand order of that path's attention, which also serves their decoding steps).
  * BF16: bf16 models only: the hi plane alone (2 bytes per element).  Halves cache size and traffic; the
- *       rounding of K and V then moves logits by several 1e-2 on N(0, 0.02)-initialised models. */
+ *       rounding of K and V then moves logits by several 1e-2 on N(0, 0.02)-initialised models.
+ * PAIR_ROWS: as AUTO, and the values are kept row by row as well (half as much cache again): the layout that the
+ *       single-row attention kernel reads, which the options "attn_mfma_min" = 0, "fused" and "pipeline" need on
+ *       models of the append path (they are ignored there without it). */
 #define ASYNCLM_KV_AUTO 0
 #define ASYNCLM_KV_BF16 1
+#define ASYNCLM_KV_PAIR_ROWS 2
 
 typedef struct asynclm_ctx asynclm_ctx;   /* opaque; owned by the library */
 

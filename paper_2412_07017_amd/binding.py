@@ -8,7 +8,7 @@ from typing import Dict, List, Optional, Sequence
 import numpy as np
 
 E_INVAL, E_STATE, E_CAPACITY, E_NOMEM, E_DEVICE = -1, -2, -3, -4, -5
-KV_AUTO, KV_BF16 = 0, 1
+KV_AUTO, KV_BF16, KV_PAIR_ROWS = 0, 1, 2
 
 API_SYMBOLS = [
     "asynclm_create", "asynclm_destroy", "asynclm_prefill", "asynclm_decode_step",

@@ -153,7 +153,8 @@ void* kv_layer_ptr(const asynclm_ctx* c, int layer) {
 struct SplitPlan { int nsplit; bool merge_in_oproj; bool mfma; };
 
 SplitPlan pick_nsplit(const asynclm_ctx* c, int len_after, bool single_row_kernel = false) {
-    if (!single_row_kernel && c->chunk_ok && c->opt_attn_mfma_min > 0 && len_after >= c->opt_attn_mfma_min) {
+    const bool no_v_rows = c->g.kv_v_offset == 0;      // the single-row kernel has nothing to read: matrix cores at any length
+    if (!single_row_kernel && c->chunk_ok && (no_v_rows || (c->opt_attn_mfma_min > 0 && len_after >= c->opt_attn_mfma_min))) {
         // attention on the matrix cores.  Measured optima: one tile of 32 keys per wave up to about 96 tiles (36 splits
         // for 35 tiles, 68 for 66), 68-96 splits for 132 tiles, 96 for 260 and 513 (more only lengthen the merge)
         const int tiles = (len_after + 31) / 32;
@@ -353,7 +354,8 @@ bool config_ok(const asynclm_config* k) {
     if (k->d_model % 8 || k->ffn % 8) return false;
     if (k->dtype != ASYNCLM_DTYPE_FP32 && k->dtype != ASYNCLM_DTYPE_BF16) return false;
     if (k->max_seqs < 1 || k->max_positions < 1) return false;
-    if (k->kv_format != ASYNCLM_KV_AUTO && !(k->kv_format == ASYNCLM_KV_BF16 && k->dtype == ASYNCLM_DTYPE_BF16)) return false;
+    if (k->kv_format != ASYNCLM_KV_AUTO &&
+        !((k->kv_format == ASYNCLM_KV_BF16 || k->kv_format == ASYNCLM_KV_PAIR_ROWS) && k->dtype == ASYNCLM_DTYPE_BF16)) return false;
     if (!(k->rms_eps >= 0.f) || !(k->rope_theta > 0.f)) return false;
     return true;
 }
@@ -552,10 +554,14 @@ int asynclm_create(asynclm_ctx** out, const asynclm_config* cfg, const asynclm_w
         c->chunk_ok = pair && g.dh == 128 && g.d % 128 == 0 && g.F % 128 == 0 && g.d <= 8192;
         const size_t plane = (size_t)g.max_pos * g.dh * g.Hkv;
         g.kv_head_stride = (size_t)g.max_pos * g.dh;
+        // row-major values: every model but those of the append path, whose attention (decoding steps included) reads
+        // the transposed planes only; PAIR_ROWS keeps both
+        const bool v_rows = !c->chunk_ok || cfg->kv_format == ASYNCLM_KV_PAIR_ROWS;
         g.kv_lo_offset = pair ? plane : 0;
-        g.kv_v_offset = pair ? 2 * plane : plane;
-        g.kv_vt_offset = c->chunk_ok ? 4 * plane : 0;
-        g.kv_layer_stride = c->chunk_ok ? 6 * plane : (pair ? 4 * plane : 2 * plane);
+        g.kv_v_offset = v_rows ? (pair ? 2 * plane : plane) : 0;
+        const size_t row_planes = (pair ? 2 : 1) * (v_rows ? 2 : 1);
+        g.kv_vt_offset = c->chunk_ok ? row_planes * plane : 0;
+        g.kv_layer_stride = (row_planes + (c->chunk_ok ? 2 : 0)) * plane;
         g.kv_seq_stride = g.kv_layer_stride * cfg->n_layers;
         if (c->chunk_ok) c->opt_chunk = CHUNK_MAX;
     }
@@ -682,12 +688,13 @@ int asynclm_create(asynclm_ctx** out, const asynclm_config* cfg, const asynclm_w
             hipMemset(c->bar, 0, FUSED_BAR_WORDS * sizeof(unsigned)) != hipSuccess)
             return bail(ASYNCLM_E_DEVICE);
         if ((e = fused_init(cfg->dtype, g, &c->fused)) != hipSuccess) { report_hip("fused_init", e); return bail(ASYNCLM_E_DEVICE); }
+        if (g.kv_v_offset == 0) c->fused.supported = false;     // its attention reads the values row by row
         c->opt_fused = 0;      // opt-in (set_option "fused"): the per-operation kernels are currently faster
         if (c->fused.supported && (e = dev_alloc(c, &c->trace, (size_t)FUSED_TRACE_MAX * c->fused.grid)) != hipSuccess) return bail(ASYNCLM_E_NOMEM);
     }
     const int max_k = g.F > g.d ? (g.F > g.Hq * g.dh ? g.F : g.Hq * g.dh) : (g.d > g.Hq * g.dh ? g.d : g.Hq * g.dh);
     if ((e = decode_init(cfg->dtype, max_k)) != hipSuccess) { report_hip("decode_init", e); return bail(ASYNCLM_E_DEVICE); }
-    c->pipe_ok = c->stream2 && decode_pipeline_fits(cfg->dtype, g, g.kv_lo_offset != 0);
+    c->pipe_ok = c->stream2 && g.kv_v_offset != 0 && decode_pipeline_fits(cfg->dtype, g, g.kv_lo_offset != 0);
     if (const char* pv = std::getenv("ASYNCLM_PIPELINE")) c->opt_pipeline = (std::atoi(pv) != 0 && c->pipe_ok) ? 1 : 0;
     if (std::getenv("ASYNCLM_VERBOSE")) std::fprintf(stderr, "[asynclm] two-stream step: fits %d, on %d\n", (int)c->pipe_ok, c->opt_pipeline);
     if ((e = hipDeviceSynchronize()) != hipSuccess) { report_hip("hipDeviceSynchronize", e); return bail(ASYNCLM_E_DEVICE); }
@@ -871,8 +878,8 @@ struct SwapHeader {
 };
 constexpr uint32_t SWAP_MAGIC = 0x4b56414cu;     // "LAVK"
 
-int swap_planes(const asynclm_ctx* c) {          // row-major planes per layer: K (+lo), V (+lo)
-    return c->g.kv_lo_offset ? 4 : 2;
+int swap_planes(const asynclm_ctx* c) {          // row-major planes per layer: K (+lo), and V (+lo) where it is kept
+    return (c->g.kv_lo_offset ? 2 : 1) * (c->g.kv_v_offset ? 2 : 1);
 }
 
 size_t swap_bytes(const asynclm_ctx* c, int len) {
@@ -897,8 +904,10 @@ hipError_t swap_copy(asynclm_ctx* c, int seq, int len, char* host, bool out) {
         size_t offs[4]; int np = 0;
         offs[np++] = 0;
         if (g.kv_lo_offset) offs[np++] = g.kv_lo_offset;
-        offs[np++] = g.kv_v_offset;
-        if (g.kv_lo_offset) offs[np++] = g.kv_v_offset + g.kv_lo_offset;
+        if (g.kv_v_offset) {
+            offs[np++] = g.kv_v_offset;
+            if (g.kv_lo_offset) offs[np++] = g.kv_v_offset + g.kv_lo_offset;
+        }
         for (int p = 0; p < np; ++p) {
             char* dev = base + offs[p] * esz;
             e = out ? hipMemcpy2DAsync(h, width, dev, pitch, width, g.Hkv, kind, c->stream)

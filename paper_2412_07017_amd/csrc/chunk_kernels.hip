@@ -274,8 +274,10 @@ __global__ void k_chunk_rope_kv(const float* __restrict__ P, int S, size_t s_str
         kp[i] = ahi; kp[i + half] = bhi; kp[g.kv_lo_offset + i] = alo; kp[g.kv_lo_offset + i + half] = blo;
     } else {
         const int vh = h - g.Hq - g.Hkv;
-        bf16_t* vp = kv_layer + g.kv_v_offset + seq_off + (size_t)vh * g.kv_head_stride + (size_t)pos * g.dh;
-        vp[i] = ahi; vp[i + half] = bhi; vp[g.kv_lo_offset + i] = alo; vp[g.kv_lo_offset + i + half] = blo;
+        if (g.kv_v_offset) {       // row-major values are only kept for the single-row attention kernel
+            bf16_t* vp = kv_layer + g.kv_v_offset + seq_off + (size_t)vh * g.kv_head_stride + (size_t)pos * g.dh;
+            vp[i] = ahi; vp[i + half] = bhi; vp[g.kv_lo_offset + i] = alo; vp[g.kv_lo_offset + i + half] = blo;
+        }
         bf16_t* vt = kv_layer + g.kv_vt_offset + seq_off + (size_t)vh * g.kv_head_stride;
         const size_t oa = vt_tile_off(pos, i), ob = vt_tile_off(pos, i + half);
         vt[oa] = ahi; vt[ob] = bhi; vt[g.kv_lo_offset + oa] = alo; vt[g.kv_lo_offset + ob] = blo;

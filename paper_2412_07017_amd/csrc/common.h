@@ -34,9 +34,10 @@ struct Geom {
     // K/V cache, element strides: [seq][layer][K | V | V^T][hi | lo][Hkv][max_pos][dh].  The lo plane
     // exists only in the paired bf16 format, where a value is stored as bf16(x) + bf16(x - bf16(x)).
     // V^T (same size per head, laid out by vt_tile_off) exists only with the append-chunk path: its PV product
-    // on the matrix cores needs 8 consecutive positions of one channel in one register quad.
+    // on the matrix cores needs 8 consecutive positions of one channel in one register quad.  Models of that path
+    // keep the row-major V only on request (it serves the single-row attention kernel).
     // max_pos is the allocated row count (capacity rounded up to a multiple of 32).
-    size_t kv_head_stride, kv_v_offset, kv_lo_offset /* 0: no lo plane */, kv_vt_offset /* 0: no V^T */;
+    size_t kv_head_stride, kv_v_offset /* 0: no row-major V */, kv_lo_offset /* 0: no lo plane */, kv_vt_offset /* 0: no V^T */;
     size_t kv_layer_stride, kv_seq_stride;
 };
 

@@ -532,8 +532,10 @@ __device__ __forceinline__ void finish_unit(int u, float sa, float sb, float e0,
             kv_store(kp + i, ra, g.kv_lo_offset); kv_store(kp + i + half, rb, g.kv_lo_offset);
         } else {
             const size_t head_off = seq_off + (size_t)(h - g.Hq - g.Hkv) * g.kv_head_stride;
-            WT* vp = (WT*)o.kv_layer + g.kv_v_offset + head_off + (size_t)o.pos * g.dh;
-            kv_store(vp + i, ra, g.kv_lo_offset); kv_store(vp + i + half, rb, g.kv_lo_offset);
+            if (g.kv_v_offset) {
+                WT* vp = (WT*)o.kv_layer + g.kv_v_offset + head_off + (size_t)o.pos * g.dh;
+                kv_store(vp + i, ra, g.kv_lo_offset); kv_store(vp + i + half, rb, g.kv_lo_offset);
+            }
             if (g.kv_vt_offset) {
                 WT* vt = (WT*)o.kv_layer + g.kv_vt_offset + head_off;
                 kv_store(vt + vt_tile_off(o.pos, i), ra, g.kv_lo_offset);

@@ -110,7 +110,7 @@ def test_two_stream_decoding_step_matches_oracle(trunc4):
     prompt, n_decode, events = spec["prompt"][:230], 48, [(20, spec["events"][0][1])]
     ref = orc.run_stream(orc.Shape.of(model), w_cpu, prompt, n_decode, events, dtype=np.float32)
     for graph in (1, 0):
-        lm = pkg.AsyncLM(model, w_dev, max_positions=640, stream=torch.cuda.Stream())
+        lm = pkg.AsyncLM(model, w_dev, max_positions=640, stream=torch.cuda.Stream(), kv_format=pkg.KV_PAIR_ROWS)
         lm.set_option("pipeline", 1)
         lm.set_option("graph", graph)
         lm.prefill(0, prompt)
@@ -174,7 +174,9 @@ def test_decode_attention_split_counts_agree_with_oracle(trunc4):
     t1 = dec.decode_step()
     want1 = dec.logits.copy()
     for nsplit in (1, 3, 8, 9, 24, 64, -4, -12, -64, -128):
-        lm = pkg.AsyncLM(model, w_dev, max_positions=320, stream=torch.cuda.Stream())
+        # the single-row kernel reads the values row by row: a cache format of its own on this model
+        lm = pkg.AsyncLM(model, w_dev, max_positions=320, stream=torch.cuda.Stream(),
+                         kv_format=pkg.KV_AUTO if nsplit < 0 else pkg.KV_PAIR_ROWS)
         lm.set_option("chunk", 1)                 # the prompt goes through the decode kernels too
         lm.set_option("attn_mfma_min", 1 if nsplit < 0 else 0)    # negative: matrix-core attention for single rows
         nsplit = abs(nsplit)
@@ -325,17 +327,24 @@ def test_step_batch_ragged_sequences_match_independent_oracle_sequences(trunc4):
 
 
 @pytest.mark.timeout(600)
-def test_kv_swap_roundtrip_on_the_paired_cache_with_transposed_planes(trunc4):
-    """Swap-out / swap-in (Sec. 5.4) on the bf16 shape: all six cache planes per layer (K, V and the tiled V^T,
-    hi and lo) come back, so both the single-row kernels and the matrix-core append path continue exactly."""
+@pytest.mark.parametrize("rows", [False, True])
+def test_kv_swap_roundtrip_on_the_paired_cache_with_transposed_planes(trunc4, rows):
+    """Swap-out / swap-in (Sec. 5.4) on the bf16 shape: all cache planes per layer come back (K and the tiled V^T, hi
+    and lo; with rows also the row-major V that the single-row attention kernel reads, which then runs the decoding
+    steps), so both the single-row kernels and the matrix-core append path continue exactly."""
     import time
     import paper_2412_07017_amd as pkg
     wl, model, w_dev, w_cpu, spec = trunc4
     toks = spec["prompt"]
-    lm = pkg.AsyncLM(model, w_dev, max_positions=1200, max_seqs=2, stream=torch.cuda.Stream())
+    lm = pkg.AsyncLM(model, w_dev, max_positions=1200, max_seqs=2, stream=torch.cuda.Stream(),
+                     kv_format=pkg.KV_PAIR_ROWS if rows else pkg.KV_AUTO)
+    if rows:
+        lm.set_option("attn_mfma_min", 0)
+    per_pos = 2 * model.n_layers * model.n_kv_heads * model.head_dim * 2 * (3 if rows else 2)     # bytes per cached position
     lm.prefill(0, toks[:1000])
     lm.decode_step(0)
     nbytes = lm.kv_bytes(0)
+    assert 1001 * per_pos <= nbytes <= 1024 * per_pos + 4 * model.vocab + 256          # two or three pairs of planes, the logits
     buf = torch.empty(nbytes, dtype=torch.uint8).pin_memory()
     t0 = time.perf_counter(); lm.kv_swap_out(0, buf.data_ptr(), nbytes); t_out = time.perf_counter() - t0
     intr = toks[1000:1024]
