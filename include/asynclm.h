@@ -29,8 +29,10 @@
  *   - One caller thread per context.  Work is enqueued on the HIP stream given at create; calls
  *     that return data to the host synchronise that stream, the others may return before the GPU
  *     has finished.
- *   - All device memory the library needs (K/V cache, rotary table, activations, logits) is
- *     allocated in asynclm_create; no other call allocates.
+ *   - All memory the library needs (K/V cache, rotary table, activations, logits, pinned staging, the captured
+ *     graphs of the decoding steps for every context length up to max_positions) is allocated in asynclm_create.
+ *     Of the other calls only asynclm_set_option allocates (options that change the launch geometry of a decoding
+ *     step build its graphs again) and asynclm_profile_step (events).
  */
 #ifndef ASYNCLM_H
 #define ASYNCLM_H
@@ -110,7 +112,7 @@ int asynclm_prefill(asynclm_ctx *ctx, int32_t seq, const int32_t *tokens, int32_
  * sequence and run one forward pass, leaving the logits for the token after it.
  * token_out (host pointer, may be NULL): receives the chosen token.  The call waits only until the
  * token has been chosen (the first kernel of the step), not for the forward pass, which is still
- * running when it returns: the caller (the token monitor of Sec. 5.3) works on the token while
+ * running when it returns: the caller (the token monitor of Sec. 5.1) works on the token while
  * the device computes, and the next call queues behind the running step.  (With the "fused"
  * option the call waits for the whole step.)  NULL: nothing is waited for. */
 int asynclm_decode_step(asynclm_ctx *ctx, int32_t seq, int32_t forced_token, int32_t *token_out);

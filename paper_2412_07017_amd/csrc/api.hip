@@ -17,10 +17,14 @@ using namespace asynclm;
 // Host-side builder of the row table of one pass.
 struct PassBuilder {
     ChunkTable t{};
-    int G = 1, max_keys = 0;
+    int G = 1, Hkv = 1, max_keys = 0;
     void clear() { t.rows = t.ngroups = t.ntasks = t.nhead = t.nblocks = 0; max_keys = 0; }
     int tiles_of(int n) const { return (G * n + 31) / 32; }
-    bool fits(int n) const { return t.rows + n <= CHUNK_MAX && t.ntasks + tiles_of(n) <= CHUNK_MAX_TASKS; }
+    // rows, attention tasks, and the attention's partial results (task x kv head x at least 4 key splits) all fit one pass
+    bool fits(int n) const {
+        return t.rows + n <= CHUNK_MAX && t.ntasks + tiles_of(n) <= CHUNK_MAX_TASKS &&
+               (long long)(t.ntasks + tiles_of(n)) * Hkv * 4 <= CHUNK_ATTN_MAX_UNITS;
+    }
     // Appends a group of n rows to sequence `seq` (length before: pos0).  forced: see ChunkGroup; `rest` holds the
     // tokens of the rows that are not chosen on the device (n of them if forced == -2, else n - 1).
     void add(int seq, int pos0, int n, int forced, const int32_t* rest, bool want_head) {
@@ -88,12 +92,23 @@ struct asynclm_ctx {
     std::vector<char> choice_stale;     // the ban list changed after the sequence's greedy token was computed
     PassBuilder pass;                   // row table of the append-chunk pass being built
     int32_t* chosen_host = nullptr;     // pinned, CHUNK_MAX ints
+    // pinned staging of what the host uploads on the hot path (a pageable source would make the copy wait for the
+    // stream): two copies of the row table and a small ring of ban-list rows, each reused once its event has passed
+    ChunkTable* tab_host[2] = {nullptr, nullptr};
+    hipEvent_t tab_ev[2] = {nullptr, nullptr};
+    int tab_next = 0;
+    static constexpr int BAN_RING = 4;
+    int32_t* ban_host = nullptr;        // [BAN_RING][1 + BAN_MAX]
+    hipEvent_t ban_ev[BAN_RING] = {};
+    int ban_next = 0;
+    std::vector<char> batch_seen;       // scratch of asynclm_step_batch (sized at create)
+    std::vector<int> batch_owner;
 
     // options
     int opt_chunk = 1, opt_graph = 1, opt_attn_split = 0, opt_chunk_split = 0, opt_fused = 0, opt_attn_mfma_min = 1;
     int opt_pipeline = 0;
 
-    std::map<int, hipGraphExec_t> graphs;   // key: nsplit * 2 + with_head
+    std::map<int, hipGraphExec_t> graphs;   // captured decoding steps by graph_key(), all instantiated by rebuild_graphs()
 
     // profiling of one step
     bool prof = false;
@@ -155,10 +170,10 @@ struct SplitPlan { int nsplit; bool merge_in_oproj; bool mfma; };
 SplitPlan pick_nsplit(const asynclm_ctx* c, int len_after, bool single_row_kernel = false) {
     const bool no_v_rows = c->g.kv_v_offset == 0;      // the single-row kernel has nothing to read: matrix cores at any length
     if (!single_row_kernel && c->chunk_ok && (no_v_rows || (c->opt_attn_mfma_min > 0 && len_after >= c->opt_attn_mfma_min))) {
-        // attention on the matrix cores.  Measured optima: one tile of 32 keys per wave up to about 96 tiles (36 splits
-        // for 35 tiles, 68 for 66), 68-96 splits for 132 tiles, 96 for 260 and 513 (more only lengthen the merge)
-        const int tiles = (len_after + 31) / 32;
-        int n = std::max(4, std::min((tiles + 3) / 4 * 4, 96));
+        // attention on the matrix cores: 96 key splits at every length (a wave takes one tile of 32 keys up to 3072 keys,
+        // more beyond; waves without keys leave at once), so one captured graph serves every context length.  Measured
+        // optima were one tile per wave up to about 96 tiles and 96 splits beyond (more only lengthen the merge).
+        int n = 96;
         if (c->opt_attn_split > 0) n = std::max(4, std::min((c->opt_attn_split + 3) / 4 * 4, CHUNK_ATTN_MAX_SPLIT));
         return {n, false, true};
     }
@@ -193,7 +208,7 @@ hipError_t forward_single(asynclm_ctx* c, int seq, bool with_head, SplitPlan sp)
     }
     if (with_head) {
         // logits of every sequence live in one array; the kernels pick the row from the descriptor
-        if ((e = run(c, KC_LMHEAD, [&] { return launch_lmhead(dt, c->lm_head, c->final_norm, c->logits + (size_t)seq * g.V, c->b, g, s); }))) return e;
+        if ((e = run(c, KC_LMHEAD, [&] { return launch_lmhead(dt, c->lm_head, c->final_norm, c->logits, c->b, g, s); }))) return e;
         if ((e = run(c, KC_ARGMAX, [&] { return launch_argmax(c->logits, c->b, g, s); }))) return e;
     }
     return hipSuccess;
@@ -251,7 +266,7 @@ hipError_t forward_single_pipelined(asynclm_ctx* c, int seq, bool with_head, Spl
         next(); if ((e = launch_down(dt, c->wdown[l], c->b, g, s, &ps, c->b.x2))) return e;
     }
     if (with_head) {
-        next(); if ((e = launch_lmhead(dt, c->lm_head, c->final_norm, c->logits + (size_t)seq * g.V, c->b, g, s, &ps))) return e;
+        next(); if ((e = launch_lmhead(dt, c->lm_head, c->final_norm, c->logits, c->b, g, s, &ps))) return e;
     }
     if ((e = hipEventRecord(c->ev_join, sb))) return e;
     if ((e = hipStreamWaitEvent(sa, c->ev_join, 0))) return e;
@@ -266,27 +281,47 @@ bool use_pipeline(const asynclm_ctx* c, int len_after) {
            c->g.Hkv * 8 <= PIPE_MAX_WORKGROUPS;      // at most 8 key splits reach this step
 }
 
-// The same pass, replayed from a captured graph (one graph per split count / head flag / sequence).
-hipError_t forward_single_graph(asynclm_ctx* c, int seq, bool with_head, SplitPlan sp, bool pipelined) {
-    constexpr int SPLIT_SLOTS = (ATTN_MAX_SPLIT > CHUNK_ATTN_MAX_SPLIT ? ATTN_MAX_SPLIT : CHUNK_ATTN_MAX_SPLIT) + 1;
-    const int key = ((((((seq * SPLIT_SLOTS + sp.nsplit) << 1) | (sp.merge_in_oproj ? 1 : 0)) << 1 | (sp.mfma ? 1 : 0)) << 1) | (with_head ? 1 : 0)) << 1 |
-                    (pipelined ? 1 : 0);
-    auto it = c->graphs.find(key);
-    if (it == c->graphs.end()) {
-        hipError_t e;
-        hipGraph_t graph = nullptr;
-        if ((e = hipStreamBeginCapture(c->stream, hipStreamCaptureModeRelaxed))) return e;
-        e = pipelined ? forward_single_pipelined(c, seq, with_head, sp) : forward_single(c, seq, with_head, sp);
-        hipError_t e2 = hipStreamEndCapture(c->stream, &graph);
-        if (e) { if (graph) hipGraphDestroy(graph); return e; }
-        if (e2) return e2;
-        hipGraphExec_t exec = nullptr;
-        e = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0);
-        hipGraphDestroy(graph);
-        if (e) return e;
-        it = c->graphs.emplace(key, exec).first;
+// Captured steps.  The kernels read token, position and sequence from the step descriptor, so a graph depends only on
+// the launch geometry: the attention plan, whether the pass ends with the output head, one or two streams.
+int graph_key(SplitPlan sp, bool with_head, bool pipelined) {
+    return ((((sp.nsplit << 1 | (sp.merge_in_oproj ? 1 : 0)) << 1 | (sp.mfma ? 1 : 0)) << 1 | (with_head ? 1 : 0)) << 1) | (pipelined ? 1 : 0);
+}
+
+hipError_t capture_step(asynclm_ctx* c, SplitPlan sp, bool with_head, bool pipelined, hipGraphExec_t* out) {
+    hipError_t e;
+    hipGraph_t graph = nullptr;
+    if ((e = hipStreamBeginCapture(c->stream, hipStreamCaptureModeRelaxed))) return e;
+    e = pipelined ? forward_single_pipelined(c, 0, with_head, sp) : forward_single(c, 0, with_head, sp);
+    hipError_t e2 = hipStreamEndCapture(c->stream, &graph);
+    if (e) { if (graph) hipGraphDestroy(graph); return e; }
+    if (e2) return e2;
+    e = hipGraphInstantiate(out, graph, nullptr, nullptr, 0);
+    hipGraphDestroy(graph);
+    return e;
+}
+
+// Instantiates every graph that a decoding step can need under the current options (all attention plans that occur
+// up to max_positions), so that no decoding step captures, instantiates or allocates.  Called by asynclm_create and by
+// the options that change the launch geometry.
+hipError_t rebuild_graphs(asynclm_ctx* c) {
+    for (auto& kv : c->graphs) hipGraphExecDestroy(kv.second);
+    c->graphs.clear();
+    if (!c->opt_graph || !c->stream || c->opt_fused) return hipSuccess;
+    const bool was_prof = c->prof;
+    c->prof = false;
+    hipError_t e = hipSuccess;
+    for (int len_after = 1; len_after <= c->cfg.max_positions && !e; ++len_after) {
+        const bool pipelined = use_pipeline(c, len_after);
+        const SplitPlan sp = pick_nsplit(c, len_after, pipelined);
+        for (int with_head = 0; with_head < 2 && !e; ++with_head) {
+            const int key = graph_key(sp, with_head != 0, pipelined);
+            if (c->graphs.count(key)) continue;
+            hipGraphExec_t exec = nullptr;
+            if ((e = capture_step(c, sp, with_head != 0, pipelined, &exec)) == hipSuccess) c->graphs.emplace(key, exec);
+        }
     }
-    return hipGraphLaunch(it->second, c->stream);
+    c->prof = was_prof;
+    return e;
 }
 
 // The greedy token of a sequence is computed when a forward pass ends; if the ban list changed since, it is
@@ -327,7 +362,8 @@ hipError_t step_one_token(asynclm_ctx* c, int seq, int forced, bool with_head) {
         c->tok_early = true;
     }
     c->pipe_kernels = pipelined ? 5 * c->cfg.n_layers + (with_head ? 1 : 0) : 0;
-    if (c->opt_graph && !c->prof) e = forward_single_graph(c, seq, with_head, sp, pipelined);
+    auto g_it = (c->opt_graph && !c->prof) ? c->graphs.find(graph_key(sp, with_head, pipelined)) : c->graphs.end();
+    if (g_it != c->graphs.end()) e = hipGraphLaunch(g_it->second, c->stream);
     else if (pipelined) e = forward_single_pipelined(c, seq, with_head, sp);
     else e = forward_single(c, seq, with_head, sp);
     if (e) return e;
@@ -451,8 +487,15 @@ hipError_t forward_chunk(asynclm_ctx* c, const PassBuilder& pb) {
     }
     const int dt = c->cfg.dtype;
     hipError_t e;
-    // pageable source: the runtime stages the table before the call returns
-    if ((e = hipMemcpyAsync(cb.tab, &t, offsetof(ChunkTable, row) + sizeof(ChunkRow) * rows, hipMemcpyHostToDevice, s))) return e;
+    {   // through pinned memory: the copy is asynchronous and the host goes on enqueuing the pass
+        const int i = c->tab_next;
+        const size_t bytes = offsetof(ChunkTable, row) + sizeof(ChunkRow) * rows;
+        if ((e = hipEventSynchronize(c->tab_ev[i]))) return e;         // the upload that last used this copy has finished
+        std::memcpy(c->tab_host[i], &t, bytes);
+        if ((e = hipMemcpyAsync(cb.tab, c->tab_host[i], bytes, hipMemcpyHostToDevice, s))) return e;
+        if ((e = hipEventRecord(c->tab_ev[i], s))) return e;
+        c->tab_next = i ^ 1;
+    }
     if ((e = run(c, KC_BEGIN, [&] { return launch_begin_chunk(cb, c->b, t.ngroups, s); }))) return e;
     if ((e = run(c, KC_CHUNK_PREP, [&] { return launch_chunk_embed(c->embed, cb, rows, g, s); }))) return e;
     for (int l = 0; l < c->cfg.n_layers; ++l) {
@@ -483,7 +526,7 @@ hipError_t forward_chunk(asynclm_ctx* c, const PassBuilder& pb) {
             if (t.group[gi].head < 0) continue;
             const int seq = t.group[gi].seq;
             if ((e = run(c, KC_CHUNK_MISC, [&] { return launch_chunk_last_row(cb, sp.down, MT, gi, c->b, g, s); }))) return e;
-            if ((e = run(c, KC_LMHEAD, [&] { return launch_lmhead(dt, c->lm_head, c->final_norm, c->logits + (size_t)seq * g.V, c->b, g, s); }))) return e;
+            if ((e = run(c, KC_LMHEAD, [&] { return launch_lmhead(dt, c->lm_head, c->final_norm, c->logits, c->b, g, s); }))) return e;
             if ((e = run(c, KC_ARGMAX, [&] { return launch_argmax(c->logits, c->b, g, s); }))) return e;
         }
     }
@@ -609,7 +652,7 @@ int asynclm_create(asynclm_ctx** out, const asynclm_config* cfg, const asynclm_w
         if ((e = chunk_init()) != hipSuccess) { report_hip("chunk_init", e); return bail(ASYNCLM_E_DEVICE); }
         cb.q_cols = (g.Hq / g.Hkv) * CHUNK_MAX + 32;
         const size_t qn = (size_t)g.Hkv * cb.q_cols * g.dh;
-        c->pass.G = g.Hq / g.Hkv;
+        c->pass.G = g.Hq / g.Hkv; c->pass.Hkv = g.Hkv;
         ALLOC(cb.tab, 1);
         ALLOC(cb.chosen, M);
         ALLOC(cb.x, M * g.d);
@@ -671,6 +714,15 @@ int asynclm_create(asynclm_ctx** out, const asynclm_config* cfg, const asynclm_w
             return bail(ASYNCLM_E_DEVICE);
     }
     if (hipHostMalloc((void**)&c->chosen_host, sizeof(int32_t) * CHUNK_MAX, hipHostMallocDefault) != hipSuccess) return bail(ASYNCLM_E_NOMEM);
+    for (int i = 0; i < 2; ++i)
+        if (hipHostMalloc((void**)&c->tab_host[i], sizeof(ChunkTable), hipHostMallocDefault) != hipSuccess ||
+            hipEventCreateWithFlags(&c->tab_ev[i], hipEventDisableTiming) != hipSuccess)
+            return bail(ASYNCLM_E_NOMEM);
+    if (hipHostMalloc((void**)&c->ban_host, sizeof(int32_t) * asynclm_ctx::BAN_RING * (1 + BAN_MAX), hipHostMallocDefault) != hipSuccess) return bail(ASYNCLM_E_NOMEM);
+    for (int i = 0; i < asynclm_ctx::BAN_RING; ++i)
+        if (hipEventCreateWithFlags(&c->ban_ev[i], hipEventDisableTiming) != hipSuccess) return bail(ASYNCLM_E_DEVICE);
+    c->batch_seen.assign(cfg->max_seqs, 0);
+    c->batch_owner.reserve(CHUNK_MAX_TASKS + 1);
     // fused decoding step: pointer table, barrier counters, launch plan
     {
         std::vector<const void*> tab;
@@ -697,6 +749,7 @@ int asynclm_create(asynclm_ctx** out, const asynclm_config* cfg, const asynclm_w
     c->pipe_ok = c->stream2 && g.kv_v_offset != 0 && decode_pipeline_fits(cfg->dtype, g, g.kv_lo_offset != 0);
     if (const char* pv = std::getenv("ASYNCLM_PIPELINE")) c->opt_pipeline = (std::atoi(pv) != 0 && c->pipe_ok) ? 1 : 0;
     if (std::getenv("ASYNCLM_VERBOSE")) std::fprintf(stderr, "[asynclm] two-stream step: fits %d, on %d\n", (int)c->pipe_ok, c->opt_pipeline);
+    if ((e = rebuild_graphs(c)) != hipSuccess) { report_hip("capture of the decoding steps", e); return bail(ASYNCLM_E_DEVICE); }
     if ((e = hipDeviceSynchronize()) != hipSuccess) { report_hip("hipDeviceSynchronize", e); return bail(ASYNCLM_E_DEVICE); }
     *out = c;
     return ASYNCLM_OK;
@@ -714,6 +767,13 @@ int asynclm_destroy(asynclm_ctx* c) {
     if (c->ev_fork) hipEventDestroy(c->ev_fork);
     if (c->ev_join) hipEventDestroy(c->ev_join);
     if (c->chosen_host) hipHostFree(c->chosen_host);
+    for (int i = 0; i < 2; ++i) {
+        if (c->tab_host[i]) hipHostFree(c->tab_host[i]);
+        if (c->tab_ev[i]) hipEventDestroy(c->tab_ev[i]);
+    }
+    if (c->ban_host) hipHostFree(c->ban_host);
+    for (int i = 0; i < asynclm_ctx::BAN_RING; ++i)
+        if (c->ban_ev[i]) hipEventDestroy(c->ban_ev[i]);
     delete c;
     return ASYNCLM_OK;
 }
@@ -764,7 +824,8 @@ int asynclm_step_batch(asynclm_ctx* c, int32_t nseq, const int32_t* seqs, const 
     if (nseq < 1 || nseq > c->cfg.max_seqs || !seqs) return ASYNCLM_E_INVAL;
     // everything is checked before anything is enqueued
     {
-        std::vector<char> seen(c->cfg.max_seqs, 0);
+        std::vector<char>& seen = c->batch_seen;
+        std::fill(seen.begin(), seen.end(), 0);
         for (int i = 0; i < nseq; ++i) {
             const int q = seqs[i];
             if (q < 0 || q >= c->cfg.max_seqs || seen[q]) return ASYNCLM_E_INVAL;
@@ -812,7 +873,8 @@ int asynclm_step_batch(asynclm_ctx* c, int32_t nseq, const int32_t* seqs, const 
     for (int i = 0; i < nseq; ++i)
         if (forced_of(i) < 0) HIPCK(c, refresh_choice(c, seqs[i]));
     PassBuilder& pb = c->pass;
-    std::vector<int> owner;                 // group of the current pass -> index i whose token it chooses, or -1
+    std::vector<int>& owner = c->batch_owner;   // group of the current pass -> index i whose token it chooses, or -1
+    owner.clear();
     auto flush = [&]() -> int {
         if (pb.t.rows == 0) return ASYNCLM_OK;
         const int ng = pb.t.ngroups;
@@ -854,14 +916,18 @@ int asynclm_set_banned_tokens(asynclm_ctx* c, int32_t seq, const int32_t* ids, i
     int r = check_seq(c, seq);
     if (r) return r;
     if (n < 0 || n > BAN_MAX || (n > 0 && !ids)) return ASYNCLM_E_INVAL;
-    int32_t row[1 + BAN_MAX] = {0};
-    row[0] = n;
-    for (int i = 0; i < n; ++i) {
+    for (int i = 0; i < n; ++i)
         if (ids[i] < 0 || ids[i] >= c->cfg.vocab) return ASYNCLM_E_INVAL;
-        row[1 + i] = ids[i];
-    }
-    // pageable source: the runtime stages the row before the call returns; stream order puts it before later steps
-    HIPCK(c, hipMemcpyAsync(c->b.banned + (size_t)seq * (1 + BAN_MAX), row, sizeof(row), hipMemcpyHostToDevice, c->stream));
+    // through a pinned row (asynchronous copy; stream order puts it before later steps)
+    const int slot = c->ban_next;
+    HIPCK(c, hipEventSynchronize(c->ban_ev[slot]));
+    int32_t* row = c->ban_host + (size_t)slot * (1 + BAN_MAX);
+    std::memset(row, 0, sizeof(int32_t) * (1 + BAN_MAX));
+    row[0] = n;
+    for (int i = 0; i < n; ++i) row[1 + i] = ids[i];
+    HIPCK(c, hipMemcpyAsync(c->b.banned + (size_t)seq * (1 + BAN_MAX), row, sizeof(int32_t) * (1 + BAN_MAX), hipMemcpyHostToDevice, c->stream));
+    HIPCK(c, hipEventRecord(c->ban_ev[slot], c->stream));
+    c->ban_next = (slot + 1) % asynclm_ctx::BAN_RING;
     c->nban[seq] = n;
     if (c->len[seq] > 0) c->choice_stale[seq] = 1;      // the next greedy choice is recomputed under the new list
     return ASYNCLM_OK;
@@ -1044,12 +1110,18 @@ int asynclm_set_option(asynclm_ctx* c, const char* name, int32_t value) {
     if (!c || !name) return ASYNCLM_E_INVAL;
     if (!std::strcmp(name, "chunk")) { if (value < 1 || value > CHUNK_MAX) return ASYNCLM_E_INVAL; c->opt_chunk = value; return ASYNCLM_OK; }
     if (!std::strcmp(name, "chunk_split")) { if (value < 0 || value > CHUNK_GEMM_MAX_SPLIT) return ASYNCLM_E_INVAL; c->opt_chunk_split = value; return ASYNCLM_OK; }
-    if (!std::strcmp(name, "gemv_grid")) { if (value < 1 || value > 4096) return ASYNCLM_E_INVAL; decode_set_gemv_grid(value); return ASYNCLM_OK; }
-    if (!std::strcmp(name, "fused")) { c->opt_fused = (value && c->fused.supported) ? 1 : 0; return ASYNCLM_OK; }
-    if (!std::strcmp(name, "pipeline")) { c->opt_pipeline = (value && c->pipe_ok) ? 1 : 0; return ASYNCLM_OK; }
-    if (!std::strcmp(name, "graph")) { c->opt_graph = (value && c->stream) ? 1 : 0; return ASYNCLM_OK; }
-    if (!std::strcmp(name, "attn_mfma_min")) { if (value < 0) return ASYNCLM_E_INVAL; c->opt_attn_mfma_min = value; return ASYNCLM_OK; }
-    if (!std::strcmp(name, "attn_split")) { if (value < 0 || value > CHUNK_ATTN_MAX_SPLIT) return ASYNCLM_E_INVAL; c->opt_attn_split = value; return ASYNCLM_OK; }
+    // the options below change the launch geometry of a decoding step: its captured graphs are built again (this call allocates)
+    auto regraph = [&]() -> int {
+        HIPCK(c, hipStreamSynchronize(c->stream));
+        HIPCK(c, rebuild_graphs(c));
+        return ASYNCLM_OK;
+    };
+    if (!std::strcmp(name, "gemv_grid")) { if (value < 1 || value > 4096) return ASYNCLM_E_INVAL; decode_set_gemv_grid(value); return regraph(); }
+    if (!std::strcmp(name, "fused")) { c->opt_fused = (value && c->fused.supported) ? 1 : 0; return regraph(); }
+    if (!std::strcmp(name, "pipeline")) { c->opt_pipeline = (value && c->pipe_ok) ? 1 : 0; return regraph(); }
+    if (!std::strcmp(name, "graph")) { c->opt_graph = (value && c->stream) ? 1 : 0; return regraph(); }
+    if (!std::strcmp(name, "attn_mfma_min")) { if (value < 0) return ASYNCLM_E_INVAL; c->opt_attn_mfma_min = value; return regraph(); }
+    if (!std::strcmp(name, "attn_split")) { if (value < 0 || value > CHUNK_ATTN_MAX_SPLIT) return ASYNCLM_E_INVAL; c->opt_attn_split = value; return regraph(); }
     return ASYNCLM_E_INVAL;
 }
 

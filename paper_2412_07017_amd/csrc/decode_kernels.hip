@@ -63,6 +63,7 @@ struct GemvArgs {
     const float* rope_sin;
     const StepDesc* step;
     int32_t layer;
+    int32_t y_seq_stride;   // EPI_STORE: y is the row step->seq of a [sequences][y_seq_stride] array
     // merged attention output as input vector (x == nullptr): see VecSource
     const float* part_acc; const float* part_ml; int32_t merge_nsplit, merge_dh, merge_hq;
     PipeSync sync;          // hand-over from / to the neighbouring kernels of a step that runs on two streams
@@ -105,6 +106,7 @@ __global__ __launch_bounds__(256, PIPE ? 2 : 1) void k_gemv(GemvArgs a, Geom g) 
     eo.y = a.y; eo.res = a.res; eo.q_out = a.q_out; eo.kv_layer = a.kv_layer;
     eo.rope_cos = a.rope_cos; eo.rope_sin = a.rope_sin; eo.rows = a.rows; eo.pos = 0; eo.seq = 0;
     if (EPI == EPI_QKV) { eo.pos = a.step->pos; eo.seq = a.step->seq; }
+    if (EPI == EPI_STORE) eo.y += (size_t)a.step->seq * a.y_seq_stride;      // the logits row of the step's sequence
     if (PIPE) {
         // nothing but weights before the hand-over: the residual may come from the kernel before the previous one,
         // which is only known to be complete once the previous one is
@@ -485,12 +487,12 @@ hipError_t launch_down(int dtype, const void* wd, const DecodeBuffers& b, const 
     return launch_gemv(dtype, EPI_RESID, a, g, s);
 }
 
-hipError_t launch_lmhead(int dtype, const void* wout, const float* gain, float* logits, const DecodeBuffers& b,
+hipError_t launch_lmhead(int dtype, const void* wout, const float* gain, float* logits_base, const DecodeBuffers& b,
                          const Geom& g, hipStream_t s, const PipeSync* sync) {
     GemvArgs a{};
     if (sync) a.sync = *sync;
     a.W = wout; a.rows = g.V; a.K = g.d; a.units = (a.rows + 1) / 2;
-    a.x = b.x; a.gain = gain; a.y = logits; a.step = b.step;
+    a.x = b.x; a.gain = gain; a.y = logits_base; a.y_seq_stride = g.V; a.step = b.step;
     return launch_gemv(dtype, EPI_STORE, a, g, s);
 }
 

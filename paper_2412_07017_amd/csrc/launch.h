@@ -150,7 +150,8 @@ hipError_t launch_gateup(int dtype, const void* wgu, const float* gain, const De
                          hipStream_t s, const PipeSync* sync = nullptr, const float* x_in = nullptr);
 hipError_t launch_down(int dtype, const void* wd, const DecodeBuffers& b, const Geom& g, hipStream_t s, const PipeSync* sync = nullptr,
                        const float* res_in = nullptr);
-hipError_t launch_lmhead(int dtype, const void* wout, const float* gain, float* logits, const DecodeBuffers& b,
+// logits_base: [sequences][V]; the kernel writes the row of the step descriptor's sequence
+hipError_t launch_lmhead(int dtype, const void* wout, const float* gain, float* logits_base, const DecodeBuffers& b,
                          const Geom& g, hipStream_t s, const PipeSync* sync = nullptr);
 // True when two workgroups of every single-row kernel of this model fit one compute unit (registers, LDS), i.e. when
 // the workgroups of two neighbouring kernels of a step can always all be resident: the condition for running the

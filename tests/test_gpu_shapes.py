@@ -75,6 +75,40 @@ def test_append_path_on_other_head_layouts(n_kv):
     print("%d q heads per kv head: max |logit err| = %.3e (%.2e of the largest logit)" % (4 // n_kv, worst_abs, worst_rel))
 
 
+def test_batched_step_of_many_sequences_with_32_kv_heads_is_cut_into_passes():
+    """40 single-row sequences of a model with 32 kv heads: their attention would need more partial results (task x
+    kv head x key split) than one pass holds, so the step is cut into two passes; every sequence against its own
+    oracle decoder, and nothing is left half done."""
+    import paper_2412_07017_amd as pkg
+    model = ModelConfig(n_layers=1, d_model=256, n_q_heads=32, n_kv_heads=32, head_dim=128, ffn=256, vocab=640,
+                        rms_eps=1e-5, rope_theta=10000.0, dtype="bf16")
+    w_dev = ai.make_weights(model, device=torch.device("cuda:0"))
+    torch.cuda.synchronize()
+    w_cpu = _host_weights(w_dev)
+    sh = orc.Shape.of(model)
+    ns = 40
+    lm = pkg.AsyncLM(model, w_dev, max_positions=64, max_seqs=ns, stream=torch.cuda.Stream())
+    decs = []
+    for s in range(ns):
+        p = [int(t) for t in ai.uniform_tokens(ai.MASTER_SEED, 931, 3 + s % 5, model.vocab, sub=s)]
+        lm.prefill(s, p)
+        d = orc.CachedDecoder(sh, w_cpu, dtype=np.float32)
+        d.prefill(p)
+        decs.append(d)
+    worst = 0.0
+    for step in range(2):
+        forced = [d.decode_step() for d in decs]
+        assert list(lm.step_batch(list(range(ns)), forced, None)) == forced
+        for s, d in enumerate(decs):
+            got = lm.logits(s)
+            assert np.isfinite(got).all()
+            worst = max(worst, float(np.abs(got - d.logits).max()))
+            assert lm.seq_len(s) == d.length
+    lm.close()
+    print("40 sequences x 32 kv heads: max |logit err| = %.3e" % worst)
+    assert worst <= TOL
+
+
 def test_session_group_on_the_batched_matrix_core_path():
     """SessionGroup (host control plane over several sessions) on a bf16 model, where every iteration really is one
     batched pass of the matrix-core append path: token streams identical to per-session oracle replays under the
