@@ -18,8 +18,11 @@ Prints ONE JSON line:
   reprefill_*, kv_swap_*, merged_*   the stateless re-prefill of the same context (Sec. 5.5), the K/V swap of a
                  trapped session (Sec. 5.4) and the interrupt riding with the next token (Sec. 5.3)
   streaming_read_ceiling   what the longest plain stream of the step (the output head) reaches on this device
-  roofline       dominant kernel (gate/up projection + SwiGLU): algorithmic bytes per launch over
-                 its mean duration measured here with HIP events on the library's stream
+  roofline       dominant kernel (gate/up projection + SwiGLU): algorithmic bytes per launch over its mean duration
+                 measured here with HIP events on the library's stream around every launch of real decoding steps (the
+                 launch gap is inside that figure); roofline.trace repeats it with the kernel's mean duration in the
+                 committed rocprofv3 kernel trace of this command (profiles/8b_bench_kernel_stats.md)
+  other_workloads   the recorded lines of `bench.py --workload W --record` for the other presets (profiles/*_bench_line.md)
   cpu_baseline   the CPU oracle timed on this host on a bounded sample (a baseline, not a target)
 Other modes: --trap-map (Sec. 5.4 swap against recomputation), --e2e-calls N (Sec. 6.3 synchronous against
 asynchronous calling, measured end to end next to the latency model).
@@ -56,14 +59,59 @@ def parse():
                     help="instead of the benchmark: N scripted function calls with timer-backed executions, run synchronously "
                          "and asynchronously through the library, against the latency model of Sec. 6.3 (one JSON line)")
     ap.add_argument("--fused", type=int, default=-1, help="1/0: force the single-kernel / per-operation decoding step (default: library's choice)")
+    ap.add_argument("--record", action="store_true",
+                    help="also write the JSON line, with its command, to profiles/<workload>_bench_line.md (the default run quotes those files)")
     return ap.parse_args()
+
+
+def trace_duration_us(kernel_row):
+    """Mean duration (us) of a kernel in the committed rocprofv3 kernel-trace summary of the default command: the `avg us`
+    column of the row of profiles/8b_bench_kernel_stats.md that starts with `kernel_row`, or None."""
+    try:
+        for line in open(os.path.join(ROOT, "profiles", "8b_bench_kernel_stats.md")):
+            if line.startswith("| " + kernel_row):
+                return float(line.split("|")[4])
+    except (OSError, ValueError, IndexError):
+        pass
+    return None
+
+
+def recorded_lines():
+    """The committed lines of the other workloads (written by --record), keyed by workload."""
+    out = {}
+    pdir = os.path.join(ROOT, "profiles")
+    for name in sorted(os.listdir(pdir)) if os.path.isdir(pdir) else []:
+        if not name.endswith("_bench_line.md"):
+            continue
+        try:
+            text = open(os.path.join(pdir, name)).read().splitlines()
+            line = next(l for l in text if l.startswith('{"metric"'))
+            cmd = next((l.strip() for l in text if l.strip().startswith("python bench.py")), None)
+            d = json.loads(line)
+            keep = ("value", "unit", "ms_per_step", "steps", "decode_tokens_per_s", "decode_ms_per_token", "decode_hbm_frac", "inject_us",
+                    "inject_tokens", "inject_in_decode_steps", "inject_hbm_frac", "batch_ms_per_step", "batch_hbm_frac", "prefill_s",
+                    "reprefill_us", "reprefill_over_inject")
+            out[name[:-len("_bench_line.md")]] = dict({k: d[k] for k in keep if k in d}, workload=d["config"]["workload"], command=cmd)
+        except (OSError, ValueError, KeyError, StopIteration):
+            continue
+    return out
+
+
+def emit(args, out):
+    line = json.dumps(out)
+    if args.record:
+        cmd = "python bench.py " + " ".join(a for a in sys.argv[1:] if a != "--record")
+        path = os.path.join(ROOT, "profiles", "%s_bench_line.md" % args.workload.replace("-", "_"))
+        with open(path, "w") as f:
+            f.write("# bench.py line of the %s workload (one MI355X; written by --record)\n\nCommand:\n\n    %s\n\nLine:\n\n%s\n" % (args.workload, cmd, line))
+    print(line)
 
 
 def recorded_traffic(model):
     """HBM bytes per launch of the gate/up kernel from the committed hardware-counter record, or None when the
     record is for another shape or the kernel's sources have changed since the counters were taken."""
     import hashlib
-    path = os.path.join(ROOT, "paper_2412_07017_amd", "traffic_gate_up.json")
+    path = os.path.join(ROOT, "traffic_gate_up.json")
     try:
         rec = json.load(open(path))
         h = hashlib.sha256()
@@ -202,7 +250,7 @@ def bench_ragged(args):
                      "bytes_per_launch": bytes_step, "ms_per_launch": ms_step},
     }
     lm.close()
-    print(json.dumps(out))
+    emit(args, out)
 
 
 def trap_map(args):
@@ -533,8 +581,14 @@ def main():
     roofline = {"bound": "hbm", "kernel": k_name, "achieved": k_bytes / (k_ms * 1e-3) / 1e9,
                 "peak": HBM_PEAK / 1e9, "unit": "GB/s",
                 "traffic": recorded_traffic(model) if "fused_step_kernel" not in classes else None,
-                "bytes_per_launch": k_bytes, "ms_per_launch": k_ms}
+                "bytes_per_launch": k_bytes, "ms_per_launch": k_ms,
+                "timing": "HIP events on the library's stream around every launch of 5 real decoding steps (graphs off for those "
+                          "steps); the gap between two launches is inside this figure"}
     roofline["frac"] = roofline["achieved"] / roofline["peak"]
+    tr_us = trace_duration_us("k_gemv<bf16, 2, 4, false>") if (args.workload == "8b" and not args.layers and "fused_step_kernel" not in classes) else None
+    if tr_us:       # the same kernel's mean duration in the committed rocprofv3 kernel trace of this command
+        roofline["trace"] = {"ms_per_launch": tr_us * 1e-3, "achieved": k_bytes / (tr_us * 1e-6) / 1e9, "frac": k_bytes / (tr_us * 1e-6) / HBM_PEAK,
+                             "source": "profiles/8b_bench_kernel_stats.md (rocprofv3 --kernel-trace --stats)"}
     per_class = {k: {"ms_per_step": v["ms"] / 5, "launches_per_step": v["launches"] // 5} for k, v in classes.items()}
     lm.synchronize()
     # what a long plain stream reaches on this device: the output head reads its vocab x d matrix exactly once
@@ -557,6 +611,7 @@ def main():
         "decode_tokens_per_s": decode_tok_s, "decode_ms_per_token": ms_dec_step,
         "decode_hbm_frac": decode_frac, "decode_bytes_per_token": bytes_step,
         "decode_ms_per_token_p10_p50_p90": [float(np.percentile(per_step_ms, q)) for q in (10, 50, 90)],
+        "decode_ms_per_token_max": float(per_step_ms.max()),
         "inject_us_min_median_max": [float(np.min(inj_ms)) * 1e3, float(np.median(inj_ms)) * 1e3, float(np.max(inj_ms)) * 1e3],
         "inject_us": ms_inject * 1e3, "inject_tokens": k_intr, "inject_in_decode_steps": ms_inject / ms_dec_step,
         # one pass over the same weights and cache: the inject's fraction of the HBM roofline
@@ -569,8 +624,12 @@ def main():
         # prompt through the matrix cores: 2 flop per layer weight and prompt token (the second activation plane and
         # the attention are not counted), over the bf16 matrix-core peak
         "prefill_mfma_frac": 2.0 * model.n_layers * model.layer_weight_elems() * wl.prompt_len / t_prefill / 2.5e15,
-        "roofline": roofline, "streaming_read_ceiling": ceiling, "kernel_classes": per_class,
+        "roofline": roofline, "streaming_read_ceiling": ceiling,
+        # per kernel class, HIP events around every launch (the launch gaps are inside: the sum exceeds the step)
+        "kernel_classes_incl_launch_gap": per_class,
     }
+    if args.workload == "8b" and not args.layers:
+        out["other_workloads"] = recorded_lines()
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, model, w_dev, spec)
     if args.copy_calibration:
@@ -581,7 +640,7 @@ def main():
         torch.cuda.synchronize()
         out["copy_calibration_bytes"] = int(src.numel() * 4)
     lm.close()
-    print(json.dumps(out))
+    emit(args, out)
 
 
 if __name__ == "__main__":

@@ -8,7 +8,9 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libasynclm.so")
-PROBE = os.path.join(HERE, "traffic_probe")      # stand-alone C-ABI consumer for hardware-counter runs
+ROOT = os.path.dirname(HERE)
+PROBE_SRC = os.path.join(ROOT, "traffic_probe.hip")   # stand-alone C-ABI consumer for hardware-counter runs (beside bench.py)
+PROBE = os.path.join(ROOT, "traffic_probe")
 SOURCES = ["api.hip", "decode_kernels.hip", "decode_fused.hip", "chunk_kernels.hip"]
 
 
@@ -32,9 +34,14 @@ def build_library(verbose: bool = False) -> str:
         print(res.stderr)
     if res.returncode != 0:
         raise RuntimeError("hipcc failed")
+    return LIB
+
+
+def build_probe(verbose: bool = False) -> str:
+    """Builds the counter-run program against the in-tree library.  Not part of the library build: measurement only."""
     cmd = [hipcc_path(), "--offload-arch=gfx950", "-O2", "-std=c++17", "-Wno-unused-command-line-argument",
-           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-           os.path.join(CSRC, "traffic_probe.hip"), "-o", PROBE, "-L", HERE, "-lasynclm", "-Wl,-rpath,$ORIGIN"]
+           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-I", ROOT,
+           PROBE_SRC, "-o", PROBE, "-L", HERE, "-lasynclm", "-Wl,-rpath," + HERE]
     res = subprocess.run(cmd, capture_output=True, text=True)
     if verbose or res.returncode != 0:
         print(" ".join(cmd))
@@ -42,8 +49,11 @@ def build_library(verbose: bool = False) -> str:
         print(res.stderr)
     if res.returncode != 0:
         raise RuntimeError("hipcc failed (traffic_probe)")
-    return LIB
+    return PROBE
 
 
 if __name__ == "__main__":
+    import sys
     print(build_library(verbose=True))
+    if "--probe" in sys.argv[1:]:
+        print(build_probe(verbose=True))

@@ -3,7 +3,7 @@
 // single-row decoding steps and one interrupt, then three plain device-to-device copy kernels of known size
 // that calibrate the byte counters.  The values of the weights do not matter for traffic; they are small and
 // finite.  Usage: traffic_probe [layers] [prompt tokens] [decode steps]
-#include "../../include/asynclm.h"
+#include "include/asynclm.h"
 
 #include <hip/hip_runtime.h>
 #include <cstdint>
