@@ -59,6 +59,9 @@ def parse():
                     help="instead of the benchmark: N scripted function calls with timer-backed executions, run synchronously "
                          "and asynchronously through the library, against the latency model of Sec. 6.3 (one JSON line)")
     ap.add_argument("--fused", type=int, default=-1, help="1/0: force the single-kernel / per-operation decoding step (default: library's choice)")
+    ap.add_argument("--step-timeline", action="store_true",
+                    help="instead of the benchmark: the decoding step on one stream and on two streams (option \"pipeline\") on the same "
+                         "context, with the device time stamps of every kernel of one two-stream step, as one JSON line")
     ap.add_argument("--record", action="store_true",
                     help="also write the JSON line, with its command, to profiles/<workload>_bench_line.md (the default run quotes those files)")
     return ap.parse_args()
@@ -253,6 +256,57 @@ def bench_ragged(args):
     emit(args, out)
 
 
+def step_timeline(args):
+    """The two ways to run a decoding step, on the same model and context: one stream (kernel boundaries between
+    dependent kernels) and two streams (neighbouring kernels overlap and hand over through counters in device
+    memory).  Per kernel of one two-stream step: when it started, when it saw the previous kernel's hand-over, when its
+    first and its last workgroup were done (100 MHz device clock, microseconds from the step's first kernel)."""
+    import numpy as np
+    import torch
+    import asynclm_inputs as ai
+    import paper_2412_07017_amd as pkg
+    wl = ai.preset(args.workload)
+    model = wl.model if not args.layers else ai.truncated(wl.model, args.layers)
+    spec = ai.build_workload(args.workload)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    w_dev = ai.make_weights(model, device=dev)
+    stream = torch.cuda.Stream(device=dev)
+    n = 64
+    # the single-row attention kernel of the two-stream step reads the values row by row: a cache format of its own
+    lm = pkg.AsyncLM(model, w_dev, max_positions=wl.prompt_len + 4 * n + 64, stream=stream, kv_format=pkg.KV_PAIR_ROWS)
+    lm.prefill(0, spec["prompt"])
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+
+    def timed():
+        for _ in range(8):
+            lm.decode_step(0)
+        lm.synchronize()
+        e0, e1 = ev(), ev()
+        e0.record(stream)
+        for _ in range(n):
+            lm.decode_step(0)
+        e1.record(stream)
+        lm.synchronize()
+        return e0.elapsed_time(e1) / n
+
+    one = timed()
+    lm.set_option("pipeline", 1)
+    two = timed()
+    tr = lm.profile_trace().astype(np.int64)            # [3 x kernels][first | last workgroup]
+    nk = tr.shape[0] // 3
+    t = (tr.reshape(nk, 3, 2) - tr[0, 0]) / 100.0
+    names = ["qkv", "attention", "o_proj", "gate_up", "down"]
+    rows = [{"kernel": (names[k % 5] if k < 5 * model.n_layers else "lm_head"), "layer": min(k // 5, model.n_layers - 1),
+             "start_us": round(float(t[k, 0, 0]), 2), "handover_seen_us": round(float(t[k, 1].max()), 2),
+             "first_done_us": round(float(t[k, 2, 0]), 2), "last_done_us": round(float(t[k, 2, 1]), 2)} for k in range(nk)]
+    per_layer = (t[5 * (model.n_layers - 1), 1].max() - t[5, 1].max()) / max(model.n_layers - 2, 1) if model.n_layers > 2 else None
+    lm.close()
+    print(json.dumps({"step_timeline": args.workload, "layers": model.n_layers, "context": wl.prompt_len + 2 * n,
+                      "one_stream_ms_per_token": one, "two_streams_ms_per_token": two, "two_streams_us_per_layer": per_layer,
+                      "kernels_of_one_two_stream_step": rows[:15] + rows[-6:]}))
+
+
 def trap_map(args):
     """Sec. 5.4: cost of the two ways to free a paused sequence's cache and get it back, per context length."""
     import numpy as np
@@ -431,6 +485,8 @@ def main():
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (--gpus must be 1)", file=sys.stderr)
         sys.exit(2)
+    if args.step_timeline:
+        return step_timeline(args)
     if args.trap_map:
         return trap_map(args)
     if args.e2e_calls:
