@@ -59,6 +59,7 @@ def parse():
                     help="instead of the benchmark: N scripted function calls with timer-backed executions, run synchronously "
                          "and asynchronously through the library, against the latency model of Sec. 6.3 (one JSON line)")
     ap.add_argument("--fused", type=int, default=-1, help="1/0: force the single-kernel / per-operation decoding step (default: library's choice)")
+    ap.add_argument("--kv-format", type=int, default=0, help="cache format of the library (0 default, 1 single bf16 plane, 2 pairs with row-major values as well)")
     ap.add_argument("--step-timeline", action="store_true",
                     help="instead of the benchmark: the decoding step on one stream and on two streams (option \"pipeline\") on the same "
                          "context, with the device time stamps of every kernel of one two-stream step, as one JSON line")
@@ -196,7 +197,7 @@ def bench_ragged(args):
     n_steps = min(args.warmup + args.steps, spec["n_decode"])
     grow = [n_steps + sum(len(t) for ev in spec["step_events"][:n_steps] for s, t in ev if s == q) for q in range(ns)]
     max_pos = max(len(p) + g for p, g in zip(spec["prompts"], grow)) + 8
-    lm = pkg.AsyncLM(model, w_dev, max_positions=max_pos, max_seqs=ns, stream=stream)
+    lm = pkg.AsyncLM(model, w_dev, max_positions=max_pos, max_seqs=ns, stream=stream, kv_format=args.kv_format)
     for kv in args.opt:
         k, v = kv.split("=")
         lm.set_option(k, int(v))
@@ -514,7 +515,7 @@ def main():
 
     stream = torch.cuda.Stream(device=dev)
     max_pos = wl.prompt_len + n_blocks * (block + k_intr) + 3 * (k_intr + 1) + 64
-    lm = pkg.AsyncLM(model, w_dev, max_positions=max_pos, max_seqs=2, stream=stream)
+    lm = pkg.AsyncLM(model, w_dev, max_positions=max_pos, max_seqs=2, stream=stream, kv_format=args.kv_format)
     if args.chunk:
         lm.set_option("chunk", args.chunk)
     if args.fused >= 0:

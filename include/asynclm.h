@@ -211,6 +211,8 @@ int asynclm_synchronize(asynclm_ctx *ctx);
  *                  models of which two workgroups per kernel fit a compute unit; ignored otherwise); 0 (default) = one
  *                  stream.  Same arithmetic per kernel (bf16 models take the single-row attention kernel here, so their
  *                  logits agree with the default within rounding).  Measured slower than the default on the 8B shape.
+ *   "gemv_grid"    workgroups per matrix-vector kernel (default: the number of compute units).  For experiments; the
+ *                  value is shared by every context of the process.
  *   "attn_split"   0 = choose the number of sequence splits of decode attention from the length,
  *                  1..128 = always use n (at most 64 apply to the single-row attention kernel, at most 128,
  *                  rounded up to a multiple of 4, to its matrix-core variant)
