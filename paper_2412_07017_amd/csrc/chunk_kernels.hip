@@ -314,6 +314,12 @@ __device__ __forceinline__ void gemm_a_load(uint4 (&a)[8], const bf16_t* wlane, 
     for (int q = 0; q < 8; ++q) a[q] = load16_stream(wlane + (size_t)blk * 128 + q * wstep);
 }
 
+// The same tile from eight rows of the lane's own choice (row q of the lane = tile row 4 q + lane / 16).
+__device__ __forceinline__ void gemm_a_load(uint4 (&a)[8], const bf16_t* const (&wrow)[8], int blk) {
+#pragma unroll
+    for (int q = 0; q < 8; ++q) a[q] = load16_stream(wrow[q] + (size_t)blk * 128);
+}
+
 // thread tid stages chunks tid and tid + 256 of the 512 16-byte chunks of each 8 KiB plane tile
 template <int MT>
 __device__ __forceinline__ void gemm_b_load(BStage<MT>& st, const bf16_t* xh, const bf16_t* xl, int nblk, int blk) {
@@ -384,27 +390,41 @@ __device__ __forceinline__ void gemm_tile_mma(const uint4 (&ta)[8], f32x16 (&acc
     }
 }
 
-// SWIGLU (S = 1 only): W holds the gate rows [0, N/2) and the up rows [N/2, N).  Waves 0, 1 of the workgroup take 64
-// gate rows, waves 2, 3 the 64 up rows of the same columns; the up products pass through LDS to the gate waves,
-// which write silu(gate) * up as hi/lo planes in operand order (act_hi, act_lo; N/2 columns).
+// SWIGLU (S = 1 only): W holds the gate rows [0, N/2) and the up rows [N/2, N).  Wave-tile t = 4 blockIdx.x + wave
+// takes `rp` <= 16 gate rows (columns t rp .. t rp + rp - 1 of the result) into tile rows 0..rp-1 and the matching up
+// rows into tile rows 16..16+rp-1: in the accumulator layout a gate product and its up product then sit in the same
+// lane (registers 4b + r and 4(b + 2) + r), and the wave writes silu(gate) * up as hi/lo planes in operand order
+// (act_hi, act_lo; N/2 columns) without any exchange.  The tile rows beyond rp repeat row rp - 1 (cache hits, results
+// dropped): the launcher picks rp so that the tiles divide evenly among the waves of the device (14 rows for
+// F = 14336 on 256 compute units: 1024 tiles), which a fixed 16 or 32 rows per wave would not.
 template <int MT, bool SWIGLU>
 __global__ __launch_bounds__(256) void k_chunk_gemm(const bf16_t* __restrict__ W, int N, int K,
                                                     const bf16_t* __restrict__ Xhi, const bf16_t* __restrict__ Xlo,
                                                     float* __restrict__ P, size_t s_stride, int n_stride, int S,
-                                                    bf16_t* __restrict__ act_hi, bf16_t* __restrict__ act_lo) {
+                                                    bf16_t* __restrict__ act_hi, bf16_t* __restrict__ act_lo, int rp) {
     extern __shared__ uint4 gemm_lds[];             // [4 waves][512] weight tiles, then [2][MT][2][512] activation tiles
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     uint4* at = gemm_lds + wave * 512;
     uint4* bt = gemm_lds + 2048;
     constexpr int BT = MT * 2 * 512;                // chunks in one activation buffer
-    const int n0 = SWIGLU ? (wave < 2 ? 0 : N >> 1) + blockIdx.x * 64 + (wave & 1) * 32 : blockIdx.x * 128 + wave * 32;
+    const int n0 = SWIGLU ? (blockIdx.x * 4 + wave) * rp : blockIdx.x * 128 + wave * 32;     // SWIGLU: first gate row
+    const int nr = SWIGLU ? max(0, min(rp, (N >> 1) - n0)) : 32;                              // SWIGLU: gate rows of this wave
     const int sp = blockIdx.y;
     const int nblk = K >> 7;
     const int b0 = (int)((long long)nblk * sp / S), b1 = (int)((long long)nblk * (sp + 1) / S);
-    const int nb = b1 - b0, last = b1 - 1;
+    const int nb = b1 - b0;
 
-    const bf16_t* wlane = W + (size_t)(n0 + (lane >> 4)) * K + (lane & 15) * 8;   // row l/16 (+4q), chunk l%16
+    const bf16_t* wlane = W + (size_t)(SWIGLU ? 0 : n0 + (lane >> 4)) * K + (lane & 15) * 8;   // row l/16 (+4q), chunk l%16
     const size_t wstep = (size_t)4 * K;
+    const bf16_t* wrow[8];
+    if (SWIGLU) {
+        const int g0 = min(n0, (N >> 1) - 1);
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            const int slot = 4 * (q & 3) + (lane >> 4);
+            wrow[q] = wlane + (size_t)((q < 4 ? 0 : N >> 1) + g0 + min(slot, max(nr, 1) - 1)) * K;
+        }
+    }
     const bf16_t* xh = Xhi + tid * 8;
     const bf16_t* xl = Xlo + tid * 8;
 
@@ -415,17 +435,27 @@ __global__ __launch_bounds__(256) void k_chunk_gemm(const bf16_t* __restrict__ W
         for (int r = 0; r < 16; ++r) acc[mt][r] = 0.f;
 
     if (nb > 0) {
+        // The workgroups walk their k-blocks in rotated order, each starting somewhere else: workgroups that all
+        // read column block 0 of their own rows at the same time (rows are a multiple of 8 KiB apart) load few memory
+        // channels at a time, and how badly depends on where the matrix lies (measured on the gate/up product, whose
+        // workgroups all start together: 42 to 52 us for the same shape at different addresses).  Block i of the
+        // walk is b0 + (i + rot) mod nb; past the end the last block is read again (a cache hit).
+        const int rot = (int)((blockIdx.x / 8 + (blockIdx.x & 7) * 4 + blockIdx.y * 3) % (unsigned)nb);
+        auto blk = [&](int i) { const int x = min(i, nb - 1) + rot; return b0 + (x >= nb ? x - nb : x); };
         // Waits are in issue order, so the activation loads of block t+2 are issued before the weight loads of
         // the newest block: waiting for the activations of block t+1 (to store them) then leaves the two newest
         // weight tiles in flight.
         constexpr int RING = GemmRing<MT>::N;
         uint4 ring[RING][8];
         BStage<MT> st[2];
-        gemm_b_load<MT>(st[0], xh, xl, nblk, b0);
-        gemm_b_load<MT>(st[1], xh, xl, nblk, min(b0 + 1, last));
+        gemm_b_load<MT>(st[0], xh, xl, nblk, blk(0));
+        gemm_b_load<MT>(st[1], xh, xl, nblk, blk(1));
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int u = 0; u < RING - 1; ++u) gemm_a_load(ring[u], wlane, wstep, min(b0 + u, last));
+        for (int u = 0; u < RING - 1; ++u) {
+            if (SWIGLU) gemm_a_load(ring[u], wrow, blk(u));
+            else gemm_a_load(ring[u], wlane, wstep, blk(u));
+        }
         gemm_b_store<MT>(st[0], bt, tid, true);
         __syncthreads();
         // unrolled over an even number of blocks, so that ring slot (u % RING) and activation buffer (u & 1) are static
@@ -433,15 +463,16 @@ __global__ __launch_bounds__(256) void k_chunk_gemm(const bf16_t* __restrict__ W
         for (int t = 0; t < nb; t += UNROLL) {
 #pragma unroll
             for (int u = 0; u < UNROLL; ++u) {
-                const int tt = b0 + t + u;                  // this block
-                if (UNROLL > RING && tt > last) break;      // long unroll only: uniform exit, nothing below is conditional
-                gemm_b_load<MT>(st[u & 1], xh, xl, nblk, min(tt + 2, last));
+                const int tt = t + u;                       // this block of the walk
+                if (UNROLL > RING && tt >= nb) break;       // long unroll only: uniform exit, nothing below is conditional
+                gemm_b_load<MT>(st[u & 1], xh, xl, nblk, blk(tt + 2));
                 __builtin_amdgcn_sched_barrier(0);
-                gemm_a_load(ring[(u + RING - 1) % RING], wlane, wstep, min(tt + RING - 1, last));
+                if (SWIGLU) gemm_a_load(ring[(u + RING - 1) % RING], wrow, blk(tt + RING - 1));
+                else gemm_a_load(ring[(u + RING - 1) % RING], wlane, wstep, blk(tt + RING - 1));
                 __builtin_amdgcn_sched_barrier(0);
                 gemm_tile_mma<MT>(ring[u % RING], acc, at, bt + (u & 1) * BT, lane);
                 __builtin_amdgcn_sched_barrier(0);
-                gemm_b_store<MT>(st[(u + 1) & 1], bt + ((u + 1) & 1) * BT, tid, tt + 1 <= last);
+                gemm_b_store<MT>(st[(u + 1) & 1], bt + ((u + 1) & 1) * BT, tid, tt + 1 < nb);
                 __syncthreads();
             }
         }
@@ -449,35 +480,22 @@ __global__ __launch_bounds__(256) void k_chunk_gemm(const bf16_t* __restrict__ W
 
     // lane (j, g) holds D[8b + 4g + r][j] in register 4b + r: four consecutive weight rows of token row j
     if (SWIGLU) {
-        // the loop's last barrier has released the activation tiles: [up wave][mt][register quad][lane] float4
-        float4* ex = reinterpret_cast<float4*>(bt);
-        if (wave >= 2) {
+        const int F = N >> 1;
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt)
+        for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-                for (int b = 0; b < 4; ++b)
-                    ex[(((wave - 2) * MT + mt) * 4 + b) * 64 + lane] = make_float4(acc[mt][4 * b], acc[mt][4 * b + 1], acc[mt][4 * b + 2], acc[mt][4 * b + 3]);
-        }
-        __syncthreads();
-        if (wave < 2) {
-            const int F = N >> 1, f0 = n0 + 4 * (lane >> 5);
+            for (int b = 0; b < 2; ++b)
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-                for (int b = 0; b < 4; ++b) {
-                    const float4 u4 = ex[((wave * MT + mt) * 4 + b) * 64 + lane];
-                    const float up[4] = {u4.x, u4.y, u4.z, u4.w};
-                    bf16_t hi[4], lo[4];
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) {
-                        const float gt = acc[mt][4 * b + r];
-                        split_bf16(gt / (1.f + expf(-gt)) * up[r], hi[r], lo[r]);
+                for (int r = 0; r < 4; ++r) {
+                    const int slot = 8 * b + 4 * (lane >> 5) + r;
+                    if (slot < nr) {
+                        const float gt = acc[mt][4 * b + r], up = acc[mt][4 * (b + 2) + r];
+                        bf16_t hi, lo;
+                        split_bf16(gt / (1.f + expf(-gt)) * up, hi, lo);
+                        const size_t o = tiled_off(mt * 32 + (lane & 31), n0 + slot, F);
+                        act_hi[o] = hi; act_lo[o] = lo;
                     }
-                    const size_t o = tiled_off(mt * 32 + (lane & 31), f0 + 8 * b, F);   // four columns inside one 8-element group
-                    *reinterpret_cast<uint2*>(act_hi + o) = make_uint2(hi[0] | ((uint32_t)hi[1] << 16), hi[2] | ((uint32_t)hi[3] << 16));
-                    *reinterpret_cast<uint2*>(act_lo + o) = make_uint2(lo[0] | ((uint32_t)lo[1] << 16), lo[2] | ((uint32_t)lo[3] << 16));
                 }
-        }
         return;
     }
 #pragma unroll
@@ -709,7 +727,7 @@ __global__ __launch_bounds__(256) void k_chunk_gemm_ks(const bf16_t* __restrict_
     const int ntile = blockIdx.x, sp = blockIdx.y;
     const int nblk = K >> 7;
     const int b0 = (int)((long long)nblk * sp / S), b1 = (int)((long long)nblk * (sp + 1) / S);
-    const int nb = b1 - b0, last = b1 - 1;
+    const int nb = b1 - b0;
     const int n0 = ntile * 128;
 
     // weights: load q of a thread covers row 32 wave + 4 q + lane / 16 of the tile, 16-byte chunk lane % 16
@@ -738,6 +756,9 @@ __global__ __launch_bounds__(256) void k_chunk_gemm_ks(const bf16_t* __restrict_
         // set i % 2, requested two blocks ahead of their use, and the activations (from L2) in a ring of three blocks.
         // (Three row tiles do not fit the register file this way; they take k_chunk_gemm_wide with an idle wave.)
         static_assert(MT == 2, "register budget");
+        // rotated walk over the k-blocks, as in k_chunk_gemm: block i of the walk is b0 + (i + rot) mod nb
+        const int rot = (int)((blockIdx.x / 8 + (blockIdx.x & 7) * 4 + blockIdx.y * 3) % (unsigned)nb);
+        auto blk = [&](int i) { const int x = min(i, nb - 1) + rot; return b0 + (x >= nb ? x - nb : x); };
         constexpr int NSET = 2, RING = 3, UNROLL = 6;   // LDS buffer u % 2 and ring slot u % RING are static
         uint4 wreg[NSET][8];
         BUnit<MT> ring[RING];
@@ -750,25 +771,25 @@ __global__ __launch_bounds__(256) void k_chunk_gemm_ks(const bf16_t* __restrict_
             }
         };
         // issue order = completion order: weights of the first block, activations of the first two, weights of the second
-        w_load(wreg[0], b0);
+        w_load(wreg[0], blk(0));
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int i = 0; i < RING - 1; ++i) wide_b_load<MT>(ring[i], xh, xl, min(b0 + i, last), wave);
+        for (int i = 0; i < RING - 1; ++i) wide_b_load<MT>(ring[i], xh, xl, blk(i), wave);
         __builtin_amdgcn_sched_barrier(0);
         w_store(wreg[0], gemm_lds);
-        w_load(wreg[NSET - 1], min(b0 + 1, last));
+        w_load(wreg[NSET - 1], blk(1));
         __builtin_amdgcn_sched_barrier(0);
         __syncthreads();
         for (int t = 0; t < nb; t += UNROLL) {
 #pragma unroll
             for (int u = 0; u < UNROLL; ++u) {
-                const int tt = b0 + t + u;                  // this block: LDS buffer u % 2, ring slot u % RING
-                if (tt > last) break;                       // uniform
+                const int tt = t + u;                       // this block of the walk: LDS buffer u % 2, ring slot u % RING
+                if (tt >= nb) break;                        // uniform
                 const uint4* at = gemm_lds + (u & 1) * 2048;
                 uint4* other = gemm_lds + ((u & 1) ^ 1) * 2048;   // its readers passed the barrier that ended the previous block
-                wide_b_load<MT>(ring[(u + RING - 1) % RING], xh, xl, min(tt + RING - 1, last), wave);
+                wide_b_load<MT>(ring[(u + RING - 1) % RING], xh, xl, blk(tt + RING - 1), wave);
                 __builtin_amdgcn_sched_barrier(0);
-                w_load(wreg[u & 1], min(tt + 2, last));     // this set's previous block was stored one block ago
+                w_load(wreg[u & 1], blk(tt + 2));           // this set's previous block was stored one block ago
                 __builtin_amdgcn_sched_barrier(0);
                 uint4 a0[4], a1[4];
                 wide_a_read(a0, at, 2 * wave, lane);
@@ -1468,7 +1489,7 @@ hipError_t launch_chunk_gemm(const void* W, int N, int K, const bf16_t* xhi, con
     // one row tile: weight-streaming kernel, a wave per 32 weight rows; two: the waves split the k-steps; three or four:
     // a wave per row tile (128-row workgroups); more: 256-row workgroups
     if (MT == 1) {
-        hipLaunchKernelGGL((k_chunk_gemm<1, false>), grid, block, lds, s, (const bf16_t*)W, N, K, xhi, xlo, c.part, ps, N, S, nullptr, nullptr);
+        hipLaunchKernelGGL((k_chunk_gemm<1, false>), grid, block, lds, s, (const bf16_t*)W, N, K, xhi, xlo, c.part, ps, N, S, nullptr, nullptr, 0);
     } else if (MT == 2) {
         hipLaunchKernelGGL((k_chunk_gemm_ks<2, false>), grid, block, GEMM_WIDE_LDS_BYTES, s, (const bf16_t*)W, N, K, xhi, xlo, c.part, ps, N, S, nullptr, nullptr);
     } else {
@@ -1484,10 +1505,19 @@ hipError_t launch_chunk_gemm(const void* W, int N, int K, const bf16_t* xhi, con
 // c.act_hi / c.act_lo.
 hipError_t launch_chunk_gemm_swiglu(const void* W, int F, int K, const bf16_t* xhi, const bf16_t* xlo, const ChunkBuffers& c,
                                     int MT, hipStream_t s) {
-    if (MT < 1 || MT > CHUNK_MAX / 32 || F % 64 || K % 128) return hipErrorInvalidValue;
+    if (MT < 1 || MT > CHUNK_MAX / 32 || F < 1 || K % 128 || (MT > 1 && F % 64)) return hipErrorInvalidValue;
     const bf16_t* Wb = (const bf16_t*)W;
     if (MT == 1) {
-        hipLaunchKernelGGL((k_chunk_gemm<1, true>), dim3(F / 64, 1), dim3(256), gemm_lds_bytes(1), s, Wb, 2 * F, K, xhi, xlo, nullptr, (size_t)0, 0, 1, c.act_hi, c.act_lo);
+        // gate rows per wave-tile: the fewest whole rounds of tiles over the device's waves that 16 rows per tile allow
+        const int waves = 4 * std::max(1, decode_gemv_grid());
+        int rp = 16;
+        for (int m = 1; m <= 64; ++m) {
+            rp = (F + waves * m - 1) / (waves * m);
+            if (rp <= 16) break;
+        }
+        rp = std::min(std::max(rp, 1), 16);
+        const int tiles = (F + rp - 1) / rp;
+        hipLaunchKernelGGL((k_chunk_gemm<1, true>), dim3((tiles + 3) / 4, 1), dim3(256), gemm_lds_bytes(1), s, Wb, 2 * F, K, xhi, xlo, nullptr, (size_t)0, 0, 1, c.act_hi, c.act_lo, rp);
     } else if (MT == 2) {
         hipLaunchKernelGGL((k_chunk_gemm_ks<2, true>), dim3(F / 64, 1), dim3(256), GEMM_WIDE_LDS_BYTES, s, Wb, 2 * F, K, xhi, xlo, nullptr, (size_t)0, 0, 1, c.act_hi, c.act_lo);
     } else {
