@@ -1166,11 +1166,13 @@ __global__ __launch_bounds__(256) void k_decode_attn_mfma(DecodeAttnArgs a, Geom
 
 }
 
-// Merge of the key splits: grid (Hkv, Y), workgroup y writes its share of the kv group's G x 128 outputs (Y = G / 2:
-// one output per thread).
+// Merge of the key splits: grid (Hkv, G * 128 / 64), a workgroup writes 64 of the kv group's G x 128 outputs.  Thread =
+// (output, quarter of the splits): the splits are few long chains of loads otherwise (96 splits at a long context), the
+// four partial sums of an output meet in LDS and are added in a fixed order.
 __global__ __launch_bounds__(256) void k_decode_attn_merge(DecodeAttnArgs a, Geom g) {
     constexpr int DH = 128;
     __shared__ float f[8 * CHUNK_ATTN_MAX_SPLIT];          // [G][nused] weights exp(m_s - M) / L
+    __shared__ float red[256];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int G = g.Hq / g.Hkv;
     const int kvh = blockIdx.x, nsplit = a.nsplit;
@@ -1178,7 +1180,9 @@ __global__ __launch_bounds__(256) void k_decode_attn_merge(DecodeAttnArgs a, Geo
     const int tps = (ntile + nsplit - 1) / nsplit;
     const int nused = (ntile + tps - 1) / tps;             // splits that had keys
     const float* ml = a.part_ml + (size_t)kvh * nsplit * 2 * G;
-    for (int gq = wave; gq < G; gq += 4) {                 // lanes over splits
+    const int per = (G * DH + (int)gridDim.y - 1) / (int)gridDim.y;
+    const int o0 = blockIdx.y * per, o1 = min(o0 + per, G * DH);
+    for (int gq = (o0 >> 7) + wave; gq <= ((o1 - 1) >> 7); gq += 4) {      // the q heads this workgroup writes; lanes over splits
         float M = -INFINITY;
         for (int sp = lane; sp < nused; sp += 64) M = fmaxf(M, ml[sp * 2 * G + gq]);
 #pragma unroll
@@ -1195,15 +1199,21 @@ __global__ __launch_bounds__(256) void k_decode_attn_merge(DecodeAttnArgs a, Geo
         for (int sp = lane; sp < nused; sp += 64) f[gq * nused + sp] *= inv;
     }
     __syncthreads();
-    const int per = (G * DH + (int)gridDim.y - 1) / (int)gridDim.y;
-    for (int idx = blockIdx.y * per + tid; idx < min((int)(blockIdx.y + 1) * per, G * DH); idx += 256) {
-        const int gq = idx >> 7, ch = idx & (DH - 1);
-        const float* po = a.part_o + ((size_t)kvh * nsplit * G + gq) * DH + ch;
-        const float* fw = f + gq * nused;
+    for (int base = o0; base < o1; base += 64) {
+        const int idx = base + lane;
         float acc = 0.f;
-#pragma unroll 16
-        for (int sp = 0; sp < nused; ++sp) acc = fmaf(po[(size_t)sp * G * DH], fw[sp], acc);
-        a.out[(size_t)(kvh * G + gq) * DH + ch] = acc;
+        if (idx < o1) {
+            const int gq = idx >> 7, ch = idx & (DH - 1);
+            const float* po = a.part_o + ((size_t)kvh * nsplit * G + gq) * DH + ch;
+            const float* fw = f + gq * nused;
+#pragma unroll 8
+            for (int sp = wave; sp < nused; sp += 4) acc = fmaf(po[(size_t)sp * G * DH], fw[sp], acc);
+        }
+        red[tid] = acc;
+        __syncthreads();
+        if (wave == 0 && idx < o1)
+            a.out[(size_t)kvh * G * DH + idx] = (red[lane] + red[64 + lane]) + (red[128 + lane] + red[192 + lane]);
+        __syncthreads();
     }
 }
 
@@ -1573,7 +1583,7 @@ hipError_t launch_decode_attn_mfma(const ChunkBuffers& c, const void* kv_layer, 
     hipLaunchKernelGGL(k_decode_attn_mfma, dim3(g.Hkv, nsplit / 4), dim3(256), ATTN_LDS_BYTES, s, a, g);
     hipError_t e = hipGetLastError();
     if (e) return e;
-    hipLaunchKernelGGL(k_decode_attn_merge, dim3(g.Hkv, std::max(1, G / 2)), dim3(256), 0, s, a, g);
+    hipLaunchKernelGGL(k_decode_attn_merge, dim3(g.Hkv, 2 * G), dim3(256), 0, s, a, g);
     return hipGetLastError();
 }
 

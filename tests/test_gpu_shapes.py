@@ -12,6 +12,7 @@ import torch
 import asynclm_inputs as ai
 from asynclm_inputs.configs import ModelConfig
 from oracle import asynclm_oracle as orc
+from cml_reference import ReferenceMonitor
 
 pytestmark = pytest.mark.gpu
 
@@ -136,7 +137,7 @@ def test_session_group_on_the_batched_matrix_core_path():
     for prompt, arr in zip(prompts, arrivals):
         dec = orc.CachedDecoder(sh, w_cpu, dtype=np.float32)
         dec.prefill(prompt)
-        mon = pkg.TokenMonitor(cml)
+        mon = ReferenceMonitor(cml)
         queue, paused, out = [], False, []
         for t in range(n_steps):
             if t in arr:

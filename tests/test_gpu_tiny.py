@@ -9,6 +9,7 @@ import torch
 
 import asynclm_inputs as ai
 from oracle import asynclm_oracle as orc
+from cml_reference import ReferenceMonitor
 
 pytestmark = pytest.mark.gpu
 
@@ -381,7 +382,7 @@ def test_interruptible_session_end_to_end_matches_oracle_replay(tiny):
     # replay with the oracle
     dec = orc.CachedDecoder(sh, w_cpu)
     dec.prefill(prompt)
-    mon = pkg.TokenMonitor(cml)
+    mon = ReferenceMonitor(cml)
     queue, paused, want_stream, deferred, calls, traps = [], False, [], 0, 0, 0
     for t in range(n_steps):
         if t in arrivals:
@@ -450,7 +451,7 @@ def test_session_group_end_to_end_matches_oracle_replays(tiny):
     for prompt, arr in zip(prompts, arrivals):
         dec = orc.CachedDecoder(sh, w_cpu)
         dec.prefill(prompt)
-        mon = pkg.TokenMonitor(cml)
+        mon = ReferenceMonitor(cml)
         queue, paused, out = [], False, []
         for t in range(n_steps):
             if t in arr:

@@ -11,6 +11,7 @@ Rules checked:
 import pytest
 
 from paper_2412_07017_amd.session import CML, InterruptibleSession, TokenMonitor
+from cml_reference import ReferenceMonitor
 
 C = CML(call=100, intr=101, trap=102, end=103, head=104)
 
@@ -78,6 +79,27 @@ def test_monitor_masks_and_detects_blocks():
         with pytest.raises(ValueError):
             for t in state_tokens:
                 mm.observe(t)
+
+
+def test_monitor_agrees_with_the_rules_restated_over_the_whole_history():
+    """Random streams that respect the masks: after every token the product's state machine and the tests' restatement
+    of the rules as a function of the whole history (used by the oracle replays of the GPU session tests) give the same
+    mask, forced token, critical flag and completed blocks."""
+    import random
+    rng = random.Random(2412_07017)
+    vocab = list(range(1, 8)) + list(C.all())
+    calls = traps = 0
+    for _ in range(200):
+        m, r = TokenMonitor(C), ReferenceMonitor(C)
+        for _ in range(60):
+            assert sorted(m.banned()) == sorted(r.banned()) and m.forced() == r.forced() and m.critical == r.critical
+            f = m.forced()
+            tok = f if f is not None else rng.choice([t for t in vocab if t not in m.banned()])
+            em, er = m.observe(tok), r.observe(tok)
+            assert em == er
+            calls += em is not None and em[0] == "call"
+            traps += em is not None and em[0] == "trap"
+    assert calls >= 200 and traps >= 200
 
 
 def test_interrupts_wait_for_the_end_of_a_call_block_and_are_appended_together():
