@@ -250,13 +250,19 @@ __global__ void k_chunk_rope_kv(const float* __restrict__ P, int S, size_t s_str
     const ChunkRow R = tab->row[m];
     const int pos = R.pos;
     const size_t seq_off = (size_t)R.seq * g.kv_seq_stride;
-    float a = 0.f, b = 0.f;
-    for (int s = 0; s < S; ++s) {
-        const float* p = P + s * s_stride + (size_t)m * n_stride + h * g.dh;
-        a += p[i]; b += p[i + half];
+    // all partial products and the rotation of this thread in one round of loads, added in split order
+    float pa[CHUNK_GEMM_MAX_SPLIT], pb[CHUNK_GEMM_MAX_SPLIT];
+#pragma unroll
+    for (int s = 0; s < CHUNK_GEMM_MAX_SPLIT; ++s) {
+        const float* p = P + (size_t)min(s, S - 1) * s_stride + (size_t)m * n_stride + h * g.dh;
+        pa[s] = p[i]; pb[s] = p[i + half];
     }
+    const float c = rope_cos[(size_t)pos * half + i], sn = rope_sin[(size_t)pos * half + i];
+    float a = 0.f, b = 0.f;
+#pragma unroll
+    for (int s = 0; s < CHUNK_GEMM_MAX_SPLIT; ++s)
+        if (s < S) { a += pa[s]; b += pb[s]; }
     if (h < g.Hq + g.Hkv) {
-        const float c = rope_cos[(size_t)pos * half + i], sn = rope_sin[(size_t)pos * half + i];
         const float ra = a * c - b * sn, rb = b * c + a * sn;
         a = ra; b = rb;
     }
@@ -1336,21 +1342,43 @@ __global__ __launch_bounds__(256) void k_chunk_attn_combine(const float* __restr
                                                             bf16_t* __restrict__ out_hi, bf16_t* __restrict__ out_lo) {
     constexpr int DH = 128;
     __shared__ float f[CHUNK_ATTN_MAX_SPLIT][32];          // running maximum of every split, then its weight
+    __shared__ float fl[CHUNK_ATTN_MAX_SPLIT][32];         // running sum of every split
     __shared__ float red[8][32];
     const int tid = threadIdx.x;
     const int G = g.Hq / g.Hkv;
     const int kvh = blockIdx.x % g.Hkv;
     const ChunkTask T = tab->task[blockIdx.x / g.Hkv];
     const float* ml = part_ml + (size_t)blockIdx.x * nsplit * 64;
+    const int j = tid & 31, dl = tid >> 5;                 // column, channel within a run of 8
+    const float* po = part_o + (size_t)blockIdx.x * nsplit * DH * 32 + (size_t)(blockIdx.y * 32 + dl) * 32 + j;
+    constexpr int PB = 8;                                  // splits whose partial results are requested together
+    float p[PB][4];
+    auto p_load = [&](int s0) {
+#pragma unroll
+        for (int k = 0; k < PB; ++k) {
+            const int sc = min(s0 + k, nsplit - 1);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) p[k][u] = po[(size_t)sc * DH * 32 + u * 8 * 32];
+        }
+    };
     float inv;
     {
-        // statistics per query column: thread (column c, slice q) covers splits q, q + 8, ...; partial results meet in LDS
+        // statistics per query column: thread (column c, slice q) covers splits q, q + 8, ...; partial results meet in
+        // LDS.  Maxima and sums of four splits per thread are requested at once, and with the first of them the partial
+        // results of the first PB splits, which do not depend on the statistics.
         const int c = tid & 31, q = tid >> 5;
         float m = -INFINITY;
-        for (int sp = q; sp < nsplit; sp += 8) {
-            const float v = ml[sp * 64 + c];
-            f[sp][c] = v;
-            m = fmaxf(m, v);
+        for (int s0 = q; s0 < nsplit || s0 == q; s0 += 32) {       // every thread runs the first round: it requests p
+            float mv[4], lv[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const int sc = min(s0 + 8 * k, nsplit - 1);
+                mv[k] = ml[sc * 64 + c]; lv[k] = ml[sc * 64 + 32 + c];
+            }
+            if (s0 == q) p_load(0);
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+                if (s0 + 8 * k < nsplit) { f[s0 + 8 * k][c] = mv[k]; fl[s0 + 8 * k][c] = lv[k]; m = fmaxf(m, mv[k]); }
         }
         red[q][c] = m;
         __syncthreads();
@@ -1361,7 +1389,7 @@ __global__ __launch_bounds__(256) void k_chunk_attn_combine(const float* __restr
         float lp = 0.f;
         for (int sp = q; sp < nsplit; sp += 8) {
             const float w = f[sp][c] > -INFINITY ? expf(f[sp][c] - M) : 0.f;
-            lp += ml[sp * 64 + 32 + c] * w;
+            lp += fl[sp][c] * w;
             f[sp][c] = w;
         }
         red[q][c] = lp;
@@ -1371,19 +1399,11 @@ __global__ __launch_bounds__(256) void k_chunk_attn_combine(const float* __restr
         for (int k = 0; k < 8; ++k) L += red[k][c];
         inv = L > 0.f ? 1.f / L : 0.f;
     }
-    const int j = tid & 31, dl = tid >> 5;                 // column, channel within a run of 8
-    const float* po = part_o + (size_t)blockIdx.x * nsplit * DH * 32 + (size_t)(blockIdx.y * 32 + dl) * 32 + j;
     float v[4] = {0.f, 0.f, 0.f, 0.f};
-    for (int s = 0; s < nsplit; s += 4) {
-        float p[4][4];
+    for (int s = 0; s < nsplit; s += PB) {
+        if (s > 0) p_load(s);
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            const int sc = min(s + k, nsplit - 1);
-#pragma unroll
-            for (int u = 0; u < 4; ++u) p[k][u] = po[(size_t)sc * DH * 32 + u * 8 * 32];
-        }
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
+        for (int k = 0; k < PB; ++k) {
             const float w = s + k < nsplit ? f[min(s + k, CHUNK_ATTN_MAX_SPLIT - 1)][j] : 0.f;
 #pragma unroll
             for (int u = 0; u < 4; ++u) v[u] = fmaf(p[k][u], w, v[u]);
