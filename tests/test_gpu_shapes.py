@@ -25,10 +25,12 @@ def _host_weights(w_dev):
     return {k: ([conv(t) for t in v] if isinstance(v, list) else conv(v)) for k, v in w_dev.items()}
 
 
-@pytest.mark.parametrize("n_kv", [4, 2, 1])
-def test_append_path_on_other_head_layouts(n_kv):
+@pytest.mark.parametrize("n_kv,ffn", [(4, 1024), (2, 1024), (1, 1024), (2, 2240)])
+def test_append_path_on_other_head_layouts(n_kv, ffn):
+    """ffn 2240: the gate/up product of a pass of up to 32 rows gives a wave 3 gate rows (2240 rows over the 1024 waves
+    of the device), which leaves a last tile of 2 rows and waves without a tile."""
     import paper_2412_07017_amd as pkg
-    model = ModelConfig(n_layers=2, d_model=512, n_q_heads=4, n_kv_heads=n_kv, head_dim=128, ffn=1024, vocab=2048,
+    model = ModelConfig(n_layers=2, d_model=512, n_q_heads=4, n_kv_heads=n_kv, head_dim=128, ffn=ffn, vocab=2048,
                         rms_eps=1e-5, rope_theta=10000.0, dtype="bf16")
     w_dev = ai.make_weights(model, device=torch.device("cuda:0"))
     torch.cuda.synchronize()
