@@ -438,6 +438,7 @@ template <typename WT>
 struct Phase {
     const WT* W;
     int rows, K, Kg, KT, units, u0, u1;   // this wave owns units [u0, u1)
+    int rot;                              // first k-tile of the wave's walk over a unit, see make_phase
 };
 
 struct Cursor { int u, kt; };
@@ -457,6 +458,10 @@ __device__ __forceinline__ Phase<WT> make_phase(const void* W, int rows, int K, 
     p.KT = (p.Kg + 255) / 256; p.units = units;
     const long long gw = (long long)blockIdx.x * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), tw = (long long)gridDim.x * 4;
     p.u0 = (int)(units * gw / tw); p.u1 = (int)(units * (gw + 1) / tw);
+    // Every wave walks the k-tiles of its units in rotated order from a tile of its own: waves that all read the same
+    // columns of their rows at the same time (the rows lie a multiple of the row length apart) load the memory channels
+    // unevenly (measured: 2 % of the decoding step at d_model 8192, 0.3 % at 4096).
+    p.rot = (int)(gw % p.KT);
     return p;
 }
 
@@ -472,7 +477,8 @@ __device__ __forceinline__ void tile_load_w(Slot& sl, const Phase<WT>& p, const 
     constexpr int EPL = Elem<WT>::EPL;
     const bool past = c.u >= p.u1;
     const int u = past ? max(min(p.u1, p.units) - 1, 0) : c.u;
-    const int kt = past ? p.KT - 1 : c.kt;
+    int kt = (past ? p.KT - 1 : c.kt) + p.rot;
+    kt = kt >= p.KT ? kt - p.KT : kt;
     int rA, rB;
     unit_rows<EPI>(u, p.rows, g, rA, rB);
     const WT* pa = p.W + (size_t)rA * p.K;
@@ -622,7 +628,8 @@ __device__ __forceinline__ void phase_run(Slot (&ring)[RING], const Phase<WT>& p
 #pragma unroll
         for (int j = 0; j < RING; ++j) {
             const bool past = cc.u >= p.u1;
-            tile_fma<WT>(ring[j].v, xs, plane_stride, zero_group, past, cc.kt, lane, accA, accB);
+            const int ktp = cc.kt + p.rot >= p.KT ? cc.kt + p.rot - p.KT : cc.kt + p.rot;      // the tile that was requested
+            tile_fma<WT>(ring[j].v, xs, plane_stride, zero_group, past, ktp, lane, accA, accB);
             // The slot's epilogue operands are parked before the slot is requested again: read after the request
             // they would have to be copied aside when the loop rotates, and the copy waits for every load in flight.
             if (!past && cc.kt == p.KT - 1) {
