@@ -261,7 +261,9 @@ def step_timeline(args):
     """The two ways to run a decoding step, on the same model and context: one stream (kernel boundaries between
     dependent kernels) and two streams (neighbouring kernels overlap and hand over through counters in device
     memory).  Per kernel of one two-stream step: when it started, when it saw the previous kernel's hand-over, when its
-    first and its last workgroup were done (100 MHz device clock, microseconds from the step's first kernel)."""
+    first and its last workgroup were done (100 MHz device clock, microseconds from the step's first kernel).  Per
+    kernel of one layer of a one-stream step: start and input vector staged of the first and the last workgroup, done
+    of the earliest and the latest workgroup (microseconds from that layer's first kernel)."""
     import numpy as np
     import torch
     import asynclm_inputs as ai
@@ -292,6 +294,22 @@ def step_timeline(args):
         return e0.elapsed_time(e1) / n
 
     one = timed()
+    # the same one-stream step with time stamps
+    lm.set_option("step_stamps", 1)
+    for _ in range(4):
+        lm.decode_step(0)
+    lm.synchronize()
+    tr1 = lm.profile_trace().astype(np.int64)           # [3 x kernels][first | last workgroup]
+    lm.set_option("step_stamps", 0)
+    nk1 = tr1.shape[0] // 3
+    t1 = (tr1.reshape(nk1, 3, 2) - tr1[0, 0]) / 100.0
+    names1 = ["qkv", "attention", "attention_merge", "o_proj", "gate_up", "down"]
+    mid = 6 * (model.n_layers // 2)
+    rows1 = [{"kernel": names1[k % 6], "layer": k // 6,
+              "start_us": [round(float(v - t1[mid, 0, 0]), 2) for v in t1[k, 0]],
+              "vector_staged_us": ([round(float(v - t1[mid, 0, 0]), 2) for v in t1[k, 1]] if k % 6 not in (1, 2) else None),
+              "done_first_last_us": [round(float(v - t1[mid, 0, 0]), 2) for v in t1[k, 2]]} for k in range(mid, min(mid + 7, nk1))]
+    one_per_layer = float(t1[6 * (model.n_layers - 1), 0, 0] - t1[6, 0, 0]) / max(model.n_layers - 2, 1) if model.n_layers > 2 else None
     lm.set_option("pipeline", 1)
     two = timed()
     tr = lm.profile_trace().astype(np.int64)            # [3 x kernels][first | last workgroup]
@@ -305,6 +323,7 @@ def step_timeline(args):
     lm.close()
     print(json.dumps({"step_timeline": args.workload, "layers": model.n_layers, "context": wl.prompt_len + 2 * n,
                       "one_stream_ms_per_token": one, "two_streams_ms_per_token": two, "two_streams_us_per_layer": per_layer,
+                      "one_stream_us_per_layer": one_per_layer, "kernels_of_one_layer_of_a_one_stream_step": rows1,
                       "kernels_of_one_two_stream_step": rows[:15] + rows[-6:]}))
 
 
@@ -642,7 +661,7 @@ def main():
                 "timing": "HIP events on the library's stream around every launch of 5 real decoding steps (graphs off for those "
                           "steps); the gap between two launches is inside this figure"}
     roofline["frac"] = roofline["achieved"] / roofline["peak"]
-    tr_us = trace_duration_us("k_gemv<bf16, 2, 4, false>") if (args.workload == "8b" and not args.layers and "fused_step_kernel" not in classes) else None
+    tr_us = trace_duration_us("k_gemv<bf16, 2, 4, 0>") if (args.workload == "8b" and not args.layers and "fused_step_kernel" not in classes) else None
     if tr_us:       # the same kernel's mean duration in the committed rocprofv3 kernel trace of this command
         roofline["trace"] = {"ms_per_launch": tr_us * 1e-3, "achieved": k_bytes / (tr_us * 1e-6) / 1e9, "frac": k_bytes / (tr_us * 1e-6) / HBM_PEAK,
                              "source": "profiles/8b_bench_kernel_stats.md (rocprofv3 --kernel-trace --stats)"}

@@ -213,6 +213,9 @@ int asynclm_synchronize(asynclm_ctx *ctx);
  *                  logits agree with the default within rounding).  Measured slower than the default on the 8B shape.
  *   "gemv_grid"    workgroups per matrix-vector kernel (default: the number of compute units).  For experiments; the
  *                  value is shared by every context of the process.
+ *   "step_stamps"  1 = the kernels of decoding steps of the default (one-stream) kind whose attention runs on the
+ *                  matrix cores leave time stamps for asynclm_profile_trace (measurement only; the step graphs are
+ *                  instantiated again when the option changes).
  *   "attn_split"   0 = choose the number of sequence splits of decode attention from the length,
  *                  1..128 = always use n (at most 64 apply to the single-row attention kernel, at most 128,
  *                  rounded up to a multiple of 4, to its matrix-core variant)
@@ -233,6 +236,9 @@ int asynclm_profile_step(asynclm_ctx *ctx, int32_t seq, int32_t forced_token, co
  * of the step (per layer: QKV, attention, O, gate/up, down; then the output head), out_host[(3 k + j) * 2 + w] is the
  * 100 MHz device clock at j = 0 kernel start, 1 hand-over from the previous kernel seen, 2 done, of w = 0 the first
  * workgroup (done: the workgroup that finished first), w = 1 the last one (done: the one that finished last).
+ * After a one-stream decoding step in stamp mode ("step_stamps"): the same layout with six kernels per layer (QKV,
+ * attention, merge of its key splits, O, gate/up, down; then the output head) and j = 1 = input vector staged in LDS
+ * (unused for the two attention kernels).
  * Otherwise, of the last asynclm_profile_step that ran as the fused kernel: out_host[i * n_workgroups + w]
  * is the 100 MHz device clock of workgroup w at phase boundary i (per layer: end of QKV, barrier passed, end of
  * attention, barrier, end of merge, barrier, end of O, barrier, end of gate/up, barrier, end of down, barrier;

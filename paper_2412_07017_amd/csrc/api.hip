@@ -58,7 +58,11 @@ struct asynclm_ctx {
     hipEvent_t ev_fork = nullptr, ev_join = nullptr;
     bool pipe_ok = false;               // two workgroups of every single-row kernel fit one compute unit
     unsigned long long* pipe_stamps = nullptr;   // per kernel of the step: see pipe_stamp
-    int pipe_kernels = 0;               // kernels of the last two-stream step (0: the last step was not one)
+    unsigned long long* stamp_done = nullptr;    // [pipe_kernels_max][STAMP_DONE_SLOTS]: see step_stamp_done
+    int pipe_kernels = 0;               // kernels of the last step that left time stamps (two streams, or stamp mode); else 0
+    int opt_step_stamps = 0;            // stamp mode: one-stream steps run as plain launches and leave time stamps
+    bool stamp_now = false;             // the pass being enqueued is such a step
+    bool last_step_stamp_mode = false;  // the last step was one
     int pipe_kernels_max = 0;
     unsigned* pipe_go = nullptr;        // [PIPE_REGIONS][PIPE_MAX_WORKGROUPS] hand-over words, one per cache line
     unsigned* pipe_counters = nullptr;  // [pipe_kernels_max] arrival counters, one per cache line
@@ -197,18 +201,39 @@ hipError_t forward_single(asynclm_ctx* c, int seq, bool with_head, SplitPlan sp)
     hipStream_t s = c->stream;
     hipError_t e;
     if ((e = run(c, KC_EMBED, [&] { return launch_embed(dt, c->embed, c->b, g, s); }))) return e;
+    // stamp mode (matrix-core attention plans): every kernel gets six stamp words, six kernels per layer, then the head
+    const bool stamps = c->stamp_now && c->pipe_stamps && c->stamp_done;
+    int idx = 0;
+    PipeSync ps{};
+    auto next = [&]() -> const PipeSync* {
+        if (!stamps) return nullptr;
+        ps.stamps = c->pipe_stamps + (size_t)idx * 6;
+        ps.done_wg = c->stamp_done + (size_t)idx * STAMP_DONE_SLOTS;
+        ++idx;
+        return &ps;
+    };
+    if (stamps && (e = launch_stamp_init(c->stamp_done, c->pipe_kernels, s))) return e;
     for (int l = 0; l < c->cfg.n_layers; ++l) {
         void* kvl = kv_layer_ptr(c, l);
-        if ((e = run(c, KC_QKV, [&] { return launch_qkv(dt, c->wqkv[l], c->attn_norm[l], kvl, c->b, g, s); }))) return e;
-        if (sp.mfma) { if ((e = run(c, KC_ATTN, [&] { return launch_decode_attn_mfma(c->cb, kvl, sp.nsplit, c->b, g, s); }))) return e; }
-        else if ((e = run(c, KC_ATTN, [&] { return launch_attn_decode(dt, kvl, sp.nsplit, sp.merge_in_oproj, c->b, g, s); }))) return e;
-        if ((e = run(c, KC_OPROJ, [&] { return launch_oproj(dt, c->wo[l], sp.merge_in_oproj ? sp.nsplit : 0, c->b, g, s); }))) return e;
-        if ((e = run(c, KC_GATEUP, [&] { return launch_gateup(dt, c->wgate_up[l], c->ffn_norm[l], c->b, g, s); }))) return e;
-        if ((e = run(c, KC_DOWN, [&] { return launch_down(dt, c->wdown[l], c->b, g, s); }))) return e;
+        const PipeSync* st = next();
+        if ((e = run(c, KC_QKV, [&] { return launch_qkv(dt, c->wqkv[l], c->attn_norm[l], kvl, c->b, g, s, st); }))) return e;
+        if (sp.mfma) {
+            unsigned long long* sw = stamps ? c->pipe_stamps + (size_t)idx * 6 : nullptr;
+            unsigned long long* dw = stamps ? c->stamp_done + (size_t)idx * STAMP_DONE_SLOTS : nullptr;
+            idx += stamps ? 2 : 0;
+            if ((e = run(c, KC_ATTN, [&] { return launch_decode_attn_mfma(c->cb, kvl, sp.nsplit, c->b, g, s, sw, dw); }))) return e;
+        } else if ((e = run(c, KC_ATTN, [&] { return launch_attn_decode(dt, kvl, sp.nsplit, sp.merge_in_oproj, c->b, g, s); }))) return e;
+        st = next();
+        if ((e = run(c, KC_OPROJ, [&] { return launch_oproj(dt, c->wo[l], sp.merge_in_oproj ? sp.nsplit : 0, c->b, g, s, st); }))) return e;
+        st = next();
+        if ((e = run(c, KC_GATEUP, [&] { return launch_gateup(dt, c->wgate_up[l], c->ffn_norm[l], c->b, g, s, st); }))) return e;
+        st = next();
+        if ((e = run(c, KC_DOWN, [&] { return launch_down(dt, c->wdown[l], c->b, g, s, st); }))) return e;
     }
     if (with_head) {
         // logits of every sequence live in one array; the kernels pick the row from the descriptor
-        if ((e = run(c, KC_LMHEAD, [&] { return launch_lmhead(dt, c->lm_head, c->final_norm, c->logits, c->b, g, s); }))) return e;
+        const PipeSync* st = next();
+        if ((e = run(c, KC_LMHEAD, [&] { return launch_lmhead(dt, c->lm_head, c->final_norm, c->logits, c->b, g, s, st); }))) return e;
         if ((e = run(c, KC_ARGMAX, [&] { return launch_argmax(c->logits, c->b, g, s); }))) return e;
     }
     return hipSuccess;
@@ -291,7 +316,14 @@ hipError_t capture_step(asynclm_ctx* c, SplitPlan sp, bool with_head, bool pipel
     hipError_t e;
     hipGraph_t graph = nullptr;
     if ((e = hipStreamBeginCapture(c->stream, hipStreamCaptureModeRelaxed))) return e;
-    e = pipelined ? forward_single_pipelined(c, 0, with_head, sp) : forward_single(c, 0, with_head, sp);
+    if (pipelined) e = forward_single_pipelined(c, 0, with_head, sp);
+    else {
+        // stamp mode: the captured kernels carry their stamp words (the graphs are rebuilt when the option changes)
+        c->stamp_now = c->opt_step_stamps && sp.mfma;
+        if (c->stamp_now) c->pipe_kernels = 6 * c->cfg.n_layers + (with_head ? 1 : 0);
+        e = forward_single(c, 0, with_head, sp);
+        c->stamp_now = false;
+    }
     hipError_t e2 = hipStreamEndCapture(c->stream, &graph);
     if (e) { if (graph) hipGraphDestroy(graph); return e; }
     if (e2) return e2;
@@ -362,10 +394,17 @@ hipError_t step_one_token(asynclm_ctx* c, int seq, int forced, bool with_head) {
         c->tok_early = true;
     }
     c->pipe_kernels = pipelined ? 5 * c->cfg.n_layers + (with_head ? 1 : 0) : 0;
+    const bool stamp_mode = c->opt_step_stamps && !pipelined && sp.mfma && !c->prof;
+    if (stamp_mode) c->pipe_kernels = 6 * c->cfg.n_layers + (with_head ? 1 : 0);
+    c->last_step_stamp_mode = stamp_mode;
     auto g_it = (c->opt_graph && !c->prof) ? c->graphs.find(graph_key(sp, with_head, pipelined)) : c->graphs.end();
     if (g_it != c->graphs.end()) e = hipGraphLaunch(g_it->second, c->stream);
     else if (pipelined) e = forward_single_pipelined(c, seq, with_head, sp);
-    else e = forward_single(c, seq, with_head, sp);
+    else {
+        c->stamp_now = stamp_mode;
+        e = forward_single(c, seq, with_head, sp);
+        c->stamp_now = false;
+    }
     if (e) return e;
     c->len[seq] += 1;
     return hipSuccess;
@@ -636,11 +675,12 @@ int asynclm_create(asynclm_ctx** out, const asynclm_config* cfg, const asynclm_w
     ALLOC(c->b.amax_i, (size_t)ARGMAX_MAX_BLOCKS);
     ALLOC(c->b.amax_counter, 1);
     ALLOC(c->b.banned, (size_t)cfg->max_seqs * (1 + BAN_MAX));
-    c->pipe_kernels_max = 5 * cfg->n_layers + 2;
+    c->pipe_kernels_max = 6 * cfg->n_layers + 2;      // two-stream step: 5 per layer; stamp mode of the one-stream step: 6
     ALLOC(c->b.pipe_abort, (size_t)PIPE_LINE_WORDS);
     ALLOC(c->pipe_go, (size_t)PIPE_REGIONS * PIPE_MAX_WORKGROUPS * PIPE_LINE_WORDS);
     ALLOC(c->pipe_counters, (size_t)c->pipe_kernels_max * PIPE_LINE_WORDS);
     ALLOC(c->pipe_stamps, (size_t)c->pipe_kernels_max * 6);
+    ALLOC(c->stamp_done, (size_t)c->pipe_kernels_max * STAMP_DONE_SLOTS);
     if (c->chunk_ok) {
         ChunkBuffers& cb = c->cb;
         const size_t M = CHUNK_MAX, qd = (size_t)g.Hq * g.dh;
@@ -1121,6 +1161,7 @@ int asynclm_set_option(asynclm_ctx* c, const char* name, int32_t value) {
     if (!std::strcmp(name, "pipeline")) { c->opt_pipeline = (value && c->pipe_ok) ? 1 : 0; return regraph(); }
     if (!std::strcmp(name, "graph")) { c->opt_graph = (value && c->stream) ? 1 : 0; return regraph(); }
     if (!std::strcmp(name, "attn_mfma_min")) { if (value < 0) return ASYNCLM_E_INVAL; c->opt_attn_mfma_min = value; return regraph(); }
+    if (!std::strcmp(name, "step_stamps")) { c->opt_step_stamps = value ? 1 : 0; return regraph(); }
     if (!std::strcmp(name, "attn_split")) { if (value < 0 || value > CHUNK_ATTN_MAX_SPLIT) return ASYNCLM_E_INVAL; c->opt_attn_split = value; return regraph(); }
     return ASYNCLM_E_INVAL;
 }
@@ -1186,13 +1227,26 @@ int asynclm_profile_step(asynclm_ctx* c, int32_t seq, int32_t forced_token, cons
 int asynclm_profile_trace(asynclm_ctx* c, uint64_t* out_host, int32_t cap, int32_t* n_stamps, int32_t* n_workgroups) {
     if (!c || !n_stamps || !n_workgroups) return ASYNCLM_E_INVAL;
     if (c->pipe_kernels > 0 && !c->opt_fused) {
-        // the last two-stream step: per kernel, start / hand-over seen / done of its first and of its last workgroup
+        // the last two-stream step (or one-stream step in stamp mode): per kernel, start / hand-over seen (input vector
+        // staged) / done of its first and of its last workgroup
         *n_stamps = 3 * c->pipe_kernels; *n_workgroups = 2;
         if (out_host) {
             if (cap < 6 * c->pipe_kernels) return ASYNCLM_E_INVAL;
             std::vector<unsigned long long> raw((size_t)6 * c->pipe_kernels);
             HIPCK(c, hipStreamSynchronize(c->stream));
             HIPCK(c, hipMemcpy(raw.data(), c->pipe_stamps, raw.size() * sizeof(unsigned long long), hipMemcpyDeviceToHost));
+            if (c->last_step_stamp_mode) {      // done: earliest and latest of the workgroups' own words
+                std::vector<unsigned long long> done((size_t)c->pipe_kernels * STAMP_DONE_SLOTS);
+                HIPCK(c, hipMemcpy(done.data(), c->stamp_done, done.size() * sizeof(unsigned long long), hipMemcpyDeviceToHost));
+                for (int k = 0; k < c->pipe_kernels; ++k) {
+                    unsigned long long lo = ~0ull, hi = 0;
+                    for (int w = 0; w < STAMP_DONE_SLOTS; ++w) {
+                        const unsigned long long t = done[(size_t)k * STAMP_DONE_SLOTS + w];
+                        if (t) { lo = std::min(lo, t); hi = std::max(hi, t); }
+                    }
+                    raw[(size_t)k * 6 + 2] = hi ? lo : 0; raw[(size_t)k * 6 + 5] = hi;
+                }
+            }
             for (int k = 0; k < c->pipe_kernels; ++k)
                 for (int w = 0; w < 2; ++w)
                     for (int j = 0; j < 3; ++j) out_host[(size_t)(3 * k + j) * 2 + w] = raw[(size_t)k * 6 + w * 3 + j];

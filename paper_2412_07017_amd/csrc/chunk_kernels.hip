@@ -1095,12 +1095,17 @@ struct DecodeAttnArgs {
     float* part_ml;             // [Hkv][nsplit][2][G]
     float* out;                 // [Hq][128]
     int32_t nsplit;
+    unsigned long long* stamps; // stamp mode of the one-stream step: six words for this kernel, six for the merge
+    unsigned long long* done_wg; // ... and STAMP_DONE_SLOTS finishing-time words each
 };
 
 __global__ __launch_bounds__(256) void k_decode_attn_mfma(DecodeAttnArgs a, Geom g) {
     constexpr int DH = 128;
     extern __shared__ uint4 attn_lds[];                    // [4 waves][hi | lo][512 chunks] K tiles
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    PipeSync stamp{};
+    stamp.stamps = a.stamps; stamp.done_wg = a.done_wg;
+    const unsigned long long t_start = clock_if(stamp.done_wg != nullptr);
     const int i = lane & 31, gh = lane >> 5;
     uint4* kt = attn_lds + wave * 1024;
     const int G = g.Hq / g.Hkv;
@@ -1169,7 +1174,7 @@ __global__ __launch_bounds__(256) void k_decode_attn_mfma(DecodeAttnArgs a, Geom
             }
         }
     }
-
+    step_stamp_done(stamp, t_start, 0);
 }
 
 // Merge of the key splits: grid (Hkv, G * 128 / 64), a workgroup writes 64 of the kv group's G x 128 outputs.  Thread =
@@ -1180,6 +1185,9 @@ __global__ __launch_bounds__(256) void k_decode_attn_merge(DecodeAttnArgs a, Geo
     __shared__ float f[8 * CHUNK_ATTN_MAX_SPLIT];          // [G][nused] weights exp(m_s - M) / L
     __shared__ float red[256];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    PipeSync stamp{};
+    stamp.stamps = a.stamps ? a.stamps + 6 : nullptr; stamp.done_wg = a.done_wg ? a.done_wg + STAMP_DONE_SLOTS : nullptr;
+    const unsigned long long t_start = clock_if(stamp.done_wg != nullptr);
     const int G = g.Hq / g.Hkv;
     const int kvh = blockIdx.x, nsplit = a.nsplit;
     const int ntile = (a.step->pos + 32) >> 5;
@@ -1221,6 +1229,7 @@ __global__ __launch_bounds__(256) void k_decode_attn_merge(DecodeAttnArgs a, Geo
             a.out[(size_t)kvh * G * DH + idx] = (red[lane] + red[64 + lane]) + (red[128 + lane] + red[192 + lane]);
         __syncthreads();
     }
+    step_stamp_done(stamp, t_start, 0);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -1592,14 +1601,14 @@ hipError_t launch_chunk_attn_wide(const ChunkBuffers& c, const void* kv_layer, i
 }
 
 hipError_t launch_decode_attn_mfma(const ChunkBuffers& c, const void* kv_layer, int nsplit, const DecodeBuffers& b, const Geom& g,
-                                   hipStream_t s) {
+                                   hipStream_t s, unsigned long long* stamps, unsigned long long* done_wg) {
     const int G = g.Hq / g.Hkv;
     if (g.dh != 128 || G > 8 || nsplit < 4 || nsplit % 4 || nsplit > CHUNK_ATTN_MAX_SPLIT ||
         (long long)g.Hkv * nsplit > CHUNK_ATTN_MAX_UNITS)
         return hipErrorInvalidValue;
     DecodeAttnArgs a{};
     a.q = b.q; a.step = b.step; a.kv_layer = (const bf16_t*)kv_layer;
-    a.part_o = c.attn_o; a.part_ml = c.attn_ml; a.out = b.o; a.nsplit = nsplit;
+    a.part_o = c.attn_o; a.part_ml = c.attn_ml; a.out = b.o; a.nsplit = nsplit; a.stamps = stamps; a.done_wg = done_wg;
     hipLaunchKernelGGL(k_decode_attn_mfma, dim3(g.Hkv, nsplit / 4), dim3(256), ATTN_LDS_BYTES, s, a, g);
     hipError_t e = hipGetLastError();
     if (e) return e;

@@ -133,7 +133,9 @@ struct PipeSync {
     const StepDesc* step;       // step number
     unsigned wait_kernel, my_kernel;   // kernel numbers within the step
     unsigned long long* stamps; // optional, see pipe_stamp
+    unsigned long long* done_wg; // optional, stamp mode of the one-stream step: see step_stamp_done
 };
+constexpr int STAMP_DONE_SLOTS = 512;   // workgroups of a kernel whose finishing times are kept
 constexpr unsigned PIPE_SPIN_LIMIT = 1u << 17;
 #ifndef PIPE_POLL_SLEEP
 #define PIPE_POLL_SLEEP 2      // x 64 clocks between two polls of a waiting workgroup
@@ -153,6 +155,34 @@ __device__ __forceinline__ void pipe_stamp(const PipeSync& ps, int which) {
     if (first) ps.stamps[which] = wall_clock64();
     if (last) ps.stamps[3 + which] = wall_clock64();
 #endif
+}
+
+// The 100 MHz clock if `on`, else 0.  The read takes about a microsecond and its result comes back with the kernel's
+// argument loads, so it must not happen at all when no stamps are wanted; as an ordinary expression the compiler
+// executes it anyway and selects (measured: 3.5 % of a decoding step), hence the volatile statement inside a branch.
+__device__ __forceinline__ unsigned long long clock_if(bool on) {
+    unsigned long long t = 0;
+    if (on) asm volatile("s_memrealtime %0\n\ts_waitcnt lgkmcnt(0)" : "=s"(t));
+    return t;
+}
+
+// One-stream steps in stamp mode use words 0, 1, 3, 4 of the same six words per kernel (start and "input vector staged"
+// of the first and of the last workgroup); every workgroup stores the time it is done to a word of its own (zero before
+// the step), and the host takes the earliest and the latest (an atomic minimum / maximum on one word would cost 11 ns
+// per workgroup, 3 us per kernel).  t_staged: the clock when the input vector was staged, read then and stored only
+// here like the start: a store that may or may not happen among a kernel's requests would keep the compiler from
+// counting the requests in flight, and it would wait for all of them (measured: 1.5-2 us per kernel).
+// All threads of the workgroup call this.
+__device__ __forceinline__ void step_stamp_done(const PipeSync& ps, unsigned long long t_start, unsigned long long t_staged) {
+    if (!ps.done_wg) return;
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    const unsigned wg = blockIdx.y * gridDim.x + blockIdx.x;
+    if (threadIdx.x == 0 && wg < (unsigned)STAMP_DONE_SLOTS) ps.done_wg[wg] = wall_clock64();
+    if (threadIdx.x == 0 && ps.stamps) {
+        if (wg == 0) { ps.stamps[0] = t_start; ps.stamps[1] = t_staged; }
+        if (wg == gridDim.x * gridDim.y - 1) { ps.stamps[3] = t_start; ps.stamps[4] = t_staged; }
+    }
 }
 
 // All threads of the workgroup call this; false: give up (uniform).

@@ -75,14 +75,20 @@ struct GemvArgs {
 // requests its first weight tiles, waits for the producer's workgroups (PipeSync), and only then reads the vector;
 // its own results are written through, and when they have arrived it counts itself into its own flag.  Two workgroups of such kernels
 // fit one compute unit (launch bounds), so the workgroups of two neighbouring kernels are always all resident.
-template <typename WT, int EPI, int NB, bool PIPE>
-__global__ __launch_bounds__(256, PIPE ? 2 : 1) void k_gemv(GemvArgs a, Geom g) {
+// MODE 0: the default kernel; 1 (PIPE): the two-stream variant above; 2 (STAMP): the default kernel leaving time stamps
+// (stamp mode of the one-stream step).  The stamps are a variant of their own because even a skipped clock read at the
+// start of the kernel costs a microsecond: the branch around it waits for one kernel argument before the other argument
+// loads are issued.
+template <typename WT, int EPI, int NB, int MODE>
+__global__ __launch_bounds__(256, MODE == 1 ? 2 : 1) void k_gemv(GemvArgs a, Geom g) {
+    constexpr bool PIPE = MODE == 1, STAMP = MODE == 2;
     constexpr int EPL = Elem<WT>::EPL;
     extern __shared__ float4 lds4[];
     __shared__ float red[4];
     __shared__ int s_go;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     if (PIPE) pipe_stamp(a.sync, 0);
+    const unsigned long long t_start = STAMP ? wall_clock64() : 0ull;      // stored at the kernel's end
 
     Phase<WT> ph = make_phase<WT, EPI>(a.W, a.rows, a.K, a.units);
     const int plane_stride = ph.KT * 256 + 64;
@@ -124,9 +130,21 @@ __global__ __launch_bounds__(256, PIPE ? 2 : 1) void k_gemv(GemvArgs a, Geom g) 
         ssq = stage_vector<WT, (EPI == EPI_RESID ? 16 : 4)>(lds4, plane_stride, vs, a.K, ph.Kg, ph.KT, true, red);
     }
     const float nscale = a.gain ? rsqrtf(ssq / (float)a.K + g.eps) : 1.f;
+    const unsigned long long t_staged = STAMP ? wall_clock64() : 0ull;
     float best_v = -INFINITY; int best_i = 0x7fffffff;
     phase_run<WT, EPI>(ring, ph, lc, lds4, plane_stride, nscale, eo, g, lane, done, best_v, best_i);
     if (PIPE) pipe_signal(a.sync, &s_go);
+    if (STAMP) step_stamp_done(a.sync, t_start, t_staged);
+}
+
+// The finishing-time words of every workgroup of every kernel of a step in stamp mode start at zero.
+__global__ void k_stamp_init(unsigned long long* done_wg, size_t n) {
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) done_wg[i] = 0ull;
+}
+
+hipError_t launch_stamp_init(unsigned long long* done_wg, int kernels, hipStream_t s) {
+    hipLaunchKernelGGL(k_stamp_init, dim3(64), dim3(256), 0, s, done_wg, (size_t)kernels * STAMP_DONE_SLOTS);
+    return hipGetLastError();
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -341,13 +359,13 @@ static size_t g_gemv_lds_limit = 48 * 1024;   // dynamic LDS a matrix-vector ker
 template <int EPI> struct EarlyNB { static constexpr int SMALL = 4, LARGE = EPI == EPI_RESID ? 16 : 8, HUGE = 32; };
 
 template <typename WT, int EPI, int NB>
-static const void* gemv_func_n(bool pipe) {
-    return pipe ? (const void*)(k_gemv<WT, EPI, NB, true>) : (const void*)(k_gemv<WT, EPI, NB, false>);
+static const void* gemv_func_n(int mode) {
+    return mode == 1 ? (const void*)(k_gemv<WT, EPI, NB, 1>) : mode == 2 ? (const void*)(k_gemv<WT, EPI, NB, 2>) : (const void*)(k_gemv<WT, EPI, NB, 0>);
 }
 
 // The instantiation that serves a product with K columns (plain_x: the input is a plain vector, not split partials).
 template <typename WT, int EPI>
-static const void* gemv_func(int K, bool plain_x, bool pipe) {
+static const void* gemv_func(int K, bool plain_x, int pipe /* mode: 0 default, 1 two-stream, 2 stamps */) {
     if (plain_x && K <= 1024 * EarlyNB<EPI>::SMALL) return gemv_func_n<WT, EPI, EarlyNB<EPI>::SMALL>(pipe);
     if (plain_x && K <= 1024 * EarlyNB<EPI>::LARGE) return gemv_func_n<WT, EPI, EarlyNB<EPI>::LARGE>(pipe);
     if (EPI == EPI_RESID && plain_x && K <= 1024 * EarlyNB<EPI>::HUGE) return gemv_func_n<WT, EPI_RESID, EarlyNB<EPI_RESID>::HUGE>(pipe);
@@ -368,10 +386,10 @@ static hipError_t launch_gemv_t(const GemvArgs& a0, const Geom& g, hipStream_t s
     if (lds > g_gemv_lds_limit) return hipErrorInvalidValue;
     if (EPI != EPI_RESID && !(a.x && a.gain)) return hipErrorInvalidValue;   // the normalising products take a vector and a gain
     if (EPI == EPI_RESID && a.gain) return hipErrorInvalidValue;
-    const bool pipe = a.sync.go_wait || a.sync.go_signal;
+    const int mode = (a.sync.go_wait || a.sync.go_signal) ? 1 : a.sync.done_wg ? 2 : 0;
     Geom gg = g;
     void* params[] = {&a, &gg};
-    return hipLaunchKernel(gemv_func<WT, EPI>(a.K, a.x != nullptr, pipe), dim3(g_gemv_grid), dim3(256), params, lds, s);
+    return hipLaunchKernel(gemv_func<WT, EPI>(a.K, a.x != nullptr, mode), dim3(g_gemv_grid), dim3(256), params, lds, s);
 }
 
 template <typename WT>
@@ -384,7 +402,7 @@ static hipError_t launch_gemv_w(int epi, const GemvArgs& a, const Geom& g, hipSt
     }
 }
 
-template <typename WT, int EPI, bool PIPE>
+template <typename WT, int EPI, int PIPE /* mode */>
 static hipError_t set_lds_p(int bytes) {
     hipError_t e;
     if ((e = hipFuncSetAttribute((const void*)(k_gemv<WT, EPI, 0, PIPE>), hipFuncAttributeMaxDynamicSharedMemorySize, bytes))) return e;
@@ -395,8 +413,9 @@ static hipError_t set_lds_p(int bytes) {
 }
 template <typename WT, int EPI>
 static hipError_t set_lds_t(int bytes) {
-    hipError_t e = set_lds_p<WT, EPI, false>(bytes);
-    return e ? e : set_lds_p<WT, EPI, true>(bytes);
+    hipError_t e = set_lds_p<WT, EPI, 0>(bytes);
+    if (!e) e = set_lds_p<WT, EPI, 1>(bytes);
+    return e ? e : set_lds_p<WT, EPI, 2>(bytes);
 }
 
 void decode_set_gemv_grid(int grid) { g_gemv_grid = grid; }
@@ -570,12 +589,12 @@ static bool pipeline_fits_t(const Geom& g, bool kv_pair) {
     Item items[6];
     int dc = 0, n = 0;
     const int nqkv = (g.Hq + 2 * g.Hkv) * g.dh, qd = g.Hq * g.dh, grid = g_gemv_grid;
-    items[n++] = {gemv_func<WT, EPI_QKV>(g.d, true, true), gemv_lds_bytes<WT>(g.d, nqkv / 2, grid, &dc)};
-    items[n++] = {gemv_func<WT, EPI_RESID>(qd, false, true), gemv_lds_bytes<WT>(qd, (g.d + 1) / 2, grid, &dc)};   // merges the key splits
-    items[n++] = {gemv_func<WT, EPI_RESID>(qd, true, true), gemv_lds_bytes<WT>(qd, (g.d + 1) / 2, grid, &dc)};
-    items[n++] = {gemv_func<WT, EPI_SWIGLU>(g.d, true, true), gemv_lds_bytes<WT>(g.d, g.F, grid, &dc)};
-    items[n++] = {gemv_func<WT, EPI_RESID>(g.F, true, true), gemv_lds_bytes<WT>(g.F, (g.d + 1) / 2, grid, &dc)};
-    items[n++] = {gemv_func<WT, EPI_STORE>(g.d, true, true), gemv_lds_bytes<WT>(g.d, (g.V + 1) / 2, grid, &dc)};
+    items[n++] = {gemv_func<WT, EPI_QKV>(g.d, true, 1), gemv_lds_bytes<WT>(g.d, nqkv / 2, grid, &dc)};
+    items[n++] = {gemv_func<WT, EPI_RESID>(qd, false, 1), gemv_lds_bytes<WT>(qd, (g.d + 1) / 2, grid, &dc)};   // merges the key splits
+    items[n++] = {gemv_func<WT, EPI_RESID>(qd, true, 1), gemv_lds_bytes<WT>(qd, (g.d + 1) / 2, grid, &dc)};
+    items[n++] = {gemv_func<WT, EPI_SWIGLU>(g.d, true, 1), gemv_lds_bytes<WT>(g.d, g.F, grid, &dc)};
+    items[n++] = {gemv_func<WT, EPI_RESID>(g.F, true, 1), gemv_lds_bytes<WT>(g.F, (g.d + 1) / 2, grid, &dc)};
+    items[n++] = {gemv_func<WT, EPI_STORE>(g.d, true, 1), gemv_lds_bytes<WT>(g.d, (g.V + 1) / 2, grid, &dc)};
     for (int i = 0; i < n; ++i) {
         int per_cu = 0;
         if (items[i].lds > g_gemv_lds_limit) return false;

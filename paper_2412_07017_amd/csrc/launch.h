@@ -131,8 +131,11 @@ hipError_t launch_chunk_attn(const ChunkBuffers& c, const void* kv_layer, int ns
 hipError_t launch_chunk_attn_wide(const ChunkBuffers& c, const void* kv_layer, int nsplit, int ntasks, int nblocks, const Geom& g,
                                   hipStream_t s);
 // single-row decoding attention on the matrix cores (long contexts): b.q -> b.o through the chunk attention
+// stamps / done_wg: null, or the stamp words (2 x 6) and finishing-time words (2 x STAMP_DONE_SLOTS) of the attention
+// kernel and of its merge kernel (see step_stamp_done)
 hipError_t launch_decode_attn_mfma(const ChunkBuffers& c, const void* kv_layer, int nsplit, const DecodeBuffers& b, const Geom& g,
-                                   hipStream_t s);
+                                   hipStream_t s, unsigned long long* stamps = nullptr, unsigned long long* done_wg = nullptr);
+hipError_t launch_stamp_init(unsigned long long* done_wg, int kernels, hipStream_t s);
 // token_early: pinned host word that also gets the chosen token (or nullptr)
 hipError_t launch_begin_step(const DecodeBuffers& b, int seq, int forced, int32_t* token_early, hipStream_t s);
 hipError_t launch_embed(int dtype, const void* E, const DecodeBuffers& b, const Geom& g, hipStream_t s);

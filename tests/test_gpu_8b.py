@@ -122,6 +122,37 @@ def test_two_stream_decoding_step_matches_oracle(trunc4):
         assert worst <= TOL, worst
 
 
+def test_step_stamps_leave_the_step_unchanged_and_are_in_order(trunc4):
+    """Stamp mode of the default decoding step (measurement aid): the kernels leave their start / vector staged / done
+    times; the logits are those of the same step without stamps, bit for bit, and the stamps of a step are ordered:
+    within a kernel start <= first done <= last done, and a kernel starts after the kernel before it is done."""
+    import paper_2412_07017_amd as pkg
+    wl, model, w_dev, w_cpu, spec = trunc4
+    prompt = spec["prompt"][:300]
+    toks = [int(t) for t in spec["prompt"][300:306]]
+    out = []
+    for stamps_on in (0, 1):
+        lm = pkg.AsyncLM(model, w_dev, max_positions=400, stream=torch.cuda.Stream())
+        lm.set_option("step_stamps", stamps_on)
+        lm.prefill(0, prompt)
+        for t in toks:
+            lm.decode_step(0, forced_token=t)
+        out.append(lm.logits(0).copy())
+        tr = lm.profile_trace().astype(np.int64)
+        if stamps_on:
+            nk = 6 * model.n_layers + 1
+            assert tr.shape == (3 * nk, 2), tr.shape
+            t = tr.reshape(nk, 3, 2)
+            for k in range(nk):
+                start, done_first, done_last = t[k, 0].min(), t[k, 2, 0], t[k, 2, 1]
+                assert 0 < start <= done_first <= done_last, (k, t[k])
+                if k:
+                    assert t[k, 0].min() >= t[k - 1, 2, 1], (k, t[k - 1], t[k])
+            assert (t[-1, 2, 1] - t[0, 0].min()) / 100.0 < 5000.0          # a 4-layer step takes well under 5 ms
+        lm.close()
+    assert np.array_equal(out[0], out[1])
+
+
 @pytest.mark.timeout(600)
 def test_append_chunk_sizes_agree_with_oracle_and_each_other(trunc4):
     """The matrix-core append path for every chunk shape (ragged tails, one to three row tiles through the
