@@ -451,6 +451,20 @@ struct Slot {
     float e0, e1;
 };
 
+// The same with the split of the units over the waves given by the host: uq = units / waves, ur = units % waves, the
+// first ur waves own one unit more.  No division in the kernel: the two 64-bit divisions of make_phase stand between
+// the kernel's start and its first weight request (about a microsecond).
+template <typename WT, int EPI>
+__device__ __forceinline__ Phase<WT> make_phase_split(const void* W, int rows, int K, int units, int uq, int ur) {
+    Phase<WT> p;
+    p.W = (const WT*)W; p.rows = rows; p.K = K; p.Kg = K / Elem<WT>::EPL;
+    p.KT = (p.Kg + 255) / 256; p.units = units;
+    const int gw = (int)blockIdx.x * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    p.u0 = gw * uq + min(gw, ur); p.u1 = p.u0 + uq + (gw < ur ? 1 : 0);
+    p.rot = (int)((unsigned)gw % (unsigned)p.KT);
+    return p;
+}
+
 template <typename WT, int EPI>
 __device__ __forceinline__ Phase<WT> make_phase(const void* W, int rows, int K, int units) {
     Phase<WT> p;

@@ -52,6 +52,7 @@ struct GemvArgs {
     const void* W;          // [rows, K] row-major
     int32_t rows, K;
     int32_t units;          // row pairs to compute
+    int32_t uq, ur;         // units / waves of the grid, units % waves (set by the launcher)
     int32_t done_cap;       // finished row pairs a wave can park in LDS
     const float* x;         // [K] fp32 input vector
     const float* gain;      // [K] RMSNorm gain, or nullptr for no normalisation
@@ -90,10 +91,6 @@ __global__ __launch_bounds__(256, MODE == 1 ? 2 : 1) void k_gemv(GemvArgs a, Geo
     if (PIPE) pipe_stamp(a.sync, 0);
     const unsigned long long t_start = STAMP ? wall_clock64() : 0ull;      // stored at the kernel's end
 
-    Phase<WT> ph = make_phase<WT, EPI>(a.W, a.rows, a.K, a.units);
-    const int plane_stride = ph.KT * 256 + 64;
-    float4* done = lds4 + (size_t)plane_stride * (EPL / 4) + (size_t)wave * a.done_cap;
-
     // NB > 0 (the vector is a plain one that fits one batch of NB x 16 bytes per thread; with a gain in the
     // normalising products, without in the residual ones): it is requested before the first weight tiles, so it is
     // back and staged long before them, and the first tile is multiplied as soon as it arrives.  NB = 0: the vector
@@ -105,6 +102,9 @@ __global__ __launch_bounds__(256, MODE == 1 ? 2 : 1) void k_gemv(GemvArgs a, Geo
         early_request(vb, a.x, a.gain, a.K);
         __builtin_amdgcn_sched_barrier(0);
     }
+    Phase<WT> ph = make_phase_split<WT, EPI>(a.W, a.rows, a.K, a.units, a.uq, a.ur);
+    const int plane_stride = ph.KT * 256 + 64;
+    float4* done = lds4 + (size_t)plane_stride * (EPL / 4) + (size_t)wave * a.done_cap;
     Slot ring[RING];
     Cursor lc;
     phase_prefetch_w<WT, EPI>(ring, ph, lane, g);
@@ -383,6 +383,7 @@ template <typename WT, int EPI>
 static hipError_t launch_gemv_t(const GemvArgs& a0, const Geom& g, hipStream_t s) {
     GemvArgs a = a0;
     const size_t lds = gemv_lds_bytes<WT>(a.K, a.units, g_gemv_grid, &a.done_cap);
+    a.uq = a.units / (g_gemv_grid * 4); a.ur = a.units % (g_gemv_grid * 4);
     if (lds > g_gemv_lds_limit) return hipErrorInvalidValue;
     if (EPI != EPI_RESID && !(a.x && a.gain)) return hipErrorInvalidValue;   // the normalising products take a vector and a gain
     if (EPI == EPI_RESID && a.gain) return hipErrorInvalidValue;
