@@ -417,7 +417,7 @@ __global__ __launch_bounds__(256) void k_chunk_gemm(const bf16_t* __restrict__ W
     const int nr = SWIGLU ? max(0, min(rp, (N >> 1) - n0)) : 32;                              // SWIGLU: gate rows of this wave
     const int sp = blockIdx.y;
     const int nblk = K >> 7;
-    const int b0 = (int)((long long)nblk * sp / S), b1 = (int)((long long)nblk * (sp + 1) / S);
+    const int b0 = (int)((unsigned)(nblk * sp) / (unsigned)S), b1 = (int)((unsigned)(nblk * (sp + 1)) / (unsigned)S);   // (K / 128) * S < 2^31
     const int nb = b1 - b0;
 
     const bf16_t* wlane = W + (size_t)(SWIGLU ? 0 : n0 + (lane >> 4)) * K + (lane & 15) * 8;   // row l/16 (+4q), chunk l%16
@@ -589,7 +589,7 @@ __global__ __launch_bounds__(NW * 64) void k_chunk_gemm_wide(const bf16_t* __res
         }
     }
     const int nblk = K >> 7;
-    const int b0 = (int)((long long)nblk * sp / S), b1 = (int)((long long)nblk * (sp + 1) / S);
+    const int b0 = (int)((unsigned)(nblk * sp) / (unsigned)S), b1 = (int)((unsigned)(nblk * (sp + 1)) / (unsigned)S);   // (K / 128) * S < 2^31
     const int nb = b1 - b0, last = b1 - 1;
     const int n0 = ntile * 128;
 
@@ -732,7 +732,7 @@ __global__ __launch_bounds__(256) void k_chunk_gemm_ks(const bf16_t* __restrict_
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int ntile = blockIdx.x, sp = blockIdx.y;
     const int nblk = K >> 7;
-    const int b0 = (int)((long long)nblk * sp / S), b1 = (int)((long long)nblk * (sp + 1) / S);
+    const int b0 = (int)((unsigned)(nblk * sp) / (unsigned)S), b1 = (int)((unsigned)(nblk * (sp + 1)) / (unsigned)S);   // (K / 128) * S < 2^31
     const int nb = b1 - b0;
     const int n0 = ntile * 128;
 
