@@ -135,7 +135,7 @@ struct PipeSync {
     unsigned long long* stamps; // optional, see pipe_stamp
     unsigned long long* done_wg; // optional, stamp mode of the one-stream step: see step_stamp_done
 };
-constexpr int STAMP_DONE_SLOTS = 512;   // workgroups of a kernel whose finishing times are kept
+constexpr int STAMP_DONE_SLOTS = 1024;  // workgroups of a kernel whose finishing times are kept
 constexpr unsigned PIPE_SPIN_LIMIT = 1u << 17;
 #ifndef PIPE_POLL_SLEEP
 #define PIPE_POLL_SLEEP 2      // x 64 clocks between two polls of a waiting workgroup

@@ -125,7 +125,7 @@ def test_two_stream_decoding_step_matches_oracle(trunc4):
 def test_step_stamps_leave_the_step_unchanged_and_are_in_order(trunc4):
     """Stamp mode of the default decoding step (measurement aid): the kernels leave their start / vector staged / done
     times; the logits are those of the same step without stamps, bit for bit, and the stamps of a step are ordered:
-    within a kernel start <= first done <= last done, and a kernel starts after the kernel before it is done."""
+    within a kernel start <= last done and first done <= last done, and a kernel starts after the kernel before it is done."""
     import paper_2412_07017_amd as pkg
     wl, model, w_dev, w_cpu, spec = trunc4
     prompt = spec["prompt"][:300]
@@ -145,7 +145,8 @@ def test_step_stamps_leave_the_step_unchanged_and_are_in_order(trunc4):
             t = tr.reshape(nk, 3, 2)
             for k in range(nk):
                 start, done_first, done_last = t[k, 0].min(), t[k, 2, 0], t[k, 2, 1]
-                assert 0 < start <= done_first <= done_last, (k, t[k])
+                # (a workgroup of the attention that has no keys can be done before workgroup 0 has read its clock)
+                assert 0 < start <= done_last and start - 100 <= done_first <= done_last, (k, t[k])
                 if k:
                     assert t[k, 0].min() >= t[k - 1, 2, 1], (k, t[k - 1], t[k])
             assert (t[-1, 2, 1] - t[0, 0].min()) / 100.0 < 5000.0          # a 4-layer step takes well under 5 ms
